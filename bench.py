@@ -1,0 +1,135 @@
+"""Benchmark of the hash-encoding hot path on one MI355X.
+
+A step is one forward plus one backward pass of the encoding over one batch of
+synthetic points (inputs resident in HBM).  Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+
+
+def algorithmic_bytes(w, s_theta, s_io):
+    """Bytes the method itself moves per point: positions, the 2^d * L gathers (or
+    fp32 atomic updates, counted once at 4 B) of F scalars, and the output / upstream-gradient row."""
+    corners = (1 << w.d) * w.L
+    fwd = 4 * w.d + corners * w.F * s_theta + w.L * w.F * s_io
+    bwd = 4 * w.d + w.L * w.F * s_io + corners * w.F * 4
+    return fwd, bwd
+
+
+def time_launches(fn, n, torch):
+    """Average duration of n back-to-back launches, HIP events on the launch stream."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(n):
+        fn()
+    e1.record()
+    e1.synchronize()
+    return e0.elapsed_time(e1) / n  # ms
+
+
+def cpu_baseline(w, x, theta, dy, budget_s=10.0):
+    import numpy as np
+    from oracle import hashgrid_oracle as orc
+
+    cfg = orc.OracleConfig(w.d, w.L, w.F, w.T, w.N_min, w.N_max)
+    nb = min(len(x), 1 << 18)
+    xs, dys = x[:nb], dy[:nb].astype(np.float64)
+    th = theta.astype(np.float64)
+    orc.encode_fwd(cfg, xs[:1024], th)  # load + first touch
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        orc.encode_fwd(cfg, xs, th)
+        orc.encode_bwd(cfg, xs, dys)
+        reps += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s or reps >= 64:
+            break
+    return {"value": nb * reps / el / 1e6, "unit": "Mpoints/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"{reps} fwd+bwd passes over the first {nb} points of the workload, {el:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="sdf3d")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only; run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2201_05989_amd import HashGrid, synth
+
+    w = synth.WORKLOADS[args.workload]
+    grid = HashGrid(w.d, w.L, w.F, w.T, w.N_min, w.N_max, w.param_dtype, w.io_dtype)
+    x, theta, dy = synth.make_inputs(w, grid.n_entries)
+    xd, td, gd = (torch.from_numpy(a).cuda() for a in (x, theta, dy))
+    y = torch.empty((w.B, w.L * w.F), dtype=grid.io_dtype, device="cuda")
+    grad = torch.zeros((grid.n_entries, w.F), dtype=torch.float32, device="cuda")
+
+    def fwd():
+        grid.encode_fwd(xd, td, y)
+
+    def bwd():
+        grid.encode_bwd(xd, gd, grad)
+
+    def step():
+        fwd()
+        bwd()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    n = max(args.steps, 20)
+    ms_fwd = time_launches(fwd, n, torch)
+    ms_bwd = time_launches(bwd, n, torch)
+    ms_zero = time_launches(lambda: grad.zero_(), 20, torch)
+
+    s_theta = 2 if w.param_dtype == "f16" else 4
+    s_io = 2 if w.io_dtype == "f16" else 4
+    b_fwd, b_bwd = algorithmic_bytes(w, s_theta, s_io)
+    dom = ("bwd", ms_bwd, b_bwd) if ms_bwd >= ms_fwd else ("fwd", ms_fwd, b_fwd)
+    achieved = dom[2] * w.B / (dom[1] * 1e-3) / 1e9
+
+    out = {
+        "metric": "hash-grid encoding fwd+bwd throughput",
+        "value": w.B / (ms_step * 1e-3) / 1e6,
+        "unit": "Mpoints/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: d={w.d} L={w.L} F={w.F} T=2^{w.T.bit_length() - 1} "
+                               f"N_min={w.N_min} N_max={w.N_max} B={w.B} points={w.points}",
+                   "param_dtype": w.param_dtype, "io_dtype": w.io_dtype, "grad_dtype": "f32"},
+        "fwd_mpoints_s": w.B / (ms_fwd * 1e-3) / 1e6,
+        "bwd_mpoints_s": w.B / (ms_bwd * 1e-3) / 1e6,
+        "ms_fwd": ms_fwd, "ms_bwd": ms_bwd, "ms_grad_zero": ms_zero,
+        "roofline": {"bound": "hbm", "kernel": dom[0], "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_point": {"fwd": b_fwd, "bwd": b_bwd}},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, x, theta, dy)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,128 @@
+/*
+ * hashgrid.h - C ABI of the multiresolution hash encoding for AMD MI355X (gfx950).
+ *
+ * The encoding y = enc(x; theta) is the one of Section 3 of "Instant Neural
+ * Graphics Primitives with a Multiresolution Hash Encoding" (Eq. 2-4, Fig. 3):
+ * for each of L levels of resolution N_l = floor(N_min * b^l) (Eq. 2-3) the
+ * point x in [0,1)^d is scaled by N_l, the 2^d corners of its voxel are mapped
+ * to entries of that level's feature array (1:1 where (N_l+1)^d <= T, else by
+ * the spatial hash of Eq. 4), the F-wide feature vectors are gathered and
+ * d-linearly interpolated with weights w_l = x_l - floor(x_l), and the L
+ * results are concatenated.  The backward pass accumulates dL/dy times the
+ * interpolation weight into the gathered entries (Fig. 3 caption).
+ *
+ * Conventions shared by every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller; the library
+ *     never allocates, frees or copies device memory and never synchronises.
+ *     Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
+ *     default stream) and the call returns at once.
+ *   - x is fp32, row-major [B, d], every coordinate finite and in [0,1).  This
+ *     is a precondition; coordinates outside the range give unspecified values
+ *     but never an out-of-bounds access.
+ *   - Tables (theta) are one flat array [n_entries, F] of `param_dtype`:
+ *     level-major, entry-major, feature-minor; level l starts at entry
+ *     `entry_offset` reported by hashgrid_level_info and holds `n_entries`
+ *     entries, with no padding between levels.
+ *   - y and dL/dy are row-major [B, L*F] of `io_dtype`, level-major inside a row
+ *     (the concatenation of Fig. 3, step 4).
+ *   - Table gradients are always fp32, same shape as theta.
+ *   - Errors are returned as status codes; nothing aborts or throws.  B = 0 is
+ *     HG_OK and launches nothing.
+ */
+#ifndef HASHGRID_H
+#define HASHGRID_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HG_MAX_LEVELS 32u
+
+typedef struct hashgrid hashgrid_t; /* opaque, host memory, owned by the library */
+
+typedef enum {
+  HG_OK = 0,
+  HG_ERR_INVALID_ARG = 1, /* NULL pointer, zero size, N_max < N_min, level out of range ... */
+  HG_ERR_UNSUPPORTED = 2, /* d > 3, F not in {1,2,4,8}, L > HG_MAX_LEVELS, table too large      */
+  HG_ERR_ALLOC = 3,       /* host allocation of the handle failed                               */
+  HG_ERR_DEVICE = 4       /* the HIP runtime refused a launch                                   */
+} hg_status;
+
+typedef enum { HG_F32 = 0, HG_F16 = 1 } hg_dtype;
+
+typedef enum {
+  HG_INTERP_LINEAR = 0,    /* Section 3: weights w and 1-w                                        */
+  HG_INTERP_SMOOTHSTEP = 1 /* Appendix A: weights S(w) = w^2 (3-2w), levels shifted by 1/(2 N_l)  */
+} hg_interp;
+
+typedef struct {
+  uint32_t d;           /* input dimensions: 1, 2 or 3 (Eq. 4 defines three primes)              */
+  uint32_t L;           /* levels, 1..HG_MAX_LEVELS (Table 1: 16)                                */
+  uint32_t F;           /* features per entry: 1, 2, 4 or 8 (Table 1: 2)                         */
+  uint32_t T;           /* maximum entries per level (Table 1: 2^14 .. 2^24); any value >= 1    */
+  uint32_t N_min;       /* coarsest resolution (Table 1: 16)                                    */
+  uint32_t N_max;       /* finest resolution, >= N_min (Table 1: 512 .. 524288)                 */
+  uint32_t param_dtype; /* hg_dtype of the tables                                               */
+  uint32_t io_dtype;    /* hg_dtype of y and dL/dy                                              */
+  uint32_t interp;      /* hg_interp                                                            */
+} hashgrid_config;
+
+/* Builds the level table of Eq. 2-3 on the host: N_l, the 1:1-or-hashed decision
+ * of Section 3 and the entry offsets.  No device work.  *out is set on HG_OK only. */
+hg_status hashgrid_create(const hashgrid_config* cfg, hashgrid_t** out);
+
+/* Frees the handle (NULL is accepted).  The caller must have finished every
+ * stream that still runs work enqueued through it: kernels hold no reference
+ * to the handle, so this is only about the caller's own bookkeeping. */
+void hashgrid_destroy(hashgrid_t* hg);
+
+/* Sum over levels of the entries per level; the tables hold n_entries * F scalars
+ * (Section 3: bounded by T * L * F).  0 for a NULL handle. */
+uint64_t hashgrid_n_entries(const hashgrid_t* hg);
+
+/* Level l of the table of Eq. 2-3: resolution N_l, first entry, entry count
+ * ((N_l+1)^d when 1:1, else T) and whether the level is 1:1 indexed.  Output
+ * pointers may be NULL. */
+hg_status hashgrid_level_info(const hashgrid_t* hg, uint32_t l, uint32_t* N_l, uint64_t* entry_offset,
+                              uint32_t* n_entries, int* is_dense);
+
+/* Forward pass (Section 3; Fig. 3 steps 1-4): y[b, l*F+f] = sum over the 2^d
+ * corners of weight * theta_l[index(corner)][f].
+ *   x      [B, d]          fp32, device, read
+ *   params [n_entries, F]  param_dtype, device, read
+ *   y      [B, L*F]        io_dtype, device, written in full */
+hg_status hashgrid_encode_fwd(const hashgrid_t* hg, uint32_t B, const float* x, const void* params, void* y,
+                              void* stream);
+
+/* Backward pass to the tables (Fig. 3 caption; collisions are summed):
+ * grad_params[offset_l + index(corner), f] += weight * dLdy[b, l*F+f].
+ *   dLdy        [B, L*F]        io_dtype, device, read
+ *   grad_params [n_entries, F]  fp32, device, ACCUMULATED INTO with atomic adds
+ *                               (zeroing it is the caller's job; the summation
+ *                               order, hence the last bits, varies run to run) */
+hg_status hashgrid_encode_bwd(const hashgrid_t* hg, uint32_t B, const float* x, const void* dLdy,
+                              float* grad_params, void* stream);
+
+/* Gradient with respect to the input position (chain rule on the weight
+ * definition of Section 3; S' of Appendix A for the smoothstep variant):
+ * dLdx[b, j] = sum_{l,f} dLdy[b, l*F+f] * d y[b, l*F+f] / d x_j.
+ *   dLdx [B, d] fp32, device, written in full */
+hg_status hashgrid_encode_bwd_input(const hashgrid_t* hg, uint32_t B, const float* x, const void* params,
+                                    const void* dLdy, float* dLdx, void* stream);
+
+/* The integer decisions of one level, for bit-exact checks: level-local entry
+ * indices idx [B, 2^d] uint32 (corner m is the upper corner along dimension i
+ * when bit i of m is set) and fractional positions w [B, d] fp32 (before any
+ * smoothstep).  Either output may be NULL. */
+hg_status hashgrid_debug_indices(const hashgrid_t* hg, uint32_t B, const float* x, uint32_t level, uint32_t* idx,
+                                 float* w, void* stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char* hashgrid_strerror(hg_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HASHGRID_H */

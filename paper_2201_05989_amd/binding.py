@@ -1,0 +1,176 @@
+"""Thin ctypes binding of libhashgrid.so (C ABI in include/hashgrid.h).
+
+Argument marshalling only: every step of the encoding runs in the library's
+HIP kernels.  PyTorch supplies device memory and the stream.  There is no CPU
+fallback: if the shared library has not been built, importing this module's
+entry points raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch  # imported before the library so that both share one HIP runtime
+
+from .build import LIB_PATH
+
+HG_OK = 0
+HG_F32, HG_F16 = 0, 1
+HG_INTERP_LINEAR, HG_INTERP_SMOOTHSTEP = 0, 1
+HG_MAX_LEVELS = 32
+
+_DTYPES = {"f32": HG_F32, "f16": HG_F16, torch.float32: HG_F32, torch.float16: HG_F16}
+_TORCH = {HG_F32: torch.float32, HG_F16: torch.float16}
+
+EXPORTS = ("hashgrid_create", "hashgrid_destroy", "hashgrid_n_entries", "hashgrid_level_info",
+           "hashgrid_encode_fwd", "hashgrid_encode_bwd", "hashgrid_encode_bwd_input",
+           "hashgrid_debug_indices", "hashgrid_strerror")
+
+
+class HashGridError(RuntimeError):
+    pass
+
+
+class hashgrid_config(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_uint32) for n in
+                ("d", "L", "F", "T", "N_min", "N_max", "param_dtype", "io_dtype", "interp")]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads the in-tree shared library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise HashGridError(
+            f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, u32, u64 = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64
+    lib.hashgrid_create.argtypes = [ctypes.POINTER(hashgrid_config), ctypes.POINTER(vp)]
+    lib.hashgrid_create.restype = ctypes.c_int
+    lib.hashgrid_destroy.argtypes = [vp]
+    lib.hashgrid_destroy.restype = None
+    lib.hashgrid_n_entries.argtypes = [vp]
+    lib.hashgrid_n_entries.restype = u64
+    lib.hashgrid_level_info.argtypes = [vp, u32, ctypes.POINTER(u32), ctypes.POINTER(u64), ctypes.POINTER(u32),
+                                        ctypes.POINTER(ctypes.c_int)]
+    lib.hashgrid_level_info.restype = ctypes.c_int
+    lib.hashgrid_encode_fwd.argtypes = [vp, u32, vp, vp, vp, vp]
+    lib.hashgrid_encode_fwd.restype = ctypes.c_int
+    lib.hashgrid_encode_bwd.argtypes = [vp, u32, vp, vp, vp, vp]
+    lib.hashgrid_encode_bwd.restype = ctypes.c_int
+    lib.hashgrid_encode_bwd_input.argtypes = [vp, u32, vp, vp, vp, vp, vp]
+    lib.hashgrid_encode_bwd_input.restype = ctypes.c_int
+    lib.hashgrid_debug_indices.argtypes = [vp, u32, vp, u32, vp, vp, vp]
+    lib.hashgrid_debug_indices.restype = ctypes.c_int
+    lib.hashgrid_strerror.argtypes = [ctypes.c_int]
+    lib.hashgrid_strerror.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def strerror(status: int) -> str:
+    return load_library().hashgrid_strerror(status).decode()
+
+
+def _check(status: int, what: str) -> None:
+    if status != HG_OK:
+        raise HashGridError(f"{what}: {strerror(status)} (status {status})")
+
+
+@dataclass(frozen=True)
+class LevelInfo:
+    N: int
+    entry_offset: int
+    n_entries: int
+    is_dense: bool
+
+
+def _stream_ptr(stream) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+def _dev(t: torch.Tensor, dtype, shape, name: str) -> int:
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous()):
+        raise HashGridError(f"{name} must be a contiguous device tensor")
+    if t.dtype != dtype or tuple(t.shape) != tuple(shape):
+        raise HashGridError(f"{name}: expected {dtype} {tuple(shape)}, got {t.dtype} {tuple(t.shape)}")
+    return t.data_ptr()
+
+
+class HashGrid:
+    """Handle on one encoding configuration (hashgrid_create / hashgrid_destroy)."""
+
+    def __init__(self, d: int, L: int, F: int, T: int, N_min: int, N_max: int, param_dtype="f16",
+                 io_dtype="f16", interp: int = HG_INTERP_LINEAR):
+        self._lib = load_library()
+        self.cfg = hashgrid_config(d, L, F, T, N_min, N_max, _DTYPES[param_dtype], _DTYPES[io_dtype], interp)
+        h = ctypes.c_void_p()
+        _check(self._lib.hashgrid_create(ctypes.byref(self.cfg), ctypes.byref(h)), "hashgrid_create")
+        self._h = h
+        self.d, self.L, self.F, self.T = d, L, F, T
+        self.param_dtype = _TORCH[self.cfg.param_dtype]
+        self.io_dtype = _TORCH[self.cfg.io_dtype]
+        self.n_entries = int(self._lib.hashgrid_n_entries(self._h))
+
+    def __del__(self):
+        h, self._h = getattr(self, "_h", None), None
+        if h:
+            self._lib.hashgrid_destroy(h)
+
+    def level_info(self, l: int) -> LevelInfo:
+        N, off, n, dense = ctypes.c_uint32(), ctypes.c_uint64(), ctypes.c_uint32(), ctypes.c_int()
+        _check(self._lib.hashgrid_level_info(self._h, l, ctypes.byref(N), ctypes.byref(off), ctypes.byref(n),
+                                             ctypes.byref(dense)), "hashgrid_level_info")
+        return LevelInfo(N.value, off.value, n.value, bool(dense.value))
+
+    def levels(self):
+        return [self.level_info(l) for l in range(self.L)]
+
+    def encode_fwd(self, x: torch.Tensor, params: torch.Tensor, y: torch.Tensor | None = None, stream=None):
+        B = x.shape[0]
+        if y is None:
+            y = torch.empty((B, self.L * self.F), dtype=self.io_dtype, device=x.device)
+        _check(self._lib.hashgrid_encode_fwd(
+            self._h, B, _dev(x, torch.float32, (B, self.d), "x"),
+            _dev(params, self.param_dtype, (self.n_entries, self.F), "params"),
+            _dev(y, self.io_dtype, (B, self.L * self.F), "y"), _stream_ptr(stream)), "hashgrid_encode_fwd")
+        return y
+
+    def encode_bwd(self, x: torch.Tensor, dLdy: torch.Tensor, grad_params: torch.Tensor | None = None,
+                   stream=None):
+        B = x.shape[0]
+        if grad_params is None:
+            grad_params = torch.zeros((self.n_entries, self.F), dtype=torch.float32, device=x.device)
+        _check(self._lib.hashgrid_encode_bwd(
+            self._h, B, _dev(x, torch.float32, (B, self.d), "x"),
+            _dev(dLdy, self.io_dtype, (B, self.L * self.F), "dLdy"),
+            _dev(grad_params, torch.float32, (self.n_entries, self.F), "grad_params"), _stream_ptr(stream)),
+            "hashgrid_encode_bwd")
+        return grad_params
+
+    def encode_bwd_input(self, x: torch.Tensor, params: torch.Tensor, dLdy: torch.Tensor,
+                         dLdx: torch.Tensor | None = None, stream=None):
+        B = x.shape[0]
+        if dLdx is None:
+            dLdx = torch.empty((B, self.d), dtype=torch.float32, device=x.device)
+        _check(self._lib.hashgrid_encode_bwd_input(
+            self._h, B, _dev(x, torch.float32, (B, self.d), "x"),
+            _dev(params, self.param_dtype, (self.n_entries, self.F), "params"),
+            _dev(dLdy, self.io_dtype, (B, self.L * self.F), "dLdy"),
+            _dev(dLdx, torch.float32, (B, self.d), "dLdx"), _stream_ptr(stream)), "hashgrid_encode_bwd_input")
+        return dLdx
+
+    def debug_indices(self, x: torch.Tensor, level: int, stream=None):
+        B = x.shape[0]
+        idx = torch.empty((B, 1 << self.d), dtype=torch.int32, device=x.device)
+        w = torch.empty((B, self.d), dtype=torch.float32, device=x.device)
+        _check(self._lib.hashgrid_debug_indices(
+            self._h, B, _dev(x, torch.float32, (B, self.d), "x"), level, idx.data_ptr(), w.data_ptr(),
+            _stream_ptr(stream)), "hashgrid_debug_indices")
+        return idx, w

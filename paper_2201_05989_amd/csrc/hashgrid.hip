@@ -1,0 +1,406 @@
+// C ABI of the multiresolution hash encoding (declared in include/hashgrid.h)
+// and the general gfx950 kernels that serve every supported configuration.
+//
+// Kernel shape: the paper evaluates the tables level by level so that only a few
+// level slices are live in cache at once (Section 4, "Performance
+// considerations"); the general kernels here keep that order: one thread per
+// (point, level), the level being the slow grid dimension.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <new>
+
+#include "hashgrid.h"
+#include "hashgrid_common.hpp"
+
+struct hashgrid {
+  hashgrid_config cfg;
+  hg::LevelTable lv;
+  uint64_t total;
+};
+
+namespace hg {
+
+constexpr int kBlock = 256;
+
+// ------------------------------------------------------------------ kernels
+
+// Per (point, level): the 2^d entry indices and interpolation weights
+// (Section 3), optionally the derivative of each weight along each axis.
+template <int D>
+struct Corners {
+  uint32_t idx[1 << D];
+  float wt[1 << D];
+};
+
+template <int D, bool WITH_DERIV>
+__device__ __forceinline__ void corners_of(const LevelTable& lv, uint32_t l, bool smooth, const float* xp,
+                                           Corners<D>& out, float (*dwt)[1 << D]) {
+  const uint32_t N = lv.N[l];
+  const bool dense = (lv.dense_mask >> l) & 1u;
+  const float Nf = (float)N;
+  const float shift = smooth ? 0.5f : 0.0f;
+  const float cmaxf = smooth ? Nf : Nf - 1.0f;
+  uint32_t c0[D];
+  float w[D], dw[D];
+#pragma unroll
+  for (int i = 0; i < D; ++i) {
+    float wf;
+    split(xp[i], Nf, shift, cmaxf, c0[i], wf);
+    w[i] = smooth ? smoothstep(wf) : wf;
+    if (WITH_DERIV) dw[i] = smooth ? dsmoothstep(wf) * Nf : Nf;
+  }
+  const CornerTerms<D> ct = corner_terms<D>(c0, dense, lv.verts[l]);
+#pragma unroll
+  for (uint32_t m = 0; m < (1u << D); ++m) {
+    out.idx[m] = corner_index<D>(ct, m, dense, lv.T, lv.T_is_pow2 != 0);
+    float wt = 1.0f;
+#pragma unroll
+    for (int i = 0; i < D; ++i) wt *= ((m >> i) & 1u) ? w[i] : 1.0f - w[i];
+    out.wt[m] = wt;
+    if (WITH_DERIV) {
+#pragma unroll
+      for (int j = 0; j < D; ++j) {
+        float g = ((m >> j) & 1u) ? dw[j] : -dw[j];
+#pragma unroll
+        for (int i = 0; i < D; ++i)
+          if (i != j) g *= ((m >> i) & 1u) ? w[i] : 1.0f - w[i];
+        dwt[j][m] = g;
+      }
+    }
+  }
+}
+
+template <int D>
+__device__ __forceinline__ void load_point(const float* __restrict__ x, uint32_t b, float (&xp)[D]) {
+#pragma unroll
+  for (int i = 0; i < D; ++i) xp[i] = x[(uint64_t)b * D + i];
+}
+
+// Forward, Section 3 / Fig. 3 steps 1-4.
+template <int D, int F, typename PT, typename IT>
+__global__ __launch_bounds__(kBlock) void fwd_general(const LevelTable lv, const bool smooth, const uint32_t B,
+                                                      const float* __restrict__ x, const PT* __restrict__ theta,
+                                                      IT* __restrict__ y) {
+  const uint32_t l = blockIdx.y;
+  const uint32_t b = blockIdx.x * kBlock + threadIdx.x;
+  if (b >= B) return;
+  float xp[D];
+  load_point<D>(x, b, xp);
+  Corners<D> cn;
+  corners_of<D, false>(lv, l, smooth, xp, cn, nullptr);
+  const Vec<PT, F>* tab = reinterpret_cast<const Vec<PT, F>*>(theta) + lv.offset[l];
+  float acc[F];
+#pragma unroll
+  for (int f = 0; f < F; ++f) acc[f] = 0.0f;
+#pragma unroll
+  for (uint32_t m = 0; m < (1u << D); ++m) {
+    const Vec<PT, F> e = tab[cn.idx[m]];
+#pragma unroll
+    for (int f = 0; f < F; ++f) acc[f] = fmaf(cn.wt[m], (float)e.v[f], acc[f]);
+  }
+  Vec<IT, F> out;
+#pragma unroll
+  for (int f = 0; f < F; ++f) out.v[f] = (IT)acc[f];
+  reinterpret_cast<Vec<IT, F>*>(y)[(uint64_t)b * lv.L + l] = out;
+}
+
+// Backward to the tables, Fig. 3 caption: scatter-add of weight * dL/dy.
+template <int D, int F, typename IT>
+__global__ __launch_bounds__(kBlock) void bwd_general(const LevelTable lv, const bool smooth, const uint32_t B,
+                                                      const float* __restrict__ x, const IT* __restrict__ dy,
+                                                      float* __restrict__ grad) {
+  const uint32_t l = blockIdx.y;
+  const uint32_t b = blockIdx.x * kBlock + threadIdx.x;
+  if (b >= B) return;
+  float xp[D];
+  load_point<D>(x, b, xp);
+  Corners<D> cn;
+  corners_of<D, false>(lv, l, smooth, xp, cn, nullptr);
+  const Vec<IT, F> g = reinterpret_cast<const Vec<IT, F>*>(dy)[(uint64_t)b * lv.L + l];
+  float* gl = grad + lv.offset[l] * F;
+#pragma unroll
+  for (uint32_t m = 0; m < (1u << D); ++m) {
+#pragma unroll
+    for (int f = 0; f < F; ++f)
+      __hip_atomic_fetch_add(gl + (uint64_t)cn.idx[m] * F + f, cn.wt[m] * (float)g.v[f], __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
+// Gradient with respect to the position: one thread per point, all levels.
+template <int D, int F, typename PT, typename IT>
+__global__ __launch_bounds__(kBlock) void bwd_input_general(const LevelTable lv, const bool smooth, const uint32_t B,
+                                                            const float* __restrict__ x,
+                                                            const PT* __restrict__ theta,
+                                                            const IT* __restrict__ dy, float* __restrict__ dx) {
+  const uint32_t b = blockIdx.x * kBlock + threadIdx.x;
+  if (b >= B) return;
+  float xp[D];
+  load_point<D>(x, b, xp);
+  float gx[D];
+#pragma unroll
+  for (int j = 0; j < D; ++j) gx[j] = 0.0f;
+  for (uint32_t l = 0; l < lv.L; ++l) {
+    Corners<D> cn;
+    float dwt[D][1 << D];
+    corners_of<D, true>(lv, l, smooth, xp, cn, dwt);
+    const Vec<PT, F>* tab = reinterpret_cast<const Vec<PT, F>*>(theta) + lv.offset[l];
+    const Vec<IT, F> g = reinterpret_cast<const Vec<IT, F>*>(dy)[(uint64_t)b * lv.L + l];
+#pragma unroll
+    for (uint32_t m = 0; m < (1u << D); ++m) {
+      const Vec<PT, F> e = tab[cn.idx[m]];
+      float s = 0.0f;
+#pragma unroll
+      for (int f = 0; f < F; ++f) s = fmaf((float)g.v[f], (float)e.v[f], s);
+#pragma unroll
+      for (int j = 0; j < D; ++j) gx[j] = fmaf(dwt[j][m], s, gx[j]);
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < D; ++j) dx[(uint64_t)b * D + j] = gx[j];
+}
+
+// The fp32 decisions of one level, for bit-exact comparison.
+template <int D>
+__global__ __launch_bounds__(kBlock) void indices_general(const LevelTable lv, const bool smooth, const uint32_t B,
+                                                          const float* __restrict__ x, const uint32_t l,
+                                                          uint32_t* __restrict__ idx, float* __restrict__ w) {
+  const uint32_t b = blockIdx.x * kBlock + threadIdx.x;
+  if (b >= B) return;
+  float xp[D];
+  load_point<D>(x, b, xp);
+  Corners<D> cn;
+  corners_of<D, false>(lv, l, smooth, xp, cn, nullptr);
+  if (idx) {
+#pragma unroll
+    for (uint32_t m = 0; m < (1u << D); ++m) idx[(uint64_t)b * (1u << D) + m] = cn.idx[m];
+  }
+  if (w) {
+    const float Nf = (float)lv.N[l];
+#pragma unroll
+    for (int i = 0; i < D; ++i) {
+      uint32_t c0;
+      float wf;
+      split(xp[i], Nf, smooth ? 0.5f : 0.0f, smooth ? Nf : Nf - 1.0f, c0, wf);
+      w[(uint64_t)b * D + i] = wf;
+    }
+  }
+}
+
+// ------------------------------------------------------------------ host side
+
+// Eq. 2-3 in extended precision.  A level whose real-valued resolution is an
+// integer (b^l landing on one, e.g. b = 2, and always level L-1 = N_max) keeps
+// that integer: the progression is defined over [N_min, N_max] (Section 3).
+static hg_status build_levels(const hashgrid_config& c, LevelTable& lv, uint64_t& total) {
+  const long double log2_b =
+      c.L > 1 ? (log2l((long double)c.N_max) - log2l((long double)c.N_min)) / (long double)(c.L - 1) : 0.0L;
+  lv = LevelTable{};
+  lv.L = c.L;
+  lv.T = c.T;
+  lv.T_is_pow2 = (c.T & (c.T - 1u)) == 0u;
+  uint64_t off = 0;
+  for (uint32_t l = 0; l < c.L; ++l) {
+    const long double s = (long double)c.N_min * exp2l((long double)l * log2_b);
+    const uint64_t N = (uint64_t)floorl(s + 1e-6L);
+    if (N + 2u > 0xFFFFFFFFull) return HG_ERR_UNSUPPORTED;
+    const uint64_t per_axis = N + 1u + (c.interp == HG_INTERP_SMOOTHSTEP ? 1u : 0u);
+    uint64_t verts = 1;
+    bool dense = true;
+    for (uint32_t i = 0; i < c.d; ++i) {
+      verts *= per_axis;
+      if (verts > (uint64_t)c.T) { dense = false; break; }
+    }
+    lv.N[l] = (uint32_t)N;
+    lv.verts[l] = (uint32_t)per_axis;
+    lv.size[l] = dense ? (uint32_t)verts : c.T;
+    lv.offset[l] = off;
+    if (dense) lv.dense_mask |= 1u << l;
+    off += lv.size[l];
+  }
+  total = off;
+  return HG_OK;
+}
+
+static inline bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+static inline size_t dtype_size(uint32_t t) { return t == HG_F16 ? 2 : 4; }
+
+static hg_status launched() { return hipGetLastError() == hipSuccess ? HG_OK : HG_ERR_DEVICE; }
+
+template <int D, int F, typename PT, typename IT>
+static hg_status launch_fwd(const hashgrid* h, uint32_t B, const float* x, const void* params, void* y,
+                            hipStream_t s) {
+  dim3 grid((B + kBlock - 1) / kBlock, h->lv.L);
+  hipLaunchKernelGGL((fwd_general<D, F, PT, IT>), grid, dim3(kBlock), 0, s, h->lv,
+                     h->cfg.interp == HG_INTERP_SMOOTHSTEP, B, x, static_cast<const PT*>(params),
+                     static_cast<IT*>(y));
+  return launched();
+}
+
+template <int D, int F, typename PT, typename IT>
+static hg_status launch_bwd_input(const hashgrid* h, uint32_t B, const float* x, const void* params,
+                                  const void* dy, float* dx, hipStream_t s) {
+  dim3 grid((B + kBlock - 1) / kBlock);
+  hipLaunchKernelGGL((bwd_input_general<D, F, PT, IT>), grid, dim3(kBlock), 0, s, h->lv,
+                     h->cfg.interp == HG_INTERP_SMOOTHSTEP, B, x, static_cast<const PT*>(params),
+                     static_cast<const IT*>(dy), dx);
+  return launched();
+}
+
+template <int D, int F, typename IT>
+static hg_status launch_bwd(const hashgrid* h, uint32_t B, const float* x, const void* dy, float* grad,
+                            hipStream_t s) {
+  dim3 grid((B + kBlock - 1) / kBlock, h->lv.L);
+  hipLaunchKernelGGL((bwd_general<D, F, IT>), grid, dim3(kBlock), 0, s, h->lv,
+                     h->cfg.interp == HG_INTERP_SMOOTHSTEP, B, x, static_cast<const IT*>(dy), grad);
+  return launched();
+}
+
+// Expands `CALL(D, F)` for the runtime (d, F) pair.
+#define HG_DISPATCH_DF(d, F, CALL)                       \
+  switch ((d) * 16 + (F)) {                              \
+    case 1 * 16 + 1: return CALL(1, 1);                  \
+    case 1 * 16 + 2: return CALL(1, 2);                  \
+    case 1 * 16 + 4: return CALL(1, 4);                  \
+    case 1 * 16 + 8: return CALL(1, 8);                  \
+    case 2 * 16 + 1: return CALL(2, 1);                  \
+    case 2 * 16 + 2: return CALL(2, 2);                  \
+    case 2 * 16 + 4: return CALL(2, 4);                  \
+    case 2 * 16 + 8: return CALL(2, 8);                  \
+    case 3 * 16 + 1: return CALL(3, 1);                  \
+    case 3 * 16 + 2: return CALL(3, 2);                  \
+    case 3 * 16 + 4: return CALL(3, 4);                  \
+    case 3 * 16 + 8: return CALL(3, 8);                  \
+    default: return HG_ERR_UNSUPPORTED;                  \
+  }
+
+}  // namespace hg
+
+// ------------------------------------------------------------------ C ABI
+
+extern "C" {
+
+hg_status hashgrid_create(const hashgrid_config* cfg, hashgrid_t** out) {
+  if (!cfg || !out) return HG_ERR_INVALID_ARG;
+  const hashgrid_config& c = *cfg;
+  if (c.d == 0 || c.L == 0 || c.F == 0 || c.T == 0 || c.N_min == 0 || c.N_max < c.N_min)
+    return HG_ERR_INVALID_ARG;
+  if (c.param_dtype > HG_F16 || c.io_dtype > HG_F16 || c.interp > HG_INTERP_SMOOTHSTEP) return HG_ERR_INVALID_ARG;
+  if (c.d > 3 || c.L > HG_MAX_LEVELS) return HG_ERR_UNSUPPORTED;
+  if (!(c.F == 1 || c.F == 2 || c.F == 4 || c.F == 8)) return HG_ERR_UNSUPPORTED;
+  hashgrid* h = new (std::nothrow) hashgrid;
+  if (!h) return HG_ERR_ALLOC;
+  h->cfg = c;
+  hg_status st = hg::build_levels(c, h->lv, h->total);
+  if (st != HG_OK) {
+    delete h;
+    return st;
+  }
+  *out = h;
+  return HG_OK;
+}
+
+void hashgrid_destroy(hashgrid_t* hg) { delete hg; }
+
+uint64_t hashgrid_n_entries(const hashgrid_t* hg) { return hg ? hg->total : 0; }
+
+hg_status hashgrid_level_info(const hashgrid_t* hg, uint32_t l, uint32_t* N_l, uint64_t* entry_offset,
+                              uint32_t* n_entries, int* is_dense) {
+  if (!hg || l >= hg->lv.L) return HG_ERR_INVALID_ARG;
+  if (N_l) *N_l = hg->lv.N[l];
+  if (entry_offset) *entry_offset = hg->lv.offset[l];
+  if (n_entries) *n_entries = hg->lv.size[l];
+  if (is_dense) *is_dense = (int)((hg->lv.dense_mask >> l) & 1u);
+  return HG_OK;
+}
+
+hg_status hashgrid_encode_fwd(const hashgrid_t* hg, uint32_t B, const float* x, const void* params, void* y,
+                              void* stream) {
+  if (!hg) return HG_ERR_INVALID_ARG;
+  if (B == 0) return HG_OK;
+  if (!x || !params || !y) return HG_ERR_INVALID_ARG;
+  const hashgrid_config& c = hg->cfg;
+  if (hg::misaligned(x, 4) || hg::misaligned(params, c.F * hg::dtype_size(c.param_dtype)) ||
+      hg::misaligned(y, c.F * hg::dtype_size(c.io_dtype)))
+    return HG_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const bool p16 = c.param_dtype == HG_F16, i16 = c.io_dtype == HG_F16;
+#define HG_FWD(D, F)                                                                            \
+  (p16 ? (i16 ? hg::launch_fwd<D, F, _Float16, _Float16>(hg, B, x, params, y, s)                \
+              : hg::launch_fwd<D, F, _Float16, float>(hg, B, x, params, y, s))                  \
+       : (i16 ? hg::launch_fwd<D, F, float, _Float16>(hg, B, x, params, y, s)                   \
+              : hg::launch_fwd<D, F, float, float>(hg, B, x, params, y, s)))
+  HG_DISPATCH_DF(c.d, c.F, HG_FWD)
+#undef HG_FWD
+}
+
+hg_status hashgrid_encode_bwd(const hashgrid_t* hg, uint32_t B, const float* x, const void* dLdy,
+                              float* grad_params, void* stream) {
+  if (!hg) return HG_ERR_INVALID_ARG;
+  if (B == 0) return HG_OK;
+  if (!x || !dLdy || !grad_params) return HG_ERR_INVALID_ARG;
+  const hashgrid_config& c = hg->cfg;
+  if (hg::misaligned(x, 4) || hg::misaligned(dLdy, c.F * hg::dtype_size(c.io_dtype)) ||
+      hg::misaligned(grad_params, 4))
+    return HG_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const bool i16 = c.io_dtype == HG_F16;
+#define HG_BWD(D, F)                                                    \
+  (i16 ? hg::launch_bwd<D, F, _Float16>(hg, B, x, dLdy, grad_params, s) \
+       : hg::launch_bwd<D, F, float>(hg, B, x, dLdy, grad_params, s))
+  HG_DISPATCH_DF(c.d, c.F, HG_BWD)
+#undef HG_BWD
+}
+
+hg_status hashgrid_encode_bwd_input(const hashgrid_t* hg, uint32_t B, const float* x, const void* params,
+                                    const void* dLdy, float* dLdx, void* stream) {
+  if (!hg) return HG_ERR_INVALID_ARG;
+  if (B == 0) return HG_OK;
+  if (!x || !params || !dLdy || !dLdx) return HG_ERR_INVALID_ARG;
+  const hashgrid_config& c = hg->cfg;
+  if (hg::misaligned(x, 4) || hg::misaligned(dLdx, 4) ||
+      hg::misaligned(params, c.F * hg::dtype_size(c.param_dtype)) ||
+      hg::misaligned(dLdy, c.F * hg::dtype_size(c.io_dtype)))
+    return HG_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const bool p16 = c.param_dtype == HG_F16, i16 = c.io_dtype == HG_F16;
+#define HG_BWI(D, F)                                                                                    \
+  (p16 ? (i16 ? hg::launch_bwd_input<D, F, _Float16, _Float16>(hg, B, x, params, dLdy, dLdx, s)         \
+              : hg::launch_bwd_input<D, F, _Float16, float>(hg, B, x, params, dLdy, dLdx, s))           \
+       : (i16 ? hg::launch_bwd_input<D, F, float, _Float16>(hg, B, x, params, dLdy, dLdx, s)            \
+              : hg::launch_bwd_input<D, F, float, float>(hg, B, x, params, dLdy, dLdx, s)))
+  HG_DISPATCH_DF(c.d, c.F, HG_BWI)
+#undef HG_BWI
+}
+
+hg_status hashgrid_debug_indices(const hashgrid_t* hg, uint32_t B, const float* x, uint32_t level, uint32_t* idx,
+                                 float* w, void* stream) {
+  if (!hg || level >= hg->lv.L) return HG_ERR_INVALID_ARG;
+  if (B == 0) return HG_OK;
+  if (!x || hg::misaligned(x, 4) || hg::misaligned(idx, 4) || hg::misaligned(w, 4)) return HG_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const bool smooth = hg->cfg.interp == HG_INTERP_SMOOTHSTEP;
+  dim3 grid((B + hg::kBlock - 1) / hg::kBlock);
+  switch (hg->cfg.d) {
+    case 1: hipLaunchKernelGGL((hg::indices_general<1>), grid, dim3(hg::kBlock), 0, s, hg->lv, smooth, B, x, level, idx, w); break;
+    case 2: hipLaunchKernelGGL((hg::indices_general<2>), grid, dim3(hg::kBlock), 0, s, hg->lv, smooth, B, x, level, idx, w); break;
+    case 3: hipLaunchKernelGGL((hg::indices_general<3>), grid, dim3(hg::kBlock), 0, s, hg->lv, smooth, B, x, level, idx, w); break;
+    default: return HG_ERR_UNSUPPORTED;
+  }
+  return hg::launched();
+}
+
+const char* hashgrid_strerror(hg_status s) {
+  switch (s) {
+    case HG_OK: return "ok";
+    case HG_ERR_INVALID_ARG: return "invalid argument";
+    case HG_ERR_UNSUPPORTED: return "unsupported configuration";
+    case HG_ERR_ALLOC: return "host allocation failed";
+    case HG_ERR_DEVICE: return "HIP launch failed";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

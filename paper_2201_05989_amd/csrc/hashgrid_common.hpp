@@ -1,0 +1,92 @@
+// Shared device-side pieces of the gfx950 hash-encoding kernels: the level table
+// passed by value to every kernel, the fp32 scale/floor step and the corner
+// index maps (paper Section 3, Eq. 2-4).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "hashgrid.h"
+
+namespace hg {
+
+// Level table of Eq. 2-3, built once on the host and handed to kernels as a
+// by-value argument (it lives in the kernarg segment, read through the scalar
+// cache; the library owns no device memory).
+struct LevelTable {
+  uint64_t offset[HG_MAX_LEVELS];  // first entry of the level in the flat table
+  uint32_t N[HG_MAX_LEVELS];       // resolution N_l
+  uint32_t verts[HG_MAX_LEVELS];   // grid vertices per axis on a 1:1 level (N_l+1; N_l+2 when shifted)
+  uint32_t size[HG_MAX_LEVELS];    // entries of the level
+  uint32_t dense_mask;             // bit l set: level l is 1:1 indexed
+  uint32_t L;
+  uint32_t T;
+  uint32_t T_is_pow2;
+};
+
+// Eq. 4: pi_1 = 1, pi_2 = 2654435761, pi_3 = 805459861.
+__device__ __forceinline__ constexpr uint32_t prime(int i) {
+  return i == 0 ? 1u : (i == 1 ? 2654435761u : 805459861u);
+}
+
+// Section 3: scale one coordinate by N_l (one rounded fp32 multiply), take the
+// lower voxel corner and the fractional position.  `shift` is the half-voxel
+// offset of Appendix A (0 or 0.5).  The corner is clamped to [0, cmax] so that a
+// coordinate outside [0,1) (a violated precondition) can never index outside a
+// 1:1 level; for valid input the clamp is the identity.
+__device__ __forceinline__ void split(float x, float Nf, float shift, float cmaxf, uint32_t& c0, float& w) {
+  float p = x * Nf;
+  p = p + shift;  // the file is compiled with fp contraction off: two roundings
+  float fl = floorf(p);
+  w = p - fl;     // exact
+  c0 = (uint32_t)fminf(fmaxf(fl, 0.0f), cmaxf);
+}
+
+// Per-dimension contribution of a corner coordinate to the entry index: on a 1:1
+// level v_i * verts^i (summed), on a hashed level v_i * pi_i (XORed).
+template <int D>
+struct CornerTerms {
+  uint32_t t[D][2];
+};
+
+template <int D>
+__device__ __forceinline__ CornerTerms<D> corner_terms(const uint32_t (&c0)[D], bool dense, uint32_t verts) {
+  CornerTerms<D> r;
+  uint32_t stride = 1;
+#pragma unroll
+  for (int i = 0; i < D; ++i) {
+    uint32_t mul = dense ? stride : prime(i);
+    r.t[i][0] = c0[i] * mul;
+    r.t[i][1] = r.t[i][0] + mul;  // (c0+1)*mul in wrap-around arithmetic
+    stride *= verts;
+  }
+  return r;
+}
+
+template <int D>
+__device__ __forceinline__ uint32_t corner_index(const CornerTerms<D>& ct, uint32_t m, bool dense, uint32_t T,
+                                                 bool pow2) {
+  if (dense) {
+    uint32_t idx = 0;
+#pragma unroll
+    for (int i = 0; i < D; ++i) idx += ct.t[i][(m >> i) & 1u];
+    return idx;
+  }
+  uint32_t h = 0;
+#pragma unroll
+  for (int i = 0; i < D; ++i) h ^= ct.t[i][(m >> i) & 1u];
+  return pow2 ? (h & (T - 1u)) : (h % T);
+}
+
+// Appendix A: S(w) = w^2 (3 - 2w), S'(w) = 6 w (1 - w).
+__device__ __forceinline__ float smoothstep(float w) { return w * w * (3.0f - 2.0f * w); }
+__device__ __forceinline__ float dsmoothstep(float w) { return 6.0f * w * (1.0f - w); }
+
+// F scalars of one table entry / one output fragment, loaded and stored as one
+// vector access.
+template <typename T, int F>
+struct alignas(sizeof(T) * F) Vec {
+  T v[F];
+};
+
+}  // namespace hg

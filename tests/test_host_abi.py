@@ -1,0 +1,98 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the
+header declares, builds the level table of Eq. 2-3 exactly as the oracle does
+(the two are written independently) and reports errors as status codes."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from oracle import hashgrid_oracle as orc
+from paper_2201_05989_amd import binding
+from paper_2201_05989_amd.build import LIB_PATH
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "hashgrid.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hashgrid_[a-z_]+)\s*\(", text)))
+
+
+def test_library_is_built_and_exports_every_declared_symbol():
+    assert os.path.exists(LIB_PATH), "build the library first: __graft_entry__.build()"
+    lib = ctypes.CDLL(LIB_PATH)
+    names = _declared_symbols()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+CFGS = [(2, 4, 2, 1 << 10, 4, 32), (2, 16, 2, 1 << 22, 16, 32768), (3, 16, 2, 1 << 19, 16, 2048),
+        (3, 16, 2, 1 << 24, 16, 524288), (3, 16, 2, 1 << 19, 16, 512), (3, 16, 2, 1 << 14, 16, 4096),
+        (2, 16, 2, 1 << 22, 16, 11733), (3, 8, 4, 1 << 19, 16, 1000), (3, 32, 1, 1 << 19, 16, 2048),
+        (1, 7, 8, 100, 3, 999), (3, 1, 2, 1 << 12, 16, 16), (3, 16, 2, 1000003, 16, 2048),
+        (2, 16, 2, 1 << 17, 16, 11733), (3, 16, 2, 1 << 21, 16, 8192), (3, 12, 2, 1 << 15, 5, 77)]
+
+
+@pytest.mark.parametrize("interp", [0, 1])
+@pytest.mark.parametrize("d,L,F,T,N_min,N_max", CFGS)
+def test_level_table_matches_oracle(d, L, F, T, N_min, N_max, interp):
+    g = binding.HashGrid(d, L, F, T, N_min, N_max, "f16", "f16", interp)
+    lv = orc.levels(orc.OracleConfig(d, L, F, T, N_min, N_max, interp))
+    assert g.n_entries == lv.total
+    for l, info in enumerate(g.levels()):
+        assert (info.N, info.entry_offset, info.n_entries, info.is_dense) == \
+            (int(lv.N[l]), int(lv.offset[l]), int(lv.size[l]), bool(lv.dense[l]))
+
+
+def test_level_table_sweep_of_resolutions_matches_oracle():
+    # every N_max in a range, three level counts: the two floor() evaluations must never disagree
+    for L in (2, 9, 16):
+        for N_max in list(range(16, 700)) + [2 ** k for k in range(10, 20)]:
+            g = binding.HashGrid(3, L, 2, 1 << 16, 16, N_max)
+            lv = orc.levels(orc.OracleConfig(3, L, 2, 1 << 16, 16, N_max))
+            assert [i.N for i in g.levels()] == list(map(int, lv.N)), (L, N_max)
+
+
+def _create(**kw):
+    base = dict(d=3, L=16, F=2, T=1 << 19, N_min=16, N_max=2048, param_dtype=1, io_dtype=1, interp=0)
+    base.update(kw)
+    lib = binding.load_library()
+    cfg = binding.hashgrid_config(*[base[k] for k, _ in binding.hashgrid_config._fields_])
+    h = ctypes.c_void_p()
+    st = lib.hashgrid_create(ctypes.byref(cfg), ctypes.byref(h))
+    if st == 0:
+        lib.hashgrid_destroy(h)
+    return st
+
+
+def test_create_status_codes():
+    assert _create() == 0
+    for bad in (dict(d=0), dict(L=0), dict(F=0), dict(T=0), dict(N_min=0), dict(N_max=8), dict(param_dtype=2),
+                dict(io_dtype=7), dict(interp=2)):
+        assert _create(**bad) == 1, bad  # HG_ERR_INVALID_ARG
+    for unsup in (dict(d=4), dict(L=33), dict(F=3), dict(F=16)):
+        assert _create(**unsup) == 2, unsup  # HG_ERR_UNSUPPORTED
+    lib = binding.load_library()
+    assert lib.hashgrid_create(None, None) == 1
+    assert lib.hashgrid_n_entries(None) == 0
+    lib.hashgrid_destroy(None)
+    assert binding.strerror(0) == "ok" and "unsupported" in binding.strerror(2)
+
+
+def test_null_and_empty_batches_need_no_device():
+    lib = binding.load_library()
+    g = binding.HashGrid(2, 4, 2, 1 << 10, 4, 32, "f32", "f32")
+    assert lib.hashgrid_encode_fwd(g._h, 0, None, None, None, None) == 0   # B = 0: nothing to do
+    assert lib.hashgrid_encode_bwd(g._h, 0, None, None, None, None) == 0
+    assert lib.hashgrid_encode_fwd(g._h, 8, None, None, None, None) == 1   # NULL data pointers
+    assert lib.hashgrid_encode_bwd(g._h, 8, None, None, None, None) == 1
+    assert lib.hashgrid_encode_bwd_input(g._h, 8, None, None, None, None, None) == 1
+    assert lib.hashgrid_encode_fwd(None, 8, None, None, None, None) == 1
+    assert lib.hashgrid_level_info(g._h, 4, None, None, None, None) == 1   # level out of range
+    assert lib.hashgrid_level_info(g._h, 3, None, None, None, None) == 0
+    assert lib.hashgrid_debug_indices(g._h, 8, None, 9, None, None, None) == 1
+    # misaligned pointers are rejected before any launch (F*sizeof = 8-byte vectors here)
+    assert lib.hashgrid_encode_fwd(g._h, 8, 4096, 4100, 4096, None) == 1
