@@ -43,12 +43,15 @@ __device__ __forceinline__ void corners_of(const LevelTable& lv, uint32_t l, boo
   const float shift = smooth ? 0.5f : 0.0f;
   const float cmaxf = smooth ? Nf : Nf - 1.0f;
   uint32_t c0[D];
-  float w[D], dw[D];
+  float w[D], u[D], dw[D];  // weight of the upper corner, of the lower corner, d(upper)/dx
 #pragma unroll
   for (int i = 0; i < D; ++i) {
     float wf;
     split(xp[i], Nf, shift, cmaxf, c0[i], wf);
+    // 1 - S(w) = S(1 - w): evaluating the lower weight this way keeps its relative
+    // accuracy when S(w) is close to 1
     w[i] = smooth ? smoothstep(wf) : wf;
+    u[i] = smooth ? smoothstep(1.0f - wf) : 1.0f - wf;
     if (WITH_DERIV) dw[i] = smooth ? dsmoothstep(wf) * Nf : Nf;
   }
   const CornerTerms<D> ct = corner_terms<D>(c0, dense, lv.verts[l]);
@@ -57,7 +60,7 @@ __device__ __forceinline__ void corners_of(const LevelTable& lv, uint32_t l, boo
     out.idx[m] = corner_index<D>(ct, m, dense, lv.T, lv.T_is_pow2 != 0);
     float wt = 1.0f;
 #pragma unroll
-    for (int i = 0; i < D; ++i) wt *= ((m >> i) & 1u) ? w[i] : 1.0f - w[i];
+    for (int i = 0; i < D; ++i) wt *= ((m >> i) & 1u) ? w[i] : u[i];
     out.wt[m] = wt;
     if (WITH_DERIV) {
 #pragma unroll
@@ -65,7 +68,7 @@ __device__ __forceinline__ void corners_of(const LevelTable& lv, uint32_t l, boo
         float g = ((m >> j) & 1u) ? dw[j] : -dw[j];
 #pragma unroll
         for (int i = 0; i < D; ++i)
-          if (i != j) g *= ((m >> i) & 1u) ? w[i] : 1.0f - w[i];
+          if (i != j) g *= ((m >> i) & 1u) ? w[i] : u[i];
         dwt[j][m] = g;
       }
     }
