@@ -39,6 +39,7 @@ extern "C" {
 #endif
 
 #define HG_MAX_LEVELS 32u
+#define HG_MAX_BATCH (1u << 28) /* points per call; larger B returns HG_ERR_UNSUPPORTED */
 
 typedef struct hashgrid hashgrid_t; /* opaque, host memory, owned by the library */
 

@@ -110,25 +110,39 @@ __global__ __launch_bounds__(kBlock) void fwd_general(const LevelTable lv, const
 }
 
 // Backward to the tables, Fig. 3 caption: scatter-add of weight * dL/dy.
+//
+// The L2 atomic units of this chip retire about one atomic *request* per clock
+// per XCD, where a request is whatever part of one wave instruction falls into
+// one aligned 64-byte block; how many lanes it carries does not matter.  So the
+// lanes are arranged to make requests fat: 2F consecutive lanes share one
+// (point, level); lane (xbit, f) owns feature f of the lower or upper corner
+// along dimension 0.  Those two corners are neighbours in memory (1:1 levels:
+// index + 1; hashed levels: pi_1 = 1 keeps them in one small aligned block), so
+// the 2F lanes of a group address 2F adjacent floats and mostly travel as one
+// request instead of 2F.
 template <int D, int F, typename IT>
 __global__ __launch_bounds__(kBlock) void bwd_general(const LevelTable lv, const bool smooth, const uint32_t B,
                                                       const float* __restrict__ x, const IT* __restrict__ dy,
                                                       float* __restrict__ grad) {
+  constexpr uint32_t G = 2 * F;  // lanes per (point, level)
   const uint32_t l = blockIdx.y;
-  const uint32_t b = blockIdx.x * kBlock + threadIdx.x;
-  if (b >= B) return;
+  const uint32_t sub = threadIdx.x % G;
+  const uint32_t xbit = sub / F, f = sub % F;
+  const uint64_t b64 = (uint64_t)blockIdx.x * (kBlock / G) + threadIdx.x / G;
+  if (b64 >= B) return;
+  const uint32_t b = (uint32_t)b64;
   float xp[D];
   load_point<D>(x, b, xp);
   Corners<D> cn;
   corners_of<D, false>(lv, l, smooth, xp, cn, nullptr);
-  const Vec<IT, F> g = reinterpret_cast<const Vec<IT, F>*>(dy)[(uint64_t)b * lv.L + l];
-  float* gl = grad + lv.offset[l] * F;
+  const float g = (float)dy[((uint64_t)b * lv.L + l) * F + f];
+  float* gl = grad + lv.offset[l] * F + f;
 #pragma unroll
-  for (uint32_t m = 0; m < (1u << D); ++m) {
-#pragma unroll
-    for (int f = 0; f < F; ++f)
-      __hip_atomic_fetch_add(gl + (uint64_t)cn.idx[m] * F + f, cn.wt[m] * (float)g.v[f], __ATOMIC_RELAXED,
-                             __HIP_MEMORY_SCOPE_AGENT);
+  for (uint32_t r = 0; r < (1u << (D - 1)); ++r) {  // corners along the other dimensions
+    const uint32_t m0 = r << 1;
+    const uint32_t idx = xbit ? cn.idx[m0 | 1u] : cn.idx[m0];
+    const float wt = xbit ? cn.wt[m0 | 1u] : cn.wt[m0];
+    __hip_atomic_fetch_add(gl + (uint64_t)idx * F, wt * g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 }
 
@@ -255,7 +269,8 @@ static hg_status launch_bwd_input(const hashgrid* h, uint32_t B, const float* x,
 template <int D, int F, typename IT>
 static hg_status launch_bwd(const hashgrid* h, uint32_t B, const float* x, const void* dy, float* grad,
                             hipStream_t s) {
-  dim3 grid((B + kBlock - 1) / kBlock, h->lv.L);
+  constexpr uint32_t per_block = kBlock / (2 * F);
+  dim3 grid((uint32_t)(((uint64_t)B + per_block - 1) / per_block), h->lv.L);
   hipLaunchKernelGGL((bwd_general<D, F, IT>), grid, dim3(kBlock), 0, s, h->lv,
                      h->cfg.interp == HG_INTERP_SMOOTHSTEP, B, x, static_cast<const IT*>(dy), grad);
   return launched();
@@ -323,6 +338,7 @@ hg_status hashgrid_encode_fwd(const hashgrid_t* hg, uint32_t B, const float* x, 
                               void* stream) {
   if (!hg) return HG_ERR_INVALID_ARG;
   if (B == 0) return HG_OK;
+  if (B > HG_MAX_BATCH) return HG_ERR_UNSUPPORTED;
   if (!x || !params || !y) return HG_ERR_INVALID_ARG;
   const hashgrid_config& c = hg->cfg;
   if (hg::misaligned(x, 4) || hg::misaligned(params, c.F * hg::dtype_size(c.param_dtype)) ||
@@ -343,6 +359,7 @@ hg_status hashgrid_encode_bwd(const hashgrid_t* hg, uint32_t B, const float* x, 
                               float* grad_params, void* stream) {
   if (!hg) return HG_ERR_INVALID_ARG;
   if (B == 0) return HG_OK;
+  if (B > HG_MAX_BATCH) return HG_ERR_UNSUPPORTED;
   if (!x || !dLdy || !grad_params) return HG_ERR_INVALID_ARG;
   const hashgrid_config& c = hg->cfg;
   if (hg::misaligned(x, 4) || hg::misaligned(dLdy, c.F * hg::dtype_size(c.io_dtype)) ||
@@ -361,6 +378,7 @@ hg_status hashgrid_encode_bwd_input(const hashgrid_t* hg, uint32_t B, const floa
                                     const void* dLdy, float* dLdx, void* stream) {
   if (!hg) return HG_ERR_INVALID_ARG;
   if (B == 0) return HG_OK;
+  if (B > HG_MAX_BATCH) return HG_ERR_UNSUPPORTED;
   if (!x || !params || !dLdy || !dLdx) return HG_ERR_INVALID_ARG;
   const hashgrid_config& c = hg->cfg;
   if (hg::misaligned(x, 4) || hg::misaligned(dLdx, 4) ||
@@ -382,6 +400,7 @@ hg_status hashgrid_debug_indices(const hashgrid_t* hg, uint32_t B, const float* 
                                  float* w, void* stream) {
   if (!hg || level >= hg->lv.L) return HG_ERR_INVALID_ARG;
   if (B == 0) return HG_OK;
+  if (B > HG_MAX_BATCH) return HG_ERR_UNSUPPORTED;
   if (!x || hg::misaligned(x, 4) || hg::misaligned(idx, 4) || hg::misaligned(w, 4)) return HG_ERR_INVALID_ARG;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool smooth = hg->cfg.interp == HG_INTERP_SMOOTHSTEP;
