@@ -106,6 +106,30 @@ hg_status hashgrid_encode_fwd(const hashgrid_t* hg, uint32_t B, const float* x, 
 hg_status hashgrid_encode_bwd(const hashgrid_t* hg, uint32_t B, const float* x, const void* dLdy,
                               float* grad_params, void* stream);
 
+/* Size in bytes of the scratch buffer hashgrid_encode_bwd_ws needs for a batch of
+ * B points, or 0 when that variant does not serve this configuration or batch
+ * (it needs F = 2, d = 2 or 3, a power-of-two T, resolutions below 4096 on hashed
+ * levels, at most 1024 chunks of 4096 entries per level and B*L*2^(d-1) < 2^32). */
+uint64_t hashgrid_bwd_workspace_bytes(const hashgrid_t* hg, uint32_t B);
+
+/* Backward pass to the tables, same result as hashgrid_encode_bwd (Fig. 3
+ * caption), computed without device-wide atomics on the hot path: the
+ * weight * dLdy contributions are bucket-sorted by destination chunk into
+ * `workspace` and each chunk is summed on-chip by one owner.  Sums are exact
+ * 64-bit fixed point scaled to the largest |dLdy| of the call (each summand is
+ * rounded to about 2^-38 of that value or finer), so the result does not depend
+ * on the order of execution, except on coarse 1:1 levels whose few chunks are
+ * shared by several workgroups and combined with fp32 atomic adds.
+ *   workspace  device, 256-byte aligned, at least hashgrid_bwd_workspace_bytes(hg, B)
+ *              bytes, owned by the caller; contents are scratch: undefined on
+ *              entry and on exit.  Calls that overlap in time need separate
+ *              workspaces.
+ * Returns HG_ERR_UNSUPPORTED when hashgrid_bwd_workspace_bytes is 0 and
+ * HG_ERR_INVALID_ARG when the buffer is missing, misaligned or too small.  x and
+ * dLdy must not be written while the call is in flight. */
+hg_status hashgrid_encode_bwd_ws(const hashgrid_t* hg, uint32_t B, const float* x, const void* dLdy,
+                                 float* grad_params, void* workspace, uint64_t workspace_bytes, void* stream);
+
 /* Gradient with respect to the input position (chain rule on the weight
  * definition of Section 3; S' of Appendix A for the smoothstep variant):
  * dLdx[b, j] = sum_{l,f} dLdy[b, l*F+f] * d y[b, l*F+f] / d x_j.

@@ -25,7 +25,8 @@ _TORCH = {HG_F32: torch.float32, HG_F16: torch.float16}
 
 EXPORTS = ("hashgrid_create", "hashgrid_destroy", "hashgrid_n_entries", "hashgrid_level_info",
            "hashgrid_encode_fwd", "hashgrid_encode_bwd", "hashgrid_encode_bwd_input",
-           "hashgrid_debug_indices", "hashgrid_strerror")
+           "hashgrid_debug_indices", "hashgrid_strerror", "hashgrid_bwd_workspace_bytes",
+           "hashgrid_encode_bwd_ws")
 
 
 class HashGridError(RuntimeError):
@@ -67,6 +68,10 @@ def load_library() -> ctypes.CDLL:
     lib.hashgrid_encode_bwd_input.restype = ctypes.c_int
     lib.hashgrid_debug_indices.argtypes = [vp, u32, vp, u32, vp, vp, vp]
     lib.hashgrid_debug_indices.restype = ctypes.c_int
+    lib.hashgrid_bwd_workspace_bytes.argtypes = [vp, u32]
+    lib.hashgrid_bwd_workspace_bytes.restype = u64
+    lib.hashgrid_encode_bwd_ws.argtypes = [vp, u32, vp, vp, vp, vp, u64, vp]
+    lib.hashgrid_encode_bwd_ws.restype = ctypes.c_int
     lib.hashgrid_strerror.argtypes = [ctypes.c_int]
     lib.hashgrid_strerror.restype = ctypes.c_char_p
     _lib = lib
@@ -117,6 +122,7 @@ class HashGrid:
         self.param_dtype = _TORCH[self.cfg.param_dtype]
         self.io_dtype = _TORCH[self.cfg.io_dtype]
         self.n_entries = int(self._lib.hashgrid_n_entries(self._h))
+        self._ws = None
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None
@@ -142,11 +148,29 @@ class HashGrid:
             _dev(y, self.io_dtype, (B, self.L * self.F), "y"), _stream_ptr(stream)), "hashgrid_encode_fwd")
         return y
 
+    def bwd_workspace_bytes(self, B: int) -> int:
+        return int(self._lib.hashgrid_bwd_workspace_bytes(self._h, B))
+
     def encode_bwd(self, x: torch.Tensor, dLdy: torch.Tensor, grad_params: torch.Tensor | None = None,
-                   stream=None):
+                   stream=None, workspace: torch.Tensor | None = None, use_workspace: bool = True):
+        """hashgrid_encode_bwd_ws when the configuration is served by it (the scratch
+        buffer is `workspace` or one kept on this object), else hashgrid_encode_bwd."""
         B = x.shape[0]
         if grad_params is None:
             grad_params = torch.zeros((self.n_entries, self.F), dtype=torch.float32, device=x.device)
+        need = self.bwd_workspace_bytes(B) if use_workspace else 0
+        if need:
+            if workspace is None:
+                if self._ws is None or self._ws.numel() < need or self._ws.device != x.device:
+                    self._ws = torch.empty(need, dtype=torch.uint8, device=x.device)
+                workspace = self._ws
+            _check(self._lib.hashgrid_encode_bwd_ws(
+                self._h, B, _dev(x, torch.float32, (B, self.d), "x"),
+                _dev(dLdy, self.io_dtype, (B, self.L * self.F), "dLdy"),
+                _dev(grad_params, torch.float32, (self.n_entries, self.F), "grad_params"),
+                workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr(stream)),
+                "hashgrid_encode_bwd_ws")
+            return grad_params
         _check(self._lib.hashgrid_encode_bwd(
             self._h, B, _dev(x, torch.float32, (B, self.d), "x"),
             _dev(dLdy, self.io_dtype, (B, self.L * self.F), "dLdy"),

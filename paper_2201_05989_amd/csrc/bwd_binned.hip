@@ -1,0 +1,529 @@
+// Binned backward pass of the hash encoding (Fig. 3 caption of the paper: the
+// gradient of the loss is accumulated in the looked-up feature vectors).
+//
+// Why not atomics: on this chip a device-scope fp32 atomic add costs one L2
+// request per 64-byte block per wave instruction and all XCDs together retire
+// about 21 G requests/s, whatever the table size; a fine hashed level needs at
+// least 2^(d-1) requests per point, which bounds an atomic backward pass far
+// below what the memory system can stream.  LDS fp32 atomics are slow as well
+// (about 0.3 lane-ops per clock per CU) while LDS *integer* atomics run at about
+// 3.6 64-bit adds per clock per CU.  So the scatter-add is done as a bucket
+// sort followed by an owner-computes accumulation:
+//
+//   count      every (point, level) emits 2^(d-1) records, one per pair of
+//              corners that differ only along dimension 0 (they are neighbours
+//              in memory: index+1 on 1:1 levels, same small aligned block on
+//              hashed levels because pi_1 = 1 in Eq. 4).  A record belongs to
+//              the bin (chunk of the level's gradient slice, at most 2^chunk_log2
+//              entries) that holds both corners.  This kernel only counts.
+//   scan       per-bin totals and per-(workgroup, bin) write offsets.
+//   scatter    recomputes the records and writes each to its slot: 16 bytes =
+//              two chunk-local indices, the fractional position along
+//              dimension 0 and dL/dy times the weight of the other dimensions.
+//   accumulate one workgroup per bin (several for the few bins of coarse 1:1
+//              levels, which receive very many records): sums its records into
+//              LDS in 64-bit fixed point with integer atomics, then adds the
+//              chunk to the fp32 gradient (plain read-modify-write when the bin
+//              has a single owner).  The fixed-point scale comes from the
+//              largest |dL/dy| of the call, with headroom for 8*B summands, so
+//              the sum is exact and independent of the order of the records;
+//              each summand is rounded to 2^-(62-H) of that largest value
+//              (H = ceil(log2(8B))).
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "hashgrid.h"
+#include "hashgrid_common.hpp"
+#include "hashgrid_internal.hpp"
+
+namespace hg {
+
+constexpr int kBinThreads = 512;       // threads of a count / scatter workgroup
+constexpr uint32_t kMaxBinTiles = 512; // count / scatter workgroups per launch
+constexpr int kScanThreads = 1024;     // = maximum bins per level
+constexpr int kAccThreads = 512;
+constexpr uint32_t kChunkLog2 = 12;
+constexpr uint32_t kTargetRecordsPerAccWg = 16384;
+constexpr uint64_t kMaxBinLds = 48 * 1024;
+
+struct Workspace {
+  uint32_t* counts;     // [n_tiles][n_bins] counts, then exclusive prefix over tiles
+  uint32_t* bin_start;  // [n_bins] first record of the bin
+  uint32_t* bin_total;  // [n_bins] records in the bin
+  float* tile_max;      // [n_tiles] largest |dL/dy| seen by the workgroup
+  uint4* records;       // [B * L * rec_per_point]
+  uint32_t n_tiles;
+  uint32_t n_bins;
+};
+
+static inline uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+
+static uint32_t tiles_for(uint32_t B) {
+  uint32_t t = (B + kBinThreads - 1) / kBinThreads;
+  return t < kMaxBinTiles ? t : kMaxBinTiles;
+}
+
+static uint64_t carve(const hashgrid* h, uint32_t B, uint8_t* base, Workspace* ws) {
+  const uint32_t nt = tiles_for(B), nb = h->bp.bin_base[h->lv.L];
+  uint64_t off = 0;
+  auto take = [&](uint64_t bytes) {
+    uint64_t o = off;
+    off = align_up(off + bytes, 256);
+    return o;
+  };
+  const uint64_t o_counts = take((uint64_t)nt * nb * 4), o_start = take((uint64_t)nb * 4),
+                 o_total = take((uint64_t)nb * 4), o_max = take((uint64_t)nt * 4),
+                 o_rec = take((uint64_t)B * h->lv.L * h->bp.rec_per_point * 16);
+  if (ws) {
+    ws->counts = reinterpret_cast<uint32_t*>(base + o_counts);
+    ws->bin_start = reinterpret_cast<uint32_t*>(base + o_start);
+    ws->bin_total = reinterpret_cast<uint32_t*>(base + o_total);
+    ws->tile_max = reinterpret_cast<float*>(base + o_max);
+    ws->records = reinterpret_cast<uint4*>(base + o_rec);
+    ws->n_tiles = nt;
+    ws->n_bins = nb;
+  }
+  return off;
+}
+
+// Chunking of every level's gradient slice.  1:1 levels are cut at grid-row
+// boundaries (a row = all vertices that share the coordinates of dimensions
+// 1..d-1, contiguous in memory), a power-of-two number of rows per chunk; hashed
+// levels are cut into aligned blocks of 2^chunk_log2 entries, which the XOR with
+// v_0 < 2^chunk_log2 cannot leave.
+void build_bin_plan(hashgrid* h) {
+  BinPlan& bp = h->bp;
+  bp = BinPlan{};
+  const hashgrid_config& c = h->cfg;
+  const LevelTable& lv = h->lv;
+  bp.chunk_log2 = kChunkLog2;
+  bp.rec_per_point = 1u << (c.d - 1);
+  if (c.F != 2 || c.d < 2 || c.d > 3 || !lv.T_is_pow2) return;
+  const uint32_t cap = 1u << kChunkLog2;
+  uint32_t bins = 0;
+  for (uint32_t l = 0; l < lv.L; ++l) {
+    const uint32_t verts = lv.verts[l];
+    uint32_t nb;
+    if ((lv.dense_mask >> l) & 1u) {
+      if (verts > cap) return;
+      uint32_t s = 0;
+      while (((uint64_t)verts << (s + 1)) <= cap) ++s;
+      const uint64_t rows = c.d == 3 ? (uint64_t)verts * verts : verts;
+      bp.row_shift[l] = (uint8_t)s;
+      nb = (uint32_t)((rows + (1ull << s) - 1) >> s);
+    } else {
+      // both corners of a pair must share the bits above the chunk: v_0 + 1 < 2^chunk_log2
+      const uint32_t top = lv.N[l] + (c.interp == HG_INTERP_SMOOTHSTEP ? 1u : 0u);
+      if (top >= cap) return;
+      nb = lv.T > cap ? lv.T >> kChunkLog2 : 1u;
+    }
+    if (nb > (uint32_t)kScanThreads) return;
+    bp.bin_base[l] = bins;
+    bins += nb;
+  }
+  bp.bin_base[lv.L] = bins;
+  if ((uint64_t)bins * 4 > kMaxBinLds) return;  // per-bin counters of one workgroup live in LDS
+  bp.supported = 1;
+}
+
+// Slices per bin of each level for a batch of B points: coarse 1:1 levels have
+// few bins and receive B * 2^(d-1) records, so their bins are shared by several
+// accumulate-workgroups.
+static void plan_slices(BinPlan& bp, const LevelTable& lv, uint32_t B) {
+  uint32_t wgs = 0;
+  for (uint32_t l = 0; l < lv.L; ++l) {
+    const uint32_t nb = bp.bin_base[l + 1] - bp.bin_base[l];
+    const uint64_t per_bin = ((uint64_t)B * bp.rec_per_point + nb - 1) / nb;
+    uint64_t s = (per_bin + kTargetRecordsPerAccWg - 1) / kTargetRecordsPerAccWg;
+    if (!((lv.dense_mask >> l) & 1u) && s < 4) s = 1;  // hashed bins are evenly filled
+    if (s > 1) s *= 2;                                 // 1:1 bins are not: leave slack
+    if (s > 256) s = 256;
+    bp.slices[l] = (uint32_t)(s < 1 ? 1 : s);
+    bp.wg_base[l] = wgs;
+    wgs += nb * bp.slices[l];
+  }
+  bp.wg_base[lv.L] = wgs;
+}
+
+// ------------------------------------------------------------------ device
+
+template <int D>
+struct Rows {
+  uint32_t bin[1 << (D - 1)];    // global bin
+  uint32_t pack[1 << (D - 1)];   // chunk-local index of the lower | upper << 16 corner along dimension 0
+  float wrow[1 << (D - 1)];      // product of the weights of dimensions 1..d-1
+  float wf0;                     // fractional position along dimension 0 (before any smoothstep)
+};
+
+template <int D, bool COUNT_ONLY>
+__device__ __forceinline__ void rows_of(const LevelTable& lv, const BinPlan& bp, uint32_t l, bool smooth,
+                                        const float (&xp)[D], Rows<D>& out) {
+  const uint32_t N = lv.N[l], verts = lv.verts[l];
+  const bool dense = (lv.dense_mask >> l) & 1u;
+  const float Nf = (float)N;
+  const float shift = smooth ? 0.5f : 0.0f;
+  const float cmaxf = smooth ? Nf : Nf - 1.0f;
+  uint32_t c0[D];
+  float w[D], u[D];
+#pragma unroll
+  for (int i = 0; i < D; ++i) {
+    float wf;
+    split(xp[i], Nf, shift, cmaxf, c0[i], wf);
+    if (i == 0) out.wf0 = wf;
+    w[i] = smooth ? smoothstep(wf) : wf;
+    u[i] = smooth ? smoothstep(1.0f - wf) : 1.0f - wf;
+  }
+  const uint32_t cl = bp.chunk_log2, cmask = (1u << cl) - 1u;
+#pragma unroll
+  for (uint32_t r = 0; r < (1u << (D - 1)); ++r) {
+    uint32_t v[D];
+    float wr = 1.0f;
+#pragma unroll
+    for (int i = 1; i < D; ++i) {
+      const uint32_t bit = (r >> (i - 1)) & 1u;
+      v[i] = c0[i] + bit;
+      wr *= bit ? w[i] : u[i];
+    }
+    uint32_t bin, la, lb;
+    if (dense) {
+      uint32_t row = v[1];
+      if (D == 3) row += v[D - 1] * verts;
+      bin = row >> bp.row_shift[l];
+      la = c0[0] + (row - (bin << bp.row_shift[l])) * verts;
+      lb = la + 1u;
+    } else {
+      uint32_t rt = v[1] * prime(1);
+      if (D == 3) rt ^= v[D - 1] * prime(2);
+      const uint32_t ia = (c0[0] ^ rt) & (lv.T - 1u), ib = ((c0[0] + 1u) ^ rt) & (lv.T - 1u);
+      bin = ia >> cl;
+      la = ia & cmask;
+      lb = ib & cmask;
+    }
+    out.bin[r] = bp.bin_base[l] + bin;
+    if (!COUNT_ONLY) {
+      out.pack[r] = la | (lb << 16);
+      out.wrow[r] = wr;
+    }
+  }
+}
+
+template <int D>
+__device__ __forceinline__ void load_x(const float* __restrict__ x, uint32_t b, float (&xp)[D]) {
+#pragma unroll
+  for (int i = 0; i < D; ++i) xp[i] = x[(uint64_t)b * D + i];
+}
+
+// count: records per (workgroup, bin) and the workgroup's largest |dL/dy|.
+template <int D, typename IT>
+__global__ __launch_bounds__(kBinThreads) void bin_count(const LevelTable lv, const BinPlan bp, const bool smooth,
+                                                         const uint32_t B, const float* __restrict__ x,
+                                                         const IT* __restrict__ dy, uint32_t* __restrict__ counts,
+                                                         float* __restrict__ tile_max, const uint32_t n_bins) {
+  extern __shared__ uint32_t hist[];
+  __shared__ float wave_max[kBinThreads / 64];
+  for (uint32_t i = threadIdx.x; i < n_bins; i += kBinThreads) hist[i] = 0;
+  __syncthreads();
+  float m = 0.0f;
+  for (uint64_t b64 = (uint64_t)blockIdx.x * kBinThreads + threadIdx.x; b64 < B;
+       b64 += (uint64_t)gridDim.x * kBinThreads) {
+    const uint32_t b = (uint32_t)b64;
+    float xp[D];
+    load_x<D>(x, b, xp);
+    const IT* row = dy + (uint64_t)b * lv.L * 2;
+    for (uint32_t l = 0; l < lv.L; ++l) {
+      Rows<D> rw;
+      rows_of<D, true>(lv, bp, l, smooth, xp, rw);
+#pragma unroll
+      for (uint32_t r = 0; r < (1u << (D - 1)); ++r)
+        __hip_atomic_fetch_add(&hist[rw.bin[r]], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      const Vec<IT, 2> g = reinterpret_cast<const Vec<IT, 2>*>(row)[l];
+      // NaN must win the maximum so that the accumulate kernel sees it
+      const float a0 = fabsf((float)g.v[0]), a1 = fabsf((float)g.v[1]);
+      m = (a0 > m || a0 != a0) ? a0 : m;
+      m = (a1 > m || a1 != a1) ? a1 : m;
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float other = __shfl_xor(m, o);
+    m = (other > m || other != other) ? other : m;
+  }
+  if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
+  __syncthreads();
+  for (uint32_t i = threadIdx.x; i < n_bins; i += kBinThreads) counts[(uint64_t)blockIdx.x * n_bins + i] = hist[i];
+  if (threadIdx.x == 0) {
+    float t = wave_max[0];
+    for (int i = 1; i < kBinThreads / 64; ++i) t = (wave_max[i] > t || wave_max[i] != wave_max[i]) ? wave_max[i] : t;
+    tile_max[blockIdx.x] = t;
+  }
+}
+
+// scan: one workgroup per level.  Turns counts[tile][bin] into the exclusive
+// prefix over tiles and writes each bin's first record and record count.
+__global__ __launch_bounds__(kScanThreads) void bin_scan(const BinPlan bp, const uint32_t B, const uint32_t n_tiles,
+                                                         const uint32_t n_bins, uint32_t* __restrict__ counts,
+                                                         uint32_t* __restrict__ bin_start,
+                                                         uint32_t* __restrict__ bin_total) {
+  __shared__ uint32_t seg_sum[kScanThreads];
+  __shared__ uint32_t tot[kScanThreads];
+  __shared__ uint32_t scan[kScanThreads];
+  const uint32_t l = blockIdx.x;
+  const uint32_t gb0 = bp.bin_base[l], nb = bp.bin_base[l + 1] - gb0;
+  const uint32_t segs = kScanThreads / nb;  // nb <= kScanThreads by construction of the plan
+  const uint32_t bin = threadIdx.x % nb, seg = threadIdx.x / nb;
+  const bool active = seg < segs;
+  const uint32_t tps = (n_tiles + segs - 1) / segs;
+  const uint32_t t0 = seg * tps, t1 = (t0 + tps < n_tiles) ? t0 + tps : n_tiles;
+  uint32_t s = 0;
+  if (active)
+    for (uint32_t t = t0; t < t1; ++t) s += counts[(uint64_t)t * n_bins + gb0 + bin];
+  seg_sum[threadIdx.x] = active ? s : 0u;
+  __syncthreads();
+  uint32_t pre = 0;
+  if (active) {
+    for (uint32_t q = 0; q < seg; ++q) pre += seg_sum[q * nb + bin];
+    if (seg == 0) {
+      uint32_t total = 0;
+      for (uint32_t q = 0; q < segs; ++q) total += seg_sum[q * nb + bin];
+      tot[bin] = total;
+    }
+  }
+  __syncthreads();
+  // exclusive scan of tot[0..nb) (Hillis-Steele, nb <= 1024)
+  uint32_t v = threadIdx.x < nb ? tot[threadIdx.x] : 0u;
+  scan[threadIdx.x] = v;
+  __syncthreads();
+  for (uint32_t o = 1; o < (uint32_t)kScanThreads; o <<= 1) {
+    const uint32_t add = threadIdx.x >= o ? scan[threadIdx.x - o] : 0u;
+    __syncthreads();
+    scan[threadIdx.x] += add;
+    __syncthreads();
+  }
+  if (threadIdx.x < nb) {
+    const uint32_t level_base = l * B * bp.rec_per_point;  // every point emits rec_per_point records per level
+    bin_start[gb0 + threadIdx.x] = level_base + scan[threadIdx.x] - v;
+    bin_total[gb0 + threadIdx.x] = v;
+  }
+  if (active) {
+    uint32_t run = pre;
+    for (uint32_t t = t0; t < t1; ++t) {
+      const uint64_t at = (uint64_t)t * n_bins + gb0 + bin;
+      const uint32_t c = counts[at];
+      counts[at] = run;
+      run += c;
+    }
+  }
+}
+
+// scatter: writes every record to its slot.
+template <int D, typename IT>
+__global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, const BinPlan bp, const bool smooth,
+                                                           const uint32_t B, const float* __restrict__ x,
+                                                           const IT* __restrict__ dy,
+                                                           const uint32_t* __restrict__ counts,
+                                                           const uint32_t* __restrict__ bin_start,
+                                                           uint4* __restrict__ records, const uint32_t n_bins,
+                                                           const uint32_t n_records) {
+  extern __shared__ uint32_t cursor[];
+  for (uint32_t i = threadIdx.x; i < n_bins; i += kBinThreads)
+    cursor[i] = bin_start[i] + counts[(uint64_t)blockIdx.x * n_bins + i];
+  __syncthreads();
+  for (uint64_t b64 = (uint64_t)blockIdx.x * kBinThreads + threadIdx.x; b64 < B;
+       b64 += (uint64_t)gridDim.x * kBinThreads) {
+    const uint32_t b = (uint32_t)b64;
+    float xp[D];
+    load_x<D>(x, b, xp);
+    const Vec<IT, 2>* row = reinterpret_cast<const Vec<IT, 2>*>(dy + (uint64_t)b * lv.L * 2);
+    for (uint32_t l = 0; l < lv.L; ++l) {
+      Rows<D> rw;
+      rows_of<D, false>(lv, bp, l, smooth, xp, rw);
+      const Vec<IT, 2> g = row[l];
+      const float g0 = (float)g.v[0], g1 = (float)g.v[1];
+#pragma unroll
+      for (uint32_t r = 0; r < (1u << (D - 1)); ++r) {
+        const uint32_t slot =
+            __hip_atomic_fetch_add(&cursor[rw.bin[r]], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        // same inputs as the count pass give the same bins, so slot < n_records; the
+        // check only keeps a caller who changed x in between from writing out of bounds
+        if (slot < n_records)
+          records[slot] = make_uint4(rw.pack[r], __float_as_uint(rw.wf0), __float_as_uint(rw.wrow[r] * g0),
+                                     __float_as_uint(rw.wrow[r] * g1));
+      }
+    }
+  }
+}
+
+__device__ __forceinline__ long long to_fixed(float t, int S) { return __float2ll_rn(ldexpf(t, S)); }
+
+// accumulate: one workgroup per (bin, slice).
+__global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable lv, const BinPlan bp, const bool smooth,
+                                                              const uint32_t B, const uint32_t n_tiles,
+                                                              const uint32_t* __restrict__ bin_start,
+                                                              const uint32_t* __restrict__ bin_total,
+                                                              const float* __restrict__ tile_max,
+                                                              const uint4* __restrict__ records,
+                                                              float* __restrict__ grad) {
+  extern __shared__ unsigned long long acc[];  // [2^chunk_log2][2] fixed point
+  __shared__ float red[kAccThreads / 64];
+  // which level, bin and slice this workgroup serves
+  uint32_t l = 0;
+  while (l + 1 < lv.L && blockIdx.x >= bp.wg_base[l + 1]) ++l;
+  const uint32_t k = blockIdx.x - bp.wg_base[l];
+  const uint32_t n_sl = bp.slices[l];
+  const uint32_t bin = k / n_sl, slice = k - bin * n_sl;
+  const uint32_t gb = bp.bin_base[l] + bin;
+  const uint32_t start = bin_start[gb], total = bin_total[gb];
+  const uint32_t per = (total + n_sl - 1) / n_sl;
+  const uint32_t r0 = start + slice * per;
+  const uint32_t r1 = (slice * per + per < total) ? r0 + per : start + total;
+  if (slice * per >= total) return;  // uniform: nothing for this workgroup
+
+  // largest |dL/dy| of the call
+  float m = 0.0f;
+  for (uint32_t i = threadIdx.x; i < n_tiles; i += kAccThreads) {
+    const float t = tile_max[i];
+    m = (t > m || t != t) ? t : m;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float other = __shfl_xor(m, o);
+    m = (other > m || other != other) ? other : m;
+  }
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+  __syncthreads();
+  m = red[0];
+  for (int i = 1; i < kAccThreads / 64; ++i) m = (red[i] > m || red[i] != red[i]) ? red[i] : m;
+  if (m == 0.0f) return;  // every summand is zero
+
+  const uint32_t cl = bp.chunk_log2, cap = 1u << cl, cmask = cap - 1u;
+  const bool dense = (lv.dense_mask >> l) & 1u;
+  // entries of this chunk in the level's slice
+  uint32_t e0, e1;
+  if (dense) {
+    e0 = (bin << bp.row_shift[l]) * lv.verts[l];
+    e1 = e0 + (lv.verts[l] << bp.row_shift[l]);
+  } else {
+    e0 = bin << cl;
+    e1 = e0 + cap;
+  }
+  if (e1 > lv.size[l]) e1 = lv.size[l];
+  float* gl = grad + (lv.offset[l] + e0) * 2;
+
+  if (!(m < INFINITY)) {
+    // inf or NaN upstream: keep IEEE semantics with direct fp32 atomics (slow, rare)
+    for (uint32_t i = r0 + threadIdx.x; i < r1; i += kAccThreads) {
+      const uint4 rec = records[i];
+      const uint32_t la = rec.x & cmask, lb = (rec.x >> 16) & cmask;
+      const float wf = __uint_as_float(rec.y), g0 = __uint_as_float(rec.z), g1 = __uint_as_float(rec.w);
+      const float wu = smooth ? smoothstep(wf) : wf, wl = smooth ? smoothstep(1.0f - wf) : 1.0f - wf;
+      if (la < e1 - e0) {
+        __hip_atomic_fetch_add(gl + 2 * la, wl * g0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_add(gl + 2 * la + 1, wl * g1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      if (lb < e1 - e0) {
+        __hip_atomic_fetch_add(gl + 2 * lb, wu * g0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_add(gl + 2 * lb + 1, wu * g1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+    return;
+  }
+
+  // fixed-point scale: |summand| <= m < 2^E, at most 8B summands per entry
+  int E;
+  (void)frexpf(m, &E);
+  const int H = 3 + (32 - __builtin_clz(B > 1 ? B - 1 : 1));
+  const int S = 62 - H - E;
+
+  for (uint32_t i = threadIdx.x; i < 2 * cap; i += kAccThreads) acc[i] = 0ull;
+  __syncthreads();
+  for (uint32_t i = r0 + threadIdx.x; i < r1; i += kAccThreads) {
+    const uint4 rec = records[i];
+    const uint32_t la = rec.x & cmask, lb = (rec.x >> 16) & cmask;
+    const float wf = __uint_as_float(rec.y), g0 = __uint_as_float(rec.z), g1 = __uint_as_float(rec.w);
+    const float wu = smooth ? smoothstep(wf) : wf, wl = smooth ? smoothstep(1.0f - wf) : 1.0f - wf;
+    __hip_atomic_fetch_add(&acc[2 * la], (unsigned long long)to_fixed(wl * g0, S), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_WORKGROUP);
+    __hip_atomic_fetch_add(&acc[2 * la + 1], (unsigned long long)to_fixed(wl * g1, S), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_WORKGROUP);
+    __hip_atomic_fetch_add(&acc[2 * lb], (unsigned long long)to_fixed(wu * g0, S), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_WORKGROUP);
+    __hip_atomic_fetch_add(&acc[2 * lb + 1], (unsigned long long)to_fixed(wu * g1, S), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_WORKGROUP);
+  }
+  __syncthreads();
+  const uint32_t n_e = e1 - e0;
+  for (uint32_t e = threadIdx.x; e < n_e; e += kAccThreads) {
+    const long long a0 = (long long)acc[2 * e], a1 = (long long)acc[2 * e + 1];
+    if ((a0 | a1) == 0) continue;  // untouched entries stay bit-for-bit as they were
+    const float v0 = (float)ldexp((double)a0, -S), v1 = (float)ldexp((double)a1, -S);
+    if (n_sl == 1) {
+      float2* p = reinterpret_cast<float2*>(gl) + e;
+      float2 cur = *p;
+      cur.x += v0;
+      cur.y += v1;
+      *p = cur;
+    } else {
+      __hip_atomic_fetch_add(gl + 2 * e, v0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_fetch_add(gl + 2 * e + 1, v1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+}
+
+template <int D, typename IT>
+static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, const void* dy, float* grad,
+                               const Workspace& ws, hipStream_t s) {
+  BinPlan bp = h->bp;
+  plan_slices(bp, h->lv, B);
+  const bool smooth = h->cfg.interp == HG_INTERP_SMOOTHSTEP;
+  const uint32_t n_records = B * h->lv.L * bp.rec_per_point;
+  const size_t lds_bins = (size_t)ws.n_bins * 4;
+  hipLaunchKernelGGL((bin_count<D, IT>), dim3(ws.n_tiles), dim3(kBinThreads), lds_bins, s, h->lv, bp, smooth, B, x,
+                     static_cast<const IT*>(dy), ws.counts, ws.tile_max, ws.n_bins);
+  hipLaunchKernelGGL(bin_scan, dim3(h->lv.L), dim3(kScanThreads), 0, s, bp, B, ws.n_tiles, ws.n_bins, ws.counts,
+                     ws.bin_start, ws.bin_total);
+  hipLaunchKernelGGL((bin_scatter<D, IT>), dim3(ws.n_tiles), dim3(kBinThreads), lds_bins, s, h->lv, bp, smooth, B,
+                     x, static_cast<const IT*>(dy), ws.counts, ws.bin_start, ws.records, ws.n_bins, n_records);
+  // 64 KiB of dynamic LDS plus a few static bytes: above the default limit
+  static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_accumulate),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, 16 << kChunkLog2);
+  if (lds_ok != hipSuccess) return HG_ERR_DEVICE;
+  hipLaunchKernelGGL(bin_accumulate, dim3(bp.wg_base[h->lv.L]), dim3(kAccThreads), (size_t)16 << bp.chunk_log2, s,
+                     h->lv, bp, smooth, B, ws.n_tiles, ws.bin_start, ws.bin_total, ws.tile_max, ws.records, grad);
+  return hipGetLastError() == hipSuccess ? HG_OK : HG_ERR_DEVICE;
+}
+
+}  // namespace hg
+
+extern "C" {
+
+uint64_t hashgrid_bwd_workspace_bytes(const hashgrid_t* hg, uint32_t B) {
+  if (!hg || !hg->bp.supported || B == 0) return 0;
+  if ((uint64_t)B * hg->lv.L * hg->bp.rec_per_point >= (1ull << 32)) return 0;
+  return hg::carve(hg, B, nullptr, nullptr);
+}
+
+hg_status hashgrid_encode_bwd_ws(const hashgrid_t* hg, uint32_t B, const float* x, const void* dLdy,
+                                 float* grad_params, void* workspace, uint64_t workspace_bytes, void* stream) {
+  if (!hg) return HG_ERR_INVALID_ARG;
+  if (B == 0) return HG_OK;
+  const uint64_t need = hashgrid_bwd_workspace_bytes(hg, B);
+  if (need == 0) return HG_ERR_UNSUPPORTED;
+  if (!x || !dLdy || !grad_params || !workspace) return HG_ERR_INVALID_ARG;
+  if (workspace_bytes < need) return HG_ERR_INVALID_ARG;
+  const size_t io = hg->cfg.io_dtype == HG_F16 ? 2 : 4;
+  if ((reinterpret_cast<uintptr_t>(x) & 3) || (reinterpret_cast<uintptr_t>(dLdy) & (2 * io - 1)) ||
+      (reinterpret_cast<uintptr_t>(grad_params) & 7) || (reinterpret_cast<uintptr_t>(workspace) & 255))
+    return HG_ERR_INVALID_ARG;
+  hg::Workspace ws;
+  hg::carve(hg, B, static_cast<uint8_t*>(workspace), &ws);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const bool i16 = hg->cfg.io_dtype == HG_F16;
+  if (hg->cfg.d == 3)
+    return i16 ? hg::launch_binned<3, _Float16>(hg, B, x, dLdy, grad_params, ws, s)
+               : hg::launch_binned<3, float>(hg, B, x, dLdy, grad_params, ws, s);
+  return i16 ? hg::launch_binned<2, _Float16>(hg, B, x, dLdy, grad_params, ws, s)
+             : hg::launch_binned<2, float>(hg, B, x, dLdy, grad_params, ws, s);
+}
+
+}  // extern "C"

@@ -13,12 +13,7 @@
 
 #include "hashgrid.h"
 #include "hashgrid_common.hpp"
-
-struct hashgrid {
-  hashgrid_config cfg;
-  hg::LevelTable lv;
-  uint64_t total;
-};
+#include "hashgrid_internal.hpp"
 
 namespace hg {
 
@@ -316,6 +311,7 @@ hg_status hashgrid_create(const hashgrid_config* cfg, hashgrid_t** out) {
     delete h;
     return st;
   }
+  hg::build_bin_plan(h);
   *out = h;
   return HG_OK;
 }

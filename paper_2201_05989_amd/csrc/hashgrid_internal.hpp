@@ -1,0 +1,32 @@
+// Host-side handle shared by the translation units of libhashgrid.
+#pragma once
+
+#include "hashgrid.h"
+#include "hashgrid_common.hpp"
+
+namespace hg {
+
+// Plan of the binned backward pass (see bwd_binned.hip): how each level's
+// gradient slice is cut into chunks that fit the LDS of one workgroup.
+struct BinPlan {
+  uint32_t bin_base[HG_MAX_LEVELS + 1];  // first global bin of the level; [L] = number of bins
+  uint32_t wg_base[HG_MAX_LEVELS + 1];   // first accumulate-workgroup of the level; [L] = their number
+  uint32_t slices[HG_MAX_LEVELS];        // workgroups that share one bin of the level
+  uint8_t row_shift[HG_MAX_LEVELS];      // 1:1 levels: log2 of grid rows per chunk
+  uint32_t chunk_log2;                   // log2 of the entries a chunk can hold
+  uint32_t rec_per_point;                // records per (point, level): 2^(d-1)
+  uint32_t supported;                    // 0: configuration not served by the binned path
+};
+
+}  // namespace hg
+
+struct hashgrid {
+  hashgrid_config cfg;
+  hg::LevelTable lv;
+  uint64_t total;
+  hg::BinPlan bp;
+};
+
+namespace hg {
+void build_bin_plan(hashgrid* h);
+}

@@ -10,6 +10,9 @@ Bars (fp32 arithmetic on the GPU, fp64 in the oracle):
                                      which still bites for the paper's U(-1e-4,1e-4) tables
   backward (atomic order varies)     |g - g*| <= 1e-5 A, with A the sum of the absolute
                                      values of the summands of that entry (oracle run on |dL/dy|)
+  backward, workspace variant        the same plus M 2^(H-54): it sums in 64-bit fixed point with
+                                     each summand rounded to at most M 2^(H-62), M = max|dL/dy|,
+                                     H = 3 + ceil(log2 B); the floor allows 256 such roundings
 """
 import numpy as np
 import pytest
@@ -39,11 +42,16 @@ def check_fwd(y_gpu, y_ref, theta_absmax, io):
     assert not bad.any(), f"{bad.sum()} of {bad.size} outputs off, worst err {err.max():.3e}"
 
 
-def check_bwd(g_gpu, g_ref, g_abs):
+def check_bwd(g_gpu, g_ref, g_abs, floor=0.0):
     err = np.abs(g_gpu.astype(np.float64) - g_ref)
-    bad = err > 1e-5 * g_abs + 1e-30
+    bad = err > 1e-5 * g_abs + 1e-30 + floor
     assert not bad.any(), f"{bad.sum()} of {bad.size} gradients off, worst {np.max(err / (g_abs + 1e-300)):.3e} of A"
     assert (g_gpu[g_abs == 0] == 0).all()  # entries no point touches stay exactly as they were
+
+
+def ws_floor(dy, B):
+    H = 3 + int(np.ceil(np.log2(max(B, 2))))
+    return float(np.abs(dy.astype(np.float64)).max()) * 2.0 ** (H - 54)
 
 
 def run_case(d, L, F, T, N_min, N_max, pdt, iot, interp, x, theta, dy, do_indices=True, do_dx=True):
@@ -64,13 +72,19 @@ def run_case(d, L, F, T, N_min, N_max, pdt, iot, interp, x, theta, dy, do_indice
     y = grid.encode_fwd(xd, td)
     check_fwd(y.cpu().numpy(), orc.encode_fwd(cfg, x, theta), theta_absmax, iot)
 
-    g = grid.encode_bwd(xd, gd)
+    g = grid.encode_bwd(xd, gd, use_workspace=False)  # hashgrid_encode_bwd: device-wide atomics
     g_ref = orc.encode_bwd(cfg, x, dy)
     g_abs = orc.encode_bwd(cfg, x, np.abs(dy.astype(np.float64)))
     check_bwd(g.cpu().numpy(), g_ref, g_abs)
     # accumulates into what is already there
-    g2 = grid.encode_bwd(xd, gd, g.clone())
+    g2 = grid.encode_bwd(xd, gd, g.clone(), use_workspace=False)
     check_bwd(g2.cpu().numpy(), 2 * g_ref, 2 * g_abs)
+    if grid.bwd_workspace_bytes(len(x)):             # hashgrid_encode_bwd_ws: binned, fixed-point sums
+        floor = ws_floor(dy, len(x))
+        gw = grid.encode_bwd(xd, gd)
+        check_bwd(gw.cpu().numpy(), g_ref, g_abs, floor)
+        gw2 = grid.encode_bwd(xd, gd, gw.clone())
+        check_bwd(gw2.cpu().numpy(), 2 * g_ref, 2 * g_abs, 2 * floor)
 
     if do_dx:
         dx = grid.encode_bwd_input(xd, td, gd).cpu().numpy().astype(np.float64)
@@ -121,6 +135,7 @@ def test_large3d_full_size_sampled_forward_and_prefix_backward():
     rows.sort()
     check_fwd(y[rows], orc.encode_fwd(cfg, x[rows], theta), 1.0, w.io_dtype)
     nb = 1 << 18
+    assert grid.bwd_workspace_bytes(nb) == 0  # resolutions above 4095 on hashed levels: atomic path only
     g = grid.encode_bwd(xd[:nb].contiguous(), dev(dy[:nb])).cpu().numpy()
     check_bwd(g, orc.encode_bwd(cfg, x[:nb], dy[:nb]), orc.encode_bwd(cfg, x[:nb], np.abs(dy[:nb].astype(np.float64))))
 
@@ -211,3 +226,64 @@ def test_non_default_stream():
         y = grid.encode_fwd(xd, td)
     s.synchronize()
     check_fwd(y.cpu().numpy(), orc.encode_fwd(cfg, x, theta), 1.0, "f32")
+
+
+def test_workspace_backward_is_reproducible_and_keeps_untouched_entries():
+    w = synth.WORKLOADS["sdf3d"]
+    grid = HashGrid(w.d, w.L, w.F, w.T, w.N_min, w.N_max, w.param_dtype, w.io_dtype)
+    x, _, dy = synth.make_inputs(w, grid.n_entries, B=50000)
+    xd, gd = dev(x), dev(dy)
+    assert grid.bwd_workspace_bytes(len(x)) > 0
+    g1 = grid.encode_bwd(xd, gd)
+    g2 = grid.encode_bwd(xd, gd)
+    hashed = [i for i in grid.levels() if not i.is_dense]
+    lo = hashed[0].entry_offset
+    # hashed levels: one owner per chunk, exact fixed-point sums: bit-for-bit equal run to run
+    assert torch.equal(g1[lo:], g2[lo:])
+    # entries no point reaches keep their previous bits (here a sentinel)
+    sentinel = torch.full((grid.n_entries, 2), 7.25, dtype=torch.float32, device="cuda")
+    g3 = grid.encode_bwd(xd, gd, sentinel.clone())
+    untouched = (g1 == 0).all(dim=1)
+    assert untouched.any() and bool((g3[untouched] == 7.25).all())
+
+
+def test_workspace_backward_argument_checks():
+    grid = HashGrid(3, 16, 2, 1 << 19, 16, 2048)
+    B = 1000
+    need = grid.bwd_workspace_bytes(B)
+    assert need > B * 16 * 4 * 16
+    x = torch.rand((B, 3), device="cuda") * 0.99
+    dy = torch.ones((B, 32), dtype=torch.float16, device="cuda")
+    g = torch.zeros((grid.n_entries, 2), dtype=torch.float32, device="cuda")
+    small = torch.empty(need - 256, dtype=torch.uint8, device="cuda")
+    lib = grid._lib
+    st = lib.hashgrid_encode_bwd_ws(grid._h, B, x.data_ptr(), dy.data_ptr(), g.data_ptr(), small.data_ptr(),
+                                    small.numel(), None)
+    assert st == 1  # too small
+    st = lib.hashgrid_encode_bwd_ws(grid._h, B, x.data_ptr(), dy.data_ptr(), g.data_ptr(), None, need, None)
+    assert st == 1
+    # configurations the binned path does not serve report 0 bytes and HG_ERR_UNSUPPORTED
+    g4 = HashGrid(3, 16, 4, 1 << 19, 16, 2048)
+    assert g4.bwd_workspace_bytes(B) == 0
+    assert lib.hashgrid_encode_bwd_ws(g4._h, B, x.data_ptr(), dy.data_ptr(), g.data_ptr(), small.data_ptr(),
+                                      small.numel(), None) == 2
+
+
+def test_workspace_backward_with_non_finite_upstream_gradient():
+    # inf / NaN in dL/dy must reach exactly the entries the oracle says they reach
+    d, L, F, T, N_min, N_max = 3, 6, 2, 1 << 14, 8, 256
+    cfg = orc.OracleConfig(d, L, F, T, N_min, N_max)
+    grid = HashGrid(d, L, F, T, N_min, N_max, "f16", "f32")
+    rng = np.random.default_rng(21)
+    x = synth.points_uniform(rng, 3000, d)
+    dy = synth.make_dy(rng, 3000, L * F, "f32")
+    dy[17, 3] = np.inf
+    dy[99, 8] = np.nan
+    with np.errstate(invalid="ignore"):
+        ref = orc.encode_bwd(cfg, x, dy)
+    for use_ws in (False, True):
+        g = grid.encode_bwd(dev(x), dev(dy), use_workspace=use_ws).cpu().numpy()
+        assert (np.isfinite(g) == np.isfinite(ref)).all()
+        assert (np.isnan(g) == np.isnan(ref)).all()
+        fin = np.isfinite(ref)
+        np.testing.assert_allclose(g[fin], ref[fin], rtol=1e-4, atol=1e-5)
