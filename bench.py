@@ -51,7 +51,7 @@ def cpu_baseline(w, x, theta, dy, budget_s=10.0):
         orc.encode_bwd(cfg, xs, dys)
         reps += 1
         el = time.perf_counter() - t0
-        if el >= budget_s or reps >= 64:
+        if el >= budget_s or reps >= 1024:
             break
     return {"value": nb * reps / el / 1e6, "unit": "Mpoints/s", "cores": orc.num_threads(), "kind": "oracle",
             "sample": f"{reps} fwd+bwd passes over the first {nb} points of the workload, {el:.1f} s"}

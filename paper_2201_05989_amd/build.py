@@ -8,7 +8,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
 CSRC = os.path.join(_PKG, "csrc")
 INCLUDE = os.path.join(_ROOT, "include")
-LIB_PATH = os.path.join(_PKG, "libhashgrid.so")
+LIB_PATH = os.environ.get("HASHGRID_LIB") or os.path.join(_PKG, "libhashgrid.so")
 
 SOURCES = ["hashgrid.hip", "bwd_binned.hip"]
 
@@ -30,15 +30,16 @@ def hipcc() -> str:
     return "hipcc"
 
 
-def build_library(verbose: bool = False) -> str:
+def build_library(verbose: bool = False, extra_flags=(), out: str | None = None) -> str:
     srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    tmp = LIB_PATH + f".tmp{os.getpid()}"
-    cmd = [hipcc(), *HIPCC_FLAGS, f"-I{INCLUDE}", f"-I{CSRC}", "-o", tmp, *srcs]
+    out = out or LIB_PATH
+    tmp = out + f".tmp{os.getpid()}"
+    cmd = [hipcc(), *HIPCC_FLAGS, *extra_flags, f"-I{INCLUDE}", f"-I{CSRC}", "-o", tmp, *srcs]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
-    os.replace(tmp, LIB_PATH)
-    return LIB_PATH
+    os.replace(tmp, out)
+    return out
 
 
 if __name__ == "__main__":

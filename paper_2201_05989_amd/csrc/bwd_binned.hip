@@ -17,9 +17,10 @@
 //              the bin (chunk of the level's gradient slice, at most 2^chunk_log2
 //              entries) that holds both corners.  This kernel only counts.
 //   scan       per-bin totals and per-(workgroup, bin) write offsets.
-//   scatter    recomputes the records and writes each to its slot: 16 bytes =
-//              two chunk-local indices, the fractional position along
-//              dimension 0 and dL/dy times the weight of the other dimensions.
+//   scatter    recomputes the records, sorts them by bin in LDS one level at a
+//              time and writes each to its slot: 16 bytes = two chunk-local
+//              indices, the fractional position along dimension 0 and dL/dy
+//              times the weight of the other dimensions.
 //   accumulate one workgroup per bin (several for the few bins of coarse 1:1
 //              levels, which receive very many records): sums its records into
 //              LDS in 64-bit fixed point with integer atomics, then adds the
@@ -39,19 +40,32 @@
 
 namespace hg {
 
+using u32x4 = uint32_t __attribute__((ext_vector_type(4)));  // one 16-byte record
+
 constexpr int kBinThreads = 512;       // threads of a count / scatter workgroup
 constexpr uint32_t kMaxBinTiles = 512; // count / scatter workgroups per launch
 constexpr int kScanThreads = 1024;     // = maximum bins per level
-constexpr int kAccThreads = 512;
-constexpr uint32_t kChunkLog2 = 12;
+#ifndef HG_ACC_THREADS
+#define HG_ACC_THREADS 512
+#endif
+constexpr int kAccThreads = HG_ACC_THREADS;
+#ifndef HG_ACC_UNROLL
+#define HG_ACC_UNROLL 8
+#endif
+constexpr int kAccUnroll = HG_ACC_UNROLL;
+#ifndef HG_CHUNK_LOG2
+#define HG_CHUNK_LOG2 12
+#endif
+constexpr uint32_t kChunkLog2 = HG_CHUNK_LOG2;
 constexpr uint32_t kTargetRecordsPerAccWg = 16384;
-constexpr uint64_t kMaxBinLds = 48 * 1024;
+constexpr uint64_t kMaxBinLds = 15 * 1024;  // keeps a scatter workgroup within 64 KiB of LDS
 
 struct Workspace {
   uint32_t* counts;     // [n_tiles][n_bins] counts, then exclusive prefix over tiles
   uint32_t* bin_start;  // [n_bins] first record of the bin
   uint32_t* bin_total;  // [n_bins] records in the bin
   float* tile_max;      // [n_tiles] largest |dL/dy| seen by the workgroup
+  float* call_max;      // [1] largest |dL/dy| of the call
   uint4* records;       // [B * L * rec_per_point]
   uint32_t n_tiles;
   uint32_t n_bins;
@@ -73,13 +87,14 @@ static uint64_t carve(const hashgrid* h, uint32_t B, uint8_t* base, Workspace* w
     return o;
   };
   const uint64_t o_counts = take((uint64_t)nt * nb * 4), o_start = take((uint64_t)nb * 4),
-                 o_total = take((uint64_t)nb * 4), o_max = take((uint64_t)nt * 4),
+                 o_total = take((uint64_t)nb * 4), o_max = take((uint64_t)nt * 4), o_cmax = take(4),
                  o_rec = take((uint64_t)B * h->lv.L * h->bp.rec_per_point * 16);
   if (ws) {
     ws->counts = reinterpret_cast<uint32_t*>(base + o_counts);
     ws->bin_start = reinterpret_cast<uint32_t*>(base + o_start);
     ws->bin_total = reinterpret_cast<uint32_t*>(base + o_total);
     ws->tile_max = reinterpret_cast<float*>(base + o_max);
+    ws->call_max = reinterpret_cast<float*>(base + o_cmax);
     ws->records = reinterpret_cast<uint4*>(base + o_rec);
     ws->n_tiles = nt;
     ws->n_bins = nb;
@@ -259,117 +274,229 @@ __global__ __launch_bounds__(kBinThreads) void bin_count(const LevelTable lv, co
   }
 }
 
-// scan: one workgroup per level.  Turns counts[tile][bin] into the exclusive
-// prefix over tiles and writes each bin's first record and record count.
-__global__ __launch_bounds__(kScanThreads) void bin_scan(const BinPlan bp, const uint32_t B, const uint32_t n_tiles,
-                                                         const uint32_t n_bins, uint32_t* __restrict__ counts,
-                                                         uint32_t* __restrict__ bin_start,
-                                                         uint32_t* __restrict__ bin_total) {
-  __shared__ uint32_t seg_sum[kScanThreads];
-  __shared__ uint32_t tot[kScanThreads];
-  __shared__ uint32_t scan[kScanThreads];
-  const uint32_t l = blockIdx.x;
-  const uint32_t gb0 = bp.bin_base[l], nb = bp.bin_base[l + 1] - gb0;
-  const uint32_t segs = kScanThreads / nb;  // nb <= kScanThreads by construction of the plan
-  const uint32_t bin = threadIdx.x % nb, seg = threadIdx.x / nb;
-  const bool active = seg < segs;
-  const uint32_t tps = (n_tiles + segs - 1) / segs;
-  const uint32_t t0 = seg * tps, t1 = (t0 + tps < n_tiles) ? t0 + tps : n_tiles;
-  uint32_t s = 0;
-  if (active)
-    for (uint32_t t = t0; t < t1; ++t) s += counts[(uint64_t)t * n_bins + gb0 + bin];
-  seg_sum[threadIdx.x] = active ? s : 0u;
+// Exclusive prefix sum of a[0..n) in LDS, in place, by all T threads of the
+// workgroup (every thread must call it).  `tmp` holds T/64 words.
+template <int T>
+__device__ __forceinline__ void block_exclusive_scan(uint32_t* a, uint32_t n, uint32_t* tmp) {
+  const uint32_t per = (n + T - 1) / T;
+  const uint32_t begin = threadIdx.x * per < n ? threadIdx.x * per : n;
+  const uint32_t end = begin + per < n ? begin + per : n;
+  uint32_t sum = 0;
+  for (uint32_t i = begin; i < end; ++i) sum += a[i];
+  uint32_t inc = sum;  // inclusive scan across the wave
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t up = __shfl_up(inc, o);
+    if ((threadIdx.x & 63) >= (uint32_t)o) inc += up;
+  }
+  if ((threadIdx.x & 63) == 63) tmp[threadIdx.x >> 6] = inc;
   __syncthreads();
-  uint32_t pre = 0;
-  if (active) {
-    for (uint32_t q = 0; q < seg; ++q) pre += seg_sum[q * nb + bin];
-    if (seg == 0) {
-      uint32_t total = 0;
-      for (uint32_t q = 0; q < segs; ++q) total += seg_sum[q * nb + bin];
-      tot[bin] = total;
+  uint32_t wave_base = 0;
+  for (uint32_t w = 0; w < (threadIdx.x >> 6); ++w) wave_base += tmp[w];
+  uint32_t run = wave_base + inc - sum;
+  for (uint32_t i = begin; i < end; ++i) {
+    const uint32_t v = a[i];
+    a[i] = run;
+    run += v;
+  }
+  __syncthreads();
+}
+
+// scan: each workgroup takes kScanBins bins and turns their column of
+// counts[tile][bin] into the exclusive prefix over tiles; it also writes the
+// bin's record count.  Workgroup 0 reduces the per-tile maxima of |dL/dy|.
+constexpr int kScanBins = 16;
+__global__ __launch_bounds__(kScanThreads) void bin_scan(const uint32_t n_tiles, const uint32_t n_bins,
+                                                         uint32_t* __restrict__ counts,
+                                                         uint32_t* __restrict__ bin_total,
+                                                         const float* __restrict__ tile_max,
+                                                         float* __restrict__ call_max) {
+  __shared__ uint32_t seg_sum[kScanThreads];
+  __shared__ float red[kScanThreads / 64];
+  if (blockIdx.x == 0) {  // largest |dL/dy| of the call; NaN wins
+    float m = 0.0f;
+    for (uint32_t i = threadIdx.x; i < n_tiles; i += kScanThreads) {
+      const float t = tile_max[i];
+      m = (t > m || t != t) ? t : m;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const float other = __shfl_xor(m, o);
+      m = (other > m || other != other) ? other : m;
+    }
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      m = red[0];
+      for (int i = 1; i < kScanThreads / 64; ++i) m = (red[i] > m || red[i] != red[i]) ? red[i] : m;
+      call_max[0] = m;
     }
   }
-  __syncthreads();
-  // exclusive scan of tot[0..nb) (Hillis-Steele, nb <= 1024)
-  uint32_t v = threadIdx.x < nb ? tot[threadIdx.x] : 0u;
-  scan[threadIdx.x] = v;
-  __syncthreads();
-  for (uint32_t o = 1; o < (uint32_t)kScanThreads; o <<= 1) {
-    const uint32_t add = threadIdx.x >= o ? scan[threadIdx.x - o] : 0u;
-    __syncthreads();
-    scan[threadIdx.x] += add;
-    __syncthreads();
-  }
-  if (threadIdx.x < nb) {
-    const uint32_t level_base = l * B * bp.rec_per_point;  // every point emits rec_per_point records per level
-    bin_start[gb0 + threadIdx.x] = level_base + scan[threadIdx.x] - v;
-    bin_total[gb0 + threadIdx.x] = v;
-  }
+  constexpr uint32_t segs = kScanThreads / kScanBins;
+  const uint32_t bin_in = threadIdx.x % kScanBins, seg = threadIdx.x / kScanBins;
+  const uint32_t gb = blockIdx.x * kScanBins + bin_in;
+  const bool active = gb < n_bins;
+  const uint32_t tps = (n_tiles + segs - 1) / segs;
+  const uint32_t t0 = seg * tps < n_tiles ? seg * tps : n_tiles;
+  const uint32_t t1 = t0 + tps < n_tiles ? t0 + tps : n_tiles;
+  uint32_t* col = counts + gb;
+  // the loads of a column are independent: issue them eight at a time
+  uint32_t s = 0;
   if (active) {
+    uint32_t t = t0;
+    for (; t + 8 <= t1; t += 8) {
+      uint32_t c[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) c[j] = col[(uint64_t)(t + j) * n_bins];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) s += c[j];
+    }
+    for (; t < t1; ++t) s += col[(uint64_t)t * n_bins];
+  }
+  seg_sum[threadIdx.x] = s;
+  __syncthreads();
+  if (active) {
+    uint32_t pre = 0, total = 0;
+    for (uint32_t q = 0; q < segs; ++q) {
+      const uint32_t v = seg_sum[q * kScanBins + bin_in];
+      pre += q < seg ? v : 0u;
+      total += v;
+    }
+    if (seg == 0) bin_total[gb] = total;
     uint32_t run = pre;
-    for (uint32_t t = t0; t < t1; ++t) {
-      const uint64_t at = (uint64_t)t * n_bins + gb0 + bin;
-      const uint32_t c = counts[at];
-      counts[at] = run;
+    uint32_t t = t0;
+    for (; t + 8 <= t1; t += 8) {
+      uint32_t c[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) c[j] = col[(uint64_t)(t + j) * n_bins];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        col[(uint64_t)(t + j) * n_bins] = run;
+        run += c[j];
+      }
+    }
+    for (; t < t1; ++t) {
+      const uint32_t c = col[(uint64_t)t * n_bins];
+      col[(uint64_t)t * n_bins] = run;
       run += c;
     }
   }
 }
 
-// scatter: writes every record to its slot.
+// scatter: writes every record to its slot.  A bin's first record is the sum of
+// the record counts of all bins before it (every level holds exactly
+// B * rec_per_point records, so this is also level-major).  Level by level the
+// workgroup sorts the records of its 512 points by bin in LDS and copies them
+// out bin after bin, so that what reaches memory is runs of whole records that
+// mostly fill whole cache lines; 16-byte stores scattered over a thousand open
+// runs leave the L2 as partial lines and cost several times the bytes.
 template <int D, typename IT>
 __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, const BinPlan bp, const bool smooth,
                                                            const uint32_t B, const float* __restrict__ x,
                                                            const IT* __restrict__ dy,
                                                            const uint32_t* __restrict__ counts,
-                                                           const uint32_t* __restrict__ bin_start,
-                                                           uint4* __restrict__ records, const uint32_t n_bins,
+                                                           const uint32_t* __restrict__ bin_total,
+                                                           uint32_t* __restrict__ bin_start,
+                                                           u32x4* __restrict__ records, const uint32_t n_bins,
                                                            const uint32_t n_records) {
-  extern __shared__ uint32_t cursor[];
-  for (uint32_t i = threadIdx.x; i < n_bins; i += kBinThreads)
-    cursor[i] = bin_start[i] + counts[(uint64_t)blockIdx.x * n_bins + i];
+  constexpr uint32_t R = 1u << (D - 1);
+  extern __shared__ uint32_t cursor[];               // [n_bins] next free slot of the bin for this workgroup
+  __shared__ uint32_t cnt[kScanThreads];             // records per bin of the current level and sub-tile
+  __shared__ uint32_t off[kScanThreads];             // their exclusive prefix
+  __shared__ uint32_t scan_tmp[kBinThreads / 64];
+  __shared__ u32x4 staging[R * kBinThreads];
+  __shared__ uint32_t dstv[R * kBinThreads];
+
+  for (uint32_t i = threadIdx.x; i < n_bins; i += kBinThreads) cursor[i] = bin_total[i];
   __syncthreads();
-  for (uint64_t b64 = (uint64_t)blockIdx.x * kBinThreads + threadIdx.x; b64 < B;
-       b64 += (uint64_t)gridDim.x * kBinThreads) {
-    const uint32_t b = (uint32_t)b64;
+  block_exclusive_scan<kBinThreads>(cursor, n_bins, scan_tmp);
+  for (uint32_t i = threadIdx.x; i < n_bins; i += kBinThreads) {
+    const uint32_t first = cursor[i];
+    if (blockIdx.x == 0) bin_start[i] = first;
+    cursor[i] = first + counts[(uint64_t)blockIdx.x * n_bins + i];
+  }
+  __syncthreads();
+
+  for (uint64_t base = (uint64_t)blockIdx.x * kBinThreads; base < B; base += (uint64_t)gridDim.x * kBinThreads) {
+    const uint64_t b64 = base + threadIdx.x;
+    const bool valid = b64 < B;
+    const uint32_t b = valid ? (uint32_t)b64 : 0u;
     float xp[D];
     load_x<D>(x, b, xp);
     const Vec<IT, 2>* row = reinterpret_cast<const Vec<IT, 2>*>(dy + (uint64_t)b * lv.L * 2);
     for (uint32_t l = 0; l < lv.L; ++l) {
+      const uint32_t gb0 = bp.bin_base[l], nb = bp.bin_base[l + 1] - gb0;
+      for (uint32_t i = threadIdx.x; i < nb; i += kBinThreads) cnt[i] = 0;
+      __syncthreads();
       Rows<D> rw;
-      rows_of<D, false>(lv, bp, l, smooth, xp, rw);
-      const Vec<IT, 2> g = row[l];
-      const float g0 = (float)g.v[0], g1 = (float)g.v[1];
+      uint32_t rank[R];
+      float g0 = 0.0f, g1 = 0.0f;
+      if (valid) {
+        rows_of<D, false>(lv, bp, l, smooth, xp, rw);
+        const Vec<IT, 2> g = row[l];
+        g0 = (float)g.v[0];
+        g1 = (float)g.v[1];
 #pragma unroll
-      for (uint32_t r = 0; r < (1u << (D - 1)); ++r) {
-        const uint32_t slot =
-            __hip_atomic_fetch_add(&cursor[rw.bin[r]], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        // same inputs as the count pass give the same bins, so slot < n_records; the
-        // check only keeps a caller who changed x in between from writing out of bounds
-        if (slot < n_records)
-          records[slot] = make_uint4(rw.pack[r], __float_as_uint(rw.wf0), __float_as_uint(rw.wrow[r] * g0),
-                                     __float_as_uint(rw.wrow[r] * g1));
+        for (uint32_t r = 0; r < R; ++r)
+          rank[r] = __hip_atomic_fetch_add(&cnt[rw.bin[r] - gb0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
       }
+      __syncthreads();
+      for (uint32_t i = threadIdx.x; i < nb; i += kBinThreads) off[i] = cnt[i];
+      __syncthreads();
+      block_exclusive_scan<kBinThreads>(off, nb, scan_tmp);
+      if (valid) {
+#pragma unroll
+        for (uint32_t r = 0; r < R; ++r) {
+          const uint32_t pos = off[rw.bin[r] - gb0] + rank[r];  // < R * kBinThreads
+          u32x4 rec;
+          rec.x = rw.pack[r];
+          rec.y = __float_as_uint(rw.wf0);
+          rec.z = __float_as_uint(rw.wrow[r] * g0);
+          rec.w = __float_as_uint(rw.wrow[r] * g1);
+          staging[pos] = rec;
+          dstv[pos] = cursor[rw.bin[r]] + rank[r];
+        }
+      }
+      __syncthreads();
+      const uint32_t emitted = off[nb - 1] + cnt[nb - 1];
+      for (uint32_t j = threadIdx.x; j < emitted; j += kBinThreads) {
+        const uint32_t d = dstv[j];
+        // the count pass saw the same inputs, so d < n_records; the check only keeps a
+        // caller who changed x in between from writing out of bounds
+        if (d < n_records) records[d] = staging[j];
+      }
+      __syncthreads();
+      for (uint32_t i = threadIdx.x; i < nb; i += kBinThreads) cursor[gb0 + i] += cnt[i];
     }
   }
 }
 
-__device__ __forceinline__ long long to_fixed(float t, int S) { return __float2ll_rn(ldexpf(t, S)); }
+// round(t * 2^S) as a 64-bit integer, for |t| * 2^S < 2^62.  An fp32 value has 24
+// significant bits, so above 2^32 the scaled magnitude splits exactly into a high
+// and a low 32-bit half; only values below 2^24 have a fraction to round.
+__device__ __forceinline__ long long to_fixed(float t, int S) {
+  const float a = ldexpf(fabsf(t), S);
+  const float hi = floorf(a * 0x1p-32f);
+  const float lo = fmaf(-hi, 0x1p32f, a);  // exact, in [0, 2^32)
+  const unsigned long long mag = ((unsigned long long)(uint32_t)hi << 32) | (unsigned long long)(uint32_t)rintf(lo);
+  const long long sgn = (long long)(__float_as_int(t) >> 31);  // 0 or -1
+  return ((long long)mag ^ sgn) - sgn;
+}
 
 // accumulate: one workgroup per (bin, slice).
 __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable lv, const BinPlan bp, const bool smooth,
-                                                              const uint32_t B, const uint32_t n_tiles,
+                                                              const uint32_t B,
                                                               const uint32_t* __restrict__ bin_start,
                                                               const uint32_t* __restrict__ bin_total,
-                                                              const float* __restrict__ tile_max,
+                                                              const float* __restrict__ call_max,
                                                               const uint4* __restrict__ records,
                                                               float* __restrict__ grad) {
   extern __shared__ unsigned long long acc[];  // [2^chunk_log2][2] fixed point
-  __shared__ float red[kAccThreads / 64];
   // which level, bin and slice this workgroup serves
+  const uint32_t wg = blockIdx.x;
   uint32_t l = 0;
-  while (l + 1 < lv.L && blockIdx.x >= bp.wg_base[l + 1]) ++l;
-  const uint32_t k = blockIdx.x - bp.wg_base[l];
+  while (l + 1 < lv.L && wg >= bp.wg_base[l + 1]) ++l;
+  const uint32_t k = wg - bp.wg_base[l];
   const uint32_t n_sl = bp.slices[l];
   const uint32_t bin = k / n_sl, slice = k - bin * n_sl;
   const uint32_t gb = bp.bin_base[l] + bin;
@@ -379,21 +506,7 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
   const uint32_t r1 = (slice * per + per < total) ? r0 + per : start + total;
   if (slice * per >= total) return;  // uniform: nothing for this workgroup
 
-  // largest |dL/dy| of the call
-  float m = 0.0f;
-  for (uint32_t i = threadIdx.x; i < n_tiles; i += kAccThreads) {
-    const float t = tile_max[i];
-    m = (t > m || t != t) ? t : m;
-  }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const float other = __shfl_xor(m, o);
-    m = (other > m || other != other) ? other : m;
-  }
-  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
-  __syncthreads();
-  m = red[0];
-  for (int i = 1; i < kAccThreads / 64; ++i) m = (red[i] > m || red[i] != red[i]) ? red[i] : m;
+  const float m = call_max[0];  // largest |dL/dy| of the call (NaN if any is NaN)
   if (m == 0.0f) return;  // every summand is zero
 
   const uint32_t cl = bp.chunk_log2, cap = 1u << cl, cmask = cap - 1u;
@@ -435,34 +548,58 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
   const int H = 3 + (32 - __builtin_clz(B > 1 ? B - 1 : 1));
   const int S = 62 - H - E;
 
+  // The chunk of the gradient this workgroup will add to is fetched now and used
+  // after the records: its latency hides behind the record stream.
+  constexpr int kPer = (1 << kChunkLog2) / kAccThreads;  // entries per lane
+  const uint32_t n_e = e1 - e0;
+  float2 cur[kPer];
+  if (n_sl == 1) {
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+      const uint32_t e = threadIdx.x + j * kAccThreads;
+      if (e < n_e) cur[j] = reinterpret_cast<const float2*>(gl)[e];
+    }
+  }
   for (uint32_t i = threadIdx.x; i < 2 * cap; i += kAccThreads) acc[i] = 0ull;
   __syncthreads();
-  for (uint32_t i = r0 + threadIdx.x; i < r1; i += kAccThreads) {
-    const uint4 rec = records[i];
+  unsigned long long* acc0 = acc;        // feature 0 of every entry, then feature 1: consecutive
+  unsigned long long* acc1 = acc + cap;  // entries map to consecutive LDS banks
+  auto add_record = [&](const u32x4 rec) {
     const uint32_t la = rec.x & cmask, lb = (rec.x >> 16) & cmask;
     const float wf = __uint_as_float(rec.y), g0 = __uint_as_float(rec.z), g1 = __uint_as_float(rec.w);
     const float wu = smooth ? smoothstep(wf) : wf, wl = smooth ? smoothstep(1.0f - wf) : 1.0f - wf;
-    __hip_atomic_fetch_add(&acc[2 * la], (unsigned long long)to_fixed(wl * g0, S), __ATOMIC_RELAXED,
+    __hip_atomic_fetch_add(&acc0[la], (unsigned long long)to_fixed(wl * g0, S), __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_WORKGROUP);
-    __hip_atomic_fetch_add(&acc[2 * la + 1], (unsigned long long)to_fixed(wl * g1, S), __ATOMIC_RELAXED,
+    __hip_atomic_fetch_add(&acc1[la], (unsigned long long)to_fixed(wl * g1, S), __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_WORKGROUP);
-    __hip_atomic_fetch_add(&acc[2 * lb], (unsigned long long)to_fixed(wu * g0, S), __ATOMIC_RELAXED,
+    __hip_atomic_fetch_add(&acc0[lb], (unsigned long long)to_fixed(wu * g0, S), __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_WORKGROUP);
-    __hip_atomic_fetch_add(&acc[2 * lb + 1], (unsigned long long)to_fixed(wu * g1, S), __ATOMIC_RELAXED,
+    __hip_atomic_fetch_add(&acc1[lb], (unsigned long long)to_fixed(wu * g1, S), __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_WORKGROUP);
+  };
+  // kAccUnroll loads in flight per lane: the record stream is latency-bound otherwise
+  uint32_t i = r0 + threadIdx.x;
+  for (; i + (kAccUnroll - 1) * kAccThreads < r1; i += kAccUnroll * kAccThreads) {
+    u32x4 rec[kAccUnroll];
+    const u32x4* rp = reinterpret_cast<const u32x4*>(records);
+#pragma unroll
+    for (int j = 0; j < kAccUnroll; ++j) rec[j] = __builtin_nontemporal_load(rp + i + j * kAccThreads);
+#pragma unroll
+    for (int j = 0; j < kAccUnroll; ++j) add_record(rec[j]);
   }
+  for (; i < r1; i += kAccThreads) add_record(__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(records) + i));
   __syncthreads();
-  const uint32_t n_e = e1 - e0;
-  for (uint32_t e = threadIdx.x; e < n_e; e += kAccThreads) {
-    const long long a0 = (long long)acc[2 * e], a1 = (long long)acc[2 * e + 1];
+#pragma unroll
+  for (int j = 0; j < kPer; ++j) {
+    const uint32_t e = threadIdx.x + j * kAccThreads;
+    if (e >= n_e) continue;
+    const long long a0 = (long long)acc0[e], a1 = (long long)acc1[e];
     if ((a0 | a1) == 0) continue;  // untouched entries stay bit-for-bit as they were
     const float v0 = (float)ldexp((double)a0, -S), v1 = (float)ldexp((double)a1, -S);
     if (n_sl == 1) {
-      float2* p = reinterpret_cast<float2*>(gl) + e;
-      float2 cur = *p;
-      cur.x += v0;
-      cur.y += v1;
-      *p = cur;
+      cur[j].x += v0;
+      cur[j].y += v1;
+      reinterpret_cast<float2*>(gl)[e] = cur[j];
     } else {
       __hip_atomic_fetch_add(gl + 2 * e, v0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       __hip_atomic_fetch_add(gl + 2 * e + 1, v1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -480,16 +617,17 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
   const size_t lds_bins = (size_t)ws.n_bins * 4;
   hipLaunchKernelGGL((bin_count<D, IT>), dim3(ws.n_tiles), dim3(kBinThreads), lds_bins, s, h->lv, bp, smooth, B, x,
                      static_cast<const IT*>(dy), ws.counts, ws.tile_max, ws.n_bins);
-  hipLaunchKernelGGL(bin_scan, dim3(h->lv.L), dim3(kScanThreads), 0, s, bp, B, ws.n_tiles, ws.n_bins, ws.counts,
-                     ws.bin_start, ws.bin_total);
-  hipLaunchKernelGGL((bin_scatter<D, IT>), dim3(ws.n_tiles), dim3(kBinThreads), lds_bins, s, h->lv, bp, smooth, B,
-                     x, static_cast<const IT*>(dy), ws.counts, ws.bin_start, ws.records, ws.n_bins, n_records);
+  hipLaunchKernelGGL(bin_scan, dim3((ws.n_bins + kScanBins - 1) / kScanBins), dim3(kScanThreads), 0, s, ws.n_tiles,
+                     ws.n_bins, ws.counts, ws.bin_total, ws.tile_max, ws.call_max);
   // 64 KiB of dynamic LDS plus a few static bytes: above the default limit
   static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_accumulate),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, 16 << kChunkLog2);
   if (lds_ok != hipSuccess) return HG_ERR_DEVICE;
+  hipLaunchKernelGGL((bin_scatter<D, IT>), dim3(ws.n_tiles), dim3(kBinThreads), lds_bins, s, h->lv, bp, smooth, B, x,
+                     static_cast<const IT*>(dy), ws.counts, ws.bin_total, ws.bin_start,
+                     reinterpret_cast<u32x4*>(ws.records), ws.n_bins, n_records);
   hipLaunchKernelGGL(bin_accumulate, dim3(bp.wg_base[h->lv.L]), dim3(kAccThreads), (size_t)16 << bp.chunk_log2, s,
-                     h->lv, bp, smooth, B, ws.n_tiles, ws.bin_start, ws.bin_total, ws.tile_max, ws.records, grad);
+                     h->lv, bp, smooth, B, ws.bin_start, ws.bin_total, ws.call_max, ws.records, grad);
   return hipGetLastError() == hipSuccess ? HG_OK : HG_ERR_DEVICE;
 }
 

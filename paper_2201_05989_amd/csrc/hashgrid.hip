@@ -104,6 +104,53 @@ __global__ __launch_bounds__(kBlock) void fwd_general(const LevelTable lv, const
   reinterpret_cast<Vec<IT, F>*>(y)[(uint64_t)b * lv.L + l] = out;
 }
 
+// Forward for F = 2, point-major: one thread owns a point and walks the levels in
+// order, so x is read once and the output row leaves the thread as 16-byte
+// pieces.  (The level-major kernel above writes 2*sizeof(io) bytes per thread
+// with a stride of a whole row; each such fragment costs a whole 32-byte sector
+// of write traffic.)  The paper's level-by-level order (Section 4), which keeps
+// one level's slice hot in cache, is kept in time rather than in the grid: all
+// resident workgroups start at level 0 together, and the barrier per level
+// keeps the 16 waves of a workgroup on the same slice, which holds the L2 hit
+// rate at that of the level-major grid.
+constexpr int kPmBlock = 1024;
+template <int D, typename PT, typename IT>
+__global__ __launch_bounds__(kPmBlock) void fwd_point_major(const LevelTable lv, const bool smooth, const uint32_t B,
+                                                            const float* __restrict__ x,
+                                                            const PT* __restrict__ theta, IT* __restrict__ y) {
+  constexpr int G = 16 / (2 * (int)sizeof(IT));  // levels per 16-byte store
+  const uint32_t b0 = blockIdx.x * kPmBlock + threadIdx.x;
+  const bool valid = b0 < B;
+  const uint32_t b = valid ? b0 : B - 1;  // idle lanes of the last workgroup shadow the last point
+  float xp[D];
+  load_point<D>(x, b, xp);
+  Vec<IT, 2 * G>* yrow = reinterpret_cast<Vec<IT, 2 * G>*>(y + (uint64_t)b * lv.L * 2);
+  for (uint32_t l0 = 0; l0 < lv.L; l0 += G) {
+    Vec<IT, 2 * G> out;
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+      const uint32_t l = l0 + j;
+      Corners<D> cn;
+      corners_of<D, false>(lv, l, smooth, xp, cn, nullptr);
+      const Vec<PT, 2>* tab = reinterpret_cast<const Vec<PT, 2>*>(theta) + lv.offset[l];
+      Vec<PT, 2> e[1 << D];
+#pragma unroll
+      for (uint32_t m = 0; m < (1u << D); ++m) e[m] = tab[cn.idx[m]];
+      float a0 = 0.0f, a1 = 0.0f;
+#pragma unroll
+      for (uint32_t m = 0; m < (1u << D); ++m) {
+        a0 = fmaf(cn.wt[m], (float)e[m].v[0], a0);
+        a1 = fmaf(cn.wt[m], (float)e[m].v[1], a1);
+      }
+      out.v[2 * j] = (IT)a0;
+      out.v[2 * j + 1] = (IT)a1;
+      asm volatile("" ::: "memory");  // keep the gathers of one level together
+      __syncthreads();
+    }
+    if (valid) yrow[l0 / G] = out;
+  }
+}
+
 // Backward to the tables, Fig. 3 caption: scatter-add of weight * dL/dy.
 //
 // The L2 atomic units of this chip retire about one atomic *request* per clock
@@ -244,6 +291,15 @@ static hg_status launched() { return hipGetLastError() == hipSuccess ? HG_OK : H
 template <int D, int F, typename PT, typename IT>
 static hg_status launch_fwd(const hashgrid* h, uint32_t B, const float* x, const void* params, void* y,
                             hipStream_t s) {
+  if constexpr (F == 2) {
+    constexpr uint32_t G = 16 / (2 * sizeof(IT));
+    if (h->lv.L % G == 0 && !misaligned(y, 16)) {
+      hipLaunchKernelGGL((fwd_point_major<D, PT, IT>), dim3((B + kPmBlock - 1) / kPmBlock), dim3(kPmBlock), 0, s,
+                         h->lv, h->cfg.interp == HG_INTERP_SMOOTHSTEP, B, x, static_cast<const PT*>(params),
+                         static_cast<IT*>(y));
+      return launched();
+    }
+  }
   dim3 grid((B + kBlock - 1) / kBlock, h->lv.L);
   hipLaunchKernelGGL((fwd_general<D, F, PT, IT>), grid, dim3(kBlock), 0, s, h->lv,
                      h->cfg.interp == HG_INTERP_SMOOTHSTEP, B, x, static_cast<const PT*>(params),
