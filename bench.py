@@ -36,6 +36,19 @@ def time_launches(fn, n, torch):
     return e0.elapsed_time(e1) / n  # ms
 
 
+def measured_traffic(workload, which):
+    """HBM bytes per launch of the dominant pass, from the committed rocprofv3 counter summary
+    (FETCH_SIZE + WRITE_SIZE scaled by the copy calibration); None when no summary covers it."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}.txt")
+    try:
+        for line in open(path):
+            if line.startswith(f"{which}_hbm_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(w, x, theta, dy, budget_s=10.0):
     import numpy as np
     from oracle import hashgrid_oracle as orc
@@ -64,6 +77,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="sdf3d")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a 1 GiB device-to-device copy (20 times): the known-size kernel that "
+                         "FETCH_SIZE / WRITE_SIZE counter readings are scaled by")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only; run with --gpus 1", file=sys.stderr)
@@ -71,6 +87,15 @@ def main():
 
     import torch
     from paper_2201_05989_amd import HashGrid, synth
+
+    if args.calibrate_copy:
+        a = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
+        b = torch.empty_like(a)
+        for _ in range(20):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": a.numel() * 4, "bytes_written": a.numel() * 4, "launches": 20}))
+        return
 
     w = synth.WORKLOADS[args.workload]
     grid = HashGrid(w.d, w.L, w.F, w.T, w.N_min, w.N_max, w.param_dtype, w.io_dtype)
@@ -108,6 +133,9 @@ def main():
     b_fwd, b_bwd = algorithmic_bytes(w, s_theta, s_io)
     dom = ("bwd", ms_bwd, b_bwd) if ms_bwd >= ms_fwd else ("fwd", ms_fwd, b_fwd)
     achieved = dom[2] * w.B / (dom[1] * 1e-3) / 1e9
+    kernels = {"fwd": "fwd_point_major", "bwd": "bin_count+bin_scan+bin_scatter+bin_accumulate "
+                                                 "(one hashgrid_encode_bwd_ws call)"}
+    traffic = measured_traffic(w.name, dom[0])
 
     out = {
         "metric": "hash-grid encoding fwd+bwd throughput",
@@ -122,9 +150,12 @@ def main():
         "fwd_mpoints_s": w.B / (ms_fwd * 1e-3) / 1e6,
         "bwd_mpoints_s": w.B / (ms_bwd * 1e-3) / 1e6,
         "ms_fwd": ms_fwd, "ms_bwd": ms_bwd, "ms_grad_zero": ms_zero,
-        "roofline": {"bound": "hbm", "kernel": dom[0], "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "algorithmic_bytes_per_point": {"fwd": b_fwd, "bwd": b_bwd}},
+        "roofline": {"bound": "hbm", "kernel": kernels[dom[0]] if grid.bwd_workspace_bytes(w.B) else dom[0],
+                     "pass": dom[0], "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "algorithmic_bytes_per_point": {"fwd": b_fwd, "bwd": b_bwd},
+                     "fwd_achieved": b_fwd * w.B / (ms_fwd * 1e-3) / 1e9,
+                     "bwd_achieved": b_bwd * w.B / (ms_bwd * 1e-3) / 1e9},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, x, theta, dy)

@@ -43,7 +43,6 @@ namespace hg {
 using u32x4 = uint32_t __attribute__((ext_vector_type(4)));  // one 16-byte record
 
 constexpr int kBinThreads = 512;       // threads of a count / scatter workgroup
-constexpr uint32_t kMaxBinTiles = 512; // count / scatter workgroups per launch
 constexpr int kScanThreads = 1024;     // = maximum bins per level
 #ifndef HG_ACC_THREADS
 #define HG_ACC_THREADS 512
@@ -58,10 +57,10 @@ constexpr int kAccUnroll = HG_ACC_UNROLL;
 #endif
 constexpr uint32_t kChunkLog2 = HG_CHUNK_LOG2;
 constexpr uint32_t kTargetRecordsPerAccWg = 16384;
-constexpr uint64_t kMaxBinLds = 15 * 1024;  // keeps a scatter workgroup within 64 KiB of LDS
+constexpr uint64_t kMaxBinLds = 7 * 1024;  // 3 such arrays + 40 KiB of staging keep a scatter workgroup within 64 KiB of LDS
 
 struct Workspace {
-  uint32_t* counts;     // [n_tiles][n_bins] counts, then exclusive prefix over tiles
+  uint32_t* counts;     // [n_tiles + 1][n_bins] counts, then exclusive prefix over tiles (last row: totals)
   uint32_t* bin_start;  // [n_bins] first record of the bin
   uint32_t* bin_total;  // [n_bins] records in the bin
   float* tile_max;      // [n_tiles] largest |dL/dy| seen by the workgroup
@@ -73,10 +72,7 @@ struct Workspace {
 
 static inline uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 
-static uint32_t tiles_for(uint32_t B) {
-  uint32_t t = (B + kBinThreads - 1) / kBinThreads;
-  return t < kMaxBinTiles ? t : kMaxBinTiles;
-}
+static uint32_t tiles_for(uint32_t B) { return (B + kBinThreads - 1) / kBinThreads; }  // one workgroup each
 
 static uint64_t carve(const hashgrid* h, uint32_t B, uint8_t* base, Workspace* ws) {
   const uint32_t nt = tiles_for(B), nb = h->bp.bin_base[h->lv.L];
@@ -86,7 +82,7 @@ static uint64_t carve(const hashgrid* h, uint32_t B, uint8_t* base, Workspace* w
     off = align_up(off + bytes, 256);
     return o;
   };
-  const uint64_t o_counts = take((uint64_t)nt * nb * 4), o_start = take((uint64_t)nb * 4),
+  const uint64_t o_counts = take((uint64_t)(nt + 1) * nb * 4), o_start = take((uint64_t)nb * 4),
                  o_total = take((uint64_t)nb * 4), o_max = take((uint64_t)nt * 4), o_cmax = take(4),
                  o_rec = take((uint64_t)B * h->lv.L * h->bp.rec_per_point * 16);
   if (ws) {
@@ -229,19 +225,33 @@ __device__ __forceinline__ void load_x(const float* __restrict__ x, uint32_t b, 
   for (int i = 0; i < D; ++i) xp[i] = x[(uint64_t)b * D + i];
 }
 
+// Workgroup -> tile of points.  Workgroup i runs on XCD i mod 8 (each XCD has its
+// own L2), so consecutive tiles are given to consecutive workgroups of one XCD:
+// the runs two neighbouring tiles write into a bin are adjacent in memory, and
+// the cache line they share is completed inside one L2 instead of being written
+// back half-filled twice.  Returns n_tiles or more for surplus workgroups.
+__device__ __forceinline__ uint32_t tile_of_workgroup(uint32_t wg, uint32_t n_tiles) {
+  const uint32_t per_xcd = (n_tiles + 7u) / 8u;
+  const uint32_t j = wg >> 3;
+  return j < per_xcd ? (wg & 7u) * per_xcd + j : n_tiles;
+}
+
 // count: records per (workgroup, bin) and the workgroup's largest |dL/dy|.
 template <int D, typename IT>
 __global__ __launch_bounds__(kBinThreads) void bin_count(const LevelTable lv, const BinPlan bp, const bool smooth,
                                                          const uint32_t B, const float* __restrict__ x,
                                                          const IT* __restrict__ dy, uint32_t* __restrict__ counts,
-                                                         float* __restrict__ tile_max, const uint32_t n_bins) {
+                                                         float* __restrict__ tile_max, const uint32_t n_bins,
+                                                         const uint32_t n_tiles) {
   extern __shared__ uint32_t hist[];
   __shared__ float wave_max[kBinThreads / 64];
+  const uint32_t tile = tile_of_workgroup(blockIdx.x, n_tiles);
+  if (tile >= n_tiles) return;  // uniform: a surplus workgroup of the rounded-up grid
   for (uint32_t i = threadIdx.x; i < n_bins; i += kBinThreads) hist[i] = 0;
   __syncthreads();
   float m = 0.0f;
-  for (uint64_t b64 = (uint64_t)blockIdx.x * kBinThreads + threadIdx.x; b64 < B;
-       b64 += (uint64_t)gridDim.x * kBinThreads) {
+  const uint64_t b64 = (uint64_t)tile * kBinThreads + threadIdx.x;
+  if (b64 < B) {
     const uint32_t b = (uint32_t)b64;
     float xp[D];
     load_x<D>(x, b, xp);
@@ -266,11 +276,11 @@ __global__ __launch_bounds__(kBinThreads) void bin_count(const LevelTable lv, co
   }
   if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
   __syncthreads();
-  for (uint32_t i = threadIdx.x; i < n_bins; i += kBinThreads) counts[(uint64_t)blockIdx.x * n_bins + i] = hist[i];
+  for (uint32_t i = threadIdx.x; i < n_bins; i += kBinThreads) counts[(uint64_t)tile * n_bins + i] = hist[i];
   if (threadIdx.x == 0) {
     float t = wave_max[0];
     for (int i = 1; i < kBinThreads / 64; ++i) t = (wave_max[i] > t || wave_max[i] != wave_max[i]) ? wave_max[i] : t;
-    tile_max[blockIdx.x] = t;
+    tile_max[tile] = t;
   }
 }
 
@@ -362,7 +372,10 @@ __global__ __launch_bounds__(kScanThreads) void bin_scan(const uint32_t n_tiles,
       pre += q < seg ? v : 0u;
       total += v;
     }
-    if (seg == 0) bin_total[gb] = total;
+    if (seg == 0) {
+      bin_total[gb] = total;
+      col[(uint64_t)n_tiles * n_bins] = total;  // closes the prefix: count of tile t = row t+1 - row t
+    }
     uint32_t run = pre;
     uint32_t t = t0;
     for (; t + 8 <= t1; t += 8) {
@@ -385,11 +398,15 @@ __global__ __launch_bounds__(kScanThreads) void bin_scan(const uint32_t n_tiles,
 
 // scatter: writes every record to its slot.  A bin's first record is the sum of
 // the record counts of all bins before it (every level holds exactly
-// B * rec_per_point records, so this is also level-major).  Level by level the
-// workgroup sorts the records of its 512 points by bin in LDS and copies them
-// out bin after bin, so that what reaches memory is runs of whole records that
+// B * rec_per_point records, so this is also level-major); inside a bin the
+// workgroups (one per tile of 512 points) follow each other.  Level by level the
+// workgroup sorts the records of its points by bin in LDS and copies them out
+// bin after bin, so that what reaches memory is runs of whole records that
 // mostly fill whole cache lines; 16-byte stores scattered over a thousand open
 // runs leave the L2 as partial lines and cost several times the bytes.
+// LDS (dynamic): first[n_bins] global slot of this tile's run in each bin,
+// local[n_bins + 1] exclusive prefix of this tile's counts, fill[n_bins] records
+// placed so far.
 template <int D, typename IT>
 __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, const BinPlan bp, const bool smooth,
                                                            const uint32_t B, const float* __restrict__ x,
@@ -398,76 +415,76 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, 
                                                            const uint32_t* __restrict__ bin_total,
                                                            uint32_t* __restrict__ bin_start,
                                                            u32x4* __restrict__ records, const uint32_t n_bins,
-                                                           const uint32_t n_records) {
+                                                           const uint32_t n_records, const uint32_t n_tiles) {
   constexpr uint32_t R = 1u << (D - 1);
-  extern __shared__ uint32_t cursor[];               // [n_bins] next free slot of the bin for this workgroup
-  __shared__ uint32_t cnt[kScanThreads];             // records per bin of the current level and sub-tile
-  __shared__ uint32_t off[kScanThreads];             // their exclusive prefix
+  extern __shared__ uint32_t lds_u32[];
+  uint32_t* first = lds_u32;
+  uint32_t* local = lds_u32 + n_bins;
+  uint32_t* fill = lds_u32 + 2 * n_bins + 1;
   __shared__ uint32_t scan_tmp[kBinThreads / 64];
   __shared__ u32x4 staging[R * kBinThreads];
   __shared__ uint32_t dstv[R * kBinThreads];
 
-  for (uint32_t i = threadIdx.x; i < n_bins; i += kBinThreads) cursor[i] = bin_total[i];
-  __syncthreads();
-  block_exclusive_scan<kBinThreads>(cursor, n_bins, scan_tmp);
+  const uint32_t tile = tile_of_workgroup(blockIdx.x, n_tiles);
+  if (tile >= n_tiles) return;  // uniform: a surplus workgroup of the rounded-up grid
+  const uint32_t* row0 = counts + (uint64_t)tile * n_bins;  // prefix over tiles before this one
+  const uint32_t* row1 = row0 + n_bins;                           // ... including this one
   for (uint32_t i = threadIdx.x; i < n_bins; i += kBinThreads) {
-    const uint32_t first = cursor[i];
-    if (blockIdx.x == 0) bin_start[i] = first;
-    cursor[i] = first + counts[(uint64_t)blockIdx.x * n_bins + i];
+    first[i] = bin_total[i];
+    local[i] = row1[i] - row0[i];
+    fill[i] = 0;
+  }
+  if (threadIdx.x == 0) local[n_bins] = 0;
+  __syncthreads();
+  block_exclusive_scan<kBinThreads>(first, n_bins, scan_tmp);
+  block_exclusive_scan<kBinThreads>(local, n_bins + 1, scan_tmp);
+  for (uint32_t i = threadIdx.x; i < n_bins; i += kBinThreads) {
+    const uint32_t f = first[i];
+    if (tile == 0) bin_start[i] = f;
+    first[i] = f + row0[i];
   }
   __syncthreads();
 
-  for (uint64_t base = (uint64_t)blockIdx.x * kBinThreads; base < B; base += (uint64_t)gridDim.x * kBinThreads) {
-    const uint64_t b64 = base + threadIdx.x;
-    const bool valid = b64 < B;
-    const uint32_t b = valid ? (uint32_t)b64 : 0u;
-    float xp[D];
-    load_x<D>(x, b, xp);
-    const Vec<IT, 2>* row = reinterpret_cast<const Vec<IT, 2>*>(dy + (uint64_t)b * lv.L * 2);
-    for (uint32_t l = 0; l < lv.L; ++l) {
-      const uint32_t gb0 = bp.bin_base[l], nb = bp.bin_base[l + 1] - gb0;
-      for (uint32_t i = threadIdx.x; i < nb; i += kBinThreads) cnt[i] = 0;
-      __syncthreads();
+  const uint64_t b64 = (uint64_t)tile * kBinThreads + threadIdx.x;
+  const bool valid = b64 < B;
+  const uint32_t b = valid ? (uint32_t)b64 : 0u;
+  float xp[D];
+  load_x<D>(x, b, xp);
+  const Vec<IT, 2>* row = reinterpret_cast<const Vec<IT, 2>*>(dy + (uint64_t)b * lv.L * 2);
+  Vec<IT, 2> g_next = row[0];
+  for (uint32_t l = 0; l < lv.L; ++l) {
+    const uint32_t gb0 = bp.bin_base[l], gb1 = bp.bin_base[l + 1];
+    const uint32_t level_first = local[gb0], emitted = local[gb1] - level_first;  // <= R * kBinThreads
+    const Vec<IT, 2> g = g_next;
+    if (l + 1 < lv.L) g_next = row[l + 1];  // in flight while this level is sorted
+    if (valid) {
       Rows<D> rw;
-      uint32_t rank[R];
-      float g0 = 0.0f, g1 = 0.0f;
-      if (valid) {
-        rows_of<D, false>(lv, bp, l, smooth, xp, rw);
-        const Vec<IT, 2> g = row[l];
-        g0 = (float)g.v[0];
-        g1 = (float)g.v[1];
+      rows_of<D, false>(lv, bp, l, smooth, xp, rw);
+      const float g0 = (float)g.v[0], g1 = (float)g.v[1];
 #pragma unroll
-        for (uint32_t r = 0; r < R; ++r)
-          rank[r] = __hip_atomic_fetch_add(&cnt[rw.bin[r] - gb0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-      }
-      __syncthreads();
-      for (uint32_t i = threadIdx.x; i < nb; i += kBinThreads) off[i] = cnt[i];
-      __syncthreads();
-      block_exclusive_scan<kBinThreads>(off, nb, scan_tmp);
-      if (valid) {
-#pragma unroll
-        for (uint32_t r = 0; r < R; ++r) {
-          const uint32_t pos = off[rw.bin[r] - gb0] + rank[r];  // < R * kBinThreads
+      for (uint32_t r = 0; r < R; ++r) {
+        const uint32_t gb = rw.bin[r];
+        const uint32_t rank = __hip_atomic_fetch_add(&fill[gb], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        const uint32_t pos = local[gb] - level_first + rank;
+        if (pos < R * kBinThreads) {  // holds when the count pass saw the same x
           u32x4 rec;
           rec.x = rw.pack[r];
           rec.y = __float_as_uint(rw.wf0);
           rec.z = __float_as_uint(rw.wrow[r] * g0);
           rec.w = __float_as_uint(rw.wrow[r] * g1);
           staging[pos] = rec;
-          dstv[pos] = cursor[rw.bin[r]] + rank[r];
+          dstv[pos] = first[gb] + rank;
         }
       }
-      __syncthreads();
-      const uint32_t emitted = off[nb - 1] + cnt[nb - 1];
-      for (uint32_t j = threadIdx.x; j < emitted; j += kBinThreads) {
-        const uint32_t d = dstv[j];
-        // the count pass saw the same inputs, so d < n_records; the check only keeps a
-        // caller who changed x in between from writing out of bounds
-        if (d < n_records) records[d] = staging[j];
-      }
-      __syncthreads();
-      for (uint32_t i = threadIdx.x; i < nb; i += kBinThreads) cursor[gb0 + i] += cnt[i];
     }
+    __syncthreads();
+    for (uint32_t j = threadIdx.x; j < emitted && j < R * kBinThreads; j += kBinThreads) {
+      const uint32_t d = dstv[j];
+      // the count pass saw the same inputs, so d < n_records; the check only keeps a
+      // caller who changed x in between from writing out of bounds
+      if (d < n_records) records[d] = staging[j];
+    }
+    __syncthreads();
   }
 }
 
@@ -614,18 +631,19 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
   plan_slices(bp, h->lv, B);
   const bool smooth = h->cfg.interp == HG_INTERP_SMOOTHSTEP;
   const uint32_t n_records = B * h->lv.L * bp.rec_per_point;
-  const size_t lds_bins = (size_t)ws.n_bins * 4;
-  hipLaunchKernelGGL((bin_count<D, IT>), dim3(ws.n_tiles), dim3(kBinThreads), lds_bins, s, h->lv, bp, smooth, B, x,
-                     static_cast<const IT*>(dy), ws.counts, ws.tile_max, ws.n_bins);
+  const size_t lds_bins = (size_t)ws.n_bins * 4, lds_scatter = (size_t)(3 * ws.n_bins + 1) * 4;
+  const uint32_t tile_wgs = (ws.n_tiles + 7u) / 8u * 8u;  // see tile_of_workgroup
+  hipLaunchKernelGGL((bin_count<D, IT>), dim3(tile_wgs), dim3(kBinThreads), lds_bins, s, h->lv, bp, smooth, B, x,
+                     static_cast<const IT*>(dy), ws.counts, ws.tile_max, ws.n_bins, ws.n_tiles);
   hipLaunchKernelGGL(bin_scan, dim3((ws.n_bins + kScanBins - 1) / kScanBins), dim3(kScanThreads), 0, s, ws.n_tiles,
                      ws.n_bins, ws.counts, ws.bin_total, ws.tile_max, ws.call_max);
   // 64 KiB of dynamic LDS plus a few static bytes: above the default limit
   static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_accumulate),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, 16 << kChunkLog2);
   if (lds_ok != hipSuccess) return HG_ERR_DEVICE;
-  hipLaunchKernelGGL((bin_scatter<D, IT>), dim3(ws.n_tiles), dim3(kBinThreads), lds_bins, s, h->lv, bp, smooth, B, x,
-                     static_cast<const IT*>(dy), ws.counts, ws.bin_total, ws.bin_start,
-                     reinterpret_cast<u32x4*>(ws.records), ws.n_bins, n_records);
+  hipLaunchKernelGGL((bin_scatter<D, IT>), dim3(tile_wgs), dim3(kBinThreads), lds_scatter, s, h->lv, bp, smooth, B,
+                     x, static_cast<const IT*>(dy), ws.counts, ws.bin_total, ws.bin_start,
+                     reinterpret_cast<u32x4*>(ws.records), ws.n_bins, n_records, ws.n_tiles);
   hipLaunchKernelGGL(bin_accumulate, dim3(bp.wg_base[h->lv.L]), dim3(kAccThreads), (size_t)16 << bp.chunk_log2, s,
                      h->lv, bp, smooth, B, ws.bin_start, ws.bin_total, ws.call_max, ws.records, grad);
   return hipGetLastError() == hipSuccess ? HG_OK : HG_ERR_DEVICE;
