@@ -42,7 +42,10 @@ namespace hg {
 
 using u32x4 = uint32_t __attribute__((ext_vector_type(4)));  // one 16-byte record
 
-constexpr int kBinThreads = 512;       // threads of a count / scatter workgroup
+#ifndef HG_BIN_THREADS
+#define HG_BIN_THREADS 512
+#endif
+constexpr int kBinThreads = HG_BIN_THREADS;  // threads (= points) of a count / scatter workgroup
 constexpr int kScanThreads = 1024;     // = maximum bins per level
 #ifndef HG_ACC_THREADS
 #define HG_ACC_THREADS 512
@@ -611,13 +614,14 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
     const uint32_t e = threadIdx.x + j * kAccThreads;
     if (e >= n_e) continue;
     const long long a0 = (long long)acc0[e], a1 = (long long)acc1[e];
-    if ((a0 | a1) == 0) continue;  // untouched entries stay bit-for-bit as they were
-    const float v0 = (float)ldexp((double)a0, -S), v1 = (float)ldexp((double)a1, -S);
+    // an entry no record reached gets -0.0f added, which leaves every float (either zero,
+    // NaNs included) exactly as it was; storing it anyway keeps the stores of a wave contiguous
+    const float v0 = a0 ? (float)ldexp((double)a0, -S) : -0.0f, v1 = a1 ? (float)ldexp((double)a1, -S) : -0.0f;
     if (n_sl == 1) {
       cur[j].x += v0;
       cur[j].y += v1;
       reinterpret_cast<float2*>(gl)[e] = cur[j];
-    } else {
+    } else if ((a0 | a1) != 0) {
       __hip_atomic_fetch_add(gl + 2 * e, v0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       __hip_atomic_fetch_add(gl + 2 * e + 1, v1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
@@ -641,6 +645,15 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
   static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_accumulate),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, 16 << kChunkLog2);
   if (lds_ok != hipSuccess) return HG_ERR_DEVICE;
+  {  // static staging plus the dynamic per-bin arrays can exceed the default 64 KiB
+    static size_t allowed = 0;
+    if (lds_scatter > allowed) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(bin_scatter<D, IT>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_scatter) != hipSuccess)
+        return HG_ERR_DEVICE;
+      allowed = lds_scatter;
+    }
+  }
   hipLaunchKernelGGL((bin_scatter<D, IT>), dim3(tile_wgs), dim3(kBinThreads), lds_scatter, s, h->lv, bp, smooth, B,
                      x, static_cast<const IT*>(dy), ws.counts, ws.bin_total, ws.bin_start,
                      reinterpret_cast<u32x4*>(ws.records), ws.n_bins, n_records, ws.n_tiles);

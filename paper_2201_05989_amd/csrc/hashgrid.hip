@@ -114,7 +114,32 @@ __global__ __launch_bounds__(kBlock) void fwd_general(const LevelTable lv, const
 // keeps the 16 waves of a workgroup on the same slice, which holds the L2 hit
 // rate at that of the level-major grid.
 constexpr int kPmBlock = 1024;
-template <int D, typename PT, typename IT>
+
+// Entry indices of the 2^D corners for a level known (uniformly) to be 1:1 or
+// hashed, T a power of two on the hashed side: no per-lane selects between the
+// two index maps and no integer division.
+template <int D, bool DENSE>
+__device__ __forceinline__ void corner_indices_uniform(const uint32_t (&c0)[D], uint32_t verts, uint32_t mask,
+                                                       uint32_t (&idx)[1 << D]) {
+  uint32_t t[D][2];
+  uint32_t stride = 1;
+#pragma unroll
+  for (int i = 0; i < D; ++i) {
+    const uint32_t mul = DENSE ? stride : prime(i);
+    t[i][0] = c0[i] * mul;
+    t[i][1] = t[i][0] + mul;
+    stride *= verts;
+  }
+#pragma unroll
+  for (uint32_t m = 0; m < (1u << D); ++m) {
+    uint32_t v = t[0][m & 1u];
+#pragma unroll
+    for (int i = 1; i < D; ++i) v = DENSE ? v + t[i][(m >> i) & 1u] : v ^ t[i][(m >> i) & 1u];
+    idx[m] = DENSE ? v : v & mask;
+  }
+}
+
+template <int D, typename PT, typename IT, bool POW2>
 __global__ __launch_bounds__(kPmBlock) void fwd_point_major(const LevelTable lv, const bool smooth, const uint32_t B,
                                                             const float* __restrict__ x,
                                                             const PT* __restrict__ theta, IT* __restrict__ y) {
@@ -125,22 +150,51 @@ __global__ __launch_bounds__(kPmBlock) void fwd_point_major(const LevelTable lv,
   float xp[D];
   load_point<D>(x, b, xp);
   Vec<IT, 2 * G>* yrow = reinterpret_cast<Vec<IT, 2 * G>*>(y + (uint64_t)b * lv.L * 2);
+  const float shift = smooth ? 0.5f : 0.0f;
   for (uint32_t l0 = 0; l0 < lv.L; l0 += G) {
     Vec<IT, 2 * G> out;
 #pragma unroll
     for (int j = 0; j < G; ++j) {
       const uint32_t l = l0 + j;
-      Corners<D> cn;
-      corners_of<D, false>(lv, l, smooth, xp, cn, nullptr);
+      const float Nf = (float)lv.N[l];
+      const float cmaxf = smooth ? Nf : Nf - 1.0f;
+      uint32_t c0[D], idx[1 << D];
+      float w[D], u[D];
+#pragma unroll
+      for (int i = 0; i < D; ++i) {
+        float wf;
+        split(xp[i], Nf, shift, cmaxf, c0[i], wf);
+        w[i] = smooth ? smoothstep(wf) : wf;
+        u[i] = smooth ? smoothstep(1.0f - wf) : 1.0f - wf;
+      }
+      if ((lv.dense_mask >> l) & 1u) {  // uniform
+        corner_indices_uniform<D, true>(c0, lv.verts[l], 0u, idx);
+      } else if (POW2) {
+        corner_indices_uniform<D, false>(c0, 0u, lv.T - 1u, idx);
+      } else {
+        const CornerTerms<D> ct = corner_terms<D>(c0, false, 0u);
+#pragma unroll
+        for (uint32_t m = 0; m < (1u << D); ++m) idx[m] = corner_index<D>(ct, m, false, lv.T, false);
+      }
       const Vec<PT, 2>* tab = reinterpret_cast<const Vec<PT, 2>*>(theta) + lv.offset[l];
       Vec<PT, 2> e[1 << D];
 #pragma unroll
-      for (uint32_t m = 0; m < (1u << D); ++m) e[m] = tab[cn.idx[m]];
+      for (uint32_t m = 0; m < (1u << D); ++m) e[m] = tab[idx[m]];
+      // weights of the corners along dimensions 1.., then dimension 0 last: 2^(D-1) + 2^D products
+      float wr[1 << (D - 1)];
+#pragma unroll
+      for (uint32_t r = 0; r < (1u << (D - 1)); ++r) {
+        float p = 1.0f;
+#pragma unroll
+        for (int i = 1; i < D; ++i) p *= ((r >> (i - 1)) & 1u) ? w[i] : u[i];
+        wr[r] = p;
+      }
       float a0 = 0.0f, a1 = 0.0f;
 #pragma unroll
       for (uint32_t m = 0; m < (1u << D); ++m) {
-        a0 = fmaf(cn.wt[m], (float)e[m].v[0], a0);
-        a1 = fmaf(cn.wt[m], (float)e[m].v[1], a1);
+        const float wt = wr[m >> 1] * ((m & 1u) ? w[0] : u[0]);
+        a0 = fmaf(wt, (float)e[m].v[0], a0);
+        a1 = fmaf(wt, (float)e[m].v[1], a1);
       }
       out.v[2 * j] = (IT)a0;
       out.v[2 * j + 1] = (IT)a1;
@@ -294,9 +348,14 @@ static hg_status launch_fwd(const hashgrid* h, uint32_t B, const float* x, const
   if constexpr (F == 2) {
     constexpr uint32_t G = 16 / (2 * sizeof(IT));
     if (h->lv.L % G == 0 && !misaligned(y, 16)) {
-      hipLaunchKernelGGL((fwd_point_major<D, PT, IT>), dim3((B + kPmBlock - 1) / kPmBlock), dim3(kPmBlock), 0, s,
-                         h->lv, h->cfg.interp == HG_INTERP_SMOOTHSTEP, B, x, static_cast<const PT*>(params),
-                         static_cast<IT*>(y));
+      const dim3 grid((B + kPmBlock - 1) / kPmBlock);
+      const bool smooth = h->cfg.interp == HG_INTERP_SMOOTHSTEP;
+      if (h->lv.T_is_pow2)
+        hipLaunchKernelGGL((fwd_point_major<D, PT, IT, true>), grid, dim3(kPmBlock), 0, s, h->lv, smooth, B, x,
+                           static_cast<const PT*>(params), static_cast<IT*>(y));
+      else
+        hipLaunchKernelGGL((fwd_point_major<D, PT, IT, false>), grid, dim3(kPmBlock), 0, s, h->lv, smooth, B, x,
+                           static_cast<const PT*>(params), static_cast<IT*>(y));
       return launched();
     }
   }
