@@ -48,11 +48,11 @@ using u32x4 = uint32_t __attribute__((ext_vector_type(4)));  // one 16-byte reco
 constexpr int kBinThreads = HG_BIN_THREADS;  // threads (= points) of a count / scatter workgroup
 constexpr int kScanThreads = 1024;     // = maximum bins per level
 #ifndef HG_ACC_THREADS
-#define HG_ACC_THREADS 512
+#define HG_ACC_THREADS 1024
 #endif
 constexpr int kAccThreads = HG_ACC_THREADS;
 #ifndef HG_ACC_UNROLL
-#define HG_ACC_UNROLL 8
+#define HG_ACC_UNROLL 4
 #endif
 constexpr int kAccUnroll = HG_ACC_UNROLL;
 #ifndef HG_CHUNK_LOG2
@@ -60,13 +60,14 @@ constexpr int kAccUnroll = HG_ACC_UNROLL;
 #endif
 constexpr uint32_t kChunkLog2 = HG_CHUNK_LOG2;
 constexpr uint32_t kTargetRecordsPerAccWg = 16384;
-constexpr uint64_t kMaxBinLds = 7 * 1024;  // 3 such arrays + 40 KiB of staging keep a scatter workgroup within 64 KiB of LDS
+constexpr uint32_t kMaxParts = 4;       // level parts of the count / scatter grids
+constexpr uint64_t kMaxBinLds = 7 * 1024;  // bound on 4 * (number of bins): per-part LDS arrays stay small
 
 struct Workspace {
   uint32_t* counts;     // [n_tiles + 1][n_bins] counts, then exclusive prefix over tiles (last row: totals)
   uint32_t* bin_start;  // [n_bins] first record of the bin
   uint32_t* bin_total;  // [n_bins] records in the bin
-  float* tile_max;      // [n_tiles] largest |dL/dy| seen by the workgroup
+  float* tile_max;      // [n_tiles * parts] largest |dL/dy| seen by each count workgroup
   float* call_max;      // [1] largest |dL/dy| of the call
   uint4* records;       // [B * L * rec_per_point]
   uint32_t n_tiles;
@@ -86,7 +87,7 @@ static uint64_t carve(const hashgrid* h, uint32_t B, uint8_t* base, Workspace* w
     return o;
   };
   const uint64_t o_counts = take((uint64_t)(nt + 1) * nb * 4), o_start = take((uint64_t)nb * 4),
-                 o_total = take((uint64_t)nb * 4), o_max = take((uint64_t)nt * 4), o_cmax = take(4),
+                 o_total = take((uint64_t)nb * 4), o_max = take((uint64_t)nt * kMaxParts * 4), o_cmax = take(4),
                  o_rec = take((uint64_t)B * h->lv.L * h->bp.rec_per_point * 16);
   if (ws) {
     ws->counts = reinterpret_cast<uint32_t*>(base + o_counts);
@@ -189,35 +190,46 @@ __device__ __forceinline__ void rows_of(const LevelTable& lv, const BinPlan& bp,
     u[i] = smooth ? smoothstep(1.0f - wf) : 1.0f - wf;
   }
   const uint32_t cl = bp.chunk_log2, cmask = (1u << cl) - 1u;
+  const uint32_t gb0 = bp.bin_base[l];
+  if (!COUNT_ONLY) {
 #pragma unroll
-  for (uint32_t r = 0; r < (1u << (D - 1)); ++r) {
-    uint32_t v[D];
-    float wr = 1.0f;
+    for (uint32_t r = 0; r < (1u << (D - 1)); ++r) {
+      float wr = 1.0f;
 #pragma unroll
-    for (int i = 1; i < D; ++i) {
-      const uint32_t bit = (r >> (i - 1)) & 1u;
-      v[i] = c0[i] + bit;
-      wr *= bit ? w[i] : u[i];
-    }
-    uint32_t bin, la, lb;
-    if (dense) {
-      uint32_t row = v[1];
-      if (D == 3) row += v[D - 1] * verts;
-      bin = row >> bp.row_shift[l];
-      la = c0[0] + (row - (bin << bp.row_shift[l])) * verts;
-      lb = la + 1u;
-    } else {
-      uint32_t rt = v[1] * prime(1);
-      if (D == 3) rt ^= v[D - 1] * prime(2);
-      const uint32_t ia = (c0[0] ^ rt) & (lv.T - 1u), ib = ((c0[0] + 1u) ^ rt) & (lv.T - 1u);
-      bin = ia >> cl;
-      la = ia & cmask;
-      lb = ib & cmask;
-    }
-    out.bin[r] = bp.bin_base[l] + bin;
-    if (!COUNT_ONLY) {
-      out.pack[r] = la | (lb << 16);
+      for (int i = 1; i < D; ++i) wr *= ((r >> (i - 1)) & 1u) ? w[i] : u[i];
       out.wrow[r] = wr;
+    }
+  }
+  // the level kind is uniform: a scalar branch, not per-lane selects between the two maps
+  if (dense) {
+    const uint32_t sh = bp.row_shift[l];
+#pragma unroll
+    for (uint32_t r = 0; r < (1u << (D - 1)); ++r) {
+      uint32_t row = c0[1] + (r & 1u);
+      if (D == 3) row += (c0[D - 1] + (r >> 1)) * verts;
+      const uint32_t bin = row >> sh;
+      out.bin[r] = gb0 + bin;
+      if (!COUNT_ONLY) {
+        const uint32_t la = c0[0] + (row - (bin << sh)) * verts;
+        out.pack[r] = la | ((la + 1u) << 16);
+      }
+    }
+  } else {
+    const uint32_t tmask = lv.T - 1u;
+    uint32_t t1[2], t2[2];
+    t1[0] = c0[1] * prime(1);
+    t1[1] = t1[0] + prime(1);
+    t2[0] = D == 3 ? c0[D - 1] * prime(2) : 0u;
+    t2[1] = t2[0] + prime(2);
+#pragma unroll
+    for (uint32_t r = 0; r < (1u << (D - 1)); ++r) {
+      const uint32_t rt = D == 3 ? t1[r & 1u] ^ t2[r >> 1] : t1[r & 1u];
+      const uint32_t ia = (c0[0] ^ rt) & tmask;
+      out.bin[r] = gb0 + (ia >> cl);
+      if (!COUNT_ONLY) {
+        const uint32_t ib = ((c0[0] + 1u) ^ rt) & tmask;
+        out.pack[r] = (ia & cmask) | ((ib & cmask) << 16);
+      }
     }
   }
 }
@@ -239,38 +251,70 @@ __device__ __forceinline__ uint32_t tile_of_workgroup(uint32_t wg, uint32_t n_ti
   return j < per_xcd ? (wg & 7u) * per_xcd + j : n_tiles;
 }
 
-// count: records per (workgroup, bin) and the workgroup's largest |dL/dy|.
+// Levels are split into gridDim.y parts; a count / scatter workgroup serves one
+// tile of points and one part.  More, lighter workgroups per CU hide the latency
+// of the LDS atomics and of the per-level barriers.
+__device__ __forceinline__ void part_levels(uint32_t L, uint32_t& l0, uint32_t& l1) {
+  l0 = blockIdx.y * L / gridDim.y;
+  l1 = (blockIdx.y + 1) * L / gridDim.y;
+}
+
+// count: records per (tile, bin) and the workgroup's largest |dL/dy|.
 template <int D, typename IT>
 __global__ __launch_bounds__(kBinThreads) void bin_count(const LevelTable lv, const BinPlan bp, const bool smooth,
                                                          const uint32_t B, const float* __restrict__ x,
                                                          const IT* __restrict__ dy, uint32_t* __restrict__ counts,
                                                          float* __restrict__ tile_max, const uint32_t n_bins,
                                                          const uint32_t n_tiles) {
-  extern __shared__ uint32_t hist[];
+  extern __shared__ uint32_t hist[];  // bins of this part's levels
   __shared__ float wave_max[kBinThreads / 64];
   const uint32_t tile = tile_of_workgroup(blockIdx.x, n_tiles);
   if (tile >= n_tiles) return;  // uniform: a surplus workgroup of the rounded-up grid
-  for (uint32_t i = threadIdx.x; i < n_bins; i += kBinThreads) hist[i] = 0;
+  uint32_t l0, l1;
+  part_levels(lv.L, l0, l1);
+  const uint32_t gb_a = bp.bin_base[l0], nbp = bp.bin_base[l1] - gb_a;
+  for (uint32_t i = threadIdx.x; i < nbp; i += kBinThreads) hist[i] = 0;
   __syncthreads();
-  float m = 0.0f;
   const uint64_t b64 = (uint64_t)tile * kBinThreads + threadIdx.x;
   if (b64 < B) {
     const uint32_t b = (uint32_t)b64;
     float xp[D];
     load_x<D>(x, b, xp);
-    const IT* row = dy + (uint64_t)b * lv.L * 2;
-    for (uint32_t l = 0; l < lv.L; ++l) {
+    for (uint32_t l = l0; l < l1; ++l) {
       Rows<D> rw;
       rows_of<D, true>(lv, bp, l, smooth, xp, rw);
 #pragma unroll
       for (uint32_t r = 0; r < (1u << (D - 1)); ++r)
-        __hip_atomic_fetch_add(&hist[rw.bin[r]], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-      const Vec<IT, 2> g = reinterpret_cast<const Vec<IT, 2>*>(row)[l];
-      // NaN must win the maximum so that the accumulate kernel sees it
-      const float a0 = fabsf((float)g.v[0]), a1 = fabsf((float)g.v[1]);
-      m = (a0 > m || a0 != a0) ? a0 : m;
-      m = (a1 > m || a1 != a1) ? a1 : m;
+        __hip_atomic_fetch_add(&hist[rw.bin[r] - gb_a], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
+  }
+  // largest |dL/dy| over this workgroup's share of the tile's rows, read as one flat,
+  // coalesced range (a 4-byte read per level with the stride of a row costs the L1 a line
+  // per two lanes).  NaN must win the maximum so that the accumulate kernel sees it.
+  float m = 0.0f;
+  {
+    const uint64_t row_elems = (uint64_t)lv.L * 2;
+    const uint64_t tile_first = (uint64_t)tile * kBinThreads * row_elems;
+    const uint64_t tile_end = ((uint64_t)tile * kBinThreads + kBinThreads < B ? (uint64_t)tile * kBinThreads + kBinThreads : B) * row_elems;
+    const uint64_t share = ((tile_end - tile_first) + gridDim.y - 1) / gridDim.y;
+    const uint64_t e0 = tile_first + blockIdx.y * share;
+    const uint64_t e1 = e0 + share < tile_end ? e0 + share : tile_end;
+    constexpr uint32_t V = 16 / sizeof(IT);  // elements per 16-byte load
+    auto take = [&](IT v) {
+      const float a = fabsf((float)v);
+      m = (a > m || a != a) ? a : m;
+    };
+    // scalar head up to 16-byte alignment, vector body, scalar tail
+    uint64_t head = e0;
+    while (head < e1 && (reinterpret_cast<uintptr_t>(dy + head) & 15)) ++head;
+    const uint64_t body = head + (e1 - head) / V * V;
+    for (uint64_t e = e0 + threadIdx.x; e < head; e += kBinThreads) take(dy[e]);
+    for (uint64_t e = head + (uint64_t)threadIdx.x * V; e < body; e += (uint64_t)kBinThreads * V) {
+      const Vec<IT, V> v = *reinterpret_cast<const Vec<IT, V>*>(dy + e);
+#pragma unroll
+      for (uint32_t q = 0; q < V; ++q) take(v.v[q]);
+    }
+    for (uint64_t e = body + threadIdx.x; e < e1; e += kBinThreads) take(dy[e]);
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
@@ -279,11 +323,11 @@ __global__ __launch_bounds__(kBinThreads) void bin_count(const LevelTable lv, co
   }
   if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
   __syncthreads();
-  for (uint32_t i = threadIdx.x; i < n_bins; i += kBinThreads) counts[(uint64_t)tile * n_bins + i] = hist[i];
+  for (uint32_t i = threadIdx.x; i < nbp; i += kBinThreads) counts[(uint64_t)tile * n_bins + gb_a + i] = hist[i];
   if (threadIdx.x == 0) {
     float t = wave_max[0];
     for (int i = 1; i < kBinThreads / 64; ++i) t = (wave_max[i] > t || wave_max[i] != wave_max[i]) ? wave_max[i] : t;
-    tile_max[tile] = t;
+    tile_max[tile * gridDim.y + blockIdx.y] = t;
   }
 }
 
@@ -319,7 +363,8 @@ __device__ __forceinline__ void block_exclusive_scan(uint32_t* a, uint32_t n, ui
 // counts[tile][bin] into the exclusive prefix over tiles; it also writes the
 // bin's record count.  Workgroup 0 reduces the per-tile maxima of |dL/dy|.
 constexpr int kScanBins = 16;
-__global__ __launch_bounds__(kScanThreads) void bin_scan(const uint32_t n_tiles, const uint32_t n_bins,
+__global__ __launch_bounds__(kScanThreads) void bin_scan(const uint32_t n_tiles, const uint32_t n_max,
+                                                         const uint32_t n_bins,
                                                          uint32_t* __restrict__ counts,
                                                          uint32_t* __restrict__ bin_total,
                                                          const float* __restrict__ tile_max,
@@ -328,7 +373,7 @@ __global__ __launch_bounds__(kScanThreads) void bin_scan(const uint32_t n_tiles,
   __shared__ float red[kScanThreads / 64];
   if (blockIdx.x == 0) {  // largest |dL/dy| of the call; NaN wins
     float m = 0.0f;
-    for (uint32_t i = threadIdx.x; i < n_tiles; i += kScanThreads) {
+    for (uint32_t i = threadIdx.x; i < n_max; i += kScanThreads) {
       const float t = tile_max[i];
       m = (t > m || t != t) ? t : m;
     }
@@ -402,14 +447,15 @@ __global__ __launch_bounds__(kScanThreads) void bin_scan(const uint32_t n_tiles,
 // scatter: writes every record to its slot.  A bin's first record is the sum of
 // the record counts of all bins before it (every level holds exactly
 // B * rec_per_point records, so this is also level-major); inside a bin the
-// workgroups (one per tile of 512 points) follow each other.  Level by level the
-// workgroup sorts the records of its points by bin in LDS and copies them out
-// bin after bin, so that what reaches memory is runs of whole records that
-// mostly fill whole cache lines; 16-byte stores scattered over a thousand open
-// runs leave the L2 as partial lines and cost several times the bytes.
-// LDS (dynamic): first[n_bins] global slot of this tile's run in each bin,
-// local[n_bins + 1] exclusive prefix of this tile's counts, fill[n_bins] records
-// placed so far.
+// tiles of 512 points follow each other.  Level by level the workgroup sorts the
+// records of its points by bin in LDS and copies them out bin after bin, so that
+// what reaches memory is runs of whole records that mostly fill whole cache
+// lines; 16-byte stores scattered over a thousand open runs leave the L2 as
+// partial lines and cost several times the bytes.
+// LDS (dynamic), indexed by bin relative to the first bin of this part's levels:
+// local[nbp + 1] exclusive prefix of this tile's counts (where a bin's records
+// sit in the tile's sorted order), cur[nbp] the same, advanced as records are
+// placed, delta[nbp] = global slot minus tile-local position.
 template <int D, typename IT>
 __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, const BinPlan bp, const bool smooth,
                                                            const uint32_t B, const float* __restrict__ x,
@@ -421,30 +467,43 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, 
                                                            const uint32_t n_records, const uint32_t n_tiles) {
   constexpr uint32_t R = 1u << (D - 1);
   extern __shared__ uint32_t lds_u32[];
-  uint32_t* first = lds_u32;
-  uint32_t* local = lds_u32 + n_bins;
-  uint32_t* fill = lds_u32 + 2 * n_bins + 1;
   __shared__ uint32_t scan_tmp[kBinThreads / 64];
   __shared__ u32x4 staging[R * kBinThreads];
-  __shared__ uint32_t dstv[R * kBinThreads];
+  __shared__ uint16_t binv[R * kBinThreads];  // part-relative bin of each staged record
 
   const uint32_t tile = tile_of_workgroup(blockIdx.x, n_tiles);
   if (tile >= n_tiles) return;  // uniform: a surplus workgroup of the rounded-up grid
-  const uint32_t* row0 = counts + (uint64_t)tile * n_bins;  // prefix over tiles before this one
-  const uint32_t* row1 = row0 + n_bins;                           // ... including this one
-  for (uint32_t i = threadIdx.x; i < n_bins; i += kBinThreads) {
-    first[i] = bin_total[i];
+  uint32_t l0, l1;
+  part_levels(lv.L, l0, l1);
+  const uint32_t gb_a = bp.bin_base[l0], nbp = bp.bin_base[l1] - gb_a;
+  uint32_t* delta = lds_u32;
+  uint32_t* local = lds_u32 + nbp;
+  uint32_t* cur = lds_u32 + 2 * nbp + 1;
+
+  // records of all bins before this part
+  uint32_t before = 0;
+  for (uint32_t i = threadIdx.x; i < gb_a; i += kBinThreads) before += bin_total[i];
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) before += __shfl_xor(before, o);
+  if ((threadIdx.x & 63) == 0) scan_tmp[threadIdx.x >> 6] = before;
+  const uint32_t* row0 = counts + (uint64_t)tile * n_bins + gb_a;  // prefix over tiles before this one
+  const uint32_t* row1 = row0 + n_bins;                             // ... including this one
+  for (uint32_t i = threadIdx.x; i < nbp; i += kBinThreads) {
+    delta[i] = bin_total[gb_a + i];
     local[i] = row1[i] - row0[i];
-    fill[i] = 0;
   }
-  if (threadIdx.x == 0) local[n_bins] = 0;
+  if (threadIdx.x == 0) local[nbp] = 0;
   __syncthreads();
-  block_exclusive_scan<kBinThreads>(first, n_bins, scan_tmp);
-  block_exclusive_scan<kBinThreads>(local, n_bins + 1, scan_tmp);
-  for (uint32_t i = threadIdx.x; i < n_bins; i += kBinThreads) {
-    const uint32_t f = first[i];
-    if (tile == 0) bin_start[i] = f;
-    first[i] = f + row0[i];
+  before = 0;
+  for (int i = 0; i < kBinThreads / 64; ++i) before += scan_tmp[i];
+  __syncthreads();
+  block_exclusive_scan<kBinThreads>(delta, nbp, scan_tmp);
+  block_exclusive_scan<kBinThreads>(local, nbp + 1, scan_tmp);
+  for (uint32_t i = threadIdx.x; i < nbp; i += kBinThreads) {
+    const uint32_t f = before + delta[i];  // first record of the bin
+    if (tile == 0) bin_start[gb_a + i] = f;
+    cur[i] = local[i];
+    delta[i] = f + row0[i] - local[i];  // wrap-around arithmetic; undone when a position is added
   }
   __syncthreads();
 
@@ -453,22 +512,39 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, 
   const uint32_t b = valid ? (uint32_t)b64 : 0u;
   float xp[D];
   load_x<D>(x, b, xp);
-  const Vec<IT, 2>* row = reinterpret_cast<const Vec<IT, 2>*>(dy + (uint64_t)b * lv.L * 2);
-  Vec<IT, 2> g_next = row[0];
-  for (uint32_t l = 0; l < lv.L; ++l) {
-    const uint32_t gb0 = bp.bin_base[l], gb1 = bp.bin_base[l + 1];
-    const uint32_t level_first = local[gb0], emitted = local[gb1] - level_first;  // <= R * kBinThreads
-    const Vec<IT, 2> g = g_next;
-    if (l + 1 < lv.L) g_next = row[l + 1];  // in flight while this level is sorted
+  // dL/dy of K consecutive levels comes in as one 16-byte load: a 4-byte read per level with
+  // the stride of a row would cost the L1 a line per two lanes, sixteen times over
+  constexpr uint32_t K = 16 / (2 * sizeof(IT));
+  const IT* row = dy + (uint64_t)b * lv.L * 2;
+  const bool vec_ok = (lv.L % K == 0) && (l0 % K == 0) && ((reinterpret_cast<uintptr_t>(dy) & 15) == 0);
+  Vec<IT, 2 * K> gv;
+  for (uint32_t l = l0; l < l1; ++l) {
+    const uint32_t rb0 = bp.bin_base[l] - gb_a, rb1 = bp.bin_base[l + 1] - gb_a;
+    const uint32_t level_first = local[rb0], emitted = local[rb1] - level_first;  // <= R * kBinThreads
+    float g0, g1;
+    if (vec_ok) {  // uniform
+      if ((l - l0) % K == 0) gv = *reinterpret_cast<const Vec<IT, 2 * K>*>(row + (uint64_t)l * 2);
+      const uint32_t k = (l - l0) % K;
+      g0 = (float)gv.v[0];
+      g1 = (float)gv.v[1];
+#pragma unroll
+      for (uint32_t q = 1; q < K; ++q) {
+        g0 = k == q ? (float)gv.v[2 * q] : g0;
+        g1 = k == q ? (float)gv.v[2 * q + 1] : g1;
+      }
+    } else {
+      const Vec<IT, 2> g = reinterpret_cast<const Vec<IT, 2>*>(row)[l];
+      g0 = (float)g.v[0];
+      g1 = (float)g.v[1];
+    }
     if (valid) {
       Rows<D> rw;
       rows_of<D, false>(lv, bp, l, smooth, xp, rw);
-      const float g0 = (float)g.v[0], g1 = (float)g.v[1];
 #pragma unroll
       for (uint32_t r = 0; r < R; ++r) {
-        const uint32_t gb = rw.bin[r];
-        const uint32_t rank = __hip_atomic_fetch_add(&fill[gb], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        const uint32_t pos = local[gb] - level_first + rank;
+        const uint32_t rb = rw.bin[r] - gb_a;
+        const uint32_t in_tile = __hip_atomic_fetch_add(&cur[rb], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        const uint32_t pos = in_tile - level_first;
         if (pos < R * kBinThreads) {  // holds when the count pass saw the same x
           u32x4 rec;
           rec.x = rw.pack[r];
@@ -476,13 +552,13 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, 
           rec.z = __float_as_uint(rw.wrow[r] * g0);
           rec.w = __float_as_uint(rw.wrow[r] * g1);
           staging[pos] = rec;
-          dstv[pos] = first[gb] + rank;
+          binv[pos] = (uint16_t)rb;
         }
       }
     }
     __syncthreads();
     for (uint32_t j = threadIdx.x; j < emitted && j < R * kBinThreads; j += kBinThreads) {
-      const uint32_t d = dstv[j];
+      const uint32_t d = delta[binv[j]] + level_first + j;
       // the count pass saw the same inputs, so d < n_records; the check only keeps a
       // caller who changed x in between from writing out of bounds
       if (d < n_records) records[d] = staging[j];
@@ -635,28 +711,25 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
   plan_slices(bp, h->lv, B);
   const bool smooth = h->cfg.interp == HG_INTERP_SMOOTHSTEP;
   const uint32_t n_records = B * h->lv.L * bp.rec_per_point;
-  const size_t lds_bins = (size_t)ws.n_bins * 4, lds_scatter = (size_t)(3 * ws.n_bins + 1) * 4;
+  const uint32_t L = h->lv.L, parts = L < kMaxParts ? L : kMaxParts;
+  uint32_t max_part_bins = 0;
+  for (uint32_t p = 0; p < parts; ++p) {
+    const uint32_t nbp = bp.bin_base[(p + 1) * L / parts] - bp.bin_base[p * L / parts];
+    max_part_bins = nbp > max_part_bins ? nbp : max_part_bins;
+  }
+  const size_t lds_count = (size_t)max_part_bins * 4, lds_scatter = (size_t)(3 * max_part_bins + 1) * 4;
   const uint32_t tile_wgs = (ws.n_tiles + 7u) / 8u * 8u;  // see tile_of_workgroup
-  hipLaunchKernelGGL((bin_count<D, IT>), dim3(tile_wgs), dim3(kBinThreads), lds_bins, s, h->lv, bp, smooth, B, x,
-                     static_cast<const IT*>(dy), ws.counts, ws.tile_max, ws.n_bins, ws.n_tiles);
+  hipLaunchKernelGGL((bin_count<D, IT>), dim3(tile_wgs, parts), dim3(kBinThreads), lds_count, s, h->lv, bp, smooth,
+                     B, x, static_cast<const IT*>(dy), ws.counts, ws.tile_max, ws.n_bins, ws.n_tiles);
   hipLaunchKernelGGL(bin_scan, dim3((ws.n_bins + kScanBins - 1) / kScanBins), dim3(kScanThreads), 0, s, ws.n_tiles,
-                     ws.n_bins, ws.counts, ws.bin_total, ws.tile_max, ws.call_max);
+                     ws.n_tiles * parts, ws.n_bins, ws.counts, ws.bin_total, ws.tile_max, ws.call_max);
+  hipLaunchKernelGGL((bin_scatter<D, IT>), dim3(tile_wgs, parts), dim3(kBinThreads), lds_scatter, s, h->lv, bp,
+                     smooth, B, x, static_cast<const IT*>(dy), ws.counts, ws.bin_total, ws.bin_start,
+                     reinterpret_cast<u32x4*>(ws.records), ws.n_bins, n_records, ws.n_tiles);
   // 64 KiB of dynamic LDS plus a few static bytes: above the default limit
   static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_accumulate),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, 16 << kChunkLog2);
   if (lds_ok != hipSuccess) return HG_ERR_DEVICE;
-  {  // static staging plus the dynamic per-bin arrays can exceed the default 64 KiB
-    static size_t allowed = 0;
-    if (lds_scatter > allowed) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(bin_scatter<D, IT>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_scatter) != hipSuccess)
-        return HG_ERR_DEVICE;
-      allowed = lds_scatter;
-    }
-  }
-  hipLaunchKernelGGL((bin_scatter<D, IT>), dim3(tile_wgs), dim3(kBinThreads), lds_scatter, s, h->lv, bp, smooth, B,
-                     x, static_cast<const IT*>(dy), ws.counts, ws.bin_total, ws.bin_start,
-                     reinterpret_cast<u32x4*>(ws.records), ws.n_bins, n_records, ws.n_tiles);
   hipLaunchKernelGGL(bin_accumulate, dim3(bp.wg_base[h->lv.L]), dim3(kAccThreads), (size_t)16 << bp.chunk_log2, s,
                      h->lv, bp, smooth, B, ws.bin_start, ws.bin_total, ws.call_max, ws.records, grad);
   return hipGetLastError() == hipSuccess ? HG_OK : HG_ERR_DEVICE;
