@@ -151,6 +151,9 @@ __global__ __launch_bounds__(kPmBlock) void fwd_point_major(const LevelTable lv,
   load_point<D>(x, b, xp);
   Vec<IT, 2 * G>* yrow = reinterpret_cast<Vec<IT, 2 * G>*>(y + (uint64_t)b * lv.L * 2);
   const float shift = smooth ? 0.5f : 0.0f;
+  // two 16-byte pieces are stored back to back so that a 32-byte sector of the row is
+  // written once, not twice
+  Vec<IT, 2 * G> held;
   for (uint32_t l0 = 0; l0 < lv.L; l0 += G) {
     Vec<IT, 2 * G> out;
 #pragma unroll
@@ -201,7 +204,13 @@ __global__ __launch_bounds__(kPmBlock) void fwd_point_major(const LevelTable lv,
       asm volatile("" ::: "memory");  // keep the gathers of one level together
       __syncthreads();
     }
-    if (valid) yrow[l0 / G] = out;
+    const uint32_t piece = l0 / G;
+    if ((piece & 1u) == 0 && l0 + G < lv.L) {
+      held = out;  // even piece with a partner: keep it until the partner is ready
+    } else if (valid) {
+      if (piece & 1u) yrow[piece - 1] = held;
+      yrow[piece] = out;
+    }
   }
 }
 
