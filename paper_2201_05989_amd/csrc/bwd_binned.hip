@@ -55,6 +55,10 @@ constexpr int kAccThreads = HG_ACC_THREADS;
 #define HG_ACC_UNROLL 4
 #endif
 constexpr int kAccUnroll = HG_ACC_UNROLL;
+#ifndef HG_ACC_PRE
+#define HG_ACC_PRE 8
+#endif
+constexpr int kAccPre = HG_ACC_PRE;  // records per lane requested one item ahead
 #ifndef HG_CHUNK_LOG2
 #define HG_CHUNK_LOG2 12
 #endif
@@ -152,7 +156,6 @@ static void plan_slices(BinPlan& bp, const LevelTable& lv, uint32_t B) {
     const uint64_t per_bin = ((uint64_t)B * bp.rec_per_point + nb - 1) / nb;
     uint64_t s = (per_bin + kTargetRecordsPerAccWg - 1) / kTargetRecordsPerAccWg;
     if (!((lv.dense_mask >> l) & 1u) && s < 4) s = 1;  // hashed bins are evenly filled
-    if (s > 1) s *= 2;                                 // 1:1 bins are not: leave slack
     if (s > 256) s = 256;
     bp.slices[l] = (uint32_t)(s < 1 ? 1 : s);
     bp.wg_base[l] = wgs;
@@ -579,128 +582,202 @@ __device__ __forceinline__ long long to_fixed(float t, int S) {
   return ((long long)mag ^ sgn) - sgn;
 }
 
-// accumulate: one workgroup per (bin, slice).
+// accumulate: work item = (bin, slice).  The grid is persistent (two workgroups
+// per CU, which is what 64 KiB of LDS each allows) and workgroup w takes items
+// w, w + gridDim.x, ...: the first record and the count of the next item are
+// fetched while the current one is streamed, so the chain "offsets -> records"
+// is paid once per workgroup, not once per bin, and the LDS accumulators are
+// re-zeroed by the lanes that have just read them.
 __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable lv, const BinPlan bp, const bool smooth,
-                                                              const uint32_t B,
+                                                              const uint32_t B, const uint32_t n_items,
                                                               const uint32_t* __restrict__ bin_start,
                                                               const uint32_t* __restrict__ bin_total,
                                                               const float* __restrict__ call_max,
                                                               const uint4* __restrict__ records,
                                                               float* __restrict__ grad) {
-  extern __shared__ unsigned long long acc[];  // [2^chunk_log2][2] fixed point
-  // which level, bin and slice this workgroup serves
-  const uint32_t wg = blockIdx.x;
-  uint32_t l = 0;
-  while (l + 1 < lv.L && wg >= bp.wg_base[l + 1]) ++l;
-  const uint32_t k = wg - bp.wg_base[l];
-  const uint32_t n_sl = bp.slices[l];
-  const uint32_t bin = k / n_sl, slice = k - bin * n_sl;
-  const uint32_t gb = bp.bin_base[l] + bin;
-  const uint32_t start = bin_start[gb], total = bin_total[gb];
-  const uint32_t per = (total + n_sl - 1) / n_sl;
-  const uint32_t r0 = start + slice * per;
-  const uint32_t r1 = (slice * per + per < total) ? r0 + per : start + total;
-  if (slice * per >= total) return;  // uniform: nothing for this workgroup
-
+  extern __shared__ unsigned long long acc[];  // [2][2^chunk_log2] fixed point: feature 0 of every entry, then
+                                               // feature 1, so that consecutive entries map to consecutive banks
   const float m = call_max[0];  // largest |dL/dy| of the call (NaN if any is NaN)
-  if (m == 0.0f) return;  // every summand is zero
-
+  if (m == 0.0f) return;        // every summand is zero
+  const bool finite = m < INFINITY;
   const uint32_t cl = bp.chunk_log2, cap = 1u << cl, cmask = cap - 1u;
-  const bool dense = (lv.dense_mask >> l) & 1u;
-  // entries of this chunk in the level's slice
-  uint32_t e0, e1;
-  if (dense) {
-    e0 = (bin << bp.row_shift[l]) * lv.verts[l];
-    e1 = e0 + (lv.verts[l] << bp.row_shift[l]);
-  } else {
-    e0 = bin << cl;
-    e1 = e0 + cap;
-  }
-  if (e1 > lv.size[l]) e1 = lv.size[l];
-  float* gl = grad + (lv.offset[l] + e0) * 2;
-
-  if (!(m < INFINITY)) {
-    // inf or NaN upstream: keep IEEE semantics with direct fp32 atomics (slow, rare)
-    for (uint32_t i = r0 + threadIdx.x; i < r1; i += kAccThreads) {
-      const uint4 rec = records[i];
-      const uint32_t la = rec.x & cmask, lb = (rec.x >> 16) & cmask;
-      const float wf = __uint_as_float(rec.y), g0 = __uint_as_float(rec.z), g1 = __uint_as_float(rec.w);
-      const float wu = smooth ? smoothstep(wf) : wf, wl = smooth ? smoothstep(1.0f - wf) : 1.0f - wf;
-      if (la < e1 - e0) {
-        __hip_atomic_fetch_add(gl + 2 * la, wl * g0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_fetch_add(gl + 2 * la + 1, wl * g1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
-      if (lb < e1 - e0) {
-        __hip_atomic_fetch_add(gl + 2 * lb, wu * g0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_fetch_add(gl + 2 * lb + 1, wu * g1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
-    }
-    return;
-  }
-
+  unsigned long long* acc0 = acc;
+  unsigned long long* acc1 = acc + cap;
   // fixed-point scale: |summand| <= m < 2^E, at most 8B summands per entry
-  int E;
-  (void)frexpf(m, &E);
+  int E = 0;
+  if (finite) (void)frexpf(m, &E);
   const int H = 3 + (32 - __builtin_clz(B > 1 ? B - 1 : 1));
   const int S = 62 - H - E;
-
-  // The chunk of the gradient this workgroup will add to is fetched now and used
-  // after the records: its latency hides behind the record stream.
   constexpr int kPer = (1 << kChunkLog2) / kAccThreads;  // entries per lane
-  const uint32_t n_e = e1 - e0;
-  float2 cur[kPer];
-  if (n_sl == 1) {
-#pragma unroll
-    for (int j = 0; j < kPer; ++j) {
-      const uint32_t e = threadIdx.x + j * kAccThreads;
-      if (e < n_e) cur[j] = reinterpret_cast<const float2*>(gl)[e];
-    }
-  }
+
   for (uint32_t i = threadIdx.x; i < 2 * cap; i += kAccThreads) acc[i] = 0ull;
   __syncthreads();
-  unsigned long long* acc0 = acc;        // feature 0 of every entry, then feature 1: consecutive
-  unsigned long long* acc1 = acc + cap;  // entries map to consecutive LDS banks
-  auto add_record = [&](const u32x4 rec) {
-    const uint32_t la = rec.x & cmask, lb = (rec.x >> 16) & cmask;
-    const float wf = __uint_as_float(rec.y), g0 = __uint_as_float(rec.z), g1 = __uint_as_float(rec.w);
-    const float wu = smooth ? smoothstep(wf) : wf, wl = smooth ? smoothstep(1.0f - wf) : 1.0f - wf;
-    __hip_atomic_fetch_add(&acc0[la], (unsigned long long)to_fixed(wl * g0, S), __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_WORKGROUP);
-    __hip_atomic_fetch_add(&acc1[la], (unsigned long long)to_fixed(wl * g1, S), __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_WORKGROUP);
-    __hip_atomic_fetch_add(&acc0[lb], (unsigned long long)to_fixed(wu * g0, S), __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_WORKGROUP);
-    __hip_atomic_fetch_add(&acc1[lb], (unsigned long long)to_fixed(wu * g1, S), __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_WORKGROUP);
+
+  // which level, bin and slice an item is
+  auto decode = [&](uint32_t item, uint32_t& l, uint32_t& bin, uint32_t& slice) {
+    l = 0;
+    while (l + 1 < lv.L && item >= bp.wg_base[l + 1]) ++l;
+    const uint32_t k = item - bp.wg_base[l];
+    bin = k / bp.slices[l];
+    slice = k - bin * bp.slices[l];
   };
-  // kAccUnroll loads in flight per lane: the record stream is latency-bound otherwise
-  uint32_t i = r0 + threadIdx.x;
-  for (; i + (kAccUnroll - 1) * kAccThreads < r1; i += kAccUnroll * kAccThreads) {
-    u32x4 rec[kAccUnroll];
-    const u32x4* rp = reinterpret_cast<const u32x4*>(records);
-#pragma unroll
-    for (int j = 0; j < kAccUnroll; ++j) rec[j] = __builtin_nontemporal_load(rp + i + j * kAccThreads);
-#pragma unroll
-    for (int j = 0; j < kAccUnroll; ++j) add_record(rec[j]);
-  }
-  for (; i < r1; i += kAccThreads) add_record(__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(records) + i));
-  __syncthreads();
-#pragma unroll
-  for (int j = 0; j < kPer; ++j) {
-    const uint32_t e = threadIdx.x + j * kAccThreads;
-    if (e >= n_e) continue;
-    const long long a0 = (long long)acc0[e], a1 = (long long)acc1[e];
-    // an entry no record reached gets -0.0f added, which leaves every float (either zero,
-    // NaNs included) exactly as it was; storing it anyway keeps the stores of a wave contiguous
-    const float v0 = a0 ? (float)ldexp((double)a0, -S) : -0.0f, v1 = a1 ? (float)ldexp((double)a1, -S) : -0.0f;
-    if (n_sl == 1) {
-      cur[j].x += v0;
-      cur[j].y += v1;
-      reinterpret_cast<float2*>(gl)[e] = cur[j];
-    } else if ((a0 | a1) != 0) {
-      __hip_atomic_fetch_add(gl + 2 * e, v0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_fetch_add(gl + 2 * e + 1, v1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+
+  // Everything an item needs before its records can be used: where they are, which chunk of
+  // the gradient it owns, and (software pipeline) its first kAccPre records per lane and its
+  // gradient chunk, both requested while the previous item is still being flushed.
+  struct Item {
+    uint32_t l, n_sl, r0, r1, n_e;
+    float* gl;
+    bool live;
+  };
+  const u32x4* rp = reinterpret_cast<const u32x4*>(records);
+  auto describe = [&](uint32_t item, uint32_t start, uint32_t total, uint32_t l, uint32_t bin, uint32_t slice) {
+    Item it;
+    it.l = l;
+    it.n_sl = bp.slices[l];
+    const uint32_t per = (total + it.n_sl - 1) / it.n_sl;
+    it.r0 = start + slice * per;
+    it.r1 = (slice * per + per < total) ? it.r0 + per : start + total;
+    it.live = item < n_items && slice * per < total;
+    uint32_t e0, e1;  // entries of this chunk in the level's slice
+    if ((lv.dense_mask >> l) & 1u) {
+      e0 = (bin << bp.row_shift[l]) * lv.verts[l];
+      e1 = e0 + (lv.verts[l] << bp.row_shift[l]);
+    } else {
+      e0 = bin << cl;
+      e1 = e0 + cap;
     }
+    if (e1 > lv.size[l]) e1 = lv.size[l];
+    it.n_e = e1 - e0;
+    it.gl = grad + (lv.offset[l] + e0) * 2;
+    return it;
+  };
+  auto request = [&](const Item& it, u32x4 (&pre)[kAccPre], float2 (&cur)[kPer]) {
+    if (!it.live || !finite) return;
+#pragma unroll
+    for (int j = 0; j < kAccPre; ++j) {
+      const uint32_t i = it.r0 + threadIdx.x + j * kAccThreads;
+      if (i < it.r1) pre[j] = __builtin_nontemporal_load(rp + i);
+    }
+    if (it.n_sl == 1) {
+#pragma unroll
+      for (int j = 0; j < kPer; ++j) {
+        const uint32_t e = threadIdx.x + j * kAccThreads;
+        if (e < it.n_e) cur[j] = reinterpret_cast<const float2*>(it.gl)[e];
+      }
+    }
+  };
+
+  uint32_t item = blockIdx.x;
+  uint32_t l = 0, bin = 0, slice = 0, start = 0, total = 0;
+  if (item < n_items) {
+    decode(item, l, bin, slice);
+    start = bin_start[bp.bin_base[l] + bin];
+    total = bin_total[bp.bin_base[l] + bin];
+  }
+  Item it = describe(item, start, total, l, bin, slice);
+  u32x4 pre[kAccPre];
+  float2 cur[kPer];
+  request(it, pre, cur);
+  while (item < n_items) {
+    // offsets of the next item: in flight while this one is processed
+    const uint32_t next = item + gridDim.x;
+    uint32_t l_n = 0, bin_n = 0, slice_n = 0, start_n = 0, total_n = 0;
+    if (next < n_items) {
+      decode(next, l_n, bin_n, slice_n);
+      start_n = bin_start[bp.bin_base[l_n] + bin_n];
+      total_n = bin_total[bp.bin_base[l_n] + bin_n];
+    }
+    Item it_n;
+    it_n.live = false;
+    float2 cur_n[kPer];
+    if (it.live && !finite) {
+      // inf or NaN upstream: keep IEEE semantics with direct fp32 atomics (slow, rare)
+      for (uint32_t i = it.r0 + threadIdx.x; i < it.r1; i += kAccThreads) {
+        const u32x4 rec = rp[i];
+        const uint32_t la = rec.x & cmask, lb = (rec.x >> 16) & cmask;
+        const float wf = __uint_as_float(rec.y), g0 = __uint_as_float(rec.z), g1 = __uint_as_float(rec.w);
+        const float wu = smooth ? smoothstep(wf) : wf, wl = smooth ? smoothstep(1.0f - wf) : 1.0f - wf;
+        if (la < it.n_e) {
+          __hip_atomic_fetch_add(it.gl + 2 * la, wl * g0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_fetch_add(it.gl + 2 * la + 1, wl * g1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (lb < it.n_e) {
+          __hip_atomic_fetch_add(it.gl + 2 * lb, wu * g0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_fetch_add(it.gl + 2 * lb + 1, wu * g1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+      }
+      it_n = describe(next, start_n, total_n, l_n, bin_n, slice_n);
+    } else if (it.live) {
+      auto add_record = [&](const u32x4 rec) {
+        const uint32_t la = rec.x & cmask, lb = (rec.x >> 16) & cmask;
+        const float wf = __uint_as_float(rec.y), g0 = __uint_as_float(rec.z), g1 = __uint_as_float(rec.w);
+        const float wu = smooth ? smoothstep(wf) : wf, wl = smooth ? smoothstep(1.0f - wf) : 1.0f - wf;
+        __hip_atomic_fetch_add(&acc0[la], (unsigned long long)to_fixed(wl * g0, S), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_WORKGROUP);
+        __hip_atomic_fetch_add(&acc1[la], (unsigned long long)to_fixed(wl * g1, S), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_WORKGROUP);
+        __hip_atomic_fetch_add(&acc0[lb], (unsigned long long)to_fixed(wu * g0, S), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_WORKGROUP);
+        __hip_atomic_fetch_add(&acc1[lb], (unsigned long long)to_fixed(wu * g1, S), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_WORKGROUP);
+      };
+      // the records requested ahead of time
+#pragma unroll
+      for (int j = 0; j < kAccPre; ++j)
+        if (it.r0 + threadIdx.x + j * kAccThreads < it.r1) add_record(pre[j]);
+      // the rest of a long item, kAccUnroll loads in flight per lane
+      uint32_t i = it.r0 + threadIdx.x + kAccPre * kAccThreads;
+      for (; i + (kAccUnroll - 1) * kAccThreads < it.r1; i += kAccUnroll * kAccThreads) {
+        u32x4 rec[kAccUnroll];
+#pragma unroll
+        for (int j = 0; j < kAccUnroll; ++j) rec[j] = __builtin_nontemporal_load(rp + i + j * kAccThreads);
+#pragma unroll
+        for (int j = 0; j < kAccUnroll; ++j) add_record(rec[j]);
+      }
+      for (; i < it.r1; i += kAccThreads) add_record(__builtin_nontemporal_load(rp + i));
+      // request the next item's records and gradient chunk, then flush this one under them
+      it_n = describe(next, start_n, total_n, l_n, bin_n, slice_n);
+      request(it_n, pre, cur_n);  // `pre` has been consumed: its registers take the next item's records
+      __syncthreads();
+      if (it.n_sl == 1) {
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+          const uint32_t e = threadIdx.x + j * kAccThreads;
+          const long long a0 = (long long)acc0[e], a1 = (long long)acc1[e];
+          acc0[e] = 0ull;  // ready for the next item
+          acc1[e] = 0ull;
+          if (e >= it.n_e) continue;
+          // an entry no record reached gets -0.0f added, which leaves every float (either zero,
+          // NaNs included) exactly as it was; storing it anyway keeps the stores of a wave contiguous
+          cur[j].x += a0 ? (float)ldexp((double)a0, -S) : -0.0f;
+          cur[j].y += a1 ? (float)ldexp((double)a1, -S) : -0.0f;
+          reinterpret_cast<float2*>(it.gl)[e] = cur[j];
+        }
+      } else {
+        // several workgroups share this chunk: fp32 atomics, one lane per float so that the
+        // two features of an entry and its neighbours travel in the same 64-byte requests
+#pragma unroll
+        for (int j = 0; j < 2 * kPer; ++j) {
+          const uint32_t q = threadIdx.x + j * kAccThreads;  // float index in the chunk
+          const uint32_t e = q >> 1;
+          unsigned long long* slot = (q & 1u) ? &acc1[e] : &acc0[e];
+          const long long a = (long long)*slot;
+          *slot = 0ull;
+          if (e < it.n_e && a != 0)
+            __hip_atomic_fetch_add(it.gl + q, (float)ldexp((double)a, -S), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+        }
+      }
+      __syncthreads();
+    } else {
+      it_n = describe(next, start_n, total_n, l_n, bin_n, slice_n);
+      request(it_n, pre, cur_n);
+    }
+    item = next;
+    it = it_n;
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) cur[j] = cur_n[j];
   }
 }
 
@@ -730,8 +807,17 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
   static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_accumulate),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, 16 << kChunkLog2);
   if (lds_ok != hipSuccess) return HG_ERR_DEVICE;
-  hipLaunchKernelGGL(bin_accumulate, dim3(bp.wg_base[h->lv.L]), dim3(kAccThreads), (size_t)16 << bp.chunk_log2, s,
-                     h->lv, bp, smooth, B, ws.bin_start, ws.bin_total, ws.call_max, ws.records, grad);
+  const uint32_t n_items = bp.wg_base[h->lv.L];
+  static const uint32_t acc_slots = [] {  // two 64-KiB workgroups fit the 160 KiB of LDS of a CU
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+      cus = 256;
+    return (uint32_t)cus * 2u;
+  }();
+  hipLaunchKernelGGL(bin_accumulate, dim3(n_items < acc_slots ? n_items : acc_slots), dim3(kAccThreads),
+                     (size_t)16 << bp.chunk_log2, s, h->lv, bp, smooth, B, n_items, ws.bin_start, ws.bin_total,
+                     ws.call_max, ws.records, grad);
   return hipGetLastError() == hipSuccess ? HG_OK : HG_ERR_DEVICE;
 }
 
