@@ -39,7 +39,10 @@
  *     per axis; to keep the coarse-level map 1:1 the dense criterion and the
  *     dense stride use N_l + 2 in place of N_l + 1 for this variant.  (The
  *     appendix does not say how the shifted grid is indexed; this is the
- *     reading taken here.)
+ *     reading taken here.  The smoothstep weights and their derivative are
+ *     pinned by closed forms; which entry a vertex of the shifted grid maps to
+ *     on a 1:1 level is a choice nothing in the paper fixes: parity unpinned
+ *     for that choice only.)
  */
 #include <math.h>
 #include <stdint.h>
@@ -287,6 +290,36 @@ int hgo_indices(const hgo_config* c, uint64_t B, const float* x, uint32_t l, uin
       for (uint32_t i = 0; i < d; ++i) v[i] = c0[i] + ((m >> i) & 1u);
       idx[b * (1u << d) + m] = hgo_index(d, lv.verts[l], c->T, lv.dense[l], v);
     }
+  }
+  return 0;
+}
+
+/* ---------------------------------------------------------------------------
+ * Optimiser step on the tables (paper Section 4, "Training"): Adam (Kingma & Ba,
+ * Algorithm 1, with bias correction) with beta1, beta2, eps as given by the
+ * caller (the paper uses 0.9, 0.99, 1e-15), no weight decay on table entries,
+ * and the paper's rule that an entry whose gradient is exactly 0 is skipped: its
+ * moments and its value are left untouched.
+ *
+ * Readings where the paper is silent: `step` (1-based) is one global counter
+ * used for the bias corrections of every entry, skipped or not; "entry" is taken
+ * per scalar (each of the F features of a table entry decides on its own
+ * gradient).  All arithmetic fp64; theta is the full-precision master copy
+ * (Section 4, "Performance considerations": the half-precision table is derived
+ * from it by rounding, which the caller does).
+ */
+int hgo_adam_step(uint64_t n, double* theta, const double* grad, double* m, double* v, double lr, double beta1,
+                  double beta2, double eps, uint32_t step) {
+  if (!theta || !grad || !m || !v || step == 0) return -1;
+  const double c1 = 1.0 - pow(beta1, (double)step); /* bias corrections */
+  const double c2 = 1.0 - pow(beta2, (double)step);
+  for (uint64_t i = 0; i < n; ++i) {
+    const double g = grad[i];
+    if (g == 0.0) continue; /* skipped entry */
+    m[i] = beta1 * m[i] + (1.0 - beta1) * g;
+    v[i] = beta2 * v[i] + (1.0 - beta2) * g * g;
+    const double m_hat = m[i] / c1, v_hat = v[i] / c2;
+    theta[i] -= lr * m_hat / (sqrt(v_hat) + eps);
   }
   return 0;
 }

@@ -71,6 +71,8 @@ def _load():
         lib.hgo_bwd.argtypes = [cfgp, u64, vp, vp, vp]
         lib.hgo_bwd_input.argtypes = [cfgp, u64, vp, vp, vp, vp]
         lib.hgo_indices.argtypes = [cfgp, u64, vp, u32, vp, vp]
+        dbl = ctypes.c_double
+        lib.hgo_adam_step.argtypes = [u64, vp, vp, vp, vp, dbl, dbl, dbl, dbl, u32]
         _lib = lib
     return _lib
 
@@ -185,3 +187,15 @@ def indices(cfg: OracleConfig, x, level: int):
     _check(_load().hgo_indices(ctypes.byref(cfg._c()), x.shape[0], x.ctypes.data, level, idx.ctypes.data,
                                w.ctypes.data))
     return idx, w
+
+
+def adam_step(theta, grad, m, v, lr, beta1=0.9, beta2=0.99, eps=1e-15, step=1):
+    """One optimiser step on fp64 arrays, in place (theta, m, v); entries with grad == 0 are skipped."""
+    for a in (theta, m, v):
+        assert a.dtype == np.float64 and a.flags.c_contiguous
+    g = np.ascontiguousarray(grad, dtype=np.float64)
+    assert theta.shape == g.shape == m.shape == v.shape
+    rc = _load().hgo_adam_step(theta.size, theta.ctypes.data, g.ctypes.data, m.ctypes.data, v.ctypes.data,
+                               float(lr), float(beta1), float(beta2), float(eps), int(step))
+    if rc != 0:
+        raise ValueError("invalid arguments")
