@@ -128,6 +128,26 @@ def main():
     ms_bwd = time_launches(bwd, n, torch)
     ms_zero = time_launches(lambda: grad.zero_(), 20, torch)
 
+    # next row of the path: the optimiser step on the tables (fp32 master + fp16 working copy,
+    # clears the gradient).  Timed as (backward + optimiser) minus backward, because the step
+    # skips entries whose gradient is zero and clears the ones it uses.
+    from paper_2201_05989_amd import adam_step
+    master = td.float()
+    m1, m2 = torch.zeros_like(master), torch.zeros_like(master)
+    counter = [0]
+
+    def bwd_adam():
+        bwd()
+        counter[0] += 1
+        adam_step(master, grad, m1, m2, counter[0], lr=1e-2, params_half=td if w.param_dtype == "f16" else None)
+
+    grad.zero_()
+    ms_bwd_adam = time_launches(bwd_adam, max(args.steps // 2, 10), torch)
+    grad.zero_()
+    ms_adam = ms_bwd_adam - ms_bwd
+    n_scalars = grid.n_entries * w.F
+    adam_bytes = n_scalars * (16 + 12 + 4 + (2 if w.param_dtype == "f16" else 0))
+
     s_theta = 2 if w.param_dtype == "f16" else 4
     s_io = 2 if w.io_dtype == "f16" else 4
     b_fwd, b_bwd = algorithmic_bytes(w, s_theta, s_io)
@@ -150,6 +170,10 @@ def main():
         "fwd_mpoints_s": w.B / (ms_fwd * 1e-3) / 1e6,
         "bwd_mpoints_s": w.B / (ms_bwd * 1e-3) / 1e6,
         "ms_fwd": ms_fwd, "ms_bwd": ms_bwd, "ms_grad_zero": ms_zero,
+        "adam": {"ms": ms_adam, "scalars": n_scalars, "algorithmic_bytes": adam_bytes,
+                 "achieved_gb_s": adam_bytes / (ms_adam * 1e-3) / 1e9 if ms_adam > 0 else None,
+                 "train_step_ms": ms_fwd + ms_bwd_adam,
+                 "train_step_mpoints_s": w.B / ((ms_fwd + ms_bwd_adam) * 1e-3) / 1e6},
         "roofline": {"bound": "hbm", "kernel": kernels[dom[0]] if grid.bwd_workspace_bytes(w.B) else dom[0],
                      "pass": dom[0], "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,

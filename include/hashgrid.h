@@ -144,6 +144,28 @@ hg_status hashgrid_encode_bwd_input(const hashgrid_t* hg, uint32_t B, const floa
 hg_status hashgrid_debug_indices(const hashgrid_t* hg, uint32_t B, const float* x, uint32_t level, uint32_t* idx,
                                  float* w, void* stream);
 
+/* Hyper-parameters of the optimiser step below (paper Section 4, "Training": Adam with
+ * beta1 = 0.9, beta2 = 0.99, eps = 1e-15; learning rate 1e-2, 1e-4 for signed distance
+ * functions; no weight decay on table entries). */
+typedef struct {
+  float lr, beta1, beta2, eps;
+} hashgrid_adam_config;
+
+/* One Adam step (Kingma & Ba, Algorithm 1, with bias correction for the 1-based global
+ * `step`) on n_scalars table scalars, following Section 4 of the paper: a scalar whose
+ * gradient is exactly 0 is skipped (value and both moments untouched); the full-precision
+ * master copy is updated and, when params_half is not NULL, rounded (nearest even) into the
+ * half-precision working copy the encoding kernels read.  All arithmetic fp32.
+ *   params_master [n] fp32  device, 16-byte aligned, read and written
+ *   params_half   [n] fp16  device, 8-byte aligned, written where updated; may be NULL
+ *   grad          [n] fp32  device, 16-byte aligned, read; set to 0 where it was not when
+ *                           zero_grad != 0 (so the next backward pass can accumulate into it)
+ *   m, v          [n] fp32  device, 16-byte aligned, first and second moment, read and written
+ * Returns HG_ERR_INVALID_ARG for step == 0, betas outside [0,1), negative eps, NULL or
+ * misaligned pointers.  n_scalars == 0 is HG_OK. */
+hg_status hashgrid_adam_step(uint64_t n_scalars, float* params_master, void* params_half, float* grad, float* m,
+                             float* v, const hashgrid_adam_config* cfg, uint32_t step, int zero_grad, void* stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char* hashgrid_strerror(hg_status s);
 

@@ -26,7 +26,7 @@ _TORCH = {HG_F32: torch.float32, HG_F16: torch.float16}
 EXPORTS = ("hashgrid_create", "hashgrid_destroy", "hashgrid_n_entries", "hashgrid_level_info",
            "hashgrid_encode_fwd", "hashgrid_encode_bwd", "hashgrid_encode_bwd_input",
            "hashgrid_debug_indices", "hashgrid_strerror", "hashgrid_bwd_workspace_bytes",
-           "hashgrid_encode_bwd_ws")
+           "hashgrid_encode_bwd_ws", "hashgrid_adam_step")
 
 
 class HashGridError(RuntimeError):
@@ -36,6 +36,10 @@ class HashGridError(RuntimeError):
 class hashgrid_config(ctypes.Structure):
     _fields_ = [(n, ctypes.c_uint32) for n in
                 ("d", "L", "F", "T", "N_min", "N_max", "param_dtype", "io_dtype", "interp")]
+
+
+class hashgrid_adam_config(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_float) for n in ("lr", "beta1", "beta2", "eps")]
 
 
 _lib = None
@@ -72,6 +76,9 @@ def load_library() -> ctypes.CDLL:
     lib.hashgrid_bwd_workspace_bytes.restype = u64
     lib.hashgrid_encode_bwd_ws.argtypes = [vp, u32, vp, vp, vp, vp, u64, vp]
     lib.hashgrid_encode_bwd_ws.restype = ctypes.c_int
+    lib.hashgrid_adam_step.argtypes = [u64, vp, vp, vp, vp, vp, ctypes.POINTER(hashgrid_adam_config), u32, ctypes.c_int,
+                                       vp]
+    lib.hashgrid_adam_step.restype = ctypes.c_int
     lib.hashgrid_strerror.argtypes = [ctypes.c_int]
     lib.hashgrid_strerror.restype = ctypes.c_char_p
     _lib = lib
@@ -198,3 +205,23 @@ class HashGrid:
             self._h, B, _dev(x, torch.float32, (B, self.d), "x"), level, idx.data_ptr(), w.data_ptr(),
             _stream_ptr(stream)), "hashgrid_debug_indices")
         return idx, w
+
+
+def adam_step(params_master: torch.Tensor, grad: torch.Tensor, m: torch.Tensor, v: torch.Tensor, step: int,
+              lr: float = 1e-2, beta1: float = 0.9, beta2: float = 0.99, eps: float = 1e-15,
+              params_half: torch.Tensor | None = None, zero_grad: bool = True, stream=None) -> None:
+    """hashgrid_adam_step on flat or [n, F] fp32 tensors (in place)."""
+    n = params_master.numel()
+    for name, t in (("params_master", params_master), ("grad", grad), ("m", m), ("v", v)):
+        if not (t.is_cuda and t.is_contiguous() and t.dtype == torch.float32 and t.numel() == n):
+            raise HashGridError(f"{name} must be a contiguous fp32 device tensor of {n} scalars")
+    half_ptr = None
+    if params_half is not None:
+        if not (params_half.is_cuda and params_half.is_contiguous() and params_half.dtype == torch.float16
+                and params_half.numel() == n):
+            raise HashGridError("params_half must be a contiguous fp16 device tensor of the same size")
+        half_ptr = params_half.data_ptr()
+    cfg = hashgrid_adam_config(lr, beta1, beta2, eps)
+    _check(load_library().hashgrid_adam_step(n, params_master.data_ptr(), half_ptr, grad.data_ptr(), m.data_ptr(),
+                                             v.data_ptr(), ctypes.byref(cfg), step, int(zero_grad),
+                                             _stream_ptr(stream)), "hashgrid_adam_step")

@@ -1,0 +1,106 @@
+// Optimiser step on the tables (paper Section 4, "Training"): Adam with the
+// caller's beta1, beta2, eps (the paper: 0.9, 0.99, 1e-15), no weight decay on
+// table entries, entries whose gradient is exactly 0 skipped, full-precision
+// master copy plus a half-precision working copy (Section 4, "Performance
+// considerations").  A pure streaming kernel: per updated scalar it reads 16
+// bytes (gradient, two moments, master value) and writes 14 to 18 (moments,
+// master, fp16 copy, and the gradient's zero when asked to clear it); a group
+// of four scalars whose gradients are all zero costs 16 bytes of reads and no
+// write at all.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "hashgrid.h"
+
+namespace hg {
+
+constexpr int kAdamThreads = 256;
+
+struct AdamArgs {
+  float lr, beta1, beta2, eps;
+  float inv_c1;       // 1 / (1 - beta1^t)
+  float inv_sqrt_c2;  // 1 / sqrt(1 - beta2^t)
+};
+
+__device__ __forceinline__ void adam_scalar(const AdamArgs& a, float g, float& m, float& v, float& p) {
+  m = a.beta1 * m + (1.0f - a.beta1) * g;
+  v = a.beta2 * v + (1.0f - a.beta2) * g * g;
+  p -= a.lr * (m * a.inv_c1) / (sqrtf(v) * a.inv_sqrt_c2 + a.eps);
+}
+
+template <bool ZERO_GRAD>
+__global__ __launch_bounds__(kAdamThreads) void adam_step(const AdamArgs a, const uint64_t n, float* __restrict__ p32,
+                                                          _Float16* __restrict__ p16, float* __restrict__ grad,
+                                                          float* __restrict__ m, float* __restrict__ v) {
+  const uint64_t n4 = n / 4;
+  for (uint64_t q = (uint64_t)blockIdx.x * kAdamThreads + threadIdx.x; q < n4; q += (uint64_t)gridDim.x * kAdamThreads) {
+    const float4 g = reinterpret_cast<const float4*>(grad)[q];
+    if (g.x == 0.0f && g.y == 0.0f && g.z == 0.0f && g.w == 0.0f) continue;  // nothing to read further, nothing to write
+    float4 mm = reinterpret_cast<const float4*>(m)[q];
+    float4 vv = reinterpret_cast<const float4*>(v)[q];
+    float4 pp = reinterpret_cast<const float4*>(p32)[q];
+    if (g.x != 0.0f) adam_scalar(a, g.x, mm.x, vv.x, pp.x);
+    if (g.y != 0.0f) adam_scalar(a, g.y, mm.y, vv.y, pp.y);
+    if (g.z != 0.0f) adam_scalar(a, g.z, mm.z, vv.z, pp.z);
+    if (g.w != 0.0f) adam_scalar(a, g.w, mm.w, vv.w, pp.w);
+    reinterpret_cast<float4*>(m)[q] = mm;
+    reinterpret_cast<float4*>(v)[q] = vv;
+    reinterpret_cast<float4*>(p32)[q] = pp;
+    if (p16) {
+      struct alignas(8) H4 { _Float16 h[4]; } h;
+      h.h[0] = (_Float16)pp.x;
+      h.h[1] = (_Float16)pp.y;
+      h.h[2] = (_Float16)pp.z;
+      h.h[3] = (_Float16)pp.w;
+      reinterpret_cast<H4*>(p16)[q] = h;
+    }
+    if (ZERO_GRAD) reinterpret_cast<float4*>(grad)[q] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+  }
+  // tail of fewer than four scalars
+  if (blockIdx.x == 0 && threadIdx.x < n - n4 * 4) {
+    const uint64_t i = n4 * 4 + threadIdx.x;
+    const float g = grad[i];
+    if (g != 0.0f) {
+      float mm = m[i], vv = v[i], pp = p32[i];
+      adam_scalar(a, g, mm, vv, pp);
+      m[i] = mm;
+      v[i] = vv;
+      p32[i] = pp;
+      if (p16) p16[i] = (_Float16)pp;
+      if (ZERO_GRAD) grad[i] = 0.0f;
+    }
+  }
+}
+
+}  // namespace hg
+
+extern "C" hg_status hashgrid_adam_step(uint64_t n_scalars, float* params_master, void* params_half, float* grad,
+                                        float* m, float* v, const hashgrid_adam_config* cfg, uint32_t step,
+                                        int zero_grad, void* stream) {
+  if (!cfg || step == 0) return HG_ERR_INVALID_ARG;
+  if (n_scalars == 0) return HG_OK;
+  if (!params_master || !grad || !m || !v) return HG_ERR_INVALID_ARG;
+  if (!(cfg->beta1 >= 0.0f && cfg->beta1 < 1.0f && cfg->beta2 >= 0.0f && cfg->beta2 < 1.0f && cfg->eps >= 0.0f))
+    return HG_ERR_INVALID_ARG;
+  const uintptr_t bits = reinterpret_cast<uintptr_t>(params_master) | reinterpret_cast<uintptr_t>(grad) |
+                         reinterpret_cast<uintptr_t>(m) | reinterpret_cast<uintptr_t>(v);
+  if ((bits & 15) || (reinterpret_cast<uintptr_t>(params_half) & 7)) return HG_ERR_INVALID_ARG;
+  hg::AdamArgs a;
+  a.lr = cfg->lr;
+  a.beta1 = cfg->beta1;
+  a.beta2 = cfg->beta2;
+  a.eps = cfg->eps;
+  a.inv_c1 = (float)(1.0 / (1.0 - pow((double)cfg->beta1, (double)step)));
+  a.inv_sqrt_c2 = (float)(1.0 / sqrt(1.0 - pow((double)cfg->beta2, (double)step)));
+  const uint64_t groups = (n_scalars / 4 + hg::kAdamThreads - 1) / hg::kAdamThreads;
+  const uint32_t blocks = (uint32_t)(groups < 1 ? 1 : (groups > 65536 ? 65536 : groups));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (zero_grad)
+    hipLaunchKernelGGL(hg::adam_step<true>, dim3(blocks), dim3(hg::kAdamThreads), 0, s, a, n_scalars, params_master,
+                       static_cast<_Float16*>(params_half), grad, m, v);
+  else
+    hipLaunchKernelGGL(hg::adam_step<false>, dim3(blocks), dim3(hg::kAdamThreads), 0, s, a, n_scalars, params_master,
+                       static_cast<_Float16*>(params_half), grad, m, v);
+  return hipGetLastError() == hipSuccess ? HG_OK : HG_ERR_DEVICE;
+}
