@@ -104,7 +104,7 @@ __global__ __launch_bounds__(kBlock) void fwd_general(const LevelTable lv, const
   reinterpret_cast<Vec<IT, F>*>(y)[(uint64_t)b * lv.L + l] = out;
 }
 
-// Forward for F = 2, point-major: one thread owns a point and walks the levels in
+// Forward, point-major: one thread owns a point and walks the levels in
 // order, so x is read once and the output row leaves the thread as 16-byte
 // pieces.  (The level-major kernel above writes 2*sizeof(io) bytes per thread
 // with a stride of a whole row; each such fragment costs a whole 32-byte sector
@@ -139,76 +139,99 @@ __device__ __forceinline__ void corner_indices_uniform(const uint32_t (&c0)[D], 
   }
 }
 
-template <int D, typename PT, typename IT, bool POW2>
+// Per level and point: the 2^D entry indices and the weights of the corners, split into the
+// product over dimensions 1.. (wr) and the two weights of dimension 0 (w0 upper, u0 lower).
+template <int D, bool POW2>
+__device__ __forceinline__ void level_corners(const LevelTable& lv, uint32_t l, bool smooth, const float (&xp)[D],
+                                              uint32_t (&idx)[1 << D], float (&wr)[1 << (D - 1)], float& w0,
+                                              float& u0) {
+  const float Nf = (float)lv.N[l];
+  const float shift = smooth ? 0.5f : 0.0f;
+  const float cmaxf = smooth ? Nf : Nf - 1.0f;
+  uint32_t c0[D];
+  float w[D], u[D];
+#pragma unroll
+  for (int i = 0; i < D; ++i) {
+    float wf;
+    split(xp[i], Nf, shift, cmaxf, c0[i], wf);
+    w[i] = smooth ? smoothstep(wf) : wf;
+    u[i] = smooth ? smoothstep(1.0f - wf) : 1.0f - wf;
+  }
+  if ((lv.dense_mask >> l) & 1u) {  // uniform
+    corner_indices_uniform<D, true>(c0, lv.verts[l], 0u, idx);
+  } else if (POW2) {
+    corner_indices_uniform<D, false>(c0, 0u, lv.T - 1u, idx);
+  } else {
+    const CornerTerms<D> ct = corner_terms<D>(c0, false, 0u);
+#pragma unroll
+    for (uint32_t m = 0; m < (1u << D); ++m) idx[m] = corner_index<D>(ct, m, false, lv.T, false);
+  }
+#pragma unroll
+  for (uint32_t r = 0; r < (1u << (D - 1)); ++r) {
+    float p = 1.0f;
+#pragma unroll
+    for (int i = 1; i < D; ++i) p *= ((r >> (i - 1)) & 1u) ? w[i] : u[i];
+    wr[r] = p;
+  }
+  w0 = w[0];
+  u0 = u[0];
+}
+
+// Levels whose outputs fill one store: 16 bytes, or one level when a level's F outputs are wider.
+template <int F, typename IT>
+struct OutPiece {
+  static constexpr int kLevelBytes = F * (int)sizeof(IT);
+  static constexpr int kBytes = kLevelBytes > 16 ? kLevelBytes : 16;
+  static constexpr int kLevels = kBytes / kLevelBytes;
+  static constexpr bool kPair = kBytes == 16;  // two pieces make a 32-byte sector
+};
+
+template <int D, int F, typename PT, typename IT, bool POW2>
 __global__ __launch_bounds__(kPmBlock) void fwd_point_major(const LevelTable lv, const bool smooth, const uint32_t B,
                                                             const float* __restrict__ x,
                                                             const PT* __restrict__ theta, IT* __restrict__ y) {
-  constexpr int G = 16 / (2 * (int)sizeof(IT));  // levels per 16-byte store
+  using Piece = OutPiece<F, IT>;
+  constexpr int G = Piece::kLevels;
   const uint32_t b0 = blockIdx.x * kPmBlock + threadIdx.x;
   const bool valid = b0 < B;
   const uint32_t b = valid ? b0 : B - 1;  // idle lanes of the last workgroup shadow the last point
   float xp[D];
   load_point<D>(x, b, xp);
-  Vec<IT, 2 * G>* yrow = reinterpret_cast<Vec<IT, 2 * G>*>(y + (uint64_t)b * lv.L * 2);
-  const float shift = smooth ? 0.5f : 0.0f;
-  // two 16-byte pieces are stored back to back so that a 32-byte sector of the row is
-  // written once, not twice
-  Vec<IT, 2 * G> held;
+  Vec<IT, F * G>* yrow = reinterpret_cast<Vec<IT, F * G>*>(y + (uint64_t)b * lv.L * F);
+  // 16-byte pieces are stored two at a time so that a 32-byte sector of the row is written
+  // once, not twice
+  Vec<IT, F * G> held;
   for (uint32_t l0 = 0; l0 < lv.L; l0 += G) {
-    Vec<IT, 2 * G> out;
+    Vec<IT, F * G> out;
 #pragma unroll
     for (int j = 0; j < G; ++j) {
       const uint32_t l = l0 + j;
-      const float Nf = (float)lv.N[l];
-      const float cmaxf = smooth ? Nf : Nf - 1.0f;
-      uint32_t c0[D], idx[1 << D];
-      float w[D], u[D];
-#pragma unroll
-      for (int i = 0; i < D; ++i) {
-        float wf;
-        split(xp[i], Nf, shift, cmaxf, c0[i], wf);
-        w[i] = smooth ? smoothstep(wf) : wf;
-        u[i] = smooth ? smoothstep(1.0f - wf) : 1.0f - wf;
-      }
-      if ((lv.dense_mask >> l) & 1u) {  // uniform
-        corner_indices_uniform<D, true>(c0, lv.verts[l], 0u, idx);
-      } else if (POW2) {
-        corner_indices_uniform<D, false>(c0, 0u, lv.T - 1u, idx);
-      } else {
-        const CornerTerms<D> ct = corner_terms<D>(c0, false, 0u);
-#pragma unroll
-        for (uint32_t m = 0; m < (1u << D); ++m) idx[m] = corner_index<D>(ct, m, false, lv.T, false);
-      }
-      const Vec<PT, 2>* tab = reinterpret_cast<const Vec<PT, 2>*>(theta) + lv.offset[l];
-      Vec<PT, 2> e[1 << D];
+      uint32_t idx[1 << D];
+      float wr[1 << (D - 1)], w0, u0;
+      level_corners<D, POW2>(lv, l, smooth, xp, idx, wr, w0, u0);
+      const Vec<PT, F>* tab = reinterpret_cast<const Vec<PT, F>*>(theta) + lv.offset[l];
+      Vec<PT, F> e[1 << D];
 #pragma unroll
       for (uint32_t m = 0; m < (1u << D); ++m) e[m] = tab[idx[m]];
-      // weights of the corners along dimensions 1.., then dimension 0 last: 2^(D-1) + 2^D products
-      float wr[1 << (D - 1)];
+      float acc[F];
 #pragma unroll
-      for (uint32_t r = 0; r < (1u << (D - 1)); ++r) {
-        float p = 1.0f;
-#pragma unroll
-        for (int i = 1; i < D; ++i) p *= ((r >> (i - 1)) & 1u) ? w[i] : u[i];
-        wr[r] = p;
-      }
-      float a0 = 0.0f, a1 = 0.0f;
+      for (int f = 0; f < F; ++f) acc[f] = 0.0f;
 #pragma unroll
       for (uint32_t m = 0; m < (1u << D); ++m) {
-        const float wt = wr[m >> 1] * ((m & 1u) ? w[0] : u[0]);
-        a0 = fmaf(wt, (float)e[m].v[0], a0);
-        a1 = fmaf(wt, (float)e[m].v[1], a1);
+        const float wt = wr[m >> 1] * ((m & 1u) ? w0 : u0);
+#pragma unroll
+        for (int f = 0; f < F; ++f) acc[f] = fmaf(wt, (float)e[m].v[f], acc[f]);
       }
-      out.v[2 * j] = (IT)a0;
-      out.v[2 * j + 1] = (IT)a1;
+#pragma unroll
+      for (int f = 0; f < F; ++f) out.v[F * j + f] = (IT)acc[f];
       asm volatile("" ::: "memory");  // keep the gathers of one level together
       __syncthreads();
     }
     const uint32_t piece = l0 / G;
-    if ((piece & 1u) == 0 && l0 + G < lv.L) {
+    if (Piece::kPair && (piece & 1u) == 0 && l0 + G < lv.L) {
       held = out;  // even piece with a partner: keep it until the partner is ready
     } else if (valid) {
-      if (piece & 1u) yrow[piece - 1] = held;
+      if (Piece::kPair && (piece & 1u)) yrow[piece - 1] = held;
       yrow[piece] = out;
     }
   }
@@ -354,16 +377,16 @@ static hg_status launched() { return hipGetLastError() == hipSuccess ? HG_OK : H
 template <int D, int F, typename PT, typename IT>
 static hg_status launch_fwd(const hashgrid* h, uint32_t B, const float* x, const void* params, void* y,
                             hipStream_t s) {
-  if constexpr (F == 2) {
-    constexpr uint32_t G = 16 / (2 * sizeof(IT));
-    if (h->lv.L % G == 0 && !misaligned(y, 16)) {
+  {
+    constexpr uint32_t G = OutPiece<F, IT>::kLevels;
+    if (h->lv.L % G == 0 && !misaligned(y, 16) && !misaligned(params, F * sizeof(PT) > 16 ? 16 : F * sizeof(PT))) {
       const dim3 grid((B + kPmBlock - 1) / kPmBlock);
       const bool smooth = h->cfg.interp == HG_INTERP_SMOOTHSTEP;
       if (h->lv.T_is_pow2)
-        hipLaunchKernelGGL((fwd_point_major<D, PT, IT, true>), grid, dim3(kPmBlock), 0, s, h->lv, smooth, B, x,
+        hipLaunchKernelGGL((fwd_point_major<D, F, PT, IT, true>), grid, dim3(kPmBlock), 0, s, h->lv, smooth, B, x,
                            static_cast<const PT*>(params), static_cast<IT*>(y));
       else
-        hipLaunchKernelGGL((fwd_point_major<D, PT, IT, false>), grid, dim3(kPmBlock), 0, s, h->lv, smooth, B, x,
+        hipLaunchKernelGGL((fwd_point_major<D, F, PT, IT, false>), grid, dim3(kPmBlock), 0, s, h->lv, smooth, B, x,
                            static_cast<const PT*>(params), static_cast<IT*>(y));
       return launched();
     }
