@@ -237,6 +237,91 @@ __global__ __launch_bounds__(kPmBlock) void fwd_point_major(const LevelTable lv,
   }
 }
 
+// Gradient with respect to the position, point-major, same structure as the forward kernel
+// (one barrier per level, dL/dy read as 16-byte pieces).  Per level the 2^D gathered entries
+// are first contracted with dL/dy (s_m = sum_f g_f theta_m,f); the derivative of the d-linear
+// blend of the s_m then follows dimension by dimension: along a dimension with weights (u, w)
+// and slope dw, a pair (lower a, upper b) becomes value u a + w b and derivative dw (b - a).
+template <int D, int F, typename PT, typename IT, bool POW2>
+__global__ __launch_bounds__(kPmBlock) void bwd_input_point_major(const LevelTable lv, const bool smooth,
+                                                                  const uint32_t B, const float* __restrict__ x,
+                                                                  const PT* __restrict__ theta,
+                                                                  const IT* __restrict__ dy, float* __restrict__ dx) {
+  using Piece = OutPiece<F, IT>;
+  constexpr int G = Piece::kLevels;
+  const uint32_t b0 = blockIdx.x * kPmBlock + threadIdx.x;
+  const bool valid = b0 < B;
+  const uint32_t b = valid ? b0 : B - 1;
+  float xp[D];
+  load_point<D>(x, b, xp);
+  const Vec<IT, F * G>* grow = reinterpret_cast<const Vec<IT, F * G>*>(dy + (uint64_t)b * lv.L * F);
+  float gx[D];
+#pragma unroll
+  for (int j = 0; j < D; ++j) gx[j] = 0.0f;
+  const float shift = smooth ? 0.5f : 0.0f;
+  for (uint32_t l0 = 0; l0 < lv.L; l0 += G) {
+    const Vec<IT, F * G> g = grow[l0 / G];
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+      const uint32_t l = l0 + j;
+      const float Nf = (float)lv.N[l];
+      const float cmaxf = smooth ? Nf : Nf - 1.0f;
+      uint32_t c0[D], idx[1 << D];
+      float w[D], u[D], dw[D];
+#pragma unroll
+      for (int i = 0; i < D; ++i) {
+        float wf;
+        split(xp[i], Nf, shift, cmaxf, c0[i], wf);
+        w[i] = smooth ? smoothstep(wf) : wf;
+        u[i] = smooth ? smoothstep(1.0f - wf) : 1.0f - wf;
+        dw[i] = smooth ? dsmoothstep(wf) * Nf : Nf;
+      }
+      if ((lv.dense_mask >> l) & 1u) {  // uniform
+        corner_indices_uniform<D, true>(c0, lv.verts[l], 0u, idx);
+      } else if (POW2) {
+        corner_indices_uniform<D, false>(c0, 0u, lv.T - 1u, idx);
+      } else {
+        const CornerTerms<D> ct = corner_terms<D>(c0, false, 0u);
+#pragma unroll
+        for (uint32_t m = 0; m < (1u << D); ++m) idx[m] = corner_index<D>(ct, m, false, lv.T, false);
+      }
+      const Vec<PT, F>* tab = reinterpret_cast<const Vec<PT, F>*>(theta) + lv.offset[l];
+      Vec<PT, F> e[1 << D];
+#pragma unroll
+      for (uint32_t m = 0; m < (1u << D); ++m) e[m] = tab[idx[m]];
+      // val[m]: blend over the dimensions folded so far; der[i][m]: its derivative along dimension i
+      float val[1 << D], der[D][1 << D];
+#pragma unroll
+      for (uint32_t m = 0; m < (1u << D); ++m) {
+        float sm = 0.0f;
+#pragma unroll
+        for (int f = 0; f < F; ++f) sm = fmaf((float)g.v[F * j + f], (float)e[m].v[f], sm);
+        val[m] = sm;
+      }
+#pragma unroll
+      for (int i = 0; i < D; ++i) {        // fold dimension i: corners m (bit i clear) and m | 1<<i
+#pragma unroll
+        for (uint32_t m = 0; m < (1u << D); ++m) {
+          if (m & ((2u << i) - 1u)) continue;  // representatives: bits 0..i clear
+          const uint32_t hi = m | (1u << i);
+#pragma unroll
+          for (int k = 0; k < i; ++k) der[k][m] = u[i] * der[k][m] + w[i] * der[k][hi];
+          der[i][m] = dw[i] * (val[hi] - val[m]);
+          val[m] = u[i] * val[m] + w[i] * val[hi];
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < D; ++i) gx[i] += der[i][0];
+      asm volatile("" ::: "memory");
+      __syncthreads();
+    }
+  }
+  if (valid) {
+#pragma unroll
+    for (int i = 0; i < D; ++i) dx[(uint64_t)b * D + i] = gx[i];
+  }
+}
+
 // Backward to the tables, Fig. 3 caption: scatter-add of weight * dL/dy.
 //
 // The L2 atomic units of this chip retire about one atomic *request* per clock
@@ -401,6 +486,20 @@ static hg_status launch_fwd(const hashgrid* h, uint32_t B, const float* x, const
 template <int D, int F, typename PT, typename IT>
 static hg_status launch_bwd_input(const hashgrid* h, uint32_t B, const float* x, const void* params,
                                   const void* dy, float* dx, hipStream_t s) {
+  {
+    constexpr uint32_t G = OutPiece<F, IT>::kLevels;
+    if (h->lv.L % G == 0 && !misaligned(dy, 16) && !misaligned(params, F * sizeof(PT) > 16 ? 16 : F * sizeof(PT))) {
+      const dim3 pm_grid((B + kPmBlock - 1) / kPmBlock);
+      const bool smooth = h->cfg.interp == HG_INTERP_SMOOTHSTEP;
+      if (h->lv.T_is_pow2)
+        hipLaunchKernelGGL((bwd_input_point_major<D, F, PT, IT, true>), pm_grid, dim3(kPmBlock), 0, s, h->lv, smooth,
+                           B, x, static_cast<const PT*>(params), static_cast<const IT*>(dy), dx);
+      else
+        hipLaunchKernelGGL((bwd_input_point_major<D, F, PT, IT, false>), pm_grid, dim3(kPmBlock), 0, s, h->lv, smooth,
+                           B, x, static_cast<const PT*>(params), static_cast<const IT*>(dy), dx);
+      return launched();
+    }
+  }
   dim3 grid((B + kBlock - 1) / kBlock);
   hipLaunchKernelGGL((bwd_input_general<D, F, PT, IT>), grid, dim3(kBlock), 0, s, h->lv,
                      h->cfg.interp == HG_INTERP_SMOOTHSTEP, B, x, static_cast<const PT*>(params),
