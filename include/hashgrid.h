@@ -119,7 +119,10 @@ uint64_t hashgrid_bwd_workspace_bytes(const hashgrid_t* hg, uint32_t B);
  * 64-bit fixed point scaled to the largest |dLdy| of the call (each summand is
  * rounded to about 2^-38 of that value or finer), so the result does not depend
  * on the order of execution, except on coarse 1:1 levels whose few chunks are
- * shared by several workgroups and combined with fp32 atomic adds.
+ * shared by several workgroups and combined with fp32 atomic adds.  When dLdy
+ * is fp16 the sorted records carry the interpolation weights as 23- and 25-bit
+ * fixed point: a gradient entry then differs from hashgrid_encode_bwd's by at
+ * most about 2^-23 times the sum of |dLdy| over the corners that touch it.
  *   workspace  device, 256-byte aligned, at least hashgrid_bwd_workspace_bytes(hg, B)
  *              bytes, owned by the caller; contents are scratch: undefined on
  *              entry and on exit.  Calls that overlap in time need separate

@@ -18,9 +18,13 @@
 //              entries) that holds both corners.  This kernel only counts.
 //   scan       per-bin totals and per-(workgroup, bin) write offsets.
 //   scatter    recomputes the records, sorts them by bin in LDS one level at a
-//              time and writes each to its slot: 16 bytes = two chunk-local
-//              indices, the fractional position along dimension 0 and dL/dy
-//              times the weight of the other dimensions.
+//              time and writes each to its slot.  A record names the two
+//              chunk-local entries and carries the fractional position along
+//              dimension 0, the weight of the other dimensions and dL/dy of the
+//              level: 16 bytes when dL/dy is fp32, 12 bytes when it is fp16
+//              (see Record below).  The passes that write and re-read the
+//              records are bound by memory bandwidth, so the record size is
+//              what sets their time.
 //   accumulate one workgroup per bin (several for the few bins of coarse 1:1
 //              levels, which receive very many records): sums its records into
 //              LDS in 64-bit fixed point with integer atomics, then adds the
@@ -28,8 +32,8 @@
 //              has a single owner).  The fixed-point scale comes from the
 //              largest |dL/dy| of the call, with headroom for 8*B summands, so
 //              the sum is exact and independent of the order of the records;
-//              each summand is rounded to 2^-(62-H) of that largest value
-//              (H = ceil(log2(8B))).
+//              each summand is rounded once to 2^-min(62-H, 51) of the power of
+//              two above that largest value (H = ceil(log2(8B))).
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
@@ -40,7 +44,7 @@
 
 namespace hg {
 
-using u32x4 = uint32_t __attribute__((ext_vector_type(4)));  // one 16-byte record
+using u32x4 = uint32_t __attribute__((ext_vector_type(4)));
 
 #ifndef HG_BIN_THREADS
 #define HG_BIN_THREADS 512
@@ -55,10 +59,14 @@ constexpr int kAccThreads = HG_ACC_THREADS;
 #define HG_ACC_UNROLL 4
 #endif
 constexpr int kAccUnroll = HG_ACC_UNROLL;
-#ifndef HG_ACC_PRE
-#define HG_ACC_PRE 8
+#ifndef HG_ACC_PRE_WORDS
+#define HG_ACC_PRE_WORDS 24
 #endif
-constexpr int kAccPre = HG_ACC_PRE;  // records per lane requested one item ahead
+constexpr int kAccPreWords = HG_ACC_PRE_WORDS;  // registers per lane for records requested one item ahead, half
+                                                // of them half an item earlier still
+#ifndef HG_ACC_WGS_PER_CU
+#define HG_ACC_WGS_PER_CU 1u
+#endif
 #ifndef HG_CHUNK_LOG2
 #define HG_CHUNK_LOG2 12
 #endif
@@ -67,13 +75,128 @@ constexpr uint32_t kTargetRecordsPerAccWg = 16384;
 constexpr uint32_t kMaxParts = 4;       // level parts of the count / scatter grids
 constexpr uint64_t kMaxBinLds = 7 * 1024;  // bound on 4 * (number of bins): per-part LDS arrays stay small
 
+// One record = one pair of corners that differ along dimension 0, both inside one
+// chunk: local indices la (lower corner) and lb (upper corner), the fractional
+// position wf0 along dimension 0 and what the pair receives in total, wrow * dL/dy.
+template <typename IT>
+struct Record;
+
+// dL/dy in fp32: 16 bytes {la | lb << 16, wf0, wrow * dL/dy_0, wrow * dL/dy_1}, all fp32.
+template <>
+struct Record<float> {
+  using Stored = u32x4;
+  static constexpr uint32_t kWords = 4;
+  static __device__ __forceinline__ Stored make(uint32_t la, uint32_t lb, uint32_t /*k*/, float wf0, float wrow,
+                                                float g0, float g1) {
+    Stored r;
+    r.x = la | (lb << 16);
+    r.y = __float_as_uint(wf0);
+    r.z = __float_as_uint(wrow * g0);
+    r.w = __float_as_uint(wrow * g1);
+    return r;
+  }
+  static __device__ __forceinline__ Stored load(const uint32_t* base, uint32_t i) {
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base) + i);
+  }
+  static __device__ __forceinline__ void unpack(const Stored& r, bool /*dense*/, uint32_t cmask, uint32_t& la,
+                                                uint32_t& lb, float& wf0, float& g0, float& g1) {
+    la = r.x & cmask;
+    lb = (r.x >> 16) & cmask;
+    wf0 = __uint_as_float(r.y);
+    g0 = __uint_as_float(r.z);
+    g1 = __uint_as_float(r.w);
+  }
+  // the same with the pair's two totals as doubles, times `scale`
+  static __device__ __forceinline__ void unpack_scaled(const Stored& r, bool dense, uint32_t cmask, double scale,
+                                                       uint32_t& la, uint32_t& lb, float& wf0, double& G0,
+                                                       double& G1) {
+    float g0, g1;
+    unpack(r, dense, cmask, la, lb, wf0, g0, g1);
+    G0 = (double)g0 * scale;
+    G1 = (double)g1 * scale;
+  }
+};
+
+// dL/dy in fp16: 12 bytes.  Bits 0-11 la; bits 12-15 k, where on a hashed level
+// lb = la ^ (2^(k+1) - 1) (k = number of trailing one bits of the lower corner's
+// coordinate along dimension 0: pi_1 = 1 in Eq. 4, so stepping that coordinate
+// XORs the index with this mask) and on a 1:1 level lb = la + 1; bits 16-38 wf0
+// in units of 2^-23 (exact whenever the scaled coordinate is 1 or more, because
+// then its fraction is a multiple of 2^-23; otherwise rounded, off by 2^-24 at
+// most); bits 39-63 wrow in units of 2^-24 (0 and 1 exact, off by 2^-25 at most);
+// the last word is the level's two fp16 values of dL/dy, untouched.  Both weights
+// lie in [0,1] and the weights of a pair, and of the rows of a point, sum to 1,
+// so the rounding moves a gradient entry by at most about 2^-23 times the sum of
+// |dL/dy| over the corners that touch it.
+struct Rec12 {
+  uint32_t a, b, c;
+};
+static_assert(kChunkLog2 <= 12, "the 12-byte record holds a 12-bit local index");
+template <>
+struct Record<_Float16> {
+  using Stored = Rec12;
+  static constexpr uint32_t kWords = 3;
+  static __device__ __forceinline__ Stored make(uint32_t la, uint32_t /*lb*/, uint32_t k, float wf0, float wrow,
+                                                _Float16 g0, _Float16 g1) {
+    uint32_t q0 = (uint32_t)rintf(wf0 * 0x1p23f);
+    q0 = q0 < 0x7fffffu ? q0 : 0x7fffffu;
+    uint32_t qr = (uint32_t)rintf(wrow * 0x1p24f);
+    qr = qr < 0x1000000u ? qr : 0x1000000u;
+    const uint64_t p = (uint64_t)(la | (k << 12)) | ((uint64_t)q0 << 16) | ((uint64_t)qr << 39);
+    Vec<_Float16, 2> g;
+    g.v[0] = g0;
+    g.v[1] = g1;
+    Stored r;
+    r.a = (uint32_t)p;
+    r.b = (uint32_t)(p >> 32);
+    r.c = *reinterpret_cast<const uint32_t*>(&g);
+    return r;
+  }
+  static __device__ __forceinline__ Stored load(const uint32_t* base, uint32_t i) {
+    const uint32_t* p = base + (uint64_t)i * 3;
+    Stored r;
+    r.a = __builtin_nontemporal_load(p);
+    r.b = __builtin_nontemporal_load(p + 1);
+    r.c = __builtin_nontemporal_load(p + 2);
+    return r;
+  }
+  static __device__ __forceinline__ void unpack(const Stored& r, bool dense, uint32_t cmask, uint32_t& la,
+                                                uint32_t& lb, float& wf0, float& g0, float& g1) {
+    const uint64_t p = (uint64_t)r.a | ((uint64_t)r.b << 32);
+    la = r.a & 0xfffu;
+    const uint32_t k = (r.a >> 12) & 0xfu;
+    lb = (dense ? la + 1u : la ^ ((2u << k) - 1u)) & cmask;
+    wf0 = (float)((uint32_t)(p >> 16) & 0x7fffffu) * 0x1p-23f;
+    const float wrow = (float)(uint32_t)(p >> 39) * 0x1p-24f;
+    const Vec<_Float16, 2> g = *reinterpret_cast<const Vec<_Float16, 2>*>(&r.c);
+    g0 = wrow * (float)g.v[0];
+    g1 = wrow * (float)g.v[1];
+  }
+  // the same with the pair's two totals as doubles, times `scale`: wrow * dL/dy is a
+  // 25-bit by 11-bit product, exact in a double
+  static __device__ __forceinline__ void unpack_scaled(const Stored& r, bool dense, uint32_t cmask, double scale,
+                                                       uint32_t& la, uint32_t& lb, float& wf0, double& G0,
+                                                       double& G1) {
+    const uint64_t p = (uint64_t)r.a | ((uint64_t)r.b << 32);
+    la = r.a & 0xfffu;
+    const uint32_t k = (r.a >> 12) & 0xfu;
+    lb = (dense ? la + 1u : la ^ ((2u << k) - 1u)) & cmask;
+    wf0 = (float)((uint32_t)(p >> 16) & 0x7fffffu) * 0x1p-23f;
+    const double wrow = (double)(uint32_t)(p >> 39) * (scale * 0x1p-24);
+    const Vec<_Float16, 2> g = *reinterpret_cast<const Vec<_Float16, 2>*>(&r.c);
+    G0 = wrow * (double)(float)g.v[0];
+    G1 = wrow * (double)(float)g.v[1];
+  }
+};
+
 struct Workspace {
   uint32_t* counts;     // [n_tiles + 1][n_bins] counts, then exclusive prefix over tiles (last row: totals)
   uint32_t* bin_start;  // [n_bins] first record of the bin
   uint32_t* bin_total;  // [n_bins] records in the bin
   float* tile_max;      // [n_tiles * parts] largest |dL/dy| seen by each count workgroup
   float* call_max;      // [1] largest |dL/dy| of the call
-  uint4* records;       // [B * L * rec_per_point]
+  uint32_t* item_counter;  // [1] next work item of the accumulate pass
+  uint32_t* records;    // [B * L * rec_per_point] records of 3 or 4 words
   uint32_t n_tiles;
   uint32_t n_bins;
 };
@@ -91,15 +214,16 @@ static uint64_t carve(const hashgrid* h, uint32_t B, uint8_t* base, Workspace* w
     return o;
   };
   const uint64_t o_counts = take((uint64_t)(nt + 1) * nb * 4), o_start = take((uint64_t)nb * 4),
-                 o_total = take((uint64_t)nb * 4), o_max = take((uint64_t)nt * kMaxParts * 4), o_cmax = take(4),
-                 o_rec = take((uint64_t)B * h->lv.L * h->bp.rec_per_point * 16);
+                 o_total = take((uint64_t)nb * 4), o_max = take((uint64_t)nt * kMaxParts * 4), o_cmax = take(4), o_item = take(4),
+                 o_rec = take((uint64_t)B * h->lv.L * h->bp.rec_per_point * (h->cfg.io_dtype == HG_F16 ? 12 : 16));
   if (ws) {
     ws->counts = reinterpret_cast<uint32_t*>(base + o_counts);
     ws->bin_start = reinterpret_cast<uint32_t*>(base + o_start);
     ws->bin_total = reinterpret_cast<uint32_t*>(base + o_total);
     ws->tile_max = reinterpret_cast<float*>(base + o_max);
     ws->call_max = reinterpret_cast<float*>(base + o_cmax);
-    ws->records = reinterpret_cast<uint4*>(base + o_rec);
+    ws->item_counter = reinterpret_cast<uint32_t*>(base + o_item);
+    ws->records = reinterpret_cast<uint32_t*>(base + o_rec);
     ws->n_tiles = nt;
     ws->n_bins = nb;
   }
@@ -172,6 +296,7 @@ struct Rows {
   uint32_t pack[1 << (D - 1)];   // chunk-local index of the lower | upper << 16 corner along dimension 0
   float wrow[1 << (D - 1)];      // product of the weights of dimensions 1..d-1
   float wf0;                     // fractional position along dimension 0 (before any smoothstep)
+  uint32_t k;                    // trailing one bits of the lower corner's coordinate along dimension 0
 };
 
 template <int D, bool COUNT_ONLY>
@@ -195,6 +320,7 @@ __device__ __forceinline__ void rows_of(const LevelTable& lv, const BinPlan& bp,
   const uint32_t cl = bp.chunk_log2, cmask = (1u << cl) - 1u;
   const uint32_t gb0 = bp.bin_base[l];
   if (!COUNT_ONLY) {
+    out.k = (uint32_t)__builtin_ctz(~c0[0]) & 15u;  // c0 + 1 < 2^chunk_log2 <= 2^15 on hashed levels
 #pragma unroll
     for (uint32_t r = 0; r < (1u << (D - 1)); ++r) {
       float wr = 1.0f;
@@ -371,7 +497,8 @@ __global__ __launch_bounds__(kScanThreads) void bin_scan(const uint32_t n_tiles,
                                                          uint32_t* __restrict__ counts,
                                                          uint32_t* __restrict__ bin_total,
                                                          const float* __restrict__ tile_max,
-                                                         float* __restrict__ call_max) {
+                                                         float* __restrict__ call_max,
+                                                         uint32_t* __restrict__ item_counter) {
   __shared__ uint32_t seg_sum[kScanThreads];
   __shared__ float red[kScanThreads / 64];
   if (blockIdx.x == 0) {  // largest |dL/dy| of the call; NaN wins
@@ -391,6 +518,7 @@ __global__ __launch_bounds__(kScanThreads) void bin_scan(const uint32_t n_tiles,
       m = red[0];
       for (int i = 1; i < kScanThreads / 64; ++i) m = (red[i] > m || red[i] != red[i]) ? red[i] : m;
       call_max[0] = m;
+      item_counter[0] = 0;  // the accumulate pass draws its work items from here
     }
   }
   constexpr uint32_t segs = kScanThreads / kScanBins;
@@ -466,12 +594,14 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, 
                                                            const uint32_t* __restrict__ counts,
                                                            const uint32_t* __restrict__ bin_total,
                                                            uint32_t* __restrict__ bin_start,
-                                                           u32x4* __restrict__ records, const uint32_t n_bins,
+                                                           uint32_t* __restrict__ records, const uint32_t n_bins,
                                                            const uint32_t n_records, const uint32_t n_tiles) {
   constexpr uint32_t R = 1u << (D - 1);
+  using Rec = Record<IT>;
+  typename Rec::Stored* out = reinterpret_cast<typename Rec::Stored*>(records);
   extern __shared__ uint32_t lds_u32[];
   __shared__ uint32_t scan_tmp[kBinThreads / 64];
-  __shared__ u32x4 staging[R * kBinThreads];
+  __shared__ typename Rec::Stored staging[R * kBinThreads];
   __shared__ uint16_t binv[R * kBinThreads];  // part-relative bin of each staged record
 
   const uint32_t tile = tile_of_workgroup(blockIdx.x, n_tiles);
@@ -524,21 +654,21 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, 
   for (uint32_t l = l0; l < l1; ++l) {
     const uint32_t rb0 = bp.bin_base[l] - gb_a, rb1 = bp.bin_base[l + 1] - gb_a;
     const uint32_t level_first = local[rb0], emitted = local[rb1] - level_first;  // <= R * kBinThreads
-    float g0, g1;
+    IT g0, g1;
     if (vec_ok) {  // uniform
       if ((l - l0) % K == 0) gv = *reinterpret_cast<const Vec<IT, 2 * K>*>(row + (uint64_t)l * 2);
       const uint32_t k = (l - l0) % K;
-      g0 = (float)gv.v[0];
-      g1 = (float)gv.v[1];
+      g0 = gv.v[0];
+      g1 = gv.v[1];
 #pragma unroll
       for (uint32_t q = 1; q < K; ++q) {
-        g0 = k == q ? (float)gv.v[2 * q] : g0;
-        g1 = k == q ? (float)gv.v[2 * q + 1] : g1;
+        g0 = k == q ? gv.v[2 * q] : g0;
+        g1 = k == q ? gv.v[2 * q + 1] : g1;
       }
     } else {
       const Vec<IT, 2> g = reinterpret_cast<const Vec<IT, 2>*>(row)[l];
-      g0 = (float)g.v[0];
-      g1 = (float)g.v[1];
+      g0 = g.v[0];
+      g1 = g.v[1];
     }
     if (valid) {
       Rows<D> rw;
@@ -549,12 +679,7 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, 
         const uint32_t in_tile = __hip_atomic_fetch_add(&cur[rb], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         const uint32_t pos = in_tile - level_first;
         if (pos < R * kBinThreads) {  // holds when the count pass saw the same x
-          u32x4 rec;
-          rec.x = rw.pack[r];
-          rec.y = __float_as_uint(rw.wf0);
-          rec.z = __float_as_uint(rw.wrow[r] * g0);
-          rec.w = __float_as_uint(rw.wrow[r] * g1);
-          staging[pos] = rec;
+          staging[pos] = Rec::make(rw.pack[r] & 0xffffu, rw.pack[r] >> 16, rw.k, rw.wf0, rw.wrow[r], g0, g1);
           binv[pos] = (uint16_t)rb;
         }
       }
@@ -564,37 +689,39 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, 
       const uint32_t d = delta[binv[j]] + level_first + j;
       // the count pass saw the same inputs, so d < n_records; the check only keeps a
       // caller who changed x in between from writing out of bounds
-      if (d < n_records) records[d] = staging[j];
+      if (d < n_records) out[d] = staging[j];
     }
     __syncthreads();
   }
 }
 
-// round(t * 2^S) as a 64-bit integer, for |t| * 2^S < 2^62.  An fp32 value has 24
-// significant bits, so above 2^32 the scaled magnitude splits exactly into a high
-// and a low 32-bit half; only values below 2^24 have a fraction to round.
-__device__ __forceinline__ long long to_fixed(float t, int S) {
-  const float a = ldexpf(fabsf(t), S);
-  const float hi = floorf(a * 0x1p-32f);
-  const float lo = fmaf(-hi, 0x1p32f, a);  // exact, in [0, 2^32)
-  const unsigned long long mag = ((unsigned long long)(uint32_t)hi << 32) | (unsigned long long)(uint32_t)rintf(lo);
-  const long long sgn = (long long)(__float_as_int(t) >> 31);  // 0 or -1
-  return ((long long)mag ^ sgn) - sgn;
+// round(w * G) to a 64-bit integer (ties to even), for |w * G| < 2^51: adding
+// 1.5 * 2^52 leaves the integer, in two's complement, in the low bits of the
+// double.  One rounding, of the exact product.
+constexpr int kFixedBits = 51;
+__device__ __forceinline__ unsigned long long fixed_product(float w, double G) {
+  const double d = __builtin_fma((double)w, G, 0x1.8p52);
+  return (unsigned long long)(__double_as_longlong(d) - __double_as_longlong(0x1.8p52));
 }
 
-// accumulate: work item = (bin, slice).  The grid is persistent (two workgroups
-// per CU, which is what 64 KiB of LDS each allows) and workgroup w takes items
-// w, w + gridDim.x, ...: the first record and the count of the next item are
-// fetched while the current one is streamed, so the chain "offsets -> records"
-// is paid once per workgroup, not once per bin, and the LDS accumulators are
-// re-zeroed by the lanes that have just read them.
-__global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable lv, const BinPlan bp, const bool smooth,
+// accumulate: work item = (bin, slice).  The grid is persistent: workgroup w
+// starts with item w and then draws items from a device-wide counter, two items
+// ahead, so that the first records and the count of the next item are fetched
+// while the current one is streamed (the chain "offsets -> records" is paid once
+// per workgroup, not once per bin) and workgroups that drew short items simply
+// draw more of them: items differ in size by a factor of ten on 1:1 levels when
+// the points crowd around a surface.  The LDS accumulators are re-zeroed by the
+// lanes that have just read them.
+template <typename IT, bool SMOOTH>
+__global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable lv, const BinPlan bp,
                                                               const uint32_t B, const uint32_t n_items,
                                                               const uint32_t* __restrict__ bin_start,
                                                               const uint32_t* __restrict__ bin_total,
                                                               const float* __restrict__ call_max,
-                                                              const uint4* __restrict__ records,
+                                                              const uint32_t* __restrict__ records,
+                                                              uint32_t* __restrict__ item_counter,
                                                               float* __restrict__ grad) {
+  __shared__ uint32_t s_ticket;
   extern __shared__ unsigned long long acc[];  // [2][2^chunk_log2] fixed point: feature 0 of every entry, then
                                                // feature 1, so that consecutive entries map to consecutive banks
   const float m = call_max[0];  // largest |dL/dy| of the call (NaN if any is NaN)
@@ -607,11 +734,18 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
   int E = 0;
   if (finite) (void)frexpf(m, &E);
   const int H = 3 + (32 - __builtin_clz(B > 1 ? B - 1 : 1));
-  const int S = 62 - H - E;
+  const int S = (62 - H < kFixedBits ? 62 - H : kFixedBits) - E;  // |summand| * 2^S < 2^min(62-H, 51)
+  const double scale = ldexp(1.0, S), inv_scale = ldexp(1.0, -S);
   constexpr int kPer = (1 << kChunkLog2) / kAccThreads;  // entries per lane
 
+  // item_counter starts at 0 (bin_scan clears it); a ticket is the item it stands for
+  auto draw = [&]() {
+    return gridDim.x + __hip_atomic_fetch_add(item_counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  };
+  if (threadIdx.x == 0) s_ticket = draw();
   for (uint32_t i = threadIdx.x; i < 2 * cap; i += kAccThreads) acc[i] = 0ull;
   __syncthreads();
+  uint32_t next = s_ticket;  // every item number of n_items or more ends the loop, and tickets only grow
 
   // which level, bin and slice an item is
   auto decode = [&](uint32_t item, uint32_t& l, uint32_t& bin, uint32_t& slice) {
@@ -623,14 +757,16 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
   };
 
   // Everything an item needs before its records can be used: where they are, which chunk of
-  // the gradient it owns, and (software pipeline) its first kAccPre records per lane and its
+  // the gradient it owns, and (software pipeline) its first kPre records per lane and its
   // gradient chunk, both requested while the previous item is still being flushed.
   struct Item {
     uint32_t l, n_sl, r0, r1, n_e;
     float* gl;
-    bool live;
+    bool live, dense;
   };
-  const u32x4* rp = reinterpret_cast<const u32x4*>(records);
+  using Rec = Record<IT>;
+  using Stored = typename Rec::Stored;
+  constexpr int kPre = kAccPreWords / (int)Rec::kWords, kHalf = kPre / 2;
   auto describe = [&](uint32_t item, uint32_t start, uint32_t total, uint32_t l, uint32_t bin, uint32_t slice) {
     Item it;
     it.l = l;
@@ -640,7 +776,8 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
     it.r1 = (slice * per + per < total) ? it.r0 + per : start + total;
     it.live = item < n_items && slice * per < total;
     uint32_t e0, e1;  // entries of this chunk in the level's slice
-    if ((lv.dense_mask >> l) & 1u) {
+    it.dense = (lv.dense_mask >> l) & 1u;
+    if (it.dense) {
       e0 = (bin << bp.row_shift[l]) * lv.verts[l];
       e1 = e0 + (lv.verts[l] << bp.row_shift[l]);
     } else {
@@ -652,13 +789,18 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
     it.gl = grad + (lv.offset[l] + e0) * 2;
     return it;
   };
-  auto request = [&](const Item& it, u32x4 (&pre)[kAccPre], float2 (&cur)[kPer]) {
+  // records j0..j1-1 of each lane's share of the item
+  auto request_records = [&](const Item& it, Stored (&pre)[kPre], const int j0, const int j1) {
     if (!it.live || !finite) return;
 #pragma unroll
-    for (int j = 0; j < kAccPre; ++j) {
+    for (int j = 0; j < kPre; ++j) {
+      if (j < j0 || j >= j1) continue;
       const uint32_t i = it.r0 + threadIdx.x + j * kAccThreads;
-      if (i < it.r1) pre[j] = __builtin_nontemporal_load(rp + i);
+      if (i < it.r1) pre[j] = Rec::load(records, i);
     }
+  };
+  auto request_chunk = [&](const Item& it, float2 (&cur)[kPer]) {
+    if (!it.live || !finite) return;
     if (it.n_sl == 1) {
 #pragma unroll
       for (int j = 0; j < kPer; ++j) {
@@ -676,12 +818,14 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
     total = bin_total[bp.bin_base[l] + bin];
   }
   Item it = describe(item, start, total, l, bin, slice);
-  u32x4 pre[kAccPre];
+  Stored pre[kPre];
   float2 cur[kPer];
-  request(it, pre, cur);
+  request_records(it, pre, 0, kPre);
+  request_chunk(it, cur);
   while (item < n_items) {
-    // offsets of the next item: in flight while this one is processed
-    const uint32_t next = item + gridDim.x;
+    // the item after the next one, and the offsets of the next one: in flight while this one is processed
+    uint32_t ticket = 0;
+    if (threadIdx.x == 0) ticket = draw();
     uint32_t l_n = 0, bin_n = 0, slice_n = 0, start_n = 0, total_n = 0;
     if (next < n_items) {
       decode(next, l_n, bin_n, slice_n);
@@ -694,10 +838,10 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
     if (it.live && !finite) {
       // inf or NaN upstream: keep IEEE semantics with direct fp32 atomics (slow, rare)
       for (uint32_t i = it.r0 + threadIdx.x; i < it.r1; i += kAccThreads) {
-        const u32x4 rec = rp[i];
-        const uint32_t la = rec.x & cmask, lb = (rec.x >> 16) & cmask;
-        const float wf = __uint_as_float(rec.y), g0 = __uint_as_float(rec.z), g1 = __uint_as_float(rec.w);
-        const float wu = smooth ? smoothstep(wf) : wf, wl = smooth ? smoothstep(1.0f - wf) : 1.0f - wf;
+        uint32_t la, lb;
+        float wf, g0, g1;
+        Rec::unpack(Rec::load(records, i), it.dense, cmask, la, lb, wf, g0, g1);
+        const float wu = SMOOTH ? smoothstep(wf) : wf, wl = SMOOTH ? smoothstep(1.0f - wf) : 1.0f - wf;
         if (la < it.n_e) {
           __hip_atomic_fetch_add(it.gl + 2 * la, wl * g0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           __hip_atomic_fetch_add(it.gl + 2 * la + 1, wl * g1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -708,38 +852,51 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
         }
       }
       it_n = describe(next, start_n, total_n, l_n, bin_n, slice_n);
-    } else if (it.live) {
-      auto add_record = [&](const u32x4 rec) {
-        const uint32_t la = rec.x & cmask, lb = (rec.x >> 16) & cmask;
-        const float wf = __uint_as_float(rec.y), g0 = __uint_as_float(rec.z), g1 = __uint_as_float(rec.w);
-        const float wu = smooth ? smoothstep(wf) : wf, wl = smooth ? smoothstep(1.0f - wf) : 1.0f - wf;
-        __hip_atomic_fetch_add(&acc0[la], (unsigned long long)to_fixed(wl * g0, S), __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_WORKGROUP);
-        __hip_atomic_fetch_add(&acc1[la], (unsigned long long)to_fixed(wl * g1, S), __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_WORKGROUP);
-        __hip_atomic_fetch_add(&acc0[lb], (unsigned long long)to_fixed(wu * g0, S), __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_WORKGROUP);
-        __hip_atomic_fetch_add(&acc1[lb], (unsigned long long)to_fixed(wu * g1, S), __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_WORKGROUP);
+    } else if (!it.live) {
+      it_n = describe(next, start_n, total_n, l_n, bin_n, slice_n);
+      request_records(it_n, pre, 0, kPre);
+      request_chunk(it_n, cur_n);
+    } else {
+      auto add_record = [&](const Stored& rec) {
+        uint32_t la, lb;
+        float wf;
+        double G0, G1;
+        Rec::unpack_scaled(rec, it.dense, cmask, scale, la, lb, wf, G0, G1);
+        const float wu = SMOOTH ? smoothstep(wf) : wf, wl = SMOOTH ? smoothstep(1.0f - wf) : 1.0f - wf;
+        __hip_atomic_fetch_add(&acc0[la], fixed_product(wl, G0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        __hip_atomic_fetch_add(&acc1[la], fixed_product(wl, G1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        __hip_atomic_fetch_add(&acc0[lb], fixed_product(wu, G0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        __hip_atomic_fetch_add(&acc1[lb], fixed_product(wu, G1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
       };
-      // the records requested ahead of time
+      // The records requested ahead of time, in two halves: as soon as the first half has been
+      // consumed its registers take the first half of the next item, so that loads stay in
+      // flight while the LDS atomics of this item run, not only while it is flushed.
 #pragma unroll
-      for (int j = 0; j < kAccPre; ++j)
+      for (int j = 0; j < kHalf; ++j)
+        if (it.r0 + threadIdx.x + j * kAccThreads < it.r1) add_record(pre[j]);
+      it_n = describe(next, start_n, total_n, l_n, bin_n, slice_n);
+      request_records(it_n, pre, 0, kHalf);
+#pragma unroll
+      for (int j = kHalf; j < kPre; ++j)
         if (it.r0 + threadIdx.x + j * kAccThreads < it.r1) add_record(pre[j]);
       // the rest of a long item, kAccUnroll loads in flight per lane
-      uint32_t i = it.r0 + threadIdx.x + kAccPre * kAccThreads;
+      uint32_t i = it.r0 + threadIdx.x + kPre * kAccThreads;
       for (; i + (kAccUnroll - 1) * kAccThreads < it.r1; i += kAccUnroll * kAccThreads) {
-        u32x4 rec[kAccUnroll];
+        Stored rec[kAccUnroll];
 #pragma unroll
-        for (int j = 0; j < kAccUnroll; ++j) rec[j] = __builtin_nontemporal_load(rp + i + j * kAccThreads);
+        for (int j = 0; j < kAccUnroll; ++j) rec[j] = Rec::load(records, i + j * kAccThreads);
 #pragma unroll
         for (int j = 0; j < kAccUnroll; ++j) add_record(rec[j]);
       }
-      for (; i < it.r1; i += kAccThreads) add_record(__builtin_nontemporal_load(rp + i));
-      // request the next item's records and gradient chunk, then flush this one under them
-      it_n = describe(next, start_n, total_n, l_n, bin_n, slice_n);
-      request(it_n, pre, cur_n);  // `pre` has been consumed: its registers take the next item's records
-      __syncthreads();
+      for (; i < it.r1; i += kAccThreads) add_record(Rec::load(records, i));
+      // request the rest of the next item's records and its gradient chunk, then flush this one under them
+      request_records(it_n, pre, kHalf, kPre);
+      request_chunk(it_n, cur_n);
+    }
+    if (threadIdx.x == 0) s_ticket = ticket;
+    __syncthreads();
+    const uint32_t after_next = s_ticket;  // written before the barrier above, rewritten only after the one below
+    if (it.live && finite) {
       if (it.n_sl == 1) {
 #pragma unroll
         for (int j = 0; j < kPer; ++j) {
@@ -750,8 +907,8 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
           if (e >= it.n_e) continue;
           // an entry no record reached gets -0.0f added, which leaves every float (either zero,
           // NaNs included) exactly as it was; storing it anyway keeps the stores of a wave contiguous
-          cur[j].x += a0 ? (float)ldexp((double)a0, -S) : -0.0f;
-          cur[j].y += a1 ? (float)ldexp((double)a1, -S) : -0.0f;
+          cur[j].x += a0 ? (float)((double)a0 * inv_scale) : -0.0f;
+          cur[j].y += a1 ? (float)((double)a1 * inv_scale) : -0.0f;
           reinterpret_cast<float2*>(it.gl)[e] = cur[j];
         }
       } else {
@@ -765,16 +922,14 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
           const long long a = (long long)*slot;
           *slot = 0ull;
           if (e < it.n_e && a != 0)
-            __hip_atomic_fetch_add(it.gl + q, (float)ldexp((double)a, -S), __ATOMIC_RELAXED,
+            __hip_atomic_fetch_add(it.gl + q, (float)((double)a * inv_scale), __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
         }
       }
-      __syncthreads();
-    } else {
-      it_n = describe(next, start_n, total_n, l_n, bin_n, slice_n);
-      request(it_n, pre, cur_n);
     }
+    __syncthreads();
     item = next;
+    next = after_next;
     it = it_n;
 #pragma unroll
     for (int j = 0; j < kPer; ++j) cur[j] = cur_n[j];
@@ -799,25 +954,36 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
   hipLaunchKernelGGL((bin_count<D, IT>), dim3(tile_wgs, parts), dim3(kBinThreads), lds_count, s, h->lv, bp, smooth,
                      B, x, static_cast<const IT*>(dy), ws.counts, ws.tile_max, ws.n_bins, ws.n_tiles);
   hipLaunchKernelGGL(bin_scan, dim3((ws.n_bins + kScanBins - 1) / kScanBins), dim3(kScanThreads), 0, s, ws.n_tiles,
-                     ws.n_tiles * parts, ws.n_bins, ws.counts, ws.bin_total, ws.tile_max, ws.call_max);
+                     ws.n_tiles * parts, ws.n_bins, ws.counts, ws.bin_total, ws.tile_max, ws.call_max,
+                     ws.item_counter);
   hipLaunchKernelGGL((bin_scatter<D, IT>), dim3(tile_wgs, parts), dim3(kBinThreads), lds_scatter, s, h->lv, bp,
                      smooth, B, x, static_cast<const IT*>(dy), ws.counts, ws.bin_total, ws.bin_start,
-                     reinterpret_cast<u32x4*>(ws.records), ws.n_bins, n_records, ws.n_tiles);
+                     ws.records, ws.n_bins, n_records, ws.n_tiles);
   // 64 KiB of dynamic LDS plus a few static bytes: above the default limit
-  static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_accumulate),
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, 16 << kChunkLog2);
+  static const hipError_t lds_ok = [] {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_accumulate<IT, false>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 16 << kChunkLog2);
+    return e != hipSuccess ? e
+                           : hipFuncSetAttribute(reinterpret_cast<const void*>(bin_accumulate<IT, true>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, 16 << kChunkLog2);
+  }();
   if (lds_ok != hipSuccess) return HG_ERR_DEVICE;
   const uint32_t n_items = bp.wg_base[h->lv.L];
-  static const uint32_t acc_slots = [] {  // two 64-KiB workgroups fit the 160 KiB of LDS of a CU
+  static const uint32_t acc_slots = [] {  // its registers let one 1024-thread workgroup run per CU; more would queue
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
       cus = 256;
-    return (uint32_t)cus * 2u;
+    return (uint32_t)cus * HG_ACC_WGS_PER_CU;
   }();
-  hipLaunchKernelGGL(bin_accumulate, dim3(n_items < acc_slots ? n_items : acc_slots), dim3(kAccThreads),
-                     (size_t)16 << bp.chunk_log2, s, h->lv, bp, smooth, B, n_items, ws.bin_start, ws.bin_total,
-                     ws.call_max, ws.records, grad);
+  const dim3 acc_grid(n_items < acc_slots ? n_items : acc_slots);
+  const size_t acc_lds = (size_t)16 << bp.chunk_log2;
+  if (smooth)
+    hipLaunchKernelGGL((bin_accumulate<IT, true>), acc_grid, dim3(kAccThreads), acc_lds, s, h->lv, bp, B, n_items,
+                       ws.bin_start, ws.bin_total, ws.call_max, ws.records, ws.item_counter, grad);
+  else
+    hipLaunchKernelGGL((bin_accumulate<IT, false>), acc_grid, dim3(kAccThreads), acc_lds, s, h->lv, bp, B, n_items,
+                       ws.bin_start, ws.bin_total, ws.call_max, ws.records, ws.item_counter, grad);
   return hipGetLastError() == hipSuccess ? HG_OK : HG_ERR_DEVICE;
 }
 

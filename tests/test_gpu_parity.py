@@ -12,7 +12,11 @@ Bars (fp32 arithmetic on the GPU, fp64 in the oracle):
                                      values of the summands of that entry (oracle run on |dL/dy|)
   backward, workspace variant        the same plus M 2^(H-54): it sums in 64-bit fixed point with
                                      each summand rounded to at most M 2^(H-62), M = max|dL/dy|,
-                                     H = 3 + ceil(log2 B); the floor allows 256 such roundings
+                                     H = max(3 + ceil(log2 B), 11); the floor allows 256 such roundings.
+                                     With fp16 dL/dy its records carry the interpolation weights as
+                                     fixed point (2^-23 and 2^-24 units), which moves each corner's
+                                     summand by at most 2^-23 |dL/dy|: the bound grows by 2^-23 G, G the
+                                     sum of |dL/dy| over the corners that touch the entry
 """
 import numpy as np
 import pytest
@@ -50,8 +54,22 @@ def check_bwd(g_gpu, g_ref, g_abs, floor=0.0):
 
 
 def ws_floor(dy, B):
-    H = 3 + int(np.ceil(np.log2(max(B, 2))))
+    H = max(3 + int(np.ceil(np.log2(max(B, 2)))), 11)  # summands carry at most 51 bits below the largest
     return float(np.abs(dy.astype(np.float64)).max()) * 2.0 ** (H - 54)
+
+
+def corner_abs_sum(cfg, lv, x, dy):
+    """G [total, F]: sum of |dL/dy| over every corner that maps to the entry (all weights taken as 1)."""
+    B = len(x)
+    a = np.abs(dy.astype(np.float64)).reshape(B, cfg.L, cfg.F)
+    G = np.zeros((lv.total, cfg.F))
+    for l in range(cfg.L):
+        idx, _ = orc.indices(cfg, x, l)
+        flat = idx.astype(np.int64).ravel()
+        for f in range(cfg.F):
+            G[int(lv.offset[l]):int(lv.offset[l]) + int(lv.size[l]), f] = np.bincount(
+                flat, weights=np.repeat(a[:, l, f], idx.shape[1]), minlength=int(lv.size[l]))
+    return G
 
 
 def run_case(d, L, F, T, N_min, N_max, pdt, iot, interp, x, theta, dy, do_indices=True, do_dx=True):
@@ -81,6 +99,8 @@ def run_case(d, L, F, T, N_min, N_max, pdt, iot, interp, x, theta, dy, do_indice
     check_bwd(g2.cpu().numpy(), 2 * g_ref, 2 * g_abs)
     if grid.bwd_workspace_bytes(len(x)):             # hashgrid_encode_bwd_ws: binned, fixed-point sums
         floor = ws_floor(dy, len(x))
+        if iot == "f16" and len(x):
+            floor = floor + 2.0 ** -23 * corner_abs_sum(cfg, lv, x, dy)
         gw = grid.encode_bwd(xd, gd)
         check_bwd(gw.cpu().numpy(), g_ref, g_abs, floor)
         gw2 = grid.encode_bwd(xd, gd, gw.clone())
@@ -251,7 +271,7 @@ def test_workspace_backward_argument_checks():
     grid = HashGrid(3, 16, 2, 1 << 19, 16, 2048)
     B = 1000
     need = grid.bwd_workspace_bytes(B)
-    assert need > B * 16 * 4 * 16
+    assert need > B * 16 * 4 * 12  # 12-byte records for fp16 dL/dy
     x = torch.rand((B, 3), device="cuda") * 0.99
     dy = torch.ones((B, 32), dtype=torch.float16, device="cuda")
     g = torch.zeros((grid.n_entries, 2), dtype=torch.float32, device="cuda")
