@@ -49,6 +49,31 @@ def measured_traffic(workload, which):
     return None
 
 
+def machine_probes(torch):
+    """What this GPU delivers on three elementary access patterns (hashgrid_probe_*): the measured
+    denominators next to the published 8 TB/s."""
+    from paper_2201_05989_amd import probe_atomic_add, probe_copy, probe_gather
+
+    out = {}
+    a = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")  # 1 GiB
+    b = torch.empty_like(a)
+    probe_copy(a, b)
+    out["copy_1GiB_gb_s"] = 2 * a.numel() * 4 / (time_launches(lambda: probe_copy(a, b), 10, torch) * 1e-3) / 1e9
+    del b
+    sink = torch.empty(1 << 22, dtype=torch.int32, device="cuda")
+    n = 1 << 26
+    for mib in (2, 64):
+        t = a[: mib << 18].view(torch.int32)
+        probe_gather(t, n, sink)
+        out[f"gather_4B_{mib}MiB_g_per_s"] = n / (time_launches(lambda: probe_gather(t, n, sink), 10, torch) * 1e-3) / 1e9
+    n = 1 << 25
+    for mib in (4, 128):
+        t = a[: mib << 18]
+        probe_atomic_add(t, n)
+        out[f"atomic_add_f32_{mib}MiB_g_per_s"] = n / (time_launches(lambda: probe_atomic_add(t, n), 5, torch) * 1e-3) / 1e9
+    return out
+
+
 def cpu_baseline(w, x, theta, dy, budget_s=10.0):
     import numpy as np
     from oracle import hashgrid_oracle as orc
@@ -77,6 +102,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="sdf3d")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-probes", action="store_true", help="skip the machine probes (copy, gather, atomic rates)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a 1 GiB device-to-device copy (20 times): the known-size kernel that "
                          "FETCH_SIZE / WRITE_SIZE counter readings are scaled by")
@@ -181,6 +207,20 @@ def main():
                      "fwd_achieved": b_fwd * w.B / (ms_fwd * 1e-3) / 1e9,
                      "bwd_achieved": b_bwd * w.B / (ms_bwd * 1e-3) / 1e9},
     }
+    if not args.no_probes:
+        # the pass rates in the elementary operations they stand for, next to what the machine does
+        # when it performs those operations one by one at random
+        corners = (1 << w.d) * w.L
+        probes = machine_probes(torch)
+        out["measured_peaks"] = probes
+        out["vs_measured"] = {
+            "fwd_gathers_g_per_s": corners * w.B / (ms_fwd * 1e-3) / 1e9,
+            "fwd_over_gather_2MiB": corners * w.B / (ms_fwd * 1e-3) / 1e9 / probes["gather_4B_2MiB_g_per_s"],
+            "bwd_scalar_adds_g_per_s": corners * w.F * w.B / (ms_bwd * 1e-3) / 1e9,
+            "bwd_over_atomic_add_4MiB": corners * w.F * w.B / (ms_bwd * 1e-3) / 1e9
+            / probes["atomic_add_f32_4MiB_g_per_s"],
+            "hbm_frac_of_copy": achieved / probes["copy_1GiB_gb_s"],
+        }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, x, theta, dy)
     print(json.dumps(out))

@@ -26,7 +26,8 @@ _TORCH = {HG_F32: torch.float32, HG_F16: torch.float16}
 EXPORTS = ("hashgrid_create", "hashgrid_destroy", "hashgrid_n_entries", "hashgrid_level_info",
            "hashgrid_encode_fwd", "hashgrid_encode_bwd", "hashgrid_encode_bwd_input",
            "hashgrid_debug_indices", "hashgrid_strerror", "hashgrid_bwd_workspace_bytes",
-           "hashgrid_encode_bwd_ws", "hashgrid_adam_step")
+           "hashgrid_encode_bwd_ws", "hashgrid_adam_step", "hashgrid_probe_copy", "hashgrid_probe_gather",
+           "hashgrid_probe_atomic_add")
 
 
 class HashGridError(RuntimeError):
@@ -79,6 +80,12 @@ def load_library() -> ctypes.CDLL:
     lib.hashgrid_adam_step.argtypes = [u64, vp, vp, vp, vp, vp, ctypes.POINTER(hashgrid_adam_config), u32, ctypes.c_int,
                                        vp]
     lib.hashgrid_adam_step.restype = ctypes.c_int
+    lib.hashgrid_probe_copy.argtypes = [vp, vp, u64, vp]
+    lib.hashgrid_probe_copy.restype = ctypes.c_int
+    lib.hashgrid_probe_gather.argtypes = [vp, u64, u64, u32, vp, vp]
+    lib.hashgrid_probe_gather.restype = ctypes.c_int
+    lib.hashgrid_probe_atomic_add.argtypes = [vp, u64, u64, u32, vp]
+    lib.hashgrid_probe_atomic_add.restype = ctypes.c_int
     lib.hashgrid_strerror.argtypes = [ctypes.c_int]
     lib.hashgrid_strerror.restype = ctypes.c_char_p
     _lib = lib
@@ -225,3 +232,30 @@ def adam_step(params_master: torch.Tensor, grad: torch.Tensor, m: torch.Tensor, 
     _check(load_library().hashgrid_adam_step(n, params_master.data_ptr(), half_ptr, grad.data_ptr(), m.data_ptr(),
                                              v.data_ptr(), ctypes.byref(cfg), step, int(zero_grad),
                                              _stream_ptr(stream)), "hashgrid_adam_step")
+
+
+def probe_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:
+    """hashgrid_probe_copy: dst = src (contiguous device tensors of equal byte size)."""
+    nbytes = src.numel() * src.element_size()
+    if not (src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()
+            and dst.numel() * dst.element_size() == nbytes):
+        raise HashGridError("src and dst must be contiguous device tensors of equal size")
+    _check(load_library().hashgrid_probe_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream_ptr(stream)),
+           "hashgrid_probe_copy")
+
+
+def probe_gather(table: torch.Tensor, n_gathers: int, sink: torch.Tensor, seed: int = 1, stream=None) -> None:
+    """hashgrid_probe_gather over an int32 device tensor with a power-of-two number of words."""
+    if not (table.is_cuda and table.is_contiguous() and table.element_size() == 4 and sink.is_cuda
+            and sink.is_contiguous() and sink.element_size() == 4 and sink.numel() >= n_gathers // 16):
+        raise HashGridError("table and sink must be contiguous 4-byte device tensors, sink of n_gathers/16 words")
+    _check(load_library().hashgrid_probe_gather(table.data_ptr(), table.numel(), n_gathers, seed, sink.data_ptr(),
+                                                _stream_ptr(stream)), "hashgrid_probe_gather")
+
+
+def probe_atomic_add(table: torch.Tensor, n_adds: int, seed: int = 1, stream=None) -> None:
+    """hashgrid_probe_atomic_add over an fp32 device tensor with a power-of-two number of words."""
+    if not (table.is_cuda and table.is_contiguous() and table.dtype == torch.float32):
+        raise HashGridError("table must be a contiguous fp32 device tensor")
+    _check(load_library().hashgrid_probe_atomic_add(table.data_ptr(), table.numel(), n_adds, seed,
+                                                    _stream_ptr(stream)), "hashgrid_probe_atomic_add")

@@ -72,7 +72,15 @@ constexpr int kAccPreWords = HG_ACC_PRE_WORDS;  // registers per lane for record
 #endif
 constexpr uint32_t kChunkLog2 = HG_CHUNK_LOG2;
 constexpr uint32_t kTargetRecordsPerAccWg = 16384;
-constexpr uint32_t kMaxParts = 4;       // level parts of the count / scatter grids
+#ifndef HG_MAX_PARTS
+#define HG_MAX_PARTS 4
+#endif
+constexpr uint32_t kMaxParts = HG_MAX_PARTS;  // level parts of the scatter grid
+#ifndef HG_COUNT_PARTS
+#define HG_COUNT_PARTS 2
+#endif
+constexpr uint32_t kCountParts = HG_COUNT_PARTS;  // ... of the count grid (its workgroups are lighter)
+static_assert(kCountParts <= kMaxParts, "tile_max is sized for kMaxParts");
 constexpr uint64_t kMaxBinLds = 7 * 1024;  // bound on 4 * (number of bins): per-part LDS arrays stay small
 
 // One record = one pair of corners that differ along dimension 0, both inside one
@@ -491,7 +499,10 @@ __device__ __forceinline__ void block_exclusive_scan(uint32_t* a, uint32_t n, ui
 // scan: each workgroup takes kScanBins bins and turns their column of
 // counts[tile][bin] into the exclusive prefix over tiles; it also writes the
 // bin's record count.  Workgroup 0 reduces the per-tile maxima of |dL/dy|.
-constexpr int kScanBins = 16;
+#ifndef HG_SCAN_BINS
+#define HG_SCAN_BINS 32
+#endif
+constexpr int kScanBins = HG_SCAN_BINS;
 __global__ __launch_bounds__(kScanThreads) void bin_scan(const uint32_t n_tiles, const uint32_t n_max,
                                                          const uint32_t n_bins,
                                                          uint32_t* __restrict__ counts,
@@ -943,18 +954,21 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
   plan_slices(bp, h->lv, B);
   const bool smooth = h->cfg.interp == HG_INTERP_SMOOTHSTEP;
   const uint32_t n_records = B * h->lv.L * bp.rec_per_point;
-  const uint32_t L = h->lv.L, parts = L < kMaxParts ? L : kMaxParts;
-  uint32_t max_part_bins = 0;
-  for (uint32_t p = 0; p < parts; ++p) {
-    const uint32_t nbp = bp.bin_base[(p + 1) * L / parts] - bp.bin_base[p * L / parts];
-    max_part_bins = nbp > max_part_bins ? nbp : max_part_bins;
-  }
-  const size_t lds_count = (size_t)max_part_bins * 4, lds_scatter = (size_t)(3 * max_part_bins + 1) * 4;
+  const uint32_t L = h->lv.L, parts = L < kMaxParts ? L : kMaxParts, cparts = L < kCountParts ? L : kCountParts;
+  auto max_part_bins = [&](uint32_t np) {
+    uint32_t m = 0;
+    for (uint32_t p = 0; p < np; ++p) {
+      const uint32_t nbp = bp.bin_base[(p + 1) * L / np] - bp.bin_base[p * L / np];
+      m = nbp > m ? nbp : m;
+    }
+    return m;
+  };
+  const size_t lds_count = (size_t)max_part_bins(cparts) * 4, lds_scatter = (size_t)(3 * max_part_bins(parts) + 1) * 4;
   const uint32_t tile_wgs = (ws.n_tiles + 7u) / 8u * 8u;  // see tile_of_workgroup
-  hipLaunchKernelGGL((bin_count<D, IT>), dim3(tile_wgs, parts), dim3(kBinThreads), lds_count, s, h->lv, bp, smooth,
+  hipLaunchKernelGGL((bin_count<D, IT>), dim3(tile_wgs, cparts), dim3(kBinThreads), lds_count, s, h->lv, bp, smooth,
                      B, x, static_cast<const IT*>(dy), ws.counts, ws.tile_max, ws.n_bins, ws.n_tiles);
   hipLaunchKernelGGL(bin_scan, dim3((ws.n_bins + kScanBins - 1) / kScanBins), dim3(kScanThreads), 0, s, ws.n_tiles,
-                     ws.n_tiles * parts, ws.n_bins, ws.counts, ws.bin_total, ws.tile_max, ws.call_max,
+                     ws.n_tiles * cparts, ws.n_bins, ws.counts, ws.bin_total, ws.tile_max, ws.call_max,
                      ws.item_counter);
   hipLaunchKernelGGL((bin_scatter<D, IT>), dim3(tile_wgs, parts), dim3(kBinThreads), lds_scatter, s, h->lv, bp,
                      smooth, B, x, static_cast<const IT*>(dy), ws.counts, ws.bin_total, ws.bin_start,

@@ -105,3 +105,16 @@ def test_adam_step_status_codes_need_no_device():
     assert lib.hashgrid_adam_step(8, None, None, None, None, None, ctypes.byref(cfg), 1, 1, None) == 1
     assert lib.hashgrid_adam_step(8, 4096, None, 4096, 4096, 4096, ctypes.byref(cfg), 0, 1, None) == 1
     assert lib.hashgrid_adam_step(8, 4096, None, 4096, 4096, 4096, None, 1, 1, None) == 1
+
+
+def test_probe_status_codes_need_no_device():
+    lib = binding.load_library()
+    assert lib.hashgrid_probe_copy(None, None, 0, None) == 0
+    assert lib.hashgrid_probe_copy(None, 4096, 64, None) == 1
+    assert lib.hashgrid_probe_copy(4096, 8192, 24, None) == 1      # not a multiple of 16
+    assert lib.hashgrid_probe_copy(4100, 8192, 64, None) == 1      # misaligned
+    assert lib.hashgrid_probe_gather(None, 1024, 0, 1, None, None) == 0
+    assert lib.hashgrid_probe_gather(4096, 1000, 4096, 1, 8192, None) == 1   # table not a power of two
+    assert lib.hashgrid_probe_gather(4096, 1024, 100, 1, 8192, None) == 1    # not a multiple of 4096
+    assert lib.hashgrid_probe_atomic_add(None, 1024, 4096, 1, None) == 1
+    assert lib.hashgrid_probe_atomic_add(4096, 1 << 33, 4096, 1, None) == 1
