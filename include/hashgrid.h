@@ -108,8 +108,9 @@ hg_status hashgrid_encode_bwd(const hashgrid_t* hg, uint32_t B, const float* x, 
 
 /* Size in bytes of the scratch buffer hashgrid_encode_bwd_ws needs for a batch of
  * B points, or 0 when that variant does not serve this configuration or batch
- * (it needs F = 2, d = 2 or 3, a power-of-two T, resolutions below 4096 on hashed
- * levels, at most 1024 chunks of 4096 entries per level and B*L*2^(d-1) < 2^32). */
+ * (it needs F = 2, d = 2 or 3, a power-of-two T of at most 2^22 (1024 chunks of 4096
+ * entries per level), at most 4096 vertices per axis on 1:1 levels and
+ * B*L*2^(d-1) < 2^32). */
 uint64_t hashgrid_bwd_workspace_bytes(const hashgrid_t* hg, uint32_t B);
 
 /* Backward pass to the tables, same result as hashgrid_encode_bwd (Fig. 3

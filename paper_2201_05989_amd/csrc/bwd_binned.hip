@@ -80,8 +80,9 @@ constexpr uint32_t kMaxParts = HG_MAX_PARTS;  // level parts of the scatter grid
 #define HG_COUNT_PARTS 2
 #endif
 constexpr uint32_t kCountParts = HG_COUNT_PARTS;  // ... of the count grid (its workgroups are lighter)
-static_assert(kCountParts <= kMaxParts, "tile_max is sized for kMaxParts");
-constexpr uint64_t kMaxBinLds = 7 * 1024;  // bound on 4 * (number of bins): per-part LDS arrays stay small
+// Level parts are doubled (up to one level per part) until one part's bins fit these bounds: a count
+// workgroup keeps one LDS word per bin of its part, a scatter workgroup three, next to its staging area.
+constexpr uint32_t kMaxCountPartBins = 4096, kMaxScatterPartBins = 2048;
 
 // One record = one pair of corners that differ along dimension 0, both inside one
 // chunk: local indices la (lower corner) and lb (upper corner), the fractional
@@ -201,7 +202,7 @@ struct Workspace {
   uint32_t* counts;     // [n_tiles + 1][n_bins] counts, then exclusive prefix over tiles (last row: totals)
   uint32_t* bin_start;  // [n_bins] first record of the bin
   uint32_t* bin_total;  // [n_bins] records in the bin
-  float* tile_max;      // [n_tiles * parts] largest |dL/dy| seen by each count workgroup
+  float* tile_max;      // [n_tiles * count_parts] largest |dL/dy| seen by each count workgroup
   float* call_max;      // [1] largest |dL/dy| of the call
   uint32_t* item_counter;  // [1] next work item of the accumulate pass
   uint32_t* records;    // [B * L * rec_per_point] records of 3 or 4 words
@@ -222,7 +223,7 @@ static uint64_t carve(const hashgrid* h, uint32_t B, uint8_t* base, Workspace* w
     return o;
   };
   const uint64_t o_counts = take((uint64_t)(nt + 1) * nb * 4), o_start = take((uint64_t)nb * 4),
-                 o_total = take((uint64_t)nb * 4), o_max = take((uint64_t)nt * kMaxParts * 4), o_cmax = take(4), o_item = take(4),
+                 o_total = take((uint64_t)nb * 4), o_max = take((uint64_t)nt * h->bp.count_parts * 4), o_cmax = take(4), o_item = take(4),
                  o_rec = take((uint64_t)B * h->lv.L * h->bp.rec_per_point * (h->cfg.io_dtype == HG_F16 ? 12 : 16));
   if (ws) {
     ws->counts = reinterpret_cast<uint32_t*>(base + o_counts);
@@ -242,7 +243,7 @@ static uint64_t carve(const hashgrid* h, uint32_t B, uint8_t* base, Workspace* w
 // boundaries (a row = all vertices that share the coordinates of dimensions
 // 1..d-1, contiguous in memory), a power-of-two number of rows per chunk; hashed
 // levels are cut into aligned blocks of 2^chunk_log2 entries, which the XOR with
-// v_0 < 2^chunk_log2 cannot leave.
+// the low chunk_log2 bits of v_0 cannot leave.
 void build_bin_plan(hashgrid* h) {
   BinPlan& bp = h->bp;
   bp = BinPlan{};
@@ -264,9 +265,9 @@ void build_bin_plan(hashgrid* h) {
       bp.row_shift[l] = (uint8_t)s;
       nb = (uint32_t)((rows + (1ull << s) - 1) >> s);
     } else {
-      // both corners of a pair must share the bits above the chunk: v_0 + 1 < 2^chunk_log2
-      const uint32_t top = lv.N[l] + (c.interp == HG_INTERP_SMOOTHSTEP ? 1u : 0u);
-      if (top >= cap) return;
+      // The two corners of a pair share the bits above the chunk unless stepping v_0 carries out of
+      // its low chunk_log2 bits, which needs a resolution of 2^chunk_log2 or more and then happens
+      // for one voxel in 2^chunk_log2: those pairs bypass the sort (see bin_scatter).
       nb = lv.T > cap ? lv.T >> kChunkLog2 : 1u;
     }
     if (nb > (uint32_t)kScanThreads) return;
@@ -274,7 +275,22 @@ void build_bin_plan(hashgrid* h) {
     bins += nb;
   }
   bp.bin_base[lv.L] = bins;
-  if ((uint64_t)bins * 4 > kMaxBinLds) return;  // per-bin counters of one workgroup live in LDS
+  auto max_part_bins = [&](uint32_t np) {
+    uint32_t m = 0;
+    for (uint32_t p = 0; p < np; ++p) {
+      const uint32_t nbp = bp.bin_base[(p + 1) * lv.L / np] - bp.bin_base[p * lv.L / np];
+      m = nbp > m ? nbp : m;
+    }
+    return m;
+  };
+  auto parts_for = [&](uint32_t start, uint32_t limit) {
+    uint32_t np = lv.L < start ? lv.L : start;
+    while (max_part_bins(np) > limit && np < lv.L) np = np * 2 < lv.L ? np * 2 : lv.L;
+    return max_part_bins(np) <= limit ? np : 0u;
+  };
+  bp.count_parts = parts_for(kCountParts, kMaxCountPartBins);
+  bp.scatter_parts = parts_for(kMaxParts, kMaxScatterPartBins);
+  if (!bp.count_parts || !bp.scatter_parts) return;
   bp.supported = 1;
 }
 
@@ -305,6 +321,7 @@ struct Rows {
   float wrow[1 << (D - 1)];      // product of the weights of dimensions 1..d-1
   float wf0;                     // fractional position along dimension 0 (before any smoothstep)
   uint32_t k;                    // trailing one bits of the lower corner's coordinate along dimension 0
+  bool cross;                    // hashed level: the pair's corners fall into different chunks (no record)
 };
 
 template <int D, bool COUNT_ONLY>
@@ -327,6 +344,7 @@ __device__ __forceinline__ void rows_of(const LevelTable& lv, const BinPlan& bp,
   }
   const uint32_t cl = bp.chunk_log2, cmask = (1u << cl) - 1u;
   const uint32_t gb0 = bp.bin_base[l];
+  out.cross = !dense && (c0[0] & cmask) == cmask;  // v_0 + 1 carries out of the chunk's index bits
   if (!COUNT_ONLY) {
     out.k = (uint32_t)__builtin_ctz(~c0[0]) & 15u;  // c0 + 1 < 2^chunk_log2 <= 2^15 on hashed levels
 #pragma unroll
@@ -368,6 +386,44 @@ __device__ __forceinline__ void rows_of(const LevelTable& lv, const BinPlan& bp,
         out.pack[r] = (ia & cmask) | ((ib & cmask) << 16);
       }
     }
+  }
+}
+
+// The pairs of a hashed level whose two corners lie in different chunks (Rows::cross; one voxel
+// in 2^chunk_log2 along dimension 0, and only at resolutions of 2^chunk_log2 or more) get no
+// record: their 2^d products go to the gradient with device-scope atomics.  T is a power of two.
+template <int D>
+__device__ __forceinline__ void add_crossing_pairs(const LevelTable& lv, uint32_t l, bool smooth, const float (&xp)[D],
+                                                float g0, float g1, float* __restrict__ grad) {
+  const float Nf = (float)lv.N[l];
+  const float shift = smooth ? 0.5f : 0.0f;
+  const float cmaxf = smooth ? Nf : Nf - 1.0f;
+  uint32_t c0[D];
+  float w[D], u[D];
+#pragma unroll
+  for (int i = 0; i < D; ++i) {
+    float wf;
+    split(xp[i], Nf, shift, cmaxf, c0[i], wf);
+    w[i] = smooth ? smoothstep(wf) : wf;
+    u[i] = smooth ? smoothstep(1.0f - wf) : 1.0f - wf;
+  }
+  const uint32_t tmask = lv.T - 1u;
+  float* gl = grad + lv.offset[l] * 2;
+#pragma unroll
+  for (uint32_t r = 0; r < (1u << (D - 1)); ++r) {
+    float wr = 1.0f;
+    uint32_t rt = 0;
+#pragma unroll
+    for (int i = 1; i < D; ++i) {
+      const uint32_t up = (r >> (i - 1)) & 1u;
+      wr *= up ? w[i] : u[i];
+      rt ^= (c0[i] + up) * prime(i);
+    }
+    const uint32_t ia = (c0[0] ^ rt) & tmask, ib = ((c0[0] + 1u) ^ rt) & tmask;
+    __hip_atomic_fetch_add(gl + 2 * (uint64_t)ia, u[0] * (wr * g0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_fetch_add(gl + 2 * (uint64_t)ia + 1, u[0] * (wr * g1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_fetch_add(gl + 2 * (uint64_t)ib, w[0] * (wr * g0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_fetch_add(gl + 2 * (uint64_t)ib + 1, w[0] * (wr * g1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 }
 
@@ -420,6 +476,7 @@ __global__ __launch_bounds__(kBinThreads) void bin_count(const LevelTable lv, co
     for (uint32_t l = l0; l < l1; ++l) {
       Rows<D> rw;
       rows_of<D, true>(lv, bp, l, smooth, xp, rw);
+      if (rw.cross) continue;
 #pragma unroll
       for (uint32_t r = 0; r < (1u << (D - 1)); ++r)
         __hip_atomic_fetch_add(&hist[rw.bin[r] - gb_a], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -606,7 +663,8 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, 
                                                            const uint32_t* __restrict__ bin_total,
                                                            uint32_t* __restrict__ bin_start,
                                                            uint32_t* __restrict__ records, const uint32_t n_bins,
-                                                           const uint32_t n_records, const uint32_t n_tiles) {
+                                                           const uint32_t n_records, const uint32_t n_tiles,
+                                                           float* __restrict__ grad) {
   constexpr uint32_t R = 1u << (D - 1);
   using Rec = Record<IT>;
   typename Rec::Stored* out = reinterpret_cast<typename Rec::Stored*>(records);
@@ -684,8 +742,9 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, 
     if (valid) {
       Rows<D> rw;
       rows_of<D, false>(lv, bp, l, smooth, xp, rw);
+      if (rw.cross) add_crossing_pairs<D>(lv, l, smooth, xp, (float)g0, (float)g1, grad);
 #pragma unroll
-      for (uint32_t r = 0; r < R; ++r) {
+      for (uint32_t r = 0; r < R && !rw.cross; ++r) {
         const uint32_t rb = rw.bin[r] - gb_a;
         const uint32_t in_tile = __hip_atomic_fetch_add(&cur[rb], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         const uint32_t pos = in_tile - level_first;
@@ -954,7 +1013,7 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
   plan_slices(bp, h->lv, B);
   const bool smooth = h->cfg.interp == HG_INTERP_SMOOTHSTEP;
   const uint32_t n_records = B * h->lv.L * bp.rec_per_point;
-  const uint32_t L = h->lv.L, parts = L < kMaxParts ? L : kMaxParts, cparts = L < kCountParts ? L : kCountParts;
+  const uint32_t L = h->lv.L, parts = bp.scatter_parts, cparts = bp.count_parts;
   auto max_part_bins = [&](uint32_t np) {
     uint32_t m = 0;
     for (uint32_t p = 0; p < np; ++p) {
@@ -972,7 +1031,7 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
                      ws.item_counter);
   hipLaunchKernelGGL((bin_scatter<D, IT>), dim3(tile_wgs, parts), dim3(kBinThreads), lds_scatter, s, h->lv, bp,
                      smooth, B, x, static_cast<const IT*>(dy), ws.counts, ws.bin_total, ws.bin_start,
-                     ws.records, ws.n_bins, n_records, ws.n_tiles);
+                     ws.records, ws.n_bins, n_records, ws.n_tiles, grad);
   // 64 KiB of dynamic LDS plus a few static bytes: above the default limit
   static const hipError_t lds_ok = [] {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_accumulate<IT, false>),

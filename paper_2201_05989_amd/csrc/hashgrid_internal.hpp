@@ -15,6 +15,7 @@ struct BinPlan {
   uint8_t row_shift[HG_MAX_LEVELS];      // 1:1 levels: log2 of grid rows per chunk
   uint32_t chunk_log2;                   // log2 of the entries a chunk can hold
   uint32_t rec_per_point;                // records per (point, level): 2^(d-1)
+  uint32_t count_parts, scatter_parts;   // level parts (gridDim.y) of the count and scatter grids
   uint32_t supported;                    // 0: configuration not served by the binned path
 };
 

@@ -209,6 +209,30 @@ def test_edge_positions_and_grid_vertices():
         run_case(d, L, F, T, N_min, N_max, "f32", "f32", interp, x, th, dy, do_dx=False)
 
 
+@pytest.mark.parametrize("d", [2, 3])
+@pytest.mark.parametrize("iot", ["f16", "f32"])
+def test_workspace_backward_when_pairs_straddle_two_chunks(d, iot):
+    # resolutions of 4096 and more on hashed levels: where the voxel coordinate along dimension 0
+    # ends in twelve one bits, its two corners hash into different 4096-entry chunks.  Half of the
+    # points sit in such voxels on every level, the rest are uniform.
+    L, F, T, N_min, N_max = 3, 2, 1 << 16, 8192, 32768
+    cfg = orc.OracleConfig(d, L, F, T, N_min, N_max)
+    lv = orc.levels(cfg)
+    assert not lv.dense.any()
+    rng = np.random.default_rng(77)
+    B = 6000
+    x = synth.points_uniform(rng, B, d)
+    k = rng.integers(0, 2, B // 2)
+    x[: B // 2, 0] = ((4095.75 + 4096.0 * k) / 8192.0).astype(np.float32)  # 4095 mod 4096 at every level
+    for l in range(L):
+        c0 = np.floor(x[: B // 2, 0].astype(np.float32) * np.float32(lv.N[l])).astype(np.int64)
+        assert ((c0 & 4095) == 4095).all()
+    theta = synth.make_tables(rng, lv.total, F, "f16", 1.0)
+    dy = synth.make_dy(rng, B, L * F, iot)
+    grid = run_case(d, L, F, T, N_min, N_max, "f16", iot, 0, x, theta, dy, do_dx=False)
+    assert grid.bwd_workspace_bytes(B) > 0
+
+
 def test_empty_batch_is_a_no_op():
     grid = HashGrid(3, 16, 2, 1 << 19, 16, 2048)
     x = torch.empty((0, 3), dtype=torch.float32, device="cuda")
