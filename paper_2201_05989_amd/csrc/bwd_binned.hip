@@ -202,8 +202,7 @@ struct Workspace {
   uint32_t* counts;     // [n_tiles + 1][n_bins] counts, then exclusive prefix over tiles (last row: totals)
   uint32_t* bin_start;  // [n_bins] first record of the bin
   uint32_t* bin_total;  // [n_bins] records in the bin
-  float* tile_max;      // [n_tiles * count_parts] largest |dL/dy| seen by each count workgroup
-  float* call_max;      // [1] largest |dL/dy| of the call
+  float* tile_max;      // [n_tiles * scatter_parts] largest |dL/dy| seen by each scatter workgroup
   uint32_t* item_counter;  // [1] next work item of the accumulate pass
   uint32_t* records;    // [B * L * rec_per_point] records of 3 or 4 words
   uint32_t n_tiles;
@@ -223,14 +222,13 @@ static uint64_t carve(const hashgrid* h, uint32_t B, uint8_t* base, Workspace* w
     return o;
   };
   const uint64_t o_counts = take((uint64_t)(nt + 1) * nb * 4), o_start = take((uint64_t)nb * 4),
-                 o_total = take((uint64_t)nb * 4), o_max = take((uint64_t)nt * h->bp.count_parts * 4), o_cmax = take(4), o_item = take(4),
+                 o_total = take((uint64_t)nb * 4), o_max = take((uint64_t)nt * h->bp.scatter_parts * 4), o_item = take(4),
                  o_rec = take((uint64_t)B * h->lv.L * h->bp.rec_per_point * (h->cfg.io_dtype == HG_F16 ? 12 : 16));
   if (ws) {
     ws->counts = reinterpret_cast<uint32_t*>(base + o_counts);
     ws->bin_start = reinterpret_cast<uint32_t*>(base + o_start);
     ws->bin_total = reinterpret_cast<uint32_t*>(base + o_total);
     ws->tile_max = reinterpret_cast<float*>(base + o_max);
-    ws->call_max = reinterpret_cast<float*>(base + o_cmax);
     ws->item_counter = reinterpret_cast<uint32_t*>(base + o_item);
     ws->records = reinterpret_cast<uint32_t*>(base + o_rec);
     ws->n_tiles = nt;
@@ -452,15 +450,13 @@ __device__ __forceinline__ void part_levels(uint32_t L, uint32_t& l0, uint32_t& 
   l1 = (blockIdx.y + 1) * L / gridDim.y;
 }
 
-// count: records per (tile, bin) and the workgroup's largest |dL/dy|.
-template <int D, typename IT>
+// count: records per (tile, bin).
+template <int D>
 __global__ __launch_bounds__(kBinThreads) void bin_count(const LevelTable lv, const BinPlan bp, const bool smooth,
                                                          const uint32_t B, const float* __restrict__ x,
-                                                         const IT* __restrict__ dy, uint32_t* __restrict__ counts,
-                                                         float* __restrict__ tile_max, const uint32_t n_bins,
+                                                         uint32_t* __restrict__ counts, const uint32_t n_bins,
                                                          const uint32_t n_tiles) {
   extern __shared__ uint32_t hist[];  // bins of this part's levels
-  __shared__ float wave_max[kBinThreads / 64];
   const uint32_t tile = tile_of_workgroup(blockIdx.x, n_tiles);
   if (tile >= n_tiles) return;  // uniform: a surplus workgroup of the rounded-up grid
   uint32_t l0, l1;
@@ -482,48 +478,12 @@ __global__ __launch_bounds__(kBinThreads) void bin_count(const LevelTable lv, co
         __hip_atomic_fetch_add(&hist[rw.bin[r] - gb_a], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
   }
-  // largest |dL/dy| over this workgroup's share of the tile's rows, read as one flat,
-  // coalesced range (a 4-byte read per level with the stride of a row costs the L1 a line
-  // per two lanes).  NaN must win the maximum so that the accumulate kernel sees it.
-  float m = 0.0f;
-  {
-    const uint64_t row_elems = (uint64_t)lv.L * 2;
-    const uint64_t tile_first = (uint64_t)tile * kBinThreads * row_elems;
-    const uint64_t tile_end = ((uint64_t)tile * kBinThreads + kBinThreads < B ? (uint64_t)tile * kBinThreads + kBinThreads : B) * row_elems;
-    const uint64_t share = ((tile_end - tile_first) + gridDim.y - 1) / gridDim.y;
-    const uint64_t e0 = tile_first + blockIdx.y * share;
-    const uint64_t e1 = e0 + share < tile_end ? e0 + share : tile_end;
-    constexpr uint32_t V = 16 / sizeof(IT);  // elements per 16-byte load
-    auto take = [&](IT v) {
-      const float a = fabsf((float)v);
-      m = (a > m || a != a) ? a : m;
-    };
-    // scalar head up to 16-byte alignment, vector body, scalar tail
-    uint64_t head = e0;
-    while (head < e1 && (reinterpret_cast<uintptr_t>(dy + head) & 15)) ++head;
-    const uint64_t body = head + (e1 - head) / V * V;
-    for (uint64_t e = e0 + threadIdx.x; e < head; e += kBinThreads) take(dy[e]);
-    for (uint64_t e = head + (uint64_t)threadIdx.x * V; e < body; e += (uint64_t)kBinThreads * V) {
-      const Vec<IT, V> v = *reinterpret_cast<const Vec<IT, V>*>(dy + e);
-#pragma unroll
-      for (uint32_t q = 0; q < V; ++q) take(v.v[q]);
-    }
-    for (uint64_t e = body + threadIdx.x; e < e1; e += kBinThreads) take(dy[e]);
-  }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const float other = __shfl_xor(m, o);
-    m = (other > m || other != other) ? other : m;
-  }
-  if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
   __syncthreads();
   for (uint32_t i = threadIdx.x; i < nbp; i += kBinThreads) counts[(uint64_t)tile * n_bins + gb_a + i] = hist[i];
-  if (threadIdx.x == 0) {
-    float t = wave_max[0];
-    for (int i = 1; i < kBinThreads / 64; ++i) t = (wave_max[i] > t || wave_max[i] != wave_max[i]) ? wave_max[i] : t;
-    tile_max[tile * gridDim.y + blockIdx.y] = t;
-  }
 }
+
+// m = max(m, v) where a NaN on either side wins, so that one NaN in dL/dy is seen at the end
+__device__ __forceinline__ float nan_max(float m, float v) { return (v > m || v != v) ? v : m; }
 
 // Exclusive prefix sum of a[0..n) in LDS, in place, by all T threads of the
 // workgroup (every thread must call it).  `tmp` holds T/64 words.
@@ -555,40 +515,17 @@ __device__ __forceinline__ void block_exclusive_scan(uint32_t* a, uint32_t n, ui
 
 // scan: each workgroup takes kScanBins bins and turns their column of
 // counts[tile][bin] into the exclusive prefix over tiles; it also writes the
-// bin's record count.  Workgroup 0 reduces the per-tile maxima of |dL/dy|.
+// bin's record count.  Workgroup 0 clears the work counter of the accumulate pass.
 #ifndef HG_SCAN_BINS
 #define HG_SCAN_BINS 32
 #endif
 constexpr int kScanBins = HG_SCAN_BINS;
-__global__ __launch_bounds__(kScanThreads) void bin_scan(const uint32_t n_tiles, const uint32_t n_max,
-                                                         const uint32_t n_bins,
+__global__ __launch_bounds__(kScanThreads) void bin_scan(const uint32_t n_tiles, const uint32_t n_bins,
                                                          uint32_t* __restrict__ counts,
                                                          uint32_t* __restrict__ bin_total,
-                                                         const float* __restrict__ tile_max,
-                                                         float* __restrict__ call_max,
                                                          uint32_t* __restrict__ item_counter) {
   __shared__ uint32_t seg_sum[kScanThreads];
-  __shared__ float red[kScanThreads / 64];
-  if (blockIdx.x == 0) {  // largest |dL/dy| of the call; NaN wins
-    float m = 0.0f;
-    for (uint32_t i = threadIdx.x; i < n_max; i += kScanThreads) {
-      const float t = tile_max[i];
-      m = (t > m || t != t) ? t : m;
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      const float other = __shfl_xor(m, o);
-      m = (other > m || other != other) ? other : m;
-    }
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      m = red[0];
-      for (int i = 1; i < kScanThreads / 64; ++i) m = (red[i] > m || red[i] != red[i]) ? red[i] : m;
-      call_max[0] = m;
-      item_counter[0] = 0;  // the accumulate pass draws its work items from here
-    }
-  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) item_counter[0] = 0;  // the accumulate pass draws its work items from here
   constexpr uint32_t segs = kScanThreads / kScanBins;
   const uint32_t bin_in = threadIdx.x % kScanBins, seg = threadIdx.x / kScanBins;
   const uint32_t gb = blockIdx.x * kScanBins + bin_in;
@@ -664,7 +601,7 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, 
                                                            uint32_t* __restrict__ bin_start,
                                                            uint32_t* __restrict__ records, const uint32_t n_bins,
                                                            const uint32_t n_records, const uint32_t n_tiles,
-                                                           float* __restrict__ grad) {
+                                                           float* __restrict__ tile_max, float* __restrict__ grad) {
   constexpr uint32_t R = 1u << (D - 1);
   using Rec = Record<IT>;
   typename Rec::Stored* out = reinterpret_cast<typename Rec::Stored*>(records);
@@ -720,6 +657,7 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, 
   const IT* row = dy + (uint64_t)b * lv.L * 2;
   const bool vec_ok = (lv.L % K == 0) && (l0 % K == 0) && ((reinterpret_cast<uintptr_t>(dy) & 15) == 0);
   Vec<IT, 2 * K> gv;
+  float gmax = 0.0f;  // largest |dL/dy| this workgroup sees (idle lanes shadow point 0)
   for (uint32_t l = l0; l < l1; ++l) {
     const uint32_t rb0 = bp.bin_base[l] - gb_a, rb1 = bp.bin_base[l + 1] - gb_a;
     const uint32_t level_first = local[rb0], emitted = local[rb1] - level_first;  // <= R * kBinThreads
@@ -739,6 +677,7 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, 
       g0 = g.v[0];
       g1 = g.v[1];
     }
+    gmax = nan_max(nan_max(gmax, fabsf((float)g0)), fabsf((float)g1));
     if (valid) {
       Rows<D> rw;
       rows_of<D, false>(lv, bp, l, smooth, xp, rw);
@@ -762,6 +701,17 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, 
       if (d < n_records) out[d] = staging[j];
     }
     __syncthreads();
+  }
+  // the accumulate pass scales its fixed point by the largest |dL/dy| of the call: one value per workgroup
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) gmax = nan_max(gmax, __shfl_xor(gmax, o));
+  float* wave_max = reinterpret_cast<float*>(scan_tmp);  // free since the prologue
+  if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = gmax;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float t = wave_max[0];
+    for (int i = 1; i < kBinThreads / 64; ++i) t = nan_max(t, wave_max[i]);
+    tile_max[tile * gridDim.y + blockIdx.y] = t;
   }
 }
 
@@ -787,15 +737,26 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
                                                               const uint32_t B, const uint32_t n_items,
                                                               const uint32_t* __restrict__ bin_start,
                                                               const uint32_t* __restrict__ bin_total,
-                                                              const float* __restrict__ call_max,
+                                                              const float* __restrict__ tile_max,
+                                                              const uint32_t n_max,
                                                               const uint32_t* __restrict__ records,
                                                               uint32_t* __restrict__ item_counter,
                                                               float* __restrict__ grad) {
   __shared__ uint32_t s_ticket;
   extern __shared__ unsigned long long acc[];  // [2][2^chunk_log2] fixed point: feature 0 of every entry, then
                                                // feature 1, so that consecutive entries map to consecutive banks
-  const float m = call_max[0];  // largest |dL/dy| of the call (NaN if any is NaN)
-  if (m == 0.0f) return;        // every summand is zero
+  // largest |dL/dy| of the call (NaN if any is NaN) from the scatter workgroups' maxima
+  __shared__ float red[kAccThreads / 64];
+  float m = 0.0f;
+  for (uint32_t i = threadIdx.x; i < n_max; i += kAccThreads) m = nan_max(m, tile_max[i]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) m = nan_max(m, __shfl_xor(m, o));
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+  __syncthreads();
+  m = red[0];
+#pragma unroll
+  for (int i = 1; i < kAccThreads / 64; ++i) m = nan_max(m, red[i]);
+  if (m == 0.0f) return;  // every summand is zero (uniform: all lanes hold the same m)
   const bool finite = m < INFINITY;
   const uint32_t cl = bp.chunk_log2, cap = 1u << cl, cmask = cap - 1u;
   unsigned long long* acc0 = acc;
@@ -1024,14 +985,13 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
   };
   const size_t lds_count = (size_t)max_part_bins(cparts) * 4, lds_scatter = (size_t)(3 * max_part_bins(parts) + 1) * 4;
   const uint32_t tile_wgs = (ws.n_tiles + 7u) / 8u * 8u;  // see tile_of_workgroup
-  hipLaunchKernelGGL((bin_count<D, IT>), dim3(tile_wgs, cparts), dim3(kBinThreads), lds_count, s, h->lv, bp, smooth,
-                     B, x, static_cast<const IT*>(dy), ws.counts, ws.tile_max, ws.n_bins, ws.n_tiles);
+  hipLaunchKernelGGL((bin_count<D>), dim3(tile_wgs, cparts), dim3(kBinThreads), lds_count, s, h->lv, bp, smooth, B, x,
+                     ws.counts, ws.n_bins, ws.n_tiles);
   hipLaunchKernelGGL(bin_scan, dim3((ws.n_bins + kScanBins - 1) / kScanBins), dim3(kScanThreads), 0, s, ws.n_tiles,
-                     ws.n_tiles * cparts, ws.n_bins, ws.counts, ws.bin_total, ws.tile_max, ws.call_max,
-                     ws.item_counter);
+                     ws.n_bins, ws.counts, ws.bin_total, ws.item_counter);
   hipLaunchKernelGGL((bin_scatter<D, IT>), dim3(tile_wgs, parts), dim3(kBinThreads), lds_scatter, s, h->lv, bp,
                      smooth, B, x, static_cast<const IT*>(dy), ws.counts, ws.bin_total, ws.bin_start,
-                     ws.records, ws.n_bins, n_records, ws.n_tiles, grad);
+                     ws.records, ws.n_bins, n_records, ws.n_tiles, ws.tile_max, grad);
   // 64 KiB of dynamic LDS plus a few static bytes: above the default limit
   static const hipError_t lds_ok = [] {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_accumulate<IT, false>),
@@ -1053,10 +1013,12 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
   const size_t acc_lds = (size_t)16 << bp.chunk_log2;
   if (smooth)
     hipLaunchKernelGGL((bin_accumulate<IT, true>), acc_grid, dim3(kAccThreads), acc_lds, s, h->lv, bp, B, n_items,
-                       ws.bin_start, ws.bin_total, ws.call_max, ws.records, ws.item_counter, grad);
+                       ws.bin_start, ws.bin_total, ws.tile_max, ws.n_tiles * parts, ws.records, ws.item_counter,
+                       grad);
   else
     hipLaunchKernelGGL((bin_accumulate<IT, false>), acc_grid, dim3(kAccThreads), acc_lds, s, h->lv, bp, B, n_items,
-                       ws.bin_start, ws.bin_total, ws.call_max, ws.records, ws.item_counter, grad);
+                       ws.bin_start, ws.bin_total, ws.tile_max, ws.n_tiles * parts, ws.records, ws.item_counter,
+                       grad);
   return hipGetLastError() == hipSuccess ? HG_OK : HG_ERR_DEVICE;
 }
 
