@@ -58,6 +58,10 @@ typedef enum {
   HG_INTERP_SMOOTHSTEP = 1 /* Appendix A: weights S(w) = w^2 (3-2w), levels shifted by 1/(2 N_l)  */
 } hg_interp;
 
+typedef enum {
+  HG_BWD_COUNTED = 1 /* the workspace already holds the counts of these points (hashgrid_encode_fwd_ws) */
+} hg_bwd_flags;
+
 typedef struct {
   uint32_t d;           /* input dimensions: 1, 2 or 3 (Eq. 4 defines three primes)              */
   uint32_t L;           /* levels, 1..HG_MAX_LEVELS (Table 1: 16)                                */
@@ -128,11 +132,26 @@ uint64_t hashgrid_bwd_workspace_bytes(const hashgrid_t* hg, uint32_t B);
  *              bytes, owned by the caller; contents are scratch: undefined on
  *              entry and on exit.  Calls that overlap in time need separate
  *              workspaces.
+ *   flags      0, or HG_BWD_COUNTED when hashgrid_encode_fwd_ws has just run on the same hg,
+ *              B, x and workspace (see there).
  * Returns HG_ERR_UNSUPPORTED when hashgrid_bwd_workspace_bytes is 0 and
- * HG_ERR_INVALID_ARG when the buffer is missing, misaligned or too small.  x and
- * dLdy must not be written while the call is in flight. */
+ * HG_ERR_INVALID_ARG when the buffer is missing, misaligned or too small or a flag is
+ * unknown.  x and dLdy must not be written while the call is in flight. */
 hg_status hashgrid_encode_bwd_ws(const hashgrid_t* hg, uint32_t B, const float* x, const void* dLdy,
-                                 float* grad_params, void* workspace, uint64_t workspace_bytes, void* stream);
+                                 float* grad_params, void* workspace, uint64_t workspace_bytes, uint32_t flags,
+                                 void* stream);
+
+/* Forward pass, same result as hashgrid_encode_fwd (Section 3; Fig. 3 steps 1-4), that also does
+ * the first step of hashgrid_encode_bwd_ws for the same points while it gathers: it counts, per
+ * tile of points and chunk of the gradient, the corner pairs that the backward pass will sort,
+ * and leaves the counts in `workspace`.  A following hashgrid_encode_bwd_ws on the same hg, B, x
+ * and workspace may then pass HG_BWD_COUNTED and skips its own counting pass.  Nothing else may
+ * write the workspace in between, and x must be unchanged.
+ * Returns HG_ERR_UNSUPPORTED when hashgrid_bwd_workspace_bytes is 0, when y or params are not
+ * 16-byte / entry aligned, or when the configuration has more than 6144 chunks in all (callers
+ * then use hashgrid_encode_fwd and pass no flag); HG_ERR_INVALID_ARG as hashgrid_encode_bwd_ws. */
+hg_status hashgrid_encode_fwd_ws(const hashgrid_t* hg, uint32_t B, const float* x, const void* params, void* y,
+                                 void* workspace, uint64_t workspace_bytes, void* stream);
 
 /* Gradient with respect to the input position (chain rule on the weight
  * definition of Section 3; S' of Appendix A for the smoothstep variant):

@@ -19,6 +19,8 @@ HG_OK = 0
 HG_F32, HG_F16 = 0, 1
 HG_INTERP_LINEAR, HG_INTERP_SMOOTHSTEP = 0, 1
 HG_MAX_LEVELS = 32
+HG_BWD_COUNTED = 1
+HG_ERR_UNSUPPORTED = 2
 
 _DTYPES = {"f32": HG_F32, "f16": HG_F16, torch.float32: HG_F32, torch.float16: HG_F16}
 _TORCH = {HG_F32: torch.float32, HG_F16: torch.float16}
@@ -26,7 +28,7 @@ _TORCH = {HG_F32: torch.float32, HG_F16: torch.float16}
 EXPORTS = ("hashgrid_create", "hashgrid_destroy", "hashgrid_n_entries", "hashgrid_level_info",
            "hashgrid_encode_fwd", "hashgrid_encode_bwd", "hashgrid_encode_bwd_input",
            "hashgrid_debug_indices", "hashgrid_strerror", "hashgrid_bwd_workspace_bytes",
-           "hashgrid_encode_bwd_ws", "hashgrid_adam_step", "hashgrid_probe_copy", "hashgrid_probe_gather",
+           "hashgrid_encode_bwd_ws", "hashgrid_encode_fwd_ws", "hashgrid_adam_step", "hashgrid_probe_copy", "hashgrid_probe_gather",
            "hashgrid_probe_atomic_add")
 
 
@@ -75,7 +77,9 @@ def load_library() -> ctypes.CDLL:
     lib.hashgrid_debug_indices.restype = ctypes.c_int
     lib.hashgrid_bwd_workspace_bytes.argtypes = [vp, u32]
     lib.hashgrid_bwd_workspace_bytes.restype = u64
-    lib.hashgrid_encode_bwd_ws.argtypes = [vp, u32, vp, vp, vp, vp, u64, vp]
+    lib.hashgrid_encode_bwd_ws.argtypes = [vp, u32, vp, vp, vp, vp, u64, u32, vp]
+    lib.hashgrid_encode_fwd_ws.argtypes = [vp, u32, vp, vp, vp, vp, u64, vp]
+    lib.hashgrid_encode_fwd_ws.restype = ctypes.c_int
     lib.hashgrid_encode_bwd_ws.restype = ctypes.c_int
     lib.hashgrid_adam_step.argtypes = [u64, vp, vp, vp, vp, vp, ctypes.POINTER(hashgrid_adam_config), u32, ctypes.c_int,
                                        vp]
@@ -137,6 +141,7 @@ class HashGrid:
         self.io_dtype = _TORCH[self.cfg.io_dtype]
         self.n_entries = int(self._lib.hashgrid_n_entries(self._h))
         self._ws = None
+        self._counted = None  # (x pointer, B, workspace pointer) the workspace holds counts for
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None
@@ -152,10 +157,31 @@ class HashGrid:
     def levels(self):
         return [self.level_info(l) for l in range(self.L)]
 
-    def encode_fwd(self, x: torch.Tensor, params: torch.Tensor, y: torch.Tensor | None = None, stream=None):
+    def _workspace(self, need: int, device) -> torch.Tensor:
+        if self._ws is None or self._ws.numel() < need or self._ws.device != device:
+            self._ws = torch.empty(need, dtype=torch.uint8, device=device)
+        return self._ws
+
+    def encode_fwd(self, x: torch.Tensor, params: torch.Tensor, y: torch.Tensor | None = None, stream=None,
+                   count_for_bwd: bool = False, workspace: torch.Tensor | None = None):
+        """hashgrid_encode_fwd; with count_for_bwd, hashgrid_encode_fwd_ws where the configuration
+        is served by it: the next encode_bwd on the same x and workspace then skips its counting pass."""
         B = x.shape[0]
         if y is None:
             y = torch.empty((B, self.L * self.F), dtype=self.io_dtype, device=x.device)
+        self._counted = None
+        need = self.bwd_workspace_bytes(B) if count_for_bwd and B else 0
+        if need:
+            ws = workspace if workspace is not None else self._workspace(need, x.device)
+            st = self._lib.hashgrid_encode_fwd_ws(
+                self._h, B, _dev(x, torch.float32, (B, self.d), "x"),
+                _dev(params, self.param_dtype, (self.n_entries, self.F), "params"),
+                _dev(y, self.io_dtype, (B, self.L * self.F), "y"), ws.data_ptr(), ws.numel() * ws.element_size(),
+                _stream_ptr(stream))
+            if st != HG_ERR_UNSUPPORTED:
+                _check(st, "hashgrid_encode_fwd_ws")
+                self._counted = (x.data_ptr(), B, ws.data_ptr())
+                return y
         _check(self._lib.hashgrid_encode_fwd(
             self._h, B, _dev(x, torch.float32, (B, self.d), "x"),
             _dev(params, self.param_dtype, (self.n_entries, self.F), "params"),
@@ -173,16 +199,16 @@ class HashGrid:
         if grad_params is None:
             grad_params = torch.zeros((self.n_entries, self.F), dtype=torch.float32, device=x.device)
         need = self.bwd_workspace_bytes(B) if use_workspace else 0
+        counted, self._counted = self._counted, None  # the pass consumes the counts
         if need:
             if workspace is None:
-                if self._ws is None or self._ws.numel() < need or self._ws.device != x.device:
-                    self._ws = torch.empty(need, dtype=torch.uint8, device=x.device)
-                workspace = self._ws
+                workspace = self._workspace(need, x.device)
+            flags = HG_BWD_COUNTED if counted == (x.data_ptr(), B, workspace.data_ptr()) else 0
             _check(self._lib.hashgrid_encode_bwd_ws(
                 self._h, B, _dev(x, torch.float32, (B, self.d), "x"),
                 _dev(dLdy, self.io_dtype, (B, self.L * self.F), "dLdy"),
                 _dev(grad_params, torch.float32, (self.n_entries, self.F), "grad_params"),
-                workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr(stream)),
+                workspace.data_ptr(), workspace.numel() * workspace.element_size(), flags, _stream_ptr(stream)),
                 "hashgrid_encode_bwd_ws")
             return grad_params
         _check(self._lib.hashgrid_encode_bwd(

@@ -41,15 +41,12 @@
 #include "hashgrid.h"
 #include "hashgrid_common.hpp"
 #include "hashgrid_internal.hpp"
+#include "bwd_bins.hpp"
 
 namespace hg {
 
 using u32x4 = uint32_t __attribute__((ext_vector_type(4)));
 
-#ifndef HG_BIN_THREADS
-#define HG_BIN_THREADS 512
-#endif
-constexpr int kBinThreads = HG_BIN_THREADS;  // threads (= points) of a count / scatter workgroup
 constexpr int kScanThreads = 1024;     // = maximum bins per level
 #ifndef HG_ACC_THREADS
 #define HG_ACC_THREADS 1024
@@ -67,10 +64,6 @@ constexpr int kAccPreWords = HG_ACC_PRE_WORDS;  // registers per lane for record
 #ifndef HG_ACC_WGS_PER_CU
 #define HG_ACC_WGS_PER_CU 1u
 #endif
-#ifndef HG_CHUNK_LOG2
-#define HG_CHUNK_LOG2 12
-#endif
-constexpr uint32_t kChunkLog2 = HG_CHUNK_LOG2;
 constexpr uint32_t kTargetRecordsPerAccWg = 16384;
 #ifndef HG_MAX_PARTS
 #define HG_MAX_PARTS 4
@@ -311,81 +304,6 @@ static void plan_slices(BinPlan& bp, const LevelTable& lv, uint32_t B) {
 }
 
 // ------------------------------------------------------------------ device
-
-template <int D>
-struct Rows {
-  uint32_t bin[1 << (D - 1)];    // global bin
-  uint32_t pack[1 << (D - 1)];   // chunk-local index of the lower | upper << 16 corner along dimension 0
-  float wrow[1 << (D - 1)];      // product of the weights of dimensions 1..d-1
-  float wf0;                     // fractional position along dimension 0 (before any smoothstep)
-  uint32_t k;                    // trailing one bits of the lower corner's coordinate along dimension 0
-  bool cross;                    // hashed level: the pair's corners fall into different chunks (no record)
-};
-
-template <int D, bool COUNT_ONLY>
-__device__ __forceinline__ void rows_of(const LevelTable& lv, const BinPlan& bp, uint32_t l, bool smooth,
-                                        const float (&xp)[D], Rows<D>& out) {
-  const uint32_t N = lv.N[l], verts = lv.verts[l];
-  const bool dense = (lv.dense_mask >> l) & 1u;
-  const float Nf = (float)N;
-  const float shift = smooth ? 0.5f : 0.0f;
-  const float cmaxf = smooth ? Nf : Nf - 1.0f;
-  uint32_t c0[D];
-  float w[D], u[D];
-#pragma unroll
-  for (int i = 0; i < D; ++i) {
-    float wf;
-    split(xp[i], Nf, shift, cmaxf, c0[i], wf);
-    if (i == 0) out.wf0 = wf;
-    w[i] = smooth ? smoothstep(wf) : wf;
-    u[i] = smooth ? smoothstep(1.0f - wf) : 1.0f - wf;
-  }
-  const uint32_t cl = bp.chunk_log2, cmask = (1u << cl) - 1u;
-  const uint32_t gb0 = bp.bin_base[l];
-  out.cross = !dense && (c0[0] & cmask) == cmask;  // v_0 + 1 carries out of the chunk's index bits
-  if (!COUNT_ONLY) {
-    out.k = (uint32_t)__builtin_ctz(~c0[0]) & 15u;  // c0 + 1 < 2^chunk_log2 <= 2^15 on hashed levels
-#pragma unroll
-    for (uint32_t r = 0; r < (1u << (D - 1)); ++r) {
-      float wr = 1.0f;
-#pragma unroll
-      for (int i = 1; i < D; ++i) wr *= ((r >> (i - 1)) & 1u) ? w[i] : u[i];
-      out.wrow[r] = wr;
-    }
-  }
-  // the level kind is uniform: a scalar branch, not per-lane selects between the two maps
-  if (dense) {
-    const uint32_t sh = bp.row_shift[l];
-#pragma unroll
-    for (uint32_t r = 0; r < (1u << (D - 1)); ++r) {
-      uint32_t row = c0[1] + (r & 1u);
-      if (D == 3) row += (c0[D - 1] + (r >> 1)) * verts;
-      const uint32_t bin = row >> sh;
-      out.bin[r] = gb0 + bin;
-      if (!COUNT_ONLY) {
-        const uint32_t la = c0[0] + (row - (bin << sh)) * verts;
-        out.pack[r] = la | ((la + 1u) << 16);
-      }
-    }
-  } else {
-    const uint32_t tmask = lv.T - 1u;
-    uint32_t t1[2], t2[2];
-    t1[0] = c0[1] * prime(1);
-    t1[1] = t1[0] + prime(1);
-    t2[0] = D == 3 ? c0[D - 1] * prime(2) : 0u;
-    t2[1] = t2[0] + prime(2);
-#pragma unroll
-    for (uint32_t r = 0; r < (1u << (D - 1)); ++r) {
-      const uint32_t rt = D == 3 ? t1[r & 1u] ^ t2[r >> 1] : t1[r & 1u];
-      const uint32_t ia = (c0[0] ^ rt) & tmask;
-      out.bin[r] = gb0 + (ia >> cl);
-      if (!COUNT_ONLY) {
-        const uint32_t ib = ((c0[0] + 1u) ^ rt) & tmask;
-        out.pack[r] = (ia & cmask) | ((ib & cmask) << 16);
-      }
-    }
-  }
-}
 
 // The pairs of a hashed level whose two corners lie in different chunks (Rows::cross; one voxel
 // in 2^chunk_log2 along dimension 0, and only at resolutions of 2^chunk_log2 or more) get no
@@ -969,7 +887,7 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
 
 template <int D, typename IT>
 static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, const void* dy, float* grad,
-                               const Workspace& ws, hipStream_t s) {
+                               const Workspace& ws, const bool counted, hipStream_t s) {
   BinPlan bp = h->bp;
   plan_slices(bp, h->lv, B);
   const bool smooth = h->cfg.interp == HG_INTERP_SMOOTHSTEP;
@@ -985,8 +903,9 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
   };
   const size_t lds_count = (size_t)max_part_bins(cparts) * 4, lds_scatter = (size_t)(3 * max_part_bins(parts) + 1) * 4;
   const uint32_t tile_wgs = (ws.n_tiles + 7u) / 8u * 8u;  // see tile_of_workgroup
-  hipLaunchKernelGGL((bin_count<D>), dim3(tile_wgs, cparts), dim3(kBinThreads), lds_count, s, h->lv, bp, smooth, B, x,
-                     ws.counts, ws.n_bins, ws.n_tiles);
+  if (!counted)
+    hipLaunchKernelGGL((bin_count<D>), dim3(tile_wgs, cparts), dim3(kBinThreads), lds_count, s, h->lv, bp, smooth, B,
+                       x, ws.counts, ws.n_bins, ws.n_tiles);
   hipLaunchKernelGGL(bin_scan, dim3((ws.n_bins + kScanBins - 1) / kScanBins), dim3(kScanThreads), 0, s, ws.n_tiles,
                      ws.n_bins, ws.counts, ws.bin_total, ws.item_counter);
   hipLaunchKernelGGL((bin_scatter<D, IT>), dim3(tile_wgs, parts), dim3(kBinThreads), lds_scatter, s, h->lv, bp,
@@ -1032,27 +951,48 @@ uint64_t hashgrid_bwd_workspace_bytes(const hashgrid_t* hg, uint32_t B) {
   return hg::carve(hg, B, nullptr, nullptr);
 }
 
-hg_status hashgrid_encode_bwd_ws(const hashgrid_t* hg, uint32_t B, const float* x, const void* dLdy,
-                                 float* grad_params, void* workspace, uint64_t workspace_bytes, void* stream) {
-  if (!hg) return HG_ERR_INVALID_ARG;
-  if (B == 0) return HG_OK;
+// shared argument checks of the two entry points that take the scratch buffer
+static hg_status check_workspace(const hashgrid_t* hg, uint32_t B, const void* workspace, uint64_t workspace_bytes) {
   const uint64_t need = hashgrid_bwd_workspace_bytes(hg, B);
   if (need == 0) return HG_ERR_UNSUPPORTED;
-  if (!x || !dLdy || !grad_params || !workspace) return HG_ERR_INVALID_ARG;
-  if (workspace_bytes < need) return HG_ERR_INVALID_ARG;
+  if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255)) return HG_ERR_INVALID_ARG;
+  return HG_OK;
+}
+
+hg_status hashgrid_encode_fwd_ws(const hashgrid_t* hg, uint32_t B, const float* x, const void* params, void* y,
+                                 void* workspace, uint64_t workspace_bytes, void* stream) {
+  if (!hg) return HG_ERR_INVALID_ARG;
+  if (B == 0) return HG_OK;
+  const hg_status ok = check_workspace(hg, B, workspace, workspace_bytes);
+  if (ok != HG_OK) return ok;
+  if (!x || !params || !y || (reinterpret_cast<uintptr_t>(x) & 3)) return HG_ERR_INVALID_ARG;
+  hg::Workspace ws;
+  hg::carve(hg, B, static_cast<uint8_t*>(workspace), &ws);
+  return hg::launch_fwd_counting(hg, B, x, params, y, ws.counts, ws.n_bins, ws.n_tiles,
+                                 static_cast<hipStream_t>(stream));
+}
+
+hg_status hashgrid_encode_bwd_ws(const hashgrid_t* hg, uint32_t B, const float* x, const void* dLdy,
+                                 float* grad_params, void* workspace, uint64_t workspace_bytes, uint32_t flags,
+                                 void* stream) {
+  if (!hg || (flags & ~(uint32_t)HG_BWD_COUNTED)) return HG_ERR_INVALID_ARG;
+  if (B == 0) return HG_OK;
+  const hg_status ok = check_workspace(hg, B, workspace, workspace_bytes);
+  if (ok != HG_OK) return ok;
+  if (!x || !dLdy || !grad_params) return HG_ERR_INVALID_ARG;
   const size_t io = hg->cfg.io_dtype == HG_F16 ? 2 : 4;
   if ((reinterpret_cast<uintptr_t>(x) & 3) || (reinterpret_cast<uintptr_t>(dLdy) & (2 * io - 1)) ||
-      (reinterpret_cast<uintptr_t>(grad_params) & 7) || (reinterpret_cast<uintptr_t>(workspace) & 255))
+      (reinterpret_cast<uintptr_t>(grad_params) & 7))
     return HG_ERR_INVALID_ARG;
   hg::Workspace ws;
   hg::carve(hg, B, static_cast<uint8_t*>(workspace), &ws);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const bool i16 = hg->cfg.io_dtype == HG_F16;
+  const bool i16 = hg->cfg.io_dtype == HG_F16, counted = flags & HG_BWD_COUNTED;
   if (hg->cfg.d == 3)
-    return i16 ? hg::launch_binned<3, _Float16>(hg, B, x, dLdy, grad_params, ws, s)
-               : hg::launch_binned<3, float>(hg, B, x, dLdy, grad_params, ws, s);
-  return i16 ? hg::launch_binned<2, _Float16>(hg, B, x, dLdy, grad_params, ws, s)
-             : hg::launch_binned<2, float>(hg, B, x, dLdy, grad_params, ws, s);
+    return i16 ? hg::launch_binned<3, _Float16>(hg, B, x, dLdy, grad_params, ws, counted, s)
+               : hg::launch_binned<3, float>(hg, B, x, dLdy, grad_params, ws, counted, s);
+  return i16 ? hg::launch_binned<2, _Float16>(hg, B, x, dLdy, grad_params, ws, counted, s)
+             : hg::launch_binned<2, float>(hg, B, x, dLdy, grad_params, ws, counted, s);
 }
 
 }  // extern "C"

@@ -1,0 +1,95 @@
+// Which bin (chunk of a level's gradient slice) each pair of corners of a point falls into:
+// shared by the passes of the binned backward (bwd_binned.hip) and by the forward kernel that
+// counts for it (hashgrid.hip).
+#pragma once
+
+#include "hashgrid_common.hpp"
+#include "hashgrid_internal.hpp"
+
+namespace hg {
+
+#ifndef HG_BIN_THREADS
+#define HG_BIN_THREADS 512
+#endif
+constexpr int kBinThreads = HG_BIN_THREADS;  // points of a tile = threads of a count / scatter workgroup
+#ifndef HG_CHUNK_LOG2
+#define HG_CHUNK_LOG2 12
+#endif
+constexpr uint32_t kChunkLog2 = HG_CHUNK_LOG2;  // log2 of the entries a chunk can hold
+
+template <int D>
+struct Rows {
+  uint32_t bin[1 << (D - 1)];    // global bin
+  uint32_t pack[1 << (D - 1)];   // chunk-local index of the lower | upper << 16 corner along dimension 0
+  float wrow[1 << (D - 1)];      // product of the weights of dimensions 1..d-1
+  float wf0;                     // fractional position along dimension 0 (before any smoothstep)
+  uint32_t k;                    // trailing one bits of the lower corner's coordinate along dimension 0
+  bool cross;                    // hashed level: the pair's corners fall into different chunks (no record)
+};
+
+template <int D, bool COUNT_ONLY>
+__device__ __forceinline__ void rows_of(const LevelTable& lv, const BinPlan& bp, uint32_t l, bool smooth,
+                                        const float (&xp)[D], Rows<D>& out) {
+  const uint32_t N = lv.N[l], verts = lv.verts[l];
+  const bool dense = (lv.dense_mask >> l) & 1u;
+  const float Nf = (float)N;
+  const float shift = smooth ? 0.5f : 0.0f;
+  const float cmaxf = smooth ? Nf : Nf - 1.0f;
+  uint32_t c0[D];
+  float w[D], u[D];
+#pragma unroll
+  for (int i = 0; i < D; ++i) {
+    float wf;
+    split(xp[i], Nf, shift, cmaxf, c0[i], wf);
+    if (i == 0) out.wf0 = wf;
+    w[i] = smooth ? smoothstep(wf) : wf;
+    u[i] = smooth ? smoothstep(1.0f - wf) : 1.0f - wf;
+  }
+  const uint32_t cl = bp.chunk_log2, cmask = (1u << cl) - 1u;
+  const uint32_t gb0 = bp.bin_base[l];
+  out.cross = !dense && (c0[0] & cmask) == cmask;  // v_0 + 1 carries out of the chunk's index bits
+  if (!COUNT_ONLY) {
+    out.k = (uint32_t)__builtin_ctz(~c0[0]) & 15u;  // c0 + 1 < 2^chunk_log2 <= 2^15 on hashed levels
+#pragma unroll
+    for (uint32_t r = 0; r < (1u << (D - 1)); ++r) {
+      float wr = 1.0f;
+#pragma unroll
+      for (int i = 1; i < D; ++i) wr *= ((r >> (i - 1)) & 1u) ? w[i] : u[i];
+      out.wrow[r] = wr;
+    }
+  }
+  // the level kind is uniform: a scalar branch, not per-lane selects between the two maps
+  if (dense) {
+    const uint32_t sh = bp.row_shift[l];
+#pragma unroll
+    for (uint32_t r = 0; r < (1u << (D - 1)); ++r) {
+      uint32_t row = c0[1] + (r & 1u);
+      if (D == 3) row += (c0[D - 1] + (r >> 1)) * verts;
+      const uint32_t bin = row >> sh;
+      out.bin[r] = gb0 + bin;
+      if (!COUNT_ONLY) {
+        const uint32_t la = c0[0] + (row - (bin << sh)) * verts;
+        out.pack[r] = la | ((la + 1u) << 16);
+      }
+    }
+  } else {
+    const uint32_t tmask = lv.T - 1u;
+    uint32_t t1[2], t2[2];
+    t1[0] = c0[1] * prime(1);
+    t1[1] = t1[0] + prime(1);
+    t2[0] = D == 3 ? c0[D - 1] * prime(2) : 0u;
+    t2[1] = t2[0] + prime(2);
+#pragma unroll
+    for (uint32_t r = 0; r < (1u << (D - 1)); ++r) {
+      const uint32_t rt = D == 3 ? t1[r & 1u] ^ t2[r >> 1] : t1[r & 1u];
+      const uint32_t ia = (c0[0] ^ rt) & tmask;
+      out.bin[r] = gb0 + (ia >> cl);
+      if (!COUNT_ONLY) {
+        const uint32_t ib = ((c0[0] + 1u) ^ rt) & tmask;
+        out.pack[r] = (ia & cmask) | ((ib & cmask) << 16);
+      }
+    }
+  }
+}
+
+}  // namespace hg

@@ -10,10 +10,12 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <new>
+#include <type_traits>
 
 #include "hashgrid.h"
 #include "hashgrid_common.hpp"
 #include "hashgrid_internal.hpp"
+#include "bwd_bins.hpp"
 
 namespace hg {
 
@@ -114,6 +116,7 @@ __global__ __launch_bounds__(kBlock) void fwd_general(const LevelTable lv, const
 // keeps the 16 waves of a workgroup on the same slice, which holds the L2 hit
 // rate at that of the level-major grid.
 constexpr int kPmBlock = 1024;
+constexpr size_t kMaxCountingLds = 48 * 1024;  // histograms of a counting forward workgroup
 
 // Entry indices of the 2^D corners for a level known (uniformly) to be 1:1 or
 // hashed, T a power of two on the hashed side: no per-lane selects between the
@@ -186,12 +189,31 @@ struct OutPiece {
   static constexpr bool kPair = kBytes == 16;  // two pieces make a 32-byte sector
 };
 
-template <int D, int F, typename PT, typename IT, bool POW2>
+// With COUNT the kernel also fills, for the binned backward pass over the same points, the
+// table that pass would otherwise count in a kernel of its own: counts[tile][bin] = pairs of
+// corners of the tile's kBinThreads points that fall into the bin (bwd_binned.hip).  The
+// gathers leave the vector ALU and the LDS idle, so the counting rides along.
+struct CountArgs {
+  BinPlan bp;
+  uint32_t* counts;  // [n_tiles][n_bins]
+  uint32_t n_bins, n_tiles;
+};
+struct NoCount {};
+
+template <int D, int F, typename PT, typename IT, bool POW2, bool COUNT>
 __global__ __launch_bounds__(kPmBlock) void fwd_point_major(const LevelTable lv, const bool smooth, const uint32_t B,
                                                             const float* __restrict__ x,
-                                                            const PT* __restrict__ theta, IT* __restrict__ y) {
+                                                            const PT* __restrict__ theta, IT* __restrict__ y,
+                                                            const typename std::conditional<COUNT, CountArgs, NoCount>::type ca) {
   using Piece = OutPiece<F, IT>;
   constexpr int G = Piece::kLevels;
+  constexpr uint32_t kTiles = kPmBlock / kBinThreads;  // tiles of the backward pass per workgroup
+  static_assert(kPmBlock % kBinThreads == 0, "a forward workgroup covers whole tiles");
+  extern __shared__ uint32_t hist[];  // COUNT: [kTiles][n_bins]
+  if constexpr (COUNT) {
+    for (uint32_t i = threadIdx.x; i < kTiles * ca.n_bins; i += kPmBlock) hist[i] = 0;
+    __syncthreads();
+  }
   const uint32_t b0 = blockIdx.x * kPmBlock + threadIdx.x;
   const bool valid = b0 < B;
   const uint32_t b = valid ? b0 : B - 1;  // idle lanes of the last workgroup shadow the last point
@@ -224,6 +246,16 @@ __global__ __launch_bounds__(kPmBlock) void fwd_point_major(const LevelTable lv,
       }
 #pragma unroll
       for (int f = 0; f < F; ++f) out.v[F * j + f] = (IT)acc[f];
+      if constexpr (COUNT) {
+        if (valid) {
+          Rows<D> rw;
+          rows_of<D, true>(lv, ca.bp, l, smooth, xp, rw);
+          uint32_t* h = hist + (threadIdx.x / kBinThreads) * ca.n_bins;
+#pragma unroll
+          for (uint32_t r = 0; r < (1u << (D - 1)); ++r)
+            if (!rw.cross) __hip_atomic_fetch_add(&h[rw.bin[r]], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+      }
       asm volatile("" ::: "memory");  // keep the gathers of one level together
       __syncthreads();
     }
@@ -233,6 +265,15 @@ __global__ __launch_bounds__(kPmBlock) void fwd_point_major(const LevelTable lv,
     } else if (valid) {
       if (Piece::kPair && (piece & 1u)) yrow[piece - 1] = held;
       yrow[piece] = out;
+    }
+  }
+  if constexpr (COUNT) {  // the last level's barrier has passed: the histograms are complete
+#pragma unroll
+    for (uint32_t t = 0; t < kTiles; ++t) {
+      const uint32_t tile = blockIdx.x * kTiles + t;
+      if (tile >= ca.n_tiles) break;
+      for (uint32_t i = threadIdx.x; i < ca.n_bins; i += kPmBlock)
+        ca.counts[(uint64_t)tile * ca.n_bins + i] = hist[t * ca.n_bins + i];
     }
   }
 }
@@ -468,11 +509,11 @@ static hg_status launch_fwd(const hashgrid* h, uint32_t B, const float* x, const
       const dim3 grid((B + kPmBlock - 1) / kPmBlock);
       const bool smooth = h->cfg.interp == HG_INTERP_SMOOTHSTEP;
       if (h->lv.T_is_pow2)
-        hipLaunchKernelGGL((fwd_point_major<D, F, PT, IT, true>), grid, dim3(kPmBlock), 0, s, h->lv, smooth, B, x,
-                           static_cast<const PT*>(params), static_cast<IT*>(y));
+        hipLaunchKernelGGL((fwd_point_major<D, F, PT, IT, true, false>), grid, dim3(kPmBlock), 0, s, h->lv, smooth, B,
+                           x, static_cast<const PT*>(params), static_cast<IT*>(y), NoCount{});
       else
-        hipLaunchKernelGGL((fwd_point_major<D, F, PT, IT, false>), grid, dim3(kPmBlock), 0, s, h->lv, smooth, B, x,
-                           static_cast<const PT*>(params), static_cast<IT*>(y));
+        hipLaunchKernelGGL((fwd_point_major<D, F, PT, IT, false, false>), grid, dim3(kPmBlock), 0, s, h->lv, smooth,
+                           B, x, static_cast<const PT*>(params), static_cast<IT*>(y), NoCount{});
       return launched();
     }
   }
@@ -515,6 +556,42 @@ static hg_status launch_bwd(const hashgrid* h, uint32_t B, const float* x, const
   hipLaunchKernelGGL((bwd_general<D, F, IT>), grid, dim3(kBlock), 0, s, h->lv,
                      h->cfg.interp == HG_INTERP_SMOOTHSTEP, B, x, static_cast<const IT*>(dy), grad);
   return launched();
+}
+
+// Forward pass that also fills counts[n_tiles][n_bins] for the binned backward pass (F = 2,
+// power-of-two T: what that pass serves).  HG_ERR_UNSUPPORTED where the point-major kernel
+// cannot run (misaligned y or tables, L odd with fp32 output) or the histograms do not fit.
+template <int D, typename PT, typename IT>
+static hg_status launch_fwd_counting_t(const hashgrid* h, uint32_t B, const float* x, const void* params, void* y,
+                                       uint32_t* counts, uint32_t n_bins, uint32_t n_tiles, hipStream_t s) {
+  constexpr uint32_t G = OutPiece<2, IT>::kLevels;
+  const size_t lds = (size_t)(kPmBlock / kBinThreads) * n_bins * 4;
+  if (h->lv.L % G != 0 || misaligned(y, 16) || misaligned(params, 2 * sizeof(PT)) || !h->lv.T_is_pow2 ||
+      lds > kMaxCountingLds)
+    return HG_ERR_UNSUPPORTED;
+  CountArgs ca;
+  ca.bp = h->bp;
+  ca.counts = counts;
+  ca.n_bins = n_bins;
+  ca.n_tiles = n_tiles;
+  hipLaunchKernelGGL((fwd_point_major<D, 2, PT, IT, true, true>), dim3((B + kPmBlock - 1) / kPmBlock), dim3(kPmBlock),
+                     lds, s, h->lv, h->cfg.interp == HG_INTERP_SMOOTHSTEP, B, x, static_cast<const PT*>(params),
+                     static_cast<IT*>(y), ca);
+  return launched();
+}
+
+hg_status launch_fwd_counting(const hashgrid* h, uint32_t B, const float* x, const void* params, void* y,
+                              uint32_t* counts, uint32_t n_bins, uint32_t n_tiles, hipStream_t s) {
+  const hashgrid_config& c = h->cfg;
+  if (c.F != 2 || c.d < 2 || c.d > 3) return HG_ERR_UNSUPPORTED;
+  const bool p16 = c.param_dtype == HG_F16, i16 = c.io_dtype == HG_F16;
+#define HG_FWDC(D)                                                                                              \
+  (p16 ? (i16 ? launch_fwd_counting_t<D, _Float16, _Float16>(h, B, x, params, y, counts, n_bins, n_tiles, s)    \
+              : launch_fwd_counting_t<D, _Float16, float>(h, B, x, params, y, counts, n_bins, n_tiles, s))      \
+       : (i16 ? launch_fwd_counting_t<D, float, _Float16>(h, B, x, params, y, counts, n_bins, n_tiles, s)       \
+              : launch_fwd_counting_t<D, float, float>(h, B, x, params, y, counts, n_bins, n_tiles, s)))
+  return c.d == 3 ? HG_FWDC(3) : HG_FWDC(2);
+#undef HG_FWDC
 }
 
 // Expands `CALL(D, F)` for the runtime (d, F) pair.

@@ -30,4 +30,7 @@ struct hashgrid {
 
 namespace hg {
 void build_bin_plan(hashgrid* h);
+// hashgrid.hip: forward pass that also fills counts[n_tiles][n_bins] of the binned backward pass
+hg_status launch_fwd_counting(const hashgrid* h, uint32_t B, const float* x, const void* params, void* y,
+                              uint32_t* counts, uint32_t n_bins, uint32_t n_tiles, hipStream_t s);
 }

@@ -105,6 +105,13 @@ def run_case(d, L, F, T, N_min, N_max, pdt, iot, interp, x, theta, dy, do_indice
         check_bwd(gw.cpu().numpy(), g_ref, g_abs, floor)
         gw2 = grid.encode_bwd(xd, gd, gw.clone())
         check_bwd(gw2.cpu().numpy(), 2 * g_ref, 2 * g_abs, 2 * floor)
+        # hashgrid_encode_fwd_ws: the same y, and its counts serve the backward pass
+        yc = grid.encode_fwd(xd, td, count_for_bwd=True)
+        assert torch.equal(yc, y)
+        if grid._counted is not None:
+            gc = grid.encode_bwd(xd, gd)
+            assert grid._counted is None
+            check_bwd(gc.cpu().numpy(), g_ref, g_abs, floor)
 
     if do_dx:
         dx = grid.encode_bwd_input(xd, td, gd).cpu().numpy().astype(np.float64)
@@ -291,6 +298,29 @@ def test_workspace_backward_is_reproducible_and_keeps_untouched_entries():
     assert untouched.any() and bool((g3[untouched] == 7.25).all())
 
 
+def test_counting_forward_gives_the_counts_of_the_count_pass():
+    # bit-for-bit the same gradient on hashed levels (exact sums), with and without the counting pass
+    for name, B in (("sdf3d", 70001), ("tiny2d", 4096), ("image2d", 30000)):
+        w = synth.WORKLOADS[name]
+        grid = HashGrid(w.d, w.L, w.F, w.T, w.N_min, w.N_max, w.param_dtype, w.io_dtype)
+        x, theta, dy = synth.make_inputs(w, grid.n_entries, B=B, table_scale=1.0)
+        xd, td, gd = dev(x), dev(theta), dev(dy)
+        y0 = grid.encode_fwd(xd, td)
+        g0 = grid.encode_bwd(xd, gd)
+        y1 = grid.encode_fwd(xd, td, count_for_bwd=True)
+        counted = grid._counted is not None
+        g1 = grid.encode_bwd(xd, gd)
+        assert torch.equal(y0, y1)
+        hashed = [i for i in grid.levels() if not i.is_dense]
+        lo = hashed[0].entry_offset
+        assert torch.equal(g0[lo:], g1[lo:])
+        torch.testing.assert_close(g0[:lo], g1[:lo], rtol=1e-4, atol=1e-4 * float(g0.abs().max()))
+        assert counted == (name != "image2d")  # 7.6 K chunks: its histograms do not fit the forward's LDS
+        # the counts are consumed: a second backward counts for itself and agrees
+        g2 = grid.encode_bwd(xd, gd)
+        assert torch.equal(g0[lo:], g2[lo:])
+
+
 def test_workspace_backward_argument_checks():
     grid = HashGrid(3, 16, 2, 1 << 19, 16, 2048)
     B = 1000
@@ -302,14 +332,21 @@ def test_workspace_backward_argument_checks():
     small = torch.empty(need - 256, dtype=torch.uint8, device="cuda")
     lib = grid._lib
     st = lib.hashgrid_encode_bwd_ws(grid._h, B, x.data_ptr(), dy.data_ptr(), g.data_ptr(), small.data_ptr(),
-                                    small.numel(), None)
+                                    small.numel(), 0, None)
     assert st == 1  # too small
-    st = lib.hashgrid_encode_bwd_ws(grid._h, B, x.data_ptr(), dy.data_ptr(), g.data_ptr(), None, need, None)
+    st = lib.hashgrid_encode_bwd_ws(grid._h, B, x.data_ptr(), dy.data_ptr(), g.data_ptr(), None, need, 0, None)
     assert st == 1
+    big = torch.empty(need, dtype=torch.uint8, device="cuda")
+    assert lib.hashgrid_encode_bwd_ws(grid._h, B, x.data_ptr(), dy.data_ptr(), g.data_ptr(), big.data_ptr(), need,
+                                      8, None) == 1  # unknown flag
     # configurations the binned path does not serve report 0 bytes and HG_ERR_UNSUPPORTED
     g4 = HashGrid(3, 16, 4, 1 << 19, 16, 2048)
     assert g4.bwd_workspace_bytes(B) == 0
     assert lib.hashgrid_encode_bwd_ws(g4._h, B, x.data_ptr(), dy.data_ptr(), g.data_ptr(), small.data_ptr(),
+                                      small.numel(), 0, None) == 2
+    th4 = torch.zeros((g4.n_entries, 4), dtype=torch.float16, device="cuda")
+    y4 = torch.empty((B, 64), dtype=torch.float16, device="cuda")
+    assert lib.hashgrid_encode_fwd_ws(g4._h, B, x.data_ptr(), th4.data_ptr(), y4.data_ptr(), small.data_ptr(),
                                       small.numel(), None) == 2
 
 
