@@ -112,9 +112,9 @@ hg_status hashgrid_encode_bwd(const hashgrid_t* hg, uint32_t B, const float* x, 
 
 /* Size in bytes of the scratch buffer hashgrid_encode_bwd_ws needs for a batch of
  * B points, or 0 when that variant does not serve this configuration or batch
- * (it needs F = 2, d = 2 or 3, a power-of-two T of at most 2^22 (1024 chunks of 4096
- * entries per level), at most 4096 vertices per axis on 1:1 levels and
- * B*L*2^(d-1) < 2^32). */
+ * (it needs d = 2 or 3, a power-of-two T of at most 2^22 (2^21 at F = 8: 1024 chunks of
+ * 4096, or 2048, entries per level), at most 4096 (2048) vertices per axis on 1:1 levels
+ * and B*L*2^(d-1) < 2^32). */
 uint64_t hashgrid_bwd_workspace_bytes(const hashgrid_t* hg, uint32_t B);
 
 /* Backward pass to the tables, same result as hashgrid_encode_bwd (Fig. 3
@@ -124,10 +124,10 @@ uint64_t hashgrid_bwd_workspace_bytes(const hashgrid_t* hg, uint32_t B);
  * 64-bit fixed point scaled to the largest |dLdy| of the call (each summand is
  * rounded to about 2^-38 of that value or finer), so the result does not depend
  * on the order of execution, except on coarse 1:1 levels whose few chunks are
- * shared by several workgroups and combined with fp32 atomic adds.  When dLdy
- * is fp16 the sorted records carry the interpolation weights as 23- and 25-bit
- * fixed point: a gradient entry then differs from hashgrid_encode_bwd's by at
- * most about 2^-23 times the sum of |dLdy| over the corners that touch it.
+ * shared by several workgroups and combined with fp32 atomic adds.  The sorted
+ * records carry the interpolation weights as 23- and 25-bit fixed point: a
+ * gradient entry differs from hashgrid_encode_bwd's by at most about 2^-23 times
+ * the sum of |dLdy| over the corners that touch it.
  *   workspace  device, 256-byte aligned, at least hashgrid_bwd_workspace_bytes(hg, B)
  *              bytes, owned by the caller; contents are scratch: undefined on
  *              entry and on exit.  Calls that overlap in time need separate

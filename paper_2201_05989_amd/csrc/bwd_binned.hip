@@ -77,119 +77,71 @@ constexpr uint32_t kCountParts = HG_COUNT_PARTS;  // ... of the count grid (its 
 // workgroup keeps one LDS word per bin of its part, a scatter workgroup three, next to its staging area.
 constexpr uint32_t kMaxCountPartBins = 4096, kMaxScatterPartBins = 2048;
 
-// One record = one pair of corners that differ along dimension 0, both inside one
-// chunk: local indices la (lower corner) and lb (upper corner), the fractional
-// position wf0 along dimension 0 and what the pair receives in total, wrow * dL/dy.
-template <typename IT>
-struct Record;
-
-// dL/dy in fp32: 16 bytes {la | lb << 16, wf0, wrow * dL/dy_0, wrow * dL/dy_1}, all fp32.
-template <>
-struct Record<float> {
-  using Stored = u32x4;
-  static constexpr uint32_t kWords = 4;
-  static __device__ __forceinline__ Stored make(uint32_t la, uint32_t lb, uint32_t /*k*/, float wf0, float wrow,
-                                                float g0, float g1) {
-    Stored r;
-    r.x = la | (lb << 16);
-    r.y = __float_as_uint(wf0);
-    r.z = __float_as_uint(wrow * g0);
-    r.w = __float_as_uint(wrow * g1);
-    return r;
-  }
-  static __device__ __forceinline__ Stored load(const uint32_t* base, uint32_t i) {
-    return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base) + i);
-  }
-  static __device__ __forceinline__ void unpack(const Stored& r, bool /*dense*/, uint32_t cmask, uint32_t& la,
-                                                uint32_t& lb, float& wf0, float& g0, float& g1) {
-    la = r.x & cmask;
-    lb = (r.x >> 16) & cmask;
-    wf0 = __uint_as_float(r.y);
-    g0 = __uint_as_float(r.z);
-    g1 = __uint_as_float(r.w);
-  }
-  // the same with the pair's two totals as doubles, times `scale`
-  static __device__ __forceinline__ void unpack_scaled(const Stored& r, bool dense, uint32_t cmask, double scale,
-                                                       uint32_t& la, uint32_t& lb, float& wf0, double& G0,
-                                                       double& G1) {
-    float g0, g1;
-    unpack(r, dense, cmask, la, lb, wf0, g0, g1);
-    G0 = (double)g0 * scale;
-    G1 = (double)g1 * scale;
-  }
-};
-
-// dL/dy in fp16: 12 bytes.  Bits 0-11 la; bits 12-15 k, where on a hashed level
-// lb = la ^ (2^(k+1) - 1) (k = number of trailing one bits of the lower corner's
-// coordinate along dimension 0: pi_1 = 1 in Eq. 4, so stepping that coordinate
-// XORs the index with this mask) and on a 1:1 level lb = la + 1; bits 16-38 wf0
-// in units of 2^-23 (exact whenever the scaled coordinate is 1 or more, because
-// then its fraction is a multiple of 2^-23; otherwise rounded, off by 2^-24 at
-// most); bits 39-63 wrow in units of 2^-24 (0 and 1 exact, off by 2^-25 at most);
-// the last word is the level's two fp16 values of dL/dy, untouched.  Both weights
-// lie in [0,1] and the weights of a pair, and of the rows of a point, sum to 1,
-// so the rounding moves a gradient entry by at most about 2^-23 times the sum of
-// |dL/dy| over the corners that touch it.
-struct Rec12 {
-  uint32_t a, b, c;
-};
-static_assert(kChunkLog2 <= 12, "the 12-byte record holds a 12-bit local index");
-template <>
-struct Record<_Float16> {
-  using Stored = Rec12;
-  static constexpr uint32_t kWords = 3;
-  static __device__ __forceinline__ Stored make(uint32_t la, uint32_t /*lb*/, uint32_t k, float wf0, float wrow,
-                                                _Float16 g0, _Float16 g1) {
+// One record = one pair of corners that differ along dimension 0, both inside one chunk.
+// Two header words, then the level's F values of dL/dy as they came (fp16 pairs share a word):
+//   bits 0-11   la, chunk-local index of the lower corner;
+//   bits 12-15  k: on a hashed level the upper corner is lb = la ^ (2^(k+1) - 1), k = number of
+//               trailing one bits of the lower corner's coordinate along dimension 0 (pi_1 = 1
+//               in Eq. 4, so stepping that coordinate XORs the index with this mask, cut to the
+//               table size when the table is smaller than a chunk); on a 1:1 level lb = la + 1;
+//   bits 16-38  wf0, fractional position along dimension 0, in units of 2^-23 (exact whenever
+//               the scaled coordinate is 1 or more, because then its fraction is a multiple of
+//               2^-23; otherwise rounded, off by 2^-24 at most);
+//   bits 39-63  wrow, product of the weights of the other dimensions, in units of 2^-24 (0 and
+//               1 exact, off by 2^-25 at most).
+// 12 bytes at F = 2 with fp16 dL/dy.  Both weights lie in [0,1] and the weights of a pair, and
+// of the rows of a point, sum to 1, so the rounding moves a gradient entry by at most about
+// 2^-23 times the sum of |dL/dy| over the corners that touch it.  The two passes over the
+// records are bound by memory bandwidth: their size is what sets the time.
+template <typename IT, int F>
+struct Record {
+  static constexpr uint32_t kPayloadWords = (F * sizeof(IT) + 3) / 4;
+  static constexpr uint32_t kWords = 2 + kPayloadWords;
+  struct Stored {
+    uint32_t w[kWords];
+  };
+  static __device__ __forceinline__ Stored make(uint32_t la, uint32_t k, float wf0, float wrow, const IT (&g)[F]) {
     uint32_t q0 = (uint32_t)rintf(wf0 * 0x1p23f);
     q0 = q0 < 0x7fffffu ? q0 : 0x7fffffu;
     uint32_t qr = (uint32_t)rintf(wrow * 0x1p24f);
     qr = qr < 0x1000000u ? qr : 0x1000000u;
     const uint64_t p = (uint64_t)(la | (k << 12)) | ((uint64_t)q0 << 16) | ((uint64_t)qr << 39);
-    Vec<_Float16, 2> g;
-    g.v[0] = g0;
-    g.v[1] = g1;
     Stored r;
-    r.a = (uint32_t)p;
-    r.b = (uint32_t)(p >> 32);
-    r.c = *reinterpret_cast<const uint32_t*>(&g);
+    r.w[0] = (uint32_t)p;
+    r.w[1] = (uint32_t)(p >> 32);
+    IT pay[kPayloadWords * 4 / sizeof(IT)];
+#pragma unroll
+    for (uint32_t f = 0; f < kPayloadWords * 4 / sizeof(IT); ++f) pay[f] = f < (uint32_t)F ? g[f] : (IT)0;
+    __builtin_memcpy(&r.w[2], pay, kPayloadWords * 4);
     return r;
   }
   static __device__ __forceinline__ Stored load(const uint32_t* base, uint32_t i) {
-    const uint32_t* p = base + (uint64_t)i * 3;
+    const uint32_t* p = base + (uint64_t)i * kWords;
     Stored r;
-    r.a = __builtin_nontemporal_load(p);
-    r.b = __builtin_nontemporal_load(p + 1);
-    r.c = __builtin_nontemporal_load(p + 2);
+#pragma unroll
+    for (uint32_t q = 0; q < kWords; ++q) r.w[q] = __builtin_nontemporal_load(p + q);
     return r;
   }
-  static __device__ __forceinline__ void unpack(const Stored& r, bool dense, uint32_t cmask, uint32_t& la,
-                                                uint32_t& lb, float& wf0, float& g0, float& g1) {
-    const uint64_t p = (uint64_t)r.a | ((uint64_t)r.b << 32);
-    la = r.a & 0xfffu;
-    const uint32_t k = (r.a >> 12) & 0xfu;
-    lb = (dense ? la + 1u : la ^ ((2u << k) - 1u)) & cmask;
-    wf0 = (float)((uint32_t)(p >> 16) & 0x7fffffu) * 0x1p-23f;
-    const float wrow = (float)(uint32_t)(p >> 39) * 0x1p-24f;
-    const Vec<_Float16, 2> g = *reinterpret_cast<const Vec<_Float16, 2>*>(&r.c);
-    g0 = wrow * (float)g.v[0];
-    g1 = wrow * (float)g.v[1];
-  }
-  // the same with the pair's two totals as doubles, times `scale`: wrow * dL/dy is a
-  // 25-bit by 11-bit product, exact in a double
-  static __device__ __forceinline__ void unpack_scaled(const Stored& r, bool dense, uint32_t cmask, double scale,
-                                                       uint32_t& la, uint32_t& lb, float& wf0, double& G0,
-                                                       double& G1) {
-    const uint64_t p = (uint64_t)r.a | ((uint64_t)r.b << 32);
-    la = r.a & 0xfffu;
-    const uint32_t k = (r.a >> 12) & 0xfu;
-    lb = (dense ? la + 1u : la ^ ((2u << k) - 1u)) & cmask;
+  // la, lb, wf0 and the F totals of the pair, wrow * dL/dy_f, as doubles times `scale`: a 25-bit
+  // by at most 24-bit product, exact in a double
+  // `xmask`: on a hashed level, the chunk's entry count minus one (a table smaller than a chunk
+  // wraps the XOR); `cmask`: the chunk capacity minus one
+  static __device__ __forceinline__ void unpack_scaled(const Stored& r, bool dense, uint32_t cmask, uint32_t xmask,
+                                                       double scale, uint32_t& la, uint32_t& lb, float& wf0,
+                                                       double (&G)[F]) {
+    const uint64_t p = (uint64_t)r.w[0] | ((uint64_t)r.w[1] << 32);
+    la = r.w[0] & 0xfffu & cmask;
+    const uint32_t k = (r.w[0] >> 12) & 0xfu;
+    lb = dense ? (la + 1u) & cmask : la ^ (((2u << k) - 1u) & xmask);
     wf0 = (float)((uint32_t)(p >> 16) & 0x7fffffu) * 0x1p-23f;
     const double wrow = (double)(uint32_t)(p >> 39) * (scale * 0x1p-24);
-    const Vec<_Float16, 2> g = *reinterpret_cast<const Vec<_Float16, 2>*>(&r.c);
-    G0 = wrow * (double)(float)g.v[0];
-    G1 = wrow * (double)(float)g.v[1];
+    IT pay[kPayloadWords * 4 / sizeof(IT)];
+    __builtin_memcpy(pay, &r.w[2], kPayloadWords * 4);
+#pragma unroll
+    for (int f = 0; f < F; ++f) G[f] = wrow * (double)(float)pay[f];
   }
 };
+static_assert(kChunkLog2 <= 12, "a record holds a 12-bit local index");
 
 struct Workspace {
   uint32_t* counts;     // [n_tiles + 1][n_bins] counts, then exclusive prefix over tiles (last row: totals)
@@ -197,7 +149,7 @@ struct Workspace {
   uint32_t* bin_total;  // [n_bins] records in the bin
   float* tile_max;      // [n_tiles * scatter_parts] largest |dL/dy| seen by each scatter workgroup
   uint32_t* item_counter;  // [1] next work item of the accumulate pass
-  uint32_t* records;    // [B * L * rec_per_point] records of 3 or 4 words
+  uint32_t* records;    // [B * L * rec_per_point] records (Record::kWords words each)
   uint32_t n_tiles;
   uint32_t n_bins;
 };
@@ -216,7 +168,8 @@ static uint64_t carve(const hashgrid* h, uint32_t B, uint8_t* base, Workspace* w
   };
   const uint64_t o_counts = take((uint64_t)(nt + 1) * nb * 4), o_start = take((uint64_t)nb * 4),
                  o_total = take((uint64_t)nb * 4), o_max = take((uint64_t)nt * h->bp.scatter_parts * 4), o_item = take(4),
-                 o_rec = take((uint64_t)B * h->lv.L * h->bp.rec_per_point * (h->cfg.io_dtype == HG_F16 ? 12 : 16));
+                 o_rec = take((uint64_t)B * h->lv.L * h->bp.rec_per_point *
+                              (8 + (h->cfg.F * (h->cfg.io_dtype == HG_F16 ? 2u : 4u) + 3u) / 4u * 4u));
   if (ws) {
     ws->counts = reinterpret_cast<uint32_t*>(base + o_counts);
     ws->bin_start = reinterpret_cast<uint32_t*>(base + o_start);
@@ -240,10 +193,10 @@ void build_bin_plan(hashgrid* h) {
   bp = BinPlan{};
   const hashgrid_config& c = h->cfg;
   const LevelTable& lv = h->lv;
-  bp.chunk_log2 = kChunkLog2;
+  bp.chunk_log2 = chunk_log2_of(c.F);
   bp.rec_per_point = 1u << (c.d - 1);
-  if (c.F != 2 || c.d < 2 || c.d > 3 || !lv.T_is_pow2) return;
-  const uint32_t cap = 1u << kChunkLog2;
+  if (c.d < 2 || c.d > 3 || !lv.T_is_pow2) return;  // F is 1, 2, 4 or 8 (hashgrid_create)
+  const uint32_t cap = 1u << bp.chunk_log2;
   uint32_t bins = 0;
   for (uint32_t l = 0; l < lv.L; ++l) {
     const uint32_t verts = lv.verts[l];
@@ -259,7 +212,7 @@ void build_bin_plan(hashgrid* h) {
       // The two corners of a pair share the bits above the chunk unless stepping v_0 carries out of
       // its low chunk_log2 bits, which needs a resolution of 2^chunk_log2 or more and then happens
       // for one voxel in 2^chunk_log2: those pairs bypass the sort (see bin_scatter).
-      nb = lv.T > cap ? lv.T >> kChunkLog2 : 1u;
+      nb = lv.T > cap ? lv.T >> bp.chunk_log2 : 1u;
     }
     if (nb > (uint32_t)kScanThreads) return;
     bp.bin_base[l] = bins;
@@ -308,9 +261,9 @@ static void plan_slices(BinPlan& bp, const LevelTable& lv, uint32_t B) {
 // The pairs of a hashed level whose two corners lie in different chunks (Rows::cross; one voxel
 // in 2^chunk_log2 along dimension 0, and only at resolutions of 2^chunk_log2 or more) get no
 // record: their 2^d products go to the gradient with device-scope atomics.  T is a power of two.
-template <int D>
+template <int D, int F>
 __device__ __forceinline__ void add_crossing_pairs(const LevelTable& lv, uint32_t l, bool smooth, const float (&xp)[D],
-                                                float g0, float g1, float* __restrict__ grad) {
+                                                   const float (&g)[F], float* __restrict__ grad) {
   const float Nf = (float)lv.N[l];
   const float shift = smooth ? 0.5f : 0.0f;
   const float cmaxf = smooth ? Nf : Nf - 1.0f;
@@ -324,7 +277,7 @@ __device__ __forceinline__ void add_crossing_pairs(const LevelTable& lv, uint32_
     u[i] = smooth ? smoothstep(1.0f - wf) : 1.0f - wf;
   }
   const uint32_t tmask = lv.T - 1u;
-  float* gl = grad + lv.offset[l] * 2;
+  float* gl = grad + lv.offset[l] * F;
 #pragma unroll
   for (uint32_t r = 0; r < (1u << (D - 1)); ++r) {
     float wr = 1.0f;
@@ -336,10 +289,11 @@ __device__ __forceinline__ void add_crossing_pairs(const LevelTable& lv, uint32_
       rt ^= (c0[i] + up) * prime(i);
     }
     const uint32_t ia = (c0[0] ^ rt) & tmask, ib = ((c0[0] + 1u) ^ rt) & tmask;
-    __hip_atomic_fetch_add(gl + 2 * (uint64_t)ia, u[0] * (wr * g0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_fetch_add(gl + 2 * (uint64_t)ia + 1, u[0] * (wr * g1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_fetch_add(gl + 2 * (uint64_t)ib, w[0] * (wr * g0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_fetch_add(gl + 2 * (uint64_t)ib + 1, w[0] * (wr * g1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+    for (int f = 0; f < F; ++f) {
+      __hip_atomic_fetch_add(gl + F * (uint64_t)ia + f, u[0] * (wr * g[f]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_fetch_add(gl + F * (uint64_t)ib + f, w[0] * (wr * g[f]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
   }
 }
 
@@ -506,11 +460,11 @@ __global__ __launch_bounds__(kScanThreads) void bin_scan(const uint32_t n_tiles,
 // what reaches memory is runs of whole records that mostly fill whole cache
 // lines; 16-byte stores scattered over a thousand open runs leave the L2 as
 // partial lines and cost several times the bytes.
-// LDS (dynamic), indexed by bin relative to the first bin of this part's levels:
+// Per-bin arrays in LDS, indexed by bin relative to the first bin of this part's levels:
 // local[nbp + 1] exclusive prefix of this tile's counts (where a bin's records
 // sit in the tile's sorted order), cur[nbp] the same, advanced as records are
 // placed, delta[nbp] = global slot minus tile-local position.
-template <int D, typename IT>
+template <int D, typename IT, int F>
 __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, const BinPlan bp, const bool smooth,
                                                            const uint32_t B, const float* __restrict__ x,
                                                            const IT* __restrict__ dy,
@@ -521,21 +475,25 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, 
                                                            const uint32_t n_records, const uint32_t n_tiles,
                                                            float* __restrict__ tile_max, float* __restrict__ grad) {
   constexpr uint32_t R = 1u << (D - 1);
-  using Rec = Record<IT>;
-  typename Rec::Stored* out = reinterpret_cast<typename Rec::Stored*>(records);
-  extern __shared__ uint32_t lds_u32[];
+  using Rec = Record<IT, F>;
+  using Stored = typename Rec::Stored;
+  Stored* out = reinterpret_cast<Stored*>(records);
   __shared__ uint32_t scan_tmp[kBinThreads / 64];
-  __shared__ typename Rec::Stored staging[R * kBinThreads];
-  __shared__ uint16_t binv[R * kBinThreads];  // part-relative bin of each staged record
+  // dynamic LDS: staging[R * kBinThreads] records, binv[R * kBinThreads] (part-relative bin of each
+  // staged record, 16 bits), then the three per-bin arrays
+  extern __shared__ uint32_t lds_u32[];
+  Stored* staging = reinterpret_cast<Stored*>(lds_u32);
+  uint16_t* binv = reinterpret_cast<uint16_t*>(lds_u32 + R * kBinThreads * Rec::kWords);
+  uint32_t* bins_lds = lds_u32 + R * kBinThreads * Rec::kWords + R * kBinThreads / 2;
 
   const uint32_t tile = tile_of_workgroup(blockIdx.x, n_tiles);
   if (tile >= n_tiles) return;  // uniform: a surplus workgroup of the rounded-up grid
   uint32_t l0, l1;
   part_levels(lv.L, l0, l1);
   const uint32_t gb_a = bp.bin_base[l0], nbp = bp.bin_base[l1] - gb_a;
-  uint32_t* delta = lds_u32;
-  uint32_t* local = lds_u32 + nbp;
-  uint32_t* cur = lds_u32 + 2 * nbp + 1;
+  uint32_t* delta = bins_lds;
+  uint32_t* local = bins_lds + nbp;
+  uint32_t* cur = bins_lds + 2 * nbp + 1;
 
   // records of all bins before this part
   uint32_t before = 0;
@@ -569,44 +527,58 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, 
   const uint32_t b = valid ? (uint32_t)b64 : 0u;
   float xp[D];
   load_x<D>(x, b, xp);
-  // dL/dy of K consecutive levels comes in as one 16-byte load: a 4-byte read per level with
-  // the stride of a row would cost the L1 a line per two lanes, sixteen times over
-  constexpr uint32_t K = 16 / (2 * sizeof(IT));
-  const IT* row = dy + (uint64_t)b * lv.L * 2;
+  // dL/dy comes in as 16-byte pieces, K levels each when a level is narrower than that: a narrow
+  // read per level with the stride of a row would cost the L1 a line per two lanes, L times over
+  constexpr uint32_t kLevelBytes = F * sizeof(IT);
+  constexpr uint32_t K = kLevelBytes >= 16 ? 1 : 16 / kLevelBytes;  // levels per piece
+  constexpr uint32_t E = 16 / sizeof(IT);                           // scalars per piece
+  constexpr uint32_t P = kLevelBytes >= 16 ? kLevelBytes / 16 : 1;  // pieces per level
+  const IT* row = dy + (uint64_t)b * lv.L * F;
   const bool vec_ok = (lv.L % K == 0) && (l0 % K == 0) && ((reinterpret_cast<uintptr_t>(dy) & 15) == 0);
-  Vec<IT, 2 * K> gv;
+  Vec<IT, E> gv;
   float gmax = 0.0f;  // largest |dL/dy| this workgroup sees (idle lanes shadow point 0)
   for (uint32_t l = l0; l < l1; ++l) {
     const uint32_t rb0 = bp.bin_base[l] - gb_a, rb1 = bp.bin_base[l + 1] - gb_a;
     const uint32_t level_first = local[rb0], emitted = local[rb1] - level_first;  // <= R * kBinThreads
-    IT g0, g1;
-    if (vec_ok) {  // uniform
-      if ((l - l0) % K == 0) gv = *reinterpret_cast<const Vec<IT, 2 * K>*>(row + (uint64_t)l * 2);
+    IT g[F];
+    if (vec_ok && K > 1) {  // uniform
+      if ((l - l0) % K == 0) gv = *reinterpret_cast<const Vec<IT, E>*>(row + (uint64_t)l * F);
       const uint32_t k = (l - l0) % K;
-      g0 = gv.v[0];
-      g1 = gv.v[1];
 #pragma unroll
-      for (uint32_t q = 1; q < K; ++q) {
-        g0 = k == q ? gv.v[2 * q] : g0;
-        g1 = k == q ? gv.v[2 * q + 1] : g1;
+      for (int f = 0; f < F; ++f) {
+        g[f] = gv.v[f];
+#pragma unroll
+        for (uint32_t q = 1; q < K; ++q) g[f] = k == q ? gv.v[F * q + f] : g[f];
+      }
+    } else if (vec_ok) {
+#pragma unroll
+      for (uint32_t q = 0; q < P; ++q) {
+        const Vec<IT, E> piece = *reinterpret_cast<const Vec<IT, E>*>(row + (uint64_t)l * F + q * E);
+#pragma unroll
+        for (uint32_t e = 0; e < E; ++e)
+          if (q * E + e < (uint32_t)F) g[q * E + e] = piece.v[e];
       }
     } else {
-      const Vec<IT, 2> g = reinterpret_cast<const Vec<IT, 2>*>(row)[l];
-      g0 = g.v[0];
-      g1 = g.v[1];
+#pragma unroll
+      for (int f = 0; f < F; ++f) g[f] = row[(uint64_t)l * F + f];
     }
-    gmax = nan_max(nan_max(gmax, fabsf((float)g0)), fabsf((float)g1));
+    float gf[F];
+#pragma unroll
+    for (int f = 0; f < F; ++f) {
+      gf[f] = (float)g[f];
+      gmax = nan_max(gmax, fabsf(gf[f]));
+    }
     if (valid) {
       Rows<D> rw;
       rows_of<D, false>(lv, bp, l, smooth, xp, rw);
-      if (rw.cross) add_crossing_pairs<D>(lv, l, smooth, xp, (float)g0, (float)g1, grad);
+      if (rw.cross) add_crossing_pairs<D, F>(lv, l, smooth, xp, gf, grad);
 #pragma unroll
       for (uint32_t r = 0; r < R && !rw.cross; ++r) {
         const uint32_t rb = rw.bin[r] - gb_a;
         const uint32_t in_tile = __hip_atomic_fetch_add(&cur[rb], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         const uint32_t pos = in_tile - level_first;
         if (pos < R * kBinThreads) {  // holds when the count pass saw the same x
-          staging[pos] = Rec::make(rw.pack[r] & 0xffffu, rw.pack[r] >> 16, rw.k, rw.wf0, rw.wrow[r], g0, g1);
+          staging[pos] = Rec::make(rw.pack[r] & 0xfffu, rw.k, rw.wf0, rw.wrow[r], g);
           binv[pos] = (uint16_t)rb;
         }
       }
@@ -650,7 +622,7 @@ __device__ __forceinline__ unsigned long long fixed_product(float w, double G) {
 // draw more of them: items differ in size by a factor of ten on 1:1 levels when
 // the points crowd around a surface.  The LDS accumulators are re-zeroed by the
 // lanes that have just read them.
-template <typename IT, bool SMOOTH>
+template <typename IT, int F, bool SMOOTH>
 __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable lv, const BinPlan bp,
                                                               const uint32_t B, const uint32_t n_items,
                                                               const uint32_t* __restrict__ bin_start,
@@ -661,8 +633,8 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
                                                               uint32_t* __restrict__ item_counter,
                                                               float* __restrict__ grad) {
   __shared__ uint32_t s_ticket;
-  extern __shared__ unsigned long long acc[];  // [2][2^chunk_log2] fixed point: feature 0 of every entry, then
-                                               // feature 1, so that consecutive entries map to consecutive banks
+  extern __shared__ unsigned long long acc[];  // [F][2^chunk_log2] fixed point: feature 0 of every entry, then
+                                               // feature 1 ..., so that consecutive entries map to consecutive banks
   // largest |dL/dy| of the call (NaN if any is NaN) from the scatter workgroups' maxima
   __shared__ float red[kAccThreads / 64];
   float m = 0.0f;
@@ -676,23 +648,24 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
   for (int i = 1; i < kAccThreads / 64; ++i) m = nan_max(m, red[i]);
   if (m == 0.0f) return;  // every summand is zero (uniform: all lanes hold the same m)
   const bool finite = m < INFINITY;
-  const uint32_t cl = bp.chunk_log2, cap = 1u << cl, cmask = cap - 1u;
-  unsigned long long* acc0 = acc;
-  unsigned long long* acc1 = acc + cap;
+  constexpr uint32_t cl = chunk_log2_of(F), cap = 1u << cl, cmask = cap - 1u;
   // fixed-point scale: |summand| <= m < 2^E, at most 8B summands per entry
   int E = 0;
   if (finite) (void)frexpf(m, &E);
   const int H = 3 + (32 - __builtin_clz(B > 1 ? B - 1 : 1));
   const int S = (62 - H < kFixedBits ? 62 - H : kFixedBits) - E;  // |summand| * 2^S < 2^min(62-H, 51)
   const double scale = ldexp(1.0, S), inv_scale = ldexp(1.0, -S);
-  constexpr int kPer = (1 << kChunkLog2) / kAccThreads;  // entries per lane
+  constexpr int kPer = (int)cap / kAccThreads;  // entries per lane
+  struct alignas(F * 4 > 16 ? 16 : F * 4) Entry {
+    float v[F];
+  };
 
   // item_counter starts at 0 (bin_scan clears it); a ticket is the item it stands for
   auto draw = [&]() {
     return gridDim.x + __hip_atomic_fetch_add(item_counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   };
   if (threadIdx.x == 0) s_ticket = draw();
-  for (uint32_t i = threadIdx.x; i < 2 * cap; i += kAccThreads) acc[i] = 0ull;
+  for (uint32_t i = threadIdx.x; i < F * cap; i += kAccThreads) acc[i] = 0ull;
   __syncthreads();
   uint32_t next = s_ticket;  // every item number of n_items or more ends the loop, and tickets only grow
 
@@ -713,9 +686,13 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
     float* gl;
     bool live, dense;
   };
-  using Rec = Record<IT>;
+  using Rec = Record<IT, F>;
   using Stored = typename Rec::Stored;
   constexpr int kPre = kAccPreWords / (int)Rec::kWords, kHalf = kPre / 2;
+  // wide entries: the registers do not hold the next item's gradient chunk and several records in
+  // flight as well, so the chunk is read when it is flushed and fewer records are unrolled
+  constexpr bool kChunkAhead = F <= 2;
+  constexpr int kUnroll = F <= 2 ? kAccUnroll : 2;
   auto describe = [&](uint32_t item, uint32_t start, uint32_t total, uint32_t l, uint32_t bin, uint32_t slice) {
     Item it;
     it.l = l;
@@ -735,7 +712,7 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
     }
     if (e1 > lv.size[l]) e1 = lv.size[l];
     it.n_e = e1 - e0;
-    it.gl = grad + (lv.offset[l] + e0) * 2;
+    it.gl = grad + (lv.offset[l] + e0) * F;
     return it;
   };
   // records j0..j1-1 of each lane's share of the item
@@ -748,13 +725,13 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
       if (i < it.r1) pre[j] = Rec::load(records, i);
     }
   };
-  auto request_chunk = [&](const Item& it, float2 (&cur)[kPer]) {
-    if (!it.live || !finite) return;
+  auto request_chunk = [&](const Item& it, Entry (&cur)[kPer]) {
+    if (!kChunkAhead || !it.live || !finite) return;
     if (it.n_sl == 1) {
 #pragma unroll
       for (int j = 0; j < kPer; ++j) {
         const uint32_t e = threadIdx.x + j * kAccThreads;
-        if (e < it.n_e) cur[j] = reinterpret_cast<const float2*>(it.gl)[e];
+        if (e < it.n_e) cur[j] = reinterpret_cast<const Entry*>(it.gl)[e];
       }
     }
   };
@@ -768,7 +745,7 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
   }
   Item it = describe(item, start, total, l, bin, slice);
   Stored pre[kPre];
-  float2 cur[kPer];
+  Entry cur[kPer];
   request_records(it, pre, 0, kPre);
   request_chunk(it, cur);
   while (item < n_items) {
@@ -783,21 +760,21 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
     }
     Item it_n;
     it_n.live = false;
-    float2 cur_n[kPer];
+    Entry cur_n[kPer];
     if (it.live && !finite) {
       // inf or NaN upstream: keep IEEE semantics with direct fp32 atomics (slow, rare)
       for (uint32_t i = it.r0 + threadIdx.x; i < it.r1; i += kAccThreads) {
         uint32_t la, lb;
-        float wf, g0, g1;
-        Rec::unpack(Rec::load(records, i), it.dense, cmask, la, lb, wf, g0, g1);
+        float wf;
+        double G[F];
+        Rec::unpack_scaled(Rec::load(records, i), it.dense, cmask, it.n_e - 1u, 1.0, la, lb, wf, G);
         const float wu = SMOOTH ? smoothstep(wf) : wf, wl = SMOOTH ? smoothstep(1.0f - wf) : 1.0f - wf;
-        if (la < it.n_e) {
-          __hip_atomic_fetch_add(it.gl + 2 * la, wl * g0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          __hip_atomic_fetch_add(it.gl + 2 * la + 1, wl * g1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        if (lb < it.n_e) {
-          __hip_atomic_fetch_add(it.gl + 2 * lb, wu * g0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          __hip_atomic_fetch_add(it.gl + 2 * lb + 1, wu * g1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int f = 0; f < F; ++f) {
+          if (la < it.n_e)
+            __hip_atomic_fetch_add(it.gl + F * la + f, wl * (float)G[f], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          if (lb < it.n_e)
+            __hip_atomic_fetch_add(it.gl + F * lb + f, wu * (float)G[f], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
       }
       it_n = describe(next, start_n, total_n, l_n, bin_n, slice_n);
@@ -809,13 +786,16 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
       auto add_record = [&](const Stored& rec) {
         uint32_t la, lb;
         float wf;
-        double G0, G1;
-        Rec::unpack_scaled(rec, it.dense, cmask, scale, la, lb, wf, G0, G1);
+        double G[F];
+        Rec::unpack_scaled(rec, it.dense, cmask, it.n_e - 1u, scale, la, lb, wf, G);
         const float wu = SMOOTH ? smoothstep(wf) : wf, wl = SMOOTH ? smoothstep(1.0f - wf) : 1.0f - wf;
-        __hip_atomic_fetch_add(&acc0[la], fixed_product(wl, G0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        __hip_atomic_fetch_add(&acc1[la], fixed_product(wl, G1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        __hip_atomic_fetch_add(&acc0[lb], fixed_product(wu, G0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        __hip_atomic_fetch_add(&acc1[lb], fixed_product(wu, G1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+#pragma unroll
+        for (int f = 0; f < F; ++f) {
+          __hip_atomic_fetch_add(&acc[f * cap + la], fixed_product(wl, G[f]), __ATOMIC_RELAXED,
+                                 __HIP_MEMORY_SCOPE_WORKGROUP);
+          __hip_atomic_fetch_add(&acc[f * cap + lb], fixed_product(wu, G[f]), __ATOMIC_RELAXED,
+                                 __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
       };
       // The records requested ahead of time, in two halves: as soon as the first half has been
       // consumed its registers take the first half of the next item, so that loads stay in
@@ -830,12 +810,12 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
         if (it.r0 + threadIdx.x + j * kAccThreads < it.r1) add_record(pre[j]);
       // the rest of a long item, kAccUnroll loads in flight per lane
       uint32_t i = it.r0 + threadIdx.x + kPre * kAccThreads;
-      for (; i + (kAccUnroll - 1) * kAccThreads < it.r1; i += kAccUnroll * kAccThreads) {
-        Stored rec[kAccUnroll];
+      for (; i + (kUnroll - 1) * kAccThreads < it.r1; i += kUnroll * kAccThreads) {
+        Stored rec[kUnroll];
 #pragma unroll
-        for (int j = 0; j < kAccUnroll; ++j) rec[j] = Rec::load(records, i + j * kAccThreads);
+        for (int j = 0; j < kUnroll; ++j) rec[j] = Rec::load(records, i + j * kAccThreads);
 #pragma unroll
-        for (int j = 0; j < kAccUnroll; ++j) add_record(rec[j]);
+        for (int j = 0; j < kUnroll; ++j) add_record(rec[j]);
       }
       for (; i < it.r1; i += kAccThreads) add_record(Rec::load(records, i));
       // request the rest of the next item's records and its gradient chunk, then flush this one under them
@@ -850,24 +830,28 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
 #pragma unroll
         for (int j = 0; j < kPer; ++j) {
           const uint32_t e = threadIdx.x + j * kAccThreads;
-          const long long a0 = (long long)acc0[e], a1 = (long long)acc1[e];
-          acc0[e] = 0ull;  // ready for the next item
-          acc1[e] = 0ull;
+          long long a[F];
+#pragma unroll
+          for (int f = 0; f < F; ++f) {
+            a[f] = (long long)acc[f * cap + e];
+            acc[f * cap + e] = 0ull;  // ready for the next item
+          }
           if (e >= it.n_e) continue;
+          if (!kChunkAhead) cur[j] = reinterpret_cast<const Entry*>(it.gl)[e];
           // an entry no record reached gets -0.0f added, which leaves every float (either zero,
           // NaNs included) exactly as it was; storing it anyway keeps the stores of a wave contiguous
-          cur[j].x += a0 ? (float)((double)a0 * inv_scale) : -0.0f;
-          cur[j].y += a1 ? (float)((double)a1 * inv_scale) : -0.0f;
-          reinterpret_cast<float2*>(it.gl)[e] = cur[j];
+#pragma unroll
+          for (int f = 0; f < F; ++f) cur[j].v[f] += a[f] ? (float)((double)a[f] * inv_scale) : -0.0f;
+          reinterpret_cast<Entry*>(it.gl)[e] = cur[j];
         }
       } else {
         // several workgroups share this chunk: fp32 atomics, one lane per float so that the
-        // two features of an entry and its neighbours travel in the same 64-byte requests
+        // features of an entry and its neighbours travel in the same 64-byte requests
 #pragma unroll
-        for (int j = 0; j < 2 * kPer; ++j) {
+        for (int j = 0; j < F * kPer; ++j) {
           const uint32_t q = threadIdx.x + j * kAccThreads;  // float index in the chunk
-          const uint32_t e = q >> 1;
-          unsigned long long* slot = (q & 1u) ? &acc1[e] : &acc0[e];
+          const uint32_t e = q / F;
+          unsigned long long* slot = &acc[(q % F) * cap + e];
           const long long a = (long long)*slot;
           *slot = 0ull;
           if (e < it.n_e && a != 0)
@@ -885,9 +869,11 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
   }
 }
 
-template <int D, typename IT>
+template <int D, typename IT, int F>
 static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, const void* dy, float* grad,
                                const Workspace& ws, const bool counted, hipStream_t s) {
+  using Rec = Record<IT, F>;
+  constexpr uint32_t R = 1u << (D - 1);
   BinPlan bp = h->bp;
   plan_slices(bp, h->lv, B);
   const bool smooth = h->cfg.interp == HG_INTERP_SMOOTHSTEP;
@@ -901,25 +887,36 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
     }
     return m;
   };
-  const size_t lds_count = (size_t)max_part_bins(cparts) * 4, lds_scatter = (size_t)(3 * max_part_bins(parts) + 1) * 4;
+  // scatter: staging area, 16-bit bin of every staged record, three words per bin of the part
+  constexpr size_t kStagingBytes = (size_t)R * kBinThreads * (Rec::kWords * 4 + 2);
+  constexpr size_t kScatterLdsMax = kStagingBytes + (3 * (size_t)kMaxScatterPartBins + 1) * 4;
+  constexpr size_t kAccLds = (size_t)F * 8 << chunk_log2_of(F);
+  // more dynamic LDS than the default limit of 64 KiB: opt in once per kernel
+  static const hipError_t lds_ok = [] {
+    hipError_t e = hipSuccess;
+    if (kScatterLdsMax > 64 * 1024)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_scatter<D, IT, F>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kScatterLdsMax);
+    if (e == hipSuccess && kAccLds > 48 * 1024)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_accumulate<IT, F, false>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAccLds);
+    if (e == hipSuccess && kAccLds > 48 * 1024)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_accumulate<IT, F, true>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAccLds);
+    return e;
+  }();
+  if (lds_ok != hipSuccess) return HG_ERR_DEVICE;
+  const size_t lds_count = (size_t)max_part_bins(cparts) * 4;
+  const size_t lds_scatter = kStagingBytes + (3 * (size_t)max_part_bins(parts) + 1) * 4;
   const uint32_t tile_wgs = (ws.n_tiles + 7u) / 8u * 8u;  // see tile_of_workgroup
   if (!counted)
     hipLaunchKernelGGL((bin_count<D>), dim3(tile_wgs, cparts), dim3(kBinThreads), lds_count, s, h->lv, bp, smooth, B,
                        x, ws.counts, ws.n_bins, ws.n_tiles);
   hipLaunchKernelGGL(bin_scan, dim3((ws.n_bins + kScanBins - 1) / kScanBins), dim3(kScanThreads), 0, s, ws.n_tiles,
                      ws.n_bins, ws.counts, ws.bin_total, ws.item_counter);
-  hipLaunchKernelGGL((bin_scatter<D, IT>), dim3(tile_wgs, parts), dim3(kBinThreads), lds_scatter, s, h->lv, bp,
+  hipLaunchKernelGGL((bin_scatter<D, IT, F>), dim3(tile_wgs, parts), dim3(kBinThreads), lds_scatter, s, h->lv, bp,
                      smooth, B, x, static_cast<const IT*>(dy), ws.counts, ws.bin_total, ws.bin_start,
                      ws.records, ws.n_bins, n_records, ws.n_tiles, ws.tile_max, grad);
-  // 64 KiB of dynamic LDS plus a few static bytes: above the default limit
-  static const hipError_t lds_ok = [] {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_accumulate<IT, false>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 16 << kChunkLog2);
-    return e != hipSuccess ? e
-                           : hipFuncSetAttribute(reinterpret_cast<const void*>(bin_accumulate<IT, true>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, 16 << kChunkLog2);
-  }();
-  if (lds_ok != hipSuccess) return HG_ERR_DEVICE;
   const uint32_t n_items = bp.wg_base[h->lv.L];
   static const uint32_t acc_slots = [] {  // its registers let one 1024-thread workgroup run per CU; more would queue
     int dev = 0, cus = 0;
@@ -929,16 +926,27 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
     return (uint32_t)cus * HG_ACC_WGS_PER_CU;
   }();
   const dim3 acc_grid(n_items < acc_slots ? n_items : acc_slots);
-  const size_t acc_lds = (size_t)16 << bp.chunk_log2;
   if (smooth)
-    hipLaunchKernelGGL((bin_accumulate<IT, true>), acc_grid, dim3(kAccThreads), acc_lds, s, h->lv, bp, B, n_items,
+    hipLaunchKernelGGL((bin_accumulate<IT, F, true>), acc_grid, dim3(kAccThreads), kAccLds, s, h->lv, bp, B, n_items,
                        ws.bin_start, ws.bin_total, ws.tile_max, ws.n_tiles * parts, ws.records, ws.item_counter,
                        grad);
   else
-    hipLaunchKernelGGL((bin_accumulate<IT, false>), acc_grid, dim3(kAccThreads), acc_lds, s, h->lv, bp, B, n_items,
+    hipLaunchKernelGGL((bin_accumulate<IT, F, false>), acc_grid, dim3(kAccThreads), kAccLds, s, h->lv, bp, B, n_items,
                        ws.bin_start, ws.bin_total, ws.tile_max, ws.n_tiles * parts, ws.records, ws.item_counter,
                        grad);
   return hipGetLastError() == hipSuccess ? HG_OK : HG_ERR_DEVICE;
+}
+
+template <int D, typename IT>
+static hg_status launch_binned_f(const hashgrid* h, uint32_t B, const float* x, const void* dy, float* grad,
+                                 const Workspace& ws, const bool counted, hipStream_t s) {
+  switch (h->cfg.F) {
+    case 1: return launch_binned<D, IT, 1>(h, B, x, dy, grad, ws, counted, s);
+    case 2: return launch_binned<D, IT, 2>(h, B, x, dy, grad, ws, counted, s);
+    case 4: return launch_binned<D, IT, 4>(h, B, x, dy, grad, ws, counted, s);
+    case 8: return launch_binned<D, IT, 8>(h, B, x, dy, grad, ws, counted, s);
+    default: return HG_ERR_UNSUPPORTED;
+  }
 }
 
 }  // namespace hg
@@ -980,19 +988,20 @@ hg_status hashgrid_encode_bwd_ws(const hashgrid_t* hg, uint32_t B, const float* 
   const hg_status ok = check_workspace(hg, B, workspace, workspace_bytes);
   if (ok != HG_OK) return ok;
   if (!x || !dLdy || !grad_params) return HG_ERR_INVALID_ARG;
-  const size_t io = hg->cfg.io_dtype == HG_F16 ? 2 : 4;
-  if ((reinterpret_cast<uintptr_t>(x) & 3) || (reinterpret_cast<uintptr_t>(dLdy) & (2 * io - 1)) ||
-      (reinterpret_cast<uintptr_t>(grad_params) & 7))
+  const size_t io = hg->cfg.io_dtype == HG_F16 ? 2 : 4, F = hg->cfg.F;
+  const size_t grad_align = F * 4 > 16 ? 16 : F * 4;  // one entry's gradient, up to 16 bytes
+  if ((reinterpret_cast<uintptr_t>(x) & 3) || (reinterpret_cast<uintptr_t>(dLdy) & (F * io - 1) & 15) ||
+      (reinterpret_cast<uintptr_t>(grad_params) & (grad_align - 1)))
     return HG_ERR_INVALID_ARG;
   hg::Workspace ws;
   hg::carve(hg, B, static_cast<uint8_t*>(workspace), &ws);
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool i16 = hg->cfg.io_dtype == HG_F16, counted = flags & HG_BWD_COUNTED;
   if (hg->cfg.d == 3)
-    return i16 ? hg::launch_binned<3, _Float16>(hg, B, x, dLdy, grad_params, ws, counted, s)
-               : hg::launch_binned<3, float>(hg, B, x, dLdy, grad_params, ws, counted, s);
-  return i16 ? hg::launch_binned<2, _Float16>(hg, B, x, dLdy, grad_params, ws, counted, s)
-             : hg::launch_binned<2, float>(hg, B, x, dLdy, grad_params, ws, counted, s);
+    return i16 ? hg::launch_binned_f<3, _Float16>(hg, B, x, dLdy, grad_params, ws, counted, s)
+               : hg::launch_binned_f<3, float>(hg, B, x, dLdy, grad_params, ws, counted, s);
+  return i16 ? hg::launch_binned_f<2, _Float16>(hg, B, x, dLdy, grad_params, ws, counted, s)
+             : hg::launch_binned_f<2, float>(hg, B, x, dLdy, grad_params, ws, counted, s);
 }
 
 }  // extern "C"

@@ -15,7 +15,9 @@ constexpr int kBinThreads = HG_BIN_THREADS;  // points of a tile = threads of a 
 #ifndef HG_CHUNK_LOG2
 #define HG_CHUNK_LOG2 12
 #endif
-constexpr uint32_t kChunkLog2 = HG_CHUNK_LOG2;  // log2 of the entries a chunk can hold
+constexpr uint32_t kChunkLog2 = HG_CHUNK_LOG2;  // log2 of the entries a chunk can hold, at most
+// The accumulators of a chunk (F 64-bit words per entry) must fit the LDS of a workgroup: 128 KiB at F = 4 and 8.
+__host__ __device__ constexpr uint32_t chunk_log2_of(uint32_t F) { return F <= 4 ? kChunkLog2 : kChunkLog2 - 1; }
 
 template <int D>
 struct Rows {

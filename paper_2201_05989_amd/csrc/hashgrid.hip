@@ -558,23 +558,24 @@ static hg_status launch_bwd(const hashgrid* h, uint32_t B, const float* x, const
   return launched();
 }
 
-// Forward pass that also fills counts[n_tiles][n_bins] for the binned backward pass (F = 2,
+// Forward pass that also fills counts[n_tiles][n_bins] for the binned backward pass (d = 2 or 3,
 // power-of-two T: what that pass serves).  HG_ERR_UNSUPPORTED where the point-major kernel
-// cannot run (misaligned y or tables, L odd with fp32 output) or the histograms do not fit.
-template <int D, typename PT, typename IT>
+// cannot run (misaligned y or tables, a row of y that is not a whole number of 16-byte pieces)
+// or the histograms do not fit.
+template <int D, int F, typename PT, typename IT>
 static hg_status launch_fwd_counting_t(const hashgrid* h, uint32_t B, const float* x, const void* params, void* y,
                                        uint32_t* counts, uint32_t n_bins, uint32_t n_tiles, hipStream_t s) {
-  constexpr uint32_t G = OutPiece<2, IT>::kLevels;
+  constexpr uint32_t G = OutPiece<F, IT>::kLevels;
   const size_t lds = (size_t)(kPmBlock / kBinThreads) * n_bins * 4;
-  if (h->lv.L % G != 0 || misaligned(y, 16) || misaligned(params, 2 * sizeof(PT)) || !h->lv.T_is_pow2 ||
-      lds > kMaxCountingLds)
+  if (h->lv.L % G != 0 || misaligned(y, 16) || misaligned(params, F * sizeof(PT) > 16 ? 16 : F * sizeof(PT)) ||
+      !h->lv.T_is_pow2 || lds > kMaxCountingLds)
     return HG_ERR_UNSUPPORTED;
   CountArgs ca;
   ca.bp = h->bp;
   ca.counts = counts;
   ca.n_bins = n_bins;
   ca.n_tiles = n_tiles;
-  hipLaunchKernelGGL((fwd_point_major<D, 2, PT, IT, true, true>), dim3((B + kPmBlock - 1) / kPmBlock), dim3(kPmBlock),
+  hipLaunchKernelGGL((fwd_point_major<D, F, PT, IT, true, true>), dim3((B + kPmBlock - 1) / kPmBlock), dim3(kPmBlock),
                      lds, s, h->lv, h->cfg.interp == HG_INTERP_SMOOTHSTEP, B, x, static_cast<const PT*>(params),
                      static_cast<IT*>(y), ca);
   return launched();
@@ -583,14 +584,23 @@ static hg_status launch_fwd_counting_t(const hashgrid* h, uint32_t B, const floa
 hg_status launch_fwd_counting(const hashgrid* h, uint32_t B, const float* x, const void* params, void* y,
                               uint32_t* counts, uint32_t n_bins, uint32_t n_tiles, hipStream_t s) {
   const hashgrid_config& c = h->cfg;
-  if (c.F != 2 || c.d < 2 || c.d > 3) return HG_ERR_UNSUPPORTED;
   const bool p16 = c.param_dtype == HG_F16, i16 = c.io_dtype == HG_F16;
-#define HG_FWDC(D)                                                                                              \
-  (p16 ? (i16 ? launch_fwd_counting_t<D, _Float16, _Float16>(h, B, x, params, y, counts, n_bins, n_tiles, s)    \
-              : launch_fwd_counting_t<D, _Float16, float>(h, B, x, params, y, counts, n_bins, n_tiles, s))      \
-       : (i16 ? launch_fwd_counting_t<D, float, _Float16>(h, B, x, params, y, counts, n_bins, n_tiles, s)       \
-              : launch_fwd_counting_t<D, float, float>(h, B, x, params, y, counts, n_bins, n_tiles, s)))
-  return c.d == 3 ? HG_FWDC(3) : HG_FWDC(2);
+#define HG_FWDC(D, F)                                                                                              \
+  (p16 ? (i16 ? launch_fwd_counting_t<D, F, _Float16, _Float16>(h, B, x, params, y, counts, n_bins, n_tiles, s)    \
+              : launch_fwd_counting_t<D, F, _Float16, float>(h, B, x, params, y, counts, n_bins, n_tiles, s))      \
+       : (i16 ? launch_fwd_counting_t<D, F, float, _Float16>(h, B, x, params, y, counts, n_bins, n_tiles, s)       \
+              : launch_fwd_counting_t<D, F, float, float>(h, B, x, params, y, counts, n_bins, n_tiles, s)))
+  switch (c.d * 16 + c.F) {
+    case 2 * 16 + 1: return HG_FWDC(2, 1);
+    case 2 * 16 + 2: return HG_FWDC(2, 2);
+    case 2 * 16 + 4: return HG_FWDC(2, 4);
+    case 2 * 16 + 8: return HG_FWDC(2, 8);
+    case 3 * 16 + 1: return HG_FWDC(3, 1);
+    case 3 * 16 + 2: return HG_FWDC(3, 2);
+    case 3 * 16 + 4: return HG_FWDC(3, 4);
+    case 3 * 16 + 8: return HG_FWDC(3, 8);
+    default: return HG_ERR_UNSUPPORTED;
+  }
 #undef HG_FWDC
 }
 

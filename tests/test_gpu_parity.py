@@ -13,10 +13,10 @@ Bars (fp32 arithmetic on the GPU, fp64 in the oracle):
   backward, workspace variant        the same plus M 2^(H-54): it sums in 64-bit fixed point with
                                      each summand rounded to at most M 2^(H-62), M = max|dL/dy|,
                                      H = max(3 + ceil(log2 B), 11); the floor allows 256 such roundings.
-                                     With fp16 dL/dy its records carry the interpolation weights as
-                                     fixed point (2^-23 and 2^-24 units), which moves each corner's
-                                     summand by at most 2^-23 |dL/dy|: the bound grows by 2^-23 G, G the
-                                     sum of |dL/dy| over the corners that touch the entry
+                                     Its records carry the interpolation weights as fixed point
+                                     (2^-23 and 2^-24 units), which moves each corner's summand by at
+                                     most 2^-23 |dL/dy|: the bound grows by 2^-23 G, G the sum of
+                                     |dL/dy| over the corners that touch the entry
 """
 import numpy as np
 import pytest
@@ -99,7 +99,7 @@ def run_case(d, L, F, T, N_min, N_max, pdt, iot, interp, x, theta, dy, do_indice
     check_bwd(g2.cpu().numpy(), 2 * g_ref, 2 * g_abs)
     if grid.bwd_workspace_bytes(len(x)):             # hashgrid_encode_bwd_ws: binned, fixed-point sums
         floor = ws_floor(dy, len(x))
-        if iot == "f16" and len(x):
+        if len(x):
             floor = floor + 2.0 ** -23 * corner_abs_sum(cfg, lv, x, dy)
         gw = grid.encode_bwd(xd, gd)
         check_bwd(gw.cpu().numpy(), g_ref, g_abs, floor)
@@ -138,6 +138,19 @@ def test_tiny2d_reference_config():
 @pytest.mark.parametrize("scale", [1e-4, 1.0])
 def test_sdf3d_full_size(scale):
     workload_case("sdf3d", table_scale=scale)
+
+
+@pytest.mark.parametrize("F", [1, 4, 8])
+def test_headline_shape_with_other_feature_counts(F):
+    # d=3 L=16 T=2^19 as in the headline configuration, F of Fig. 5; 40 001 points: 79 tiles, a ragged last one
+    w = synth.WORKLOADS["sdf3d"]
+    lv = orc.levels(orc.OracleConfig(w.d, w.L, F, w.T, w.N_min, w.N_max))
+    rng = np.random.default_rng(100 + F)
+    x = synth.points_sdf(rng, 40001, 3)
+    theta = synth.make_tables(rng, lv.total, F, "f16", 1.0)
+    dy = synth.make_dy(rng, len(x), w.L * F, "f16")
+    grid = run_case(w.d, w.L, F, w.T, w.N_min, w.N_max, "f16", "f16", 0, x, theta, dy, do_indices=False)
+    assert grid.bwd_workspace_bytes(len(x)) > 0
 
 
 def test_nerf3d_full_size():
@@ -340,7 +353,7 @@ def test_workspace_backward_argument_checks():
     assert lib.hashgrid_encode_bwd_ws(grid._h, B, x.data_ptr(), dy.data_ptr(), g.data_ptr(), big.data_ptr(), need,
                                       8, None) == 1  # unknown flag
     # configurations the binned path does not serve report 0 bytes and HG_ERR_UNSUPPORTED
-    g4 = HashGrid(3, 16, 4, 1 << 19, 16, 2048)
+    g4 = HashGrid(3, 16, 4, 1000003, 16, 2048)  # T is not a power of two
     assert g4.bwd_workspace_bytes(B) == 0
     assert lib.hashgrid_encode_bwd_ws(g4._h, B, x.data_ptr(), dy.data_ptr(), g.data_ptr(), small.data_ptr(),
                                       small.numel(), 0, None) == 2
