@@ -141,7 +141,8 @@ hg_status hashgrid_encode_bwd_ws(const hashgrid_t* hg, uint32_t B, const float* 
                                  float* grad_params, void* workspace, uint64_t workspace_bytes, uint32_t flags,
                                  void* stream);
 
-/* Forward pass, same result as hashgrid_encode_fwd (Section 3; Fig. 3 steps 1-4), that also does
+/* Forward pass, the arithmetic of hashgrid_encode_fwd (Section 3; Fig. 3 steps 1-4; an fp16 output
+ * that is an exact tie may differ from that call's in its last bit), that also does
  * the first step of hashgrid_encode_bwd_ws for the same points while it gathers: it counts, per
  * tile of points and chunk of the gradient, the corner pairs that the backward pass will sort,
  * and leaves the counts in `workspace`.  A following hashgrid_encode_bwd_ws on the same hg, B, x

@@ -245,6 +245,9 @@ __global__ __launch_bounds__(kPmBlock) void fwd_point_major(const LevelTable lv,
         for (int f = 0; f < F; ++f) acc[f] = fmaf(wt, (float)e[m].v[f], acc[f]);
       }
 #pragma unroll
+      // (the compiler folds this conversion into the last multiply-add in some instantiations and
+      // not in others - one rounding instead of two - so two variants of the kernel may differ in
+      // the last bit of an fp16 output that is an exact tie)
       for (int f = 0; f < F; ++f) out.v[F * j + f] = (IT)acc[f];
       if constexpr (COUNT) {
         if (valid) {
