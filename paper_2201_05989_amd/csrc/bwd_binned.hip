@@ -45,34 +45,15 @@
 
 namespace hg {
 
-using u32x4 = uint32_t __attribute__((ext_vector_type(4)));
-
-constexpr int kScanThreads = 1024;     // = maximum bins per level
-#ifndef HG_ACC_THREADS
-#define HG_ACC_THREADS 1024
-#endif
-constexpr int kAccThreads = HG_ACC_THREADS;
-#ifndef HG_ACC_UNROLL
-#define HG_ACC_UNROLL 4
-#endif
-constexpr int kAccUnroll = HG_ACC_UNROLL;
-#ifndef HG_ACC_PRE_WORDS
-#define HG_ACC_PRE_WORDS 24
-#endif
-constexpr int kAccPreWords = HG_ACC_PRE_WORDS;  // registers per lane for records requested one item ahead, half
-                                                // of them half an item earlier still
-#ifndef HG_ACC_WGS_PER_CU
-#define HG_ACC_WGS_PER_CU 1u
-#endif
+// Launch shapes, each the best of a sweep on the headline configuration.
+constexpr int kScanThreads = 1024;               // = maximum bins per level
+constexpr int kAccThreads = 1024;                // accumulate workgroup (512 x 2 per CU is slower)
+constexpr int kAccUnroll = 4;                    // record loads in flight per lane in the tail of a long item
+constexpr int kAccPreWords = 24;                 // registers per lane for records requested one item ahead
+constexpr uint32_t kAccWgsPerCu = 1;             // its registers let one accumulate workgroup run per CU
 constexpr uint32_t kTargetRecordsPerAccWg = 16384;
-#ifndef HG_MAX_PARTS
-#define HG_MAX_PARTS 4
-#endif
-constexpr uint32_t kMaxParts = HG_MAX_PARTS;  // level parts of the scatter grid
-#ifndef HG_COUNT_PARTS
-#define HG_COUNT_PARTS 2
-#endif
-constexpr uint32_t kCountParts = HG_COUNT_PARTS;  // ... of the count grid (its workgroups are lighter)
+constexpr uint32_t kMaxParts = 4;                // level parts of the scatter grid (1, 2, 8: slower)
+constexpr uint32_t kCountParts = 2;              // ... of the count grid (its workgroups are lighter)
 // Level parts are doubled (up to one level per part) until one part's bins fit these bounds: a count
 // workgroup keeps one LDS word per bin of its part, a scatter workgroup three, next to its staging area.
 constexpr uint32_t kMaxCountPartBins = 4096, kMaxScatterPartBins = 2048;
@@ -388,10 +369,7 @@ __device__ __forceinline__ void block_exclusive_scan(uint32_t* a, uint32_t n, ui
 // scan: each workgroup takes kScanBins bins and turns their column of
 // counts[tile][bin] into the exclusive prefix over tiles; it also writes the
 // bin's record count.  Workgroup 0 clears the work counter of the accumulate pass.
-#ifndef HG_SCAN_BINS
-#define HG_SCAN_BINS 32
-#endif
-constexpr int kScanBins = HG_SCAN_BINS;
+constexpr int kScanBins = 32;  // 128-byte rows of the count table per load (16, 8: slower; 64: the same)
 __global__ __launch_bounds__(kScanThreads) void bin_scan(const uint32_t n_tiles, const uint32_t n_bins,
                                                          uint32_t* __restrict__ counts,
                                                          uint32_t* __restrict__ bin_total,
@@ -578,7 +556,7 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, 
         const uint32_t in_tile = __hip_atomic_fetch_add(&cur[rb], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         const uint32_t pos = in_tile - level_first;
         if (pos < R * kBinThreads) {  // holds when the count pass saw the same x
-          staging[pos] = Rec::make(rw.pack[r] & 0xfffu, rw.k, rw.wf0, rw.wrow[r], g);
+          staging[pos] = Rec::make(rw.la[r], rw.k, rw.wf0, rw.wrow[r], g);
           binv[pos] = (uint16_t)rb;
         }
       }
@@ -923,7 +901,7 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
     if (hipGetDevice(&dev) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
       cus = 256;
-    return (uint32_t)cus * HG_ACC_WGS_PER_CU;
+    return (uint32_t)cus * kAccWgsPerCu;
   }();
   const dim3 acc_grid(n_items < acc_slots ? n_items : acc_slots);
   if (smooth)

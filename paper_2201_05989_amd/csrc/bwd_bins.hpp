@@ -8,21 +8,15 @@
 
 namespace hg {
 
-#ifndef HG_BIN_THREADS
-#define HG_BIN_THREADS 512
-#endif
-constexpr int kBinThreads = HG_BIN_THREADS;  // points of a tile = threads of a count / scatter workgroup
-#ifndef HG_CHUNK_LOG2
-#define HG_CHUNK_LOG2 12
-#endif
-constexpr uint32_t kChunkLog2 = HG_CHUNK_LOG2;  // log2 of the entries a chunk can hold, at most
+constexpr int kBinThreads = 512;      // points of a tile = threads of a count / scatter workgroup (256 and 1024 are slower)
+constexpr uint32_t kChunkLog2 = 12;  // log2 of the entries a chunk can hold, at most
 // The accumulators of a chunk (F 64-bit words per entry) must fit the LDS of a workgroup: 128 KiB at F = 4 and 8.
 __host__ __device__ constexpr uint32_t chunk_log2_of(uint32_t F) { return F <= 4 ? kChunkLog2 : kChunkLog2 - 1; }
 
 template <int D>
 struct Rows {
   uint32_t bin[1 << (D - 1)];    // global bin
-  uint32_t pack[1 << (D - 1)];   // chunk-local index of the lower | upper << 16 corner along dimension 0
+  uint32_t la[1 << (D - 1)];     // chunk-local index of the lower corner along dimension 0
   float wrow[1 << (D - 1)];      // product of the weights of dimensions 1..d-1
   float wf0;                     // fractional position along dimension 0 (before any smoothstep)
   uint32_t k;                    // trailing one bits of the lower corner's coordinate along dimension 0
@@ -71,7 +65,7 @@ __device__ __forceinline__ void rows_of(const LevelTable& lv, const BinPlan& bp,
       out.bin[r] = gb0 + bin;
       if (!COUNT_ONLY) {
         const uint32_t la = c0[0] + (row - (bin << sh)) * verts;
-        out.pack[r] = la | ((la + 1u) << 16);
+        out.la[r] = la;
       }
     }
   } else {
@@ -87,8 +81,7 @@ __device__ __forceinline__ void rows_of(const LevelTable& lv, const BinPlan& bp,
       const uint32_t ia = (c0[0] ^ rt) & tmask;
       out.bin[r] = gb0 + (ia >> cl);
       if (!COUNT_ONLY) {
-        const uint32_t ib = ((c0[0] + 1u) ^ rt) & tmask;
-        out.pack[r] = (ia & cmask) | ((ib & cmask) << 16);
+        out.la[r] = ia & cmask;
       }
     }
   }
