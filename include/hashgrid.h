@@ -117,6 +117,11 @@ hg_status hashgrid_encode_bwd(const hashgrid_t* hg, uint32_t B, const float* x, 
  * and B*L*2^(d-1) < 2^32). */
 uint64_t hashgrid_bwd_workspace_bytes(const hashgrid_t* hg, uint32_t B);
 
+/* 1 when hashgrid_encode_bwd_ws serves this configuration and batch and is expected to be the
+ * faster of the two backward passes, else 0: it visits every chunk of the gradient whatever the
+ * batch, so below some ten thousand points (at Table 1's sizes) the atomic pass wins. */
+int hashgrid_bwd_ws_pays(const hashgrid_t* hg, uint32_t B);
+
 /* Backward pass to the tables, same result as hashgrid_encode_bwd (Fig. 3
  * caption), computed without device-wide atomics on the hot path: the
  * weight * dLdy contributions are bucket-sorted by destination chunk into

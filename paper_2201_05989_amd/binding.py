@@ -28,7 +28,7 @@ _TORCH = {HG_F32: torch.float32, HG_F16: torch.float16}
 EXPORTS = ("hashgrid_create", "hashgrid_destroy", "hashgrid_n_entries", "hashgrid_level_info",
            "hashgrid_encode_fwd", "hashgrid_encode_bwd", "hashgrid_encode_bwd_input",
            "hashgrid_debug_indices", "hashgrid_strerror", "hashgrid_bwd_workspace_bytes",
-           "hashgrid_encode_bwd_ws", "hashgrid_encode_fwd_ws", "hashgrid_adam_step", "hashgrid_probe_copy", "hashgrid_probe_gather",
+           "hashgrid_encode_bwd_ws", "hashgrid_encode_fwd_ws", "hashgrid_bwd_ws_pays", "hashgrid_adam_step", "hashgrid_probe_copy", "hashgrid_probe_gather",
            "hashgrid_probe_atomic_add")
 
 
@@ -80,6 +80,8 @@ def load_library() -> ctypes.CDLL:
     lib.hashgrid_encode_bwd_ws.argtypes = [vp, u32, vp, vp, vp, vp, u64, u32, vp]
     lib.hashgrid_encode_fwd_ws.argtypes = [vp, u32, vp, vp, vp, vp, u64, vp]
     lib.hashgrid_encode_fwd_ws.restype = ctypes.c_int
+    lib.hashgrid_bwd_ws_pays.argtypes = [vp, u32]
+    lib.hashgrid_bwd_ws_pays.restype = ctypes.c_int
     lib.hashgrid_encode_bwd_ws.restype = ctypes.c_int
     lib.hashgrid_adam_step.argtypes = [u64, vp, vp, vp, vp, vp, ctypes.POINTER(hashgrid_adam_config), u32, ctypes.c_int,
                                        vp]
@@ -162,15 +164,21 @@ class HashGrid:
             self._ws = torch.empty(need, dtype=torch.uint8, device=device)
         return self._ws
 
+    def bwd_ws_pays(self, B: int) -> bool:
+        return bool(self._lib.hashgrid_bwd_ws_pays(self._h, B))
+
     def encode_fwd(self, x: torch.Tensor, params: torch.Tensor, y: torch.Tensor | None = None, stream=None,
-                   count_for_bwd: bool = False, workspace: torch.Tensor | None = None):
+                   count_for_bwd=False, workspace: torch.Tensor | None = None):
         """hashgrid_encode_fwd; with count_for_bwd, hashgrid_encode_fwd_ws where the configuration
-        is served by it: the next encode_bwd on the same x and workspace then skips its counting pass."""
+        is served by it and the batch is large enough for the sorted backward pass to pay
+        (count_for_bwd="always": whatever the batch): the next encode_bwd on the same x and workspace
+        then skips its counting pass."""
         B = x.shape[0]
         if y is None:
             y = torch.empty((B, self.L * self.F), dtype=self.io_dtype, device=x.device)
         self._counted = None
-        need = self.bwd_workspace_bytes(B) if count_for_bwd and B else 0
+        want = bool(count_for_bwd) and B and (count_for_bwd == "always" or self.bwd_ws_pays(B))
+        need = self.bwd_workspace_bytes(B) if want else 0
         if need:
             ws = workspace if workspace is not None else self._workspace(need, x.device)
             st = self._lib.hashgrid_encode_fwd_ws(
@@ -192,12 +200,15 @@ class HashGrid:
         return int(self._lib.hashgrid_bwd_workspace_bytes(self._h, B))
 
     def encode_bwd(self, x: torch.Tensor, dLdy: torch.Tensor, grad_params: torch.Tensor | None = None,
-                   stream=None, workspace: torch.Tensor | None = None, use_workspace: bool = True):
-        """hashgrid_encode_bwd_ws when the configuration is served by it (the scratch
-        buffer is `workspace` or one kept on this object), else hashgrid_encode_bwd."""
+                   stream=None, workspace: torch.Tensor | None = None, use_workspace: bool | None = None):
+        """hashgrid_encode_bwd_ws (the scratch buffer is `workspace` or one kept on this object) or
+        hashgrid_encode_bwd.  use_workspace: True = the former wherever the configuration is served
+        by it, False = the latter, None = whichever hashgrid_bwd_ws_pays expects to be faster."""
         B = x.shape[0]
         if grad_params is None:
             grad_params = torch.zeros((self.n_entries, self.F), dtype=torch.float32, device=x.device)
+        if use_workspace is None:
+            use_workspace = self._counted is not None or self.bwd_ws_pays(B)
         need = self.bwd_workspace_bytes(B) if use_workspace else 0
         counted, self._counted = self._counted, None  # the pass consumes the counts
         if need:

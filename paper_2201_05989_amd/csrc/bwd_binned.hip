@@ -937,6 +937,15 @@ uint64_t hashgrid_bwd_workspace_bytes(const hashgrid_t* hg, uint32_t B) {
   return hg::carve(hg, B, nullptr, nullptr);
 }
 
+int hashgrid_bwd_ws_pays(const hashgrid_t* hg, uint32_t B) {
+  if (hashgrid_bwd_workspace_bytes(hg, B) == 0) return 0;
+  // Measured on an MI355X: the sorted pass costs about 20 us of launches plus 0.027 us per chunk
+  // (every chunk of the gradient is visited) and then ~200 K corner pairs per us; the atomic pass
+  // about 13 K pairs per us from the first pair on.
+  const uint64_t pairs = (uint64_t)B * hg->lv.L * hg->bp.rec_per_point;
+  return pairs > 258000ull + 348ull * hg->bp.bin_base[hg->lv.L] ? 1 : 0;
+}
+
 // shared argument checks of the two entry points that take the scratch buffer
 static hg_status check_workspace(const hashgrid_t* hg, uint32_t B, const void* workspace, uint64_t workspace_bytes) {
   const uint64_t need = hashgrid_bwd_workspace_bytes(hg, B);

@@ -114,12 +114,12 @@ def run_case(d, L, F, T, N_min, N_max, pdt, iot, interp, x, theta, dy, do_indice
         floor = ws_floor(dy, len(x))
         if len(x):
             floor = floor + 2.0 ** -23 * corner_abs_sum(cfg, lv, x, dy)
-        gw = grid.encode_bwd(xd, gd)
+        gw = grid.encode_bwd(xd, gd, use_workspace=True)
         check_bwd(gw.cpu().numpy(), g_ref, g_abs, floor)
-        gw2 = grid.encode_bwd(xd, gd, gw.clone())
+        gw2 = grid.encode_bwd(xd, gd, gw.clone(), use_workspace=True)
         check_bwd(gw2.cpu().numpy(), 2 * g_ref, 2 * g_abs, 2 * floor)
         # hashgrid_encode_fwd_ws: the same y, and its counts serve the backward pass
-        yc = grid.encode_fwd(xd, td, count_for_bwd=True)
+        yc = grid.encode_fwd(xd, td, count_for_bwd="always")
         same_forward(yc, y, iot)
         if grid._counted is not None:
             gc = grid.encode_bwd(xd, gd)
@@ -311,15 +311,15 @@ def test_workspace_backward_is_reproducible_and_keeps_untouched_entries():
     x, _, dy = synth.make_inputs(w, grid.n_entries, B=50000)
     xd, gd = dev(x), dev(dy)
     assert grid.bwd_workspace_bytes(len(x)) > 0
-    g1 = grid.encode_bwd(xd, gd)
-    g2 = grid.encode_bwd(xd, gd)
+    g1 = grid.encode_bwd(xd, gd, use_workspace=True)
+    g2 = grid.encode_bwd(xd, gd, use_workspace=True)
     hashed = [i for i in grid.levels() if not i.is_dense]
     lo = hashed[0].entry_offset
     # hashed levels: one owner per chunk, exact fixed-point sums: bit-for-bit equal run to run
     assert torch.equal(g1[lo:], g2[lo:])
     # entries no point reaches keep their previous bits (here a sentinel)
     sentinel = torch.full((grid.n_entries, 2), 7.25, dtype=torch.float32, device="cuda")
-    g3 = grid.encode_bwd(xd, gd, sentinel.clone())
+    g3 = grid.encode_bwd(xd, gd, sentinel.clone(), use_workspace=True)
     untouched = (g1 == 0).all(dim=1)
     assert untouched.any() and bool((g3[untouched] == 7.25).all())
 
@@ -332,10 +332,10 @@ def test_counting_forward_gives_the_counts_of_the_count_pass():
         x, theta, dy = synth.make_inputs(w, grid.n_entries, B=B, table_scale=1.0)
         xd, td, gd = dev(x), dev(theta), dev(dy)
         y0 = grid.encode_fwd(xd, td)
-        g0 = grid.encode_bwd(xd, gd)
-        y1 = grid.encode_fwd(xd, td, count_for_bwd=True)
+        g0 = grid.encode_bwd(xd, gd, use_workspace=True)
+        y1 = grid.encode_fwd(xd, td, count_for_bwd="always")
         counted = grid._counted is not None
-        g1 = grid.encode_bwd(xd, gd)
+        g1 = grid.encode_bwd(xd, gd, use_workspace=True)
         same_forward(y0, y1, w.io_dtype)
         hashed = [i for i in grid.levels() if not i.is_dense]
         lo = hashed[0].entry_offset
@@ -343,8 +343,21 @@ def test_counting_forward_gives_the_counts_of_the_count_pass():
         torch.testing.assert_close(g0[:lo], g1[:lo], rtol=1e-4, atol=1e-4 * float(g0.abs().max()))
         assert counted == (name != "image2d")  # 7.6 K chunks: its histograms do not fit the forward's LDS
         # the counts are consumed: a second backward counts for itself and agrees
-        g2 = grid.encode_bwd(xd, gd)
+        g2 = grid.encode_bwd(xd, gd, use_workspace=True)
         assert torch.equal(g0[lo:], g2[lo:])
+
+
+def test_binding_picks_the_backward_pass_by_batch_size():
+    grid = HashGrid(3, 16, 2, 1 << 19, 16, 2048)
+    assert not grid.bwd_ws_pays(1024) and grid.bwd_ws_pays(1 << 16)
+    assert not HashGrid(3, 16, 2, 1000003, 16, 2048).bwd_ws_pays(1 << 20)  # not served at all
+    for B in (1000, 1 << 16):
+        x = torch.rand((B, 3), device="cuda") * 0.99
+        dy = torch.randn((B, 32), device="cuda").half()
+        ga = grid.encode_bwd(x, dy)                        # the binding's choice
+        gb = grid.encode_bwd(x, dy, use_workspace=False)   # atomics
+        torch.testing.assert_close(ga, gb, rtol=1e-4, atol=1e-4 * float(gb.abs().max()))
+        assert (grid._ws is not None) == (B == 1 << 16)    # the scratch buffer appears only when the sort is used
 
 
 def test_workspace_backward_argument_checks():
