@@ -112,9 +112,11 @@ hg_status hashgrid_encode_bwd(const hashgrid_t* hg, uint32_t B, const float* x, 
 
 /* Size in bytes of the scratch buffer hashgrid_encode_bwd_ws needs for a batch of
  * B points, or 0 when that variant does not serve this configuration or batch
- * (it needs d = 2 or 3, a power-of-two T of at most 2^22 (2^21 at F = 8: 1024 chunks of
+ * (it needs d = 2 or 3, a power-of-two T of at most 2^24 (2^23 at F = 8: 4096 chunks of
  * 4096, or 2048, entries per level), at most 4096 (2048) vertices per axis on 1:1 levels
- * and B*L*2^(d-1) < 2^32). */
+ * and B*L*2^(d-1) < 2^32).  The buffer holds 8 + F * sizeof(dLdy scalar) bytes (rounded up
+ * to 4) per pair of corners, B*L*2^(d-1) of them, plus 4 bytes per (tile of 512 points,
+ * chunk): 195 MiB at Table 1's sizes with 2^18 points, 2.3 GiB at T = 2^24 with 2^21. */
 uint64_t hashgrid_bwd_workspace_bytes(const hashgrid_t* hg, uint32_t B);
 
 /* 1 when hashgrid_encode_bwd_ws serves this configuration and batch and is expected to be the

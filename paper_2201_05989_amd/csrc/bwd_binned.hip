@@ -46,7 +46,7 @@
 namespace hg {
 
 // Launch shapes, each the best of a sweep on the headline configuration.
-constexpr int kScanThreads = 1024;               // = maximum bins per level
+constexpr int kScanThreads = 1024;
 constexpr int kAccThreads = 1024;                // accumulate workgroup (512 x 2 per CU is slower)
 constexpr int kAccUnroll = 4;                    // record loads in flight per lane in the tail of a long item
 constexpr int kAccPreWords = 24;                 // registers per lane for records requested one item ahead
@@ -56,7 +56,9 @@ constexpr uint32_t kMaxParts = 4;                // level parts of the scatter g
 constexpr uint32_t kCountParts = 2;              // ... of the count grid (its workgroups are lighter)
 // Level parts are doubled (up to one level per part) until one part's bins fit these bounds: a count
 // workgroup keeps one LDS word per bin of its part, a scatter workgroup three, next to its staging area.
-constexpr uint32_t kMaxCountPartBins = 4096, kMaxScatterPartBins = 2048;
+constexpr uint32_t kMaxCountPartBins = 4096, kMaxScatterPartBins = 4096;
+// A level may have this many chunks (one level is the smallest part): T up to 2^24 at 4096 entries per chunk.
+constexpr uint32_t kMaxLevelBins = 4096;
 
 // One record = one pair of corners that differ along dimension 0, both inside one chunk.
 // Two header words, then the level's F values of dL/dy as they came (fp16 pairs share a word):
@@ -195,7 +197,7 @@ void build_bin_plan(hashgrid* h) {
       // for one voxel in 2^chunk_log2: those pairs bypass the sort (see bin_scatter).
       nb = lv.T > cap ? lv.T >> bp.chunk_log2 : 1u;
     }
-    if (nb > (uint32_t)kScanThreads) return;
+    if (nb > kMaxLevelBins) return;
     bp.bin_base[l] = bins;
     bins += nb;
   }

@@ -188,9 +188,17 @@ def test_large3d_full_size_sampled_forward_and_prefix_backward():
     rows.sort()
     check_fwd(y[rows], orc.encode_fwd(cfg, x[rows], theta), 1.0, w.io_dtype)
     nb = 1 << 18
-    assert grid.bwd_workspace_bytes(nb) == 0  # resolutions above 4095 on hashed levels: atomic path only
-    g = grid.encode_bwd(xd[:nb].contiguous(), dev(dy[:nb])).cpu().numpy()
-    check_bwd(g, orc.encode_bwd(cfg, x[:nb], dy[:nb]), orc.encode_bwd(cfg, x[:nb], np.abs(dy[:nb].astype(np.float64))))
+    xs, dys = x[:nb], dy[:nb]
+    g_ref = orc.encode_bwd(cfg, xs, dys)
+    g_abs = orc.encode_bwd(cfg, xs, np.abs(dys.astype(np.float64)))
+    g = grid.encode_bwd(dev(xs), dev(dys), use_workspace=False).cpu().numpy()  # atomics
+    check_bwd(g, g_ref, g_abs)
+    del g
+    # the sorted pass: 49 K chunks, less than one pair of corners per tile and chunk
+    assert grid.bwd_workspace_bytes(nb) > 0
+    floor = ws_floor(dys, nb) + 2.0 ** -23 * corner_abs_sum(cfg, lv, xs, dys)
+    g = grid.encode_bwd(dev(xs), dev(dys), use_workspace=True).cpu().numpy()
+    check_bwd(g, g_ref, g_abs, floor)
 
 
 SWEEP = [
