@@ -156,7 +156,7 @@ hg_status hashgrid_encode_bwd_ws(const hashgrid_t* hg, uint32_t B, const float* 
  * and workspace may then pass HG_BWD_COUNTED and skips its own counting pass.  Nothing else may
  * write the workspace in between, and x must be unchanged.
  * Returns HG_ERR_UNSUPPORTED when hashgrid_bwd_workspace_bytes is 0, when y or params are not
- * 16-byte / entry aligned, or when the configuration has more than 6144 chunks in all (callers
+ * 16-byte / entry aligned, or when the configuration has more than 16384 chunks in all (callers
  * then use hashgrid_encode_fwd and pass no flag); HG_ERR_INVALID_ARG as hashgrid_encode_bwd_ws. */
 hg_status hashgrid_encode_fwd_ws(const hashgrid_t* hg, uint32_t B, const float* x, const void* params, void* y,
                                  void* workspace, uint64_t workspace_bytes, void* stream);

@@ -116,7 +116,7 @@ __global__ __launch_bounds__(kBlock) void fwd_general(const LevelTable lv, const
 // keeps the 16 waves of a workgroup on the same slice, which holds the L2 hit
 // rate at that of the level-major grid.
 constexpr int kPmBlock = 1024;
-constexpr size_t kMaxCountingLds = 48 * 1024;  // histograms of a counting forward workgroup
+constexpr size_t kMaxCountingLds = 128 * 1024;  // histograms of a counting forward workgroup (one workgroup per CU)
 
 // Entry indices of the 2^D corners for a level known (uniformly) to be 1:1 or
 // hashed, T a power of two on the hashed side: no per-lane selects between the
@@ -573,6 +573,12 @@ static hg_status launch_fwd_counting_t(const hashgrid* h, uint32_t B, const floa
   if (h->lv.L % G != 0 || misaligned(y, 16) || misaligned(params, F * sizeof(PT) > 16 ? 16 : F * sizeof(PT)) ||
       !h->lv.T_is_pow2 || lds > kMaxCountingLds)
     return HG_ERR_UNSUPPORTED;
+  if (lds > 64 * 1024) {  // more dynamic LDS than the default limit: opt in once per kernel
+    static const hipError_t lds_ok =
+        hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_point_major<D, F, PT, IT, true, true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxCountingLds);
+    if (lds_ok != hipSuccess) return HG_ERR_DEVICE;
+  }
   CountArgs ca;
   ca.bp = h->bp;
   ca.counts = counts;
