@@ -118,68 +118,6 @@ __global__ __launch_bounds__(kBlock) void fwd_general(const LevelTable lv, const
 constexpr int kPmBlock = 1024;
 constexpr size_t kMaxCountingLds = 128 * 1024;  // histograms of a counting forward workgroup (one workgroup per CU)
 
-// Entry indices of the 2^D corners for a level known (uniformly) to be 1:1 or
-// hashed, T a power of two on the hashed side: no per-lane selects between the
-// two index maps and no integer division.
-template <int D, bool DENSE>
-__device__ __forceinline__ void corner_indices_uniform(const uint32_t (&c0)[D], uint32_t verts, uint32_t mask,
-                                                       uint32_t (&idx)[1 << D]) {
-  uint32_t t[D][2];
-  uint32_t stride = 1;
-#pragma unroll
-  for (int i = 0; i < D; ++i) {
-    const uint32_t mul = DENSE ? stride : prime(i);
-    t[i][0] = c0[i] * mul;
-    t[i][1] = t[i][0] + mul;
-    stride *= verts;
-  }
-#pragma unroll
-  for (uint32_t m = 0; m < (1u << D); ++m) {
-    uint32_t v = t[0][m & 1u];
-#pragma unroll
-    for (int i = 1; i < D; ++i) v = DENSE ? v + t[i][(m >> i) & 1u] : v ^ t[i][(m >> i) & 1u];
-    idx[m] = DENSE ? v : v & mask;
-  }
-}
-
-// Per level and point: the 2^D entry indices and the weights of the corners, split into the
-// product over dimensions 1.. (wr) and the two weights of dimension 0 (w0 upper, u0 lower).
-template <int D, bool POW2>
-__device__ __forceinline__ void level_corners(const LevelTable& lv, uint32_t l, bool smooth, const float (&xp)[D],
-                                              uint32_t (&idx)[1 << D], float (&wr)[1 << (D - 1)], float& w0,
-                                              float& u0) {
-  const float Nf = (float)lv.N[l];
-  const float shift = smooth ? 0.5f : 0.0f;
-  const float cmaxf = smooth ? Nf : Nf - 1.0f;
-  uint32_t c0[D];
-  float w[D], u[D];
-#pragma unroll
-  for (int i = 0; i < D; ++i) {
-    float wf;
-    split(xp[i], Nf, shift, cmaxf, c0[i], wf);
-    w[i] = smooth ? smoothstep(wf) : wf;
-    u[i] = smooth ? smoothstep(1.0f - wf) : 1.0f - wf;
-  }
-  if ((lv.dense_mask >> l) & 1u) {  // uniform
-    corner_indices_uniform<D, true>(c0, lv.verts[l], 0u, idx);
-  } else if (POW2) {
-    corner_indices_uniform<D, false>(c0, 0u, lv.T - 1u, idx);
-  } else {
-    const CornerTerms<D> ct = corner_terms<D>(c0, false, 0u);
-#pragma unroll
-    for (uint32_t m = 0; m < (1u << D); ++m) idx[m] = corner_index<D>(ct, m, false, lv.T, false);
-  }
-#pragma unroll
-  for (uint32_t r = 0; r < (1u << (D - 1)); ++r) {
-    float p = 1.0f;
-#pragma unroll
-    for (int i = 1; i < D; ++i) p *= ((r >> (i - 1)) & 1u) ? w[i] : u[i];
-    wr[r] = p;
-  }
-  w0 = w[0];
-  u0 = u[0];
-}
-
 // Levels whose outputs fill one store: 16 bytes, or one level when a level's F outputs are wider.
 template <int F, typename IT>
 struct OutPiece {
