@@ -197,6 +197,22 @@ typedef struct {
 hg_status hashgrid_adam_step(uint64_t n_scalars, float* params_master, void* params_half, float* grad, float* m,
                              float* v, const hashgrid_adam_config* cfg, uint32_t step, int zero_grad, void* stream);
 
+/* The encoding followed by the paper's network (Section 4, "Architecture": two hidden layers of 64
+ * neurons, ReLU on the hidden layers, a linear output layer), in one kernel: the encoded features
+ * never reach memory.  out[b, i] = sum_k W3[i,k] h2[k], h2 = relu(W2 h1), h1 = relu(W1 y),
+ * y = enc(x_b; params).  Half-precision operands on the matrix cores with fp32 accumulation: y, h1
+ * and h2 are rounded to fp16 (nearest even) where they are stored, out is fp32.
+ *   params  [n_entries, F]  fp16 (param_dtype must be HG_F16), device, read
+ *   W1      [64, L*F]       fp16, device, read; row = neuron (as W2, W3)
+ *   W2      [64, 64]        fp16
+ *   W3      [n_out, 64]     fp16, 1 <= n_out <= 32
+ *   out     [B, n_out]      fp32, device, written in full
+ * HG_ERR_UNSUPPORTED unless d is 2 or 3, T a power of two, L*F a multiple of 8 and at most 64 and
+ * the tables fp16; HG_ERR_INVALID_ARG for NULL or misaligned pointers or n_out == 0. */
+hg_status hashgrid_encode_mlp_fwd(const hashgrid_t* hg, uint32_t B, const float* x, const void* params,
+                                  const void* W1, const void* W2, const void* W3, uint32_t n_out, float* out,
+                                  void* stream);
+
 /* Machine probes (not part of the method; for callers that have no paper to cite: the
  * benchmark, which states its rates as fractions of what this GPU delivers).  Each call
  * enqueues one kernel on `stream`; the caller times it.  All pointers are device pointers.

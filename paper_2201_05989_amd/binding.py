@@ -28,7 +28,8 @@ _TORCH = {HG_F32: torch.float32, HG_F16: torch.float16}
 EXPORTS = ("hashgrid_create", "hashgrid_destroy", "hashgrid_n_entries", "hashgrid_level_info",
            "hashgrid_encode_fwd", "hashgrid_encode_bwd", "hashgrid_encode_bwd_input",
            "hashgrid_debug_indices", "hashgrid_strerror", "hashgrid_bwd_workspace_bytes",
-           "hashgrid_encode_bwd_ws", "hashgrid_encode_fwd_ws", "hashgrid_bwd_ws_pays", "hashgrid_adam_step", "hashgrid_probe_copy", "hashgrid_probe_gather",
+           "hashgrid_encode_bwd_ws", "hashgrid_encode_fwd_ws", "hashgrid_bwd_ws_pays", "hashgrid_adam_step",
+           "hashgrid_encode_mlp_fwd", "hashgrid_probe_copy", "hashgrid_probe_gather",
            "hashgrid_probe_atomic_add")
 
 
@@ -80,6 +81,8 @@ def load_library() -> ctypes.CDLL:
     lib.hashgrid_encode_bwd_ws.argtypes = [vp, u32, vp, vp, vp, vp, u64, u32, vp]
     lib.hashgrid_encode_fwd_ws.argtypes = [vp, u32, vp, vp, vp, vp, u64, vp]
     lib.hashgrid_encode_fwd_ws.restype = ctypes.c_int
+    lib.hashgrid_encode_mlp_fwd.argtypes = [vp, u32, vp, vp, vp, vp, vp, u32, vp, vp]
+    lib.hashgrid_encode_mlp_fwd.restype = ctypes.c_int
     lib.hashgrid_bwd_ws_pays.argtypes = [vp, u32]
     lib.hashgrid_bwd_ws_pays.restype = ctypes.c_int
     lib.hashgrid_encode_bwd_ws.restype = ctypes.c_int
@@ -240,6 +243,21 @@ class HashGrid:
             _dev(dLdy, self.io_dtype, (B, self.L * self.F), "dLdy"),
             _dev(dLdx, torch.float32, (B, self.d), "dLdx"), _stream_ptr(stream)), "hashgrid_encode_bwd_input")
         return dLdx
+
+    def encode_mlp_fwd(self, x: torch.Tensor, params: torch.Tensor, W1: torch.Tensor, W2: torch.Tensor,
+                       W3: torch.Tensor, out: torch.Tensor | None = None, stream=None):
+        """hashgrid_encode_mlp_fwd: the encoding followed by the 64-64 ReLU network, fp16 weights
+        W1 [64, L*F], W2 [64, 64], W3 [n_out, 64]; returns out [B, n_out] fp32."""
+        B, n_out = x.shape[0], W3.shape[0]
+        if out is None:
+            out = torch.empty((B, n_out), dtype=torch.float32, device=x.device)
+        _check(self._lib.hashgrid_encode_mlp_fwd(
+            self._h, B, _dev(x, torch.float32, (B, self.d), "x"),
+            _dev(params, self.param_dtype, (self.n_entries, self.F), "params"),
+            _dev(W1, torch.float16, (64, self.L * self.F), "W1"), _dev(W2, torch.float16, (64, 64), "W2"),
+            _dev(W3, torch.float16, (n_out, 64), "W3"), n_out, _dev(out, torch.float32, (B, n_out), "out"),
+            _stream_ptr(stream)), "hashgrid_encode_mlp_fwd")
+        return out
 
     def debug_indices(self, x: torch.Tensor, level: int, stream=None):
         B = x.shape[0]

@@ -10,7 +10,7 @@ CSRC = os.path.join(_PKG, "csrc")
 INCLUDE = os.path.join(_ROOT, "include")
 LIB_PATH = os.environ.get("HASHGRID_LIB") or os.path.join(_PKG, "libhashgrid.so")
 
-SOURCES = ["hashgrid.hip", "bwd_binned.hip", "adam.hip", "probes.hip"]
+SOURCES = ["hashgrid.hip", "bwd_binned.hip", "adam.hip", "probes.hip", "mlp_fused.hip"]
 
 # fp contraction is off so that the scale step of the encoding stays one rounded
 # fp32 multiply (it decides voxel corners); FMAs are written out where wanted.

@@ -1,0 +1,207 @@
+// The encoding followed by the small network of the paper (Section 4, "Architecture": two hidden
+// layers of 64 neurons, ReLU, linear output layer), in one kernel: the encoded features go from
+// the gathers into LDS and through three matrix products on the matrix cores without ever
+// reaching memory.  The network is tiny next to the gathers (7168 multiply-adds per point against
+// 128 random table reads), so the kernel keeps the shape of the forward kernel - one thread per
+// point, 1024-thread workgroups, one barrier per level so that the workgroups walk the level
+// slices together - and appends the network per wave: each wave owns the 64 rows of activations
+// of its own points.
+//
+// Matrix products: D[neuron][point] = sum_k W[neuron][k] * act[point][k] with
+// v_mfma_f32_32x32x8_f16 (fp16 operands, fp32 accumulation).  Per lane l of a wave:
+//   A operand (32 neurons x 8 inputs): neuron l % 32, inputs 4 * (l / 32) .. + 3;
+//   B operand (8 inputs x 32 points):  point l % 32, inputs 4 * (l / 32) .. + 3;
+//   D (32 neurons x 32 points), 16 values: point l % 32, neurons 8 * (r / 4) + 4 * (l / 32) + r % 4.
+// Both operands are therefore 8-byte reads of four consecutive inputs of one row, and a lane's
+// results are four runs of four consecutive neurons of one point: activations are kept in LDS as
+// [point][neuron] rows, weights as [neuron][input] rows, each row padded by four halves so that
+// the 32 rows a read touches fall into different banks.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "hashgrid.h"
+#include "hashgrid_common.hpp"
+#include "hashgrid_internal.hpp"
+
+namespace hg {
+
+constexpr int kMlpBlock = 1024;   // threads = points of a workgroup
+constexpr int kHidden = 64;       // neurons of a hidden layer
+constexpr int kRowPad = 4;        // halves of padding per LDS row
+constexpr int kActStride = kHidden + kRowPad;
+constexpr int kMaxOut = 32;       // output neurons (one 32-row block of the matrix instruction)
+
+using half4 = _Float16 __attribute__((ext_vector_type(4)));
+using float16v = float __attribute__((ext_vector_type(16)));
+
+// One 32 x 32 block of W[32 rows from w_row0][K] * act[32 points from p_row0][K]^T.
+template <int K>
+__device__ __forceinline__ float16v block_product(const _Float16* __restrict__ w, int w_stride, int w_row0,
+                                                  const _Float16* __restrict__ act, int p_row0) {
+  const int lane = threadIdx.x & 63, r = lane & 31, k0 = 4 * (lane >> 5);
+  const _Float16* wa = w + (w_row0 + r) * w_stride + k0;
+  const _Float16* pb = act + (p_row0 + r) * kActStride + k0;
+  float16v acc;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
+#pragma unroll
+  for (int ks = 0; ks < K / 8; ++ks) {
+    const half4 a = *reinterpret_cast<const half4*>(wa + ks * 8);
+    const half4 b = *reinterpret_cast<const half4*>(pb + ks * 8);
+    acc = __builtin_amdgcn_mfma_f32_32x32x8f16(a, b, acc, 0, 0, 0);
+  }
+  return acc;
+}
+
+// relu, round to half, store a lane's 16 results of one block: point p_row0 + lane % 32, neurons
+// n_row0 + 8 q + 4 (lane / 32) + t
+__device__ __forceinline__ void store_hidden(_Float16* __restrict__ act, int p_row0, int n_row0, const float16v& acc) {
+  const int lane = threadIdx.x & 63;
+  _Float16* row = act + (p_row0 + (lane & 31)) * kActStride + n_row0 + 4 * (lane >> 5);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    half4 h;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) h[t] = (_Float16)fmaxf(acc[4 * q + t], 0.0f);
+    *reinterpret_cast<half4*>(row + 8 * q) = h;
+  }
+}
+
+template <int D, int F>
+__global__ __launch_bounds__(kMlpBlock) void encode_mlp_fwd(const LevelTable lv, const bool smooth, const uint32_t B,
+                                                            const float* __restrict__ x,
+                                                            const _Float16* __restrict__ theta,
+                                                            const _Float16* __restrict__ W1,
+                                                            const _Float16* __restrict__ W2,
+                                                            const _Float16* __restrict__ W3, const uint32_t n_out,
+                                                            float* __restrict__ out) {
+  extern __shared__ _Float16 lds[];
+  const int n_in = (int)lv.L * F;  // a multiple of 8, at most 64 (checked on the host)
+  const int w1_stride = n_in + kRowPad;
+  _Float16* act = lds;                                // [kMlpBlock][kActStride]
+  _Float16* w1 = act + kMlpBlock * kActStride;        // [kHidden][n_in + pad]
+  _Float16* w2 = w1 + kHidden * w1_stride;            // [kHidden][kActStride]
+  _Float16* w3 = w2 + kHidden * kActStride;           // [kMaxOut][kActStride], rows from n_out on are zero
+
+  for (int i = threadIdx.x; i < kHidden * n_in; i += kMlpBlock) w1[(i / n_in) * w1_stride + i % n_in] = W1[i];
+  for (int i = threadIdx.x; i < kHidden * kHidden; i += kMlpBlock)
+    w2[(i / kHidden) * kActStride + i % kHidden] = W2[i];
+  for (int i = threadIdx.x; i < kMaxOut * kHidden; i += kMlpBlock)
+    w3[(i / kHidden) * kActStride + i % kHidden] = (uint32_t)(i / kHidden) < n_out ? W3[i] : (_Float16)0.0f;
+
+  // the encoding, as in the forward kernel: one thread per point, level by level
+  const uint32_t b0 = blockIdx.x * kMlpBlock + threadIdx.x;
+  const uint32_t b = b0 < B ? b0 : B - 1;  // idle lanes of the last workgroup shadow the last point
+  float xp[D];
+#pragma unroll
+  for (int i = 0; i < D; ++i) xp[i] = x[(uint64_t)b * D + i];
+  _Float16* my_row = act + threadIdx.x * kActStride;
+  for (uint32_t l = 0; l < lv.L; ++l) {
+    uint32_t idx[1 << D];
+    float wr[1 << (D - 1)], w0, u0;
+    level_corners<D, true>(lv, l, smooth, xp, idx, wr, w0, u0);
+    const Vec<_Float16, F>* tab = reinterpret_cast<const Vec<_Float16, F>*>(theta) + lv.offset[l];
+    Vec<_Float16, F> e[1 << D];
+#pragma unroll
+    for (uint32_t m = 0; m < (1u << D); ++m) e[m] = tab[idx[m]];
+    float acc[F];
+#pragma unroll
+    for (int f = 0; f < F; ++f) acc[f] = 0.0f;
+#pragma unroll
+    for (uint32_t m = 0; m < (1u << D); ++m) {
+      const float wt = wr[m >> 1] * ((m & 1u) ? w0 : u0);
+#pragma unroll
+      for (int f = 0; f < F; ++f) acc[f] = fmaf(wt, (float)e[m].v[f], acc[f]);
+    }
+#pragma unroll
+    for (int f = 0; f < F; ++f) my_row[l * F + f] = (_Float16)acc[f];  // rows are 8-byte, not 16-byte, aligned
+    asm volatile("" ::: "memory");  // keep the gathers of one level together
+    __syncthreads();                // (also: the weights are in place before the first product)
+  }
+
+  // the network, per wave on its own 64 points; a layer's four blocks are computed before its
+  // results overwrite the activations they were computed from
+  const int p0 = (int)(threadIdx.x & ~63u);
+  float16v h[4];
+#pragma unroll
+  for (int blk = 0; blk < 4; ++blk) {
+    const int pr = p0 + 32 * (blk & 1), nr = 32 * (blk >> 1);
+    h[blk] = n_in == 64   ? block_product<64>(w1, w1_stride, nr, act, pr)
+             : n_in == 32 ? block_product<32>(w1, w1_stride, nr, act, pr)
+             : n_in == 16 ? block_product<16>(w1, w1_stride, nr, act, pr)
+             : n_in == 8  ? block_product<8>(w1, w1_stride, nr, act, pr)
+             : n_in == 24 ? block_product<24>(w1, w1_stride, nr, act, pr)
+             : n_in == 40 ? block_product<40>(w1, w1_stride, nr, act, pr)
+             : n_in == 48 ? block_product<48>(w1, w1_stride, nr, act, pr)
+                          : block_product<56>(w1, w1_stride, nr, act, pr);
+  }
+#pragma unroll
+  for (int blk = 0; blk < 4; ++blk) store_hidden(act, p0 + 32 * (blk & 1), 32 * (blk >> 1), h[blk]);
+#pragma unroll
+  for (int blk = 0; blk < 4; ++blk)
+    h[blk] = block_product<kHidden>(w2, kActStride, 32 * (blk >> 1), act, p0 + 32 * (blk & 1));
+#pragma unroll
+  for (int blk = 0; blk < 4; ++blk) store_hidden(act, p0 + 32 * (blk & 1), 32 * (blk >> 1), h[blk]);
+  const int lane = threadIdx.x & 63;
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    const float16v o = block_product<kHidden>(w3, kActStride, 0, act, p0 + 32 * half);
+    const uint64_t point = (uint64_t)blockIdx.x * kMlpBlock + p0 + 32 * half + (lane & 31);
+    if (point < B) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const uint32_t neuron = 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
+        if (neuron < n_out) out[point * n_out + neuron] = o[r];
+      }
+    }
+  }
+}
+
+template <int D, int F>
+static hg_status launch_mlp(const hashgrid* h, uint32_t B, const float* x, const void* params, const void* W1,
+                            const void* W2, const void* W3, uint32_t n_out, float* out, hipStream_t s) {
+  const int n_in = (int)h->lv.L * F;
+  const size_t lds = ((size_t)kMlpBlock * kActStride + (size_t)kHidden * (n_in + kRowPad) +
+                      (size_t)(kHidden + kMaxOut) * kActStride) * sizeof(_Float16);
+  static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(encode_mlp_fwd<D, F>),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  if (lds_ok != hipSuccess) return HG_ERR_DEVICE;
+  hipLaunchKernelGGL((encode_mlp_fwd<D, F>), dim3((B + kMlpBlock - 1) / kMlpBlock), dim3(kMlpBlock), lds, s, h->lv,
+                     h->cfg.interp == HG_INTERP_SMOOTHSTEP, B, x, static_cast<const _Float16*>(params),
+                     static_cast<const _Float16*>(W1), static_cast<const _Float16*>(W2),
+                     static_cast<const _Float16*>(W3), n_out, out);
+  return hipGetLastError() == hipSuccess ? HG_OK : HG_ERR_DEVICE;
+}
+
+}  // namespace hg
+
+extern "C" hg_status hashgrid_encode_mlp_fwd(const hashgrid_t* hg, uint32_t B, const float* x, const void* params,
+                                             const void* W1, const void* W2, const void* W3, uint32_t n_out,
+                                             float* out, void* stream) {
+  if (!hg) return HG_ERR_INVALID_ARG;
+  if (B == 0) return HG_OK;
+  if (B > HG_MAX_BATCH) return HG_ERR_UNSUPPORTED;
+  if (!x || !params || !W1 || !W2 || !W3 || !out || n_out == 0) return HG_ERR_INVALID_ARG;
+  const hashgrid_config& c = hg->cfg;
+  const uint32_t n_in = c.L * c.F;
+  if (c.param_dtype != HG_F16 || !hg->lv.T_is_pow2 || c.d < 2 || n_in % 8 != 0 || n_in > (uint32_t)hg::kHidden ||
+      n_out > (uint32_t)hg::kMaxOut)
+    return HG_ERR_UNSUPPORTED;
+  auto bad = [](const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; };
+  if (bad(x, 4) || bad(params, c.F * 2) || bad(W1, 2) || bad(W2, 2) || bad(W3, 2) || bad(out, 4))
+    return HG_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+#define HG_MLP(D, F) hg::launch_mlp<D, F>(hg, B, x, params, W1, W2, W3, n_out, out, s)
+  switch (c.d * 16 + c.F) {
+    case 2 * 16 + 1: return HG_MLP(2, 1);
+    case 2 * 16 + 2: return HG_MLP(2, 2);
+    case 2 * 16 + 4: return HG_MLP(2, 4);
+    case 2 * 16 + 8: return HG_MLP(2, 8);
+    case 3 * 16 + 1: return HG_MLP(3, 1);
+    case 3 * 16 + 2: return HG_MLP(3, 2);
+    case 3 * 16 + 4: return HG_MLP(3, 4);
+    case 3 * 16 + 8: return HG_MLP(3, 8);
+    default: return HG_ERR_UNSUPPORTED;
+  }
+#undef HG_MLP
+}

@@ -1,0 +1,109 @@
+"""Parity of hashgrid_encode_mlp_fwd (the encoding followed by the 64-64 ReLU network of Section 4,
+one kernel, matrix cores) with the CPU oracle.
+
+Bars: with integer-valued tables, inputs at grid vertices and small integer weights nothing rounds
+anywhere, on either side: the outputs must be equal.  In general the kernel accumulates in fp32
+and rounds y, h1, h2 to fp16 where the oracle rounds fp64 values, so an activation may land on the
+other side of an fp16 rounding boundary: |out - out*| <= 2^-10 M, M = |W3| (|W2| (|W1| |y|)) (one
+fp16 step of every activation at once, never reached), and the typical error is far smaller,
+which the test also asserts on the median."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import hashgrid_oracle as orc
+from oracle import mlp_oracle as mlp
+from paper_2201_05989_amd import HashGrid, synth
+
+pytestmark = pytest.mark.gpu
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def run(d, L, F, T, N_min, N_max, x, theta, W1, W2, W3, interp=0):
+    cfg = orc.OracleConfig(d, L, F, T, N_min, N_max, interp)
+    grid = HashGrid(d, L, F, T, N_min, N_max, "f16", "f16", interp)
+    out = grid.encode_mlp_fwd(dev(x), dev(theta), dev(W1), dev(W2), dev(W3)).cpu().numpy().astype(np.float64)
+    y = orc.encode_fwd(cfg, x, theta)
+    ref = mlp.mlp_fwd(y, W1, W2, W3)
+    return out, ref, mlp.magnitude_bound(y, W1, W2, W3)
+
+
+def weights(rng, n_in, n_out, scale=1.0):
+    # He-style scale so that activations stay O(1) through the layers
+    W1 = (rng.standard_normal((64, n_in)) * scale * np.sqrt(2.0 / n_in)).astype(np.float16)
+    W2 = (rng.standard_normal((64, 64)) * np.sqrt(2.0 / 64)).astype(np.float16)
+    W3 = (rng.standard_normal((n_out, 64)) * np.sqrt(1.0 / 64)).astype(np.float16)
+    return W1, W2, W3
+
+
+def test_exact_when_nothing_rounds():
+    # one dense level per ... all levels dense (T large), points exactly at grid vertices, integer tables
+    d, L, F, T, N_min, N_max = 3, 4, 2, 1 << 19, 4, 32   # N = 4, 8, 16, 32: all 1:1 indexed; n_in = 8
+    cfg = orc.OracleConfig(d, L, F, T, N_min, N_max)
+    lv = orc.levels(cfg)
+    assert lv.dense.all()
+    rng = np.random.default_rng(0)
+    theta = rng.integers(-3, 4, (lv.total, F)).astype(np.float16)
+    x = (rng.integers(0, 4, (3000, d)) / 4.0).astype(np.float32)   # vertices of every level
+    W1 = (rng.integers(-1, 2, (64, L * F)) * (rng.random((64, L * F)) < 0.5)).astype(np.float16)
+    W2 = (rng.integers(-1, 2, (64, 64)) * (rng.random((64, 64)) < 0.1)).astype(np.float16)
+    W3 = rng.integers(-2, 3, (5, 64)).astype(np.float16)
+    out, ref, _ = run(d, L, F, T, N_min, N_max, x, theta, W1, W2, W3)
+    assert np.abs(ref).max() > 0 and np.abs(ref).max() < 2048
+    np.testing.assert_array_equal(out, ref)
+
+
+def test_each_weight_lands_on_its_neuron_and_input():
+    # one non-zero weight per layer at a time: catches a transposed or permuted operand layout
+    d, L, F, T, N_min, N_max = 2, 8, 4, 1 << 16, 4, 64   # n_in = 32
+    cfg = orc.OracleConfig(d, L, F, T, N_min, N_max)
+    lv = orc.levels(cfg)
+    rng = np.random.default_rng(1)
+    theta = rng.integers(1, 5, (lv.total, F)).astype(np.float16)      # positive: ReLU passes everything
+    x = (rng.integers(0, 4, (257, d)) / 4.0).astype(np.float32)
+    for trial in range(6):
+        i1, k1, i2, i3 = rng.integers(0, 64), rng.integers(0, 32), rng.integers(0, 64), rng.integers(0, 7)
+        W1 = np.zeros((64, 32), np.float16); W1[i1, k1] = 1
+        W2 = np.zeros((64, 64), np.float16); W2[i2, i1] = 2
+        W3 = np.zeros((7, 64), np.float16); W3[i3, i2] = 1
+        out, ref, _ = run(d, L, F, T, N_min, N_max, x, theta, W1, W2, W3)
+        assert ref[:, i3].min() > 0
+        np.testing.assert_array_equal(out, ref)
+
+
+@pytest.mark.parametrize("d,L,F,T,N_max,n_out,B,interp", [
+    (3, 16, 2, 1 << 19, 2048, 1, 70001, 0),    # the paper's configuration, SDF-style single output
+    (3, 16, 4, 1 << 15, 512, 16, 5000, 0),     # 64 inputs, 16 outputs
+    (3, 16, 1, 1 << 15, 512, 4, 4097, 1),      # 16 inputs, smoothstep
+    (2, 8, 2, 1 << 12, 256, 3, 1025, 0),       # 2-D, 16 inputs
+    (3, 8, 8, 1 << 14, 128, 32, 999, 0),       # F = 8, 32 outputs
+    (2, 4, 2, 1 << 10, 32, 2, 64, 0),          # 8 inputs, a single wave
+])
+def test_against_oracle(d, L, F, T, N_max, n_out, B, interp):
+    cfg = orc.OracleConfig(d, L, F, T, 16 if N_max > 64 else 4, N_max, interp)
+    lv = orc.levels(cfg)
+    rng = np.random.default_rng(d * 1000 + L * 10 + F)
+    x = synth.points_sdf(rng, B, 3) if d == 3 else synth.points_uniform(rng, B, d)
+    theta = synth.make_tables(rng, lv.total, F, "f16", 1.0)
+    W1, W2, W3 = weights(rng, L * F, n_out)
+    out, ref, M = run(d, L, F, T, cfg.N_min, N_max, x, theta, W1, W2, W3, interp)
+    err = np.abs(out - ref)
+    assert (err <= 2.0 ** -10 * M + 1e-12).all(), f"worst {np.max(err / (M + 1e-300)):.2e} of M"
+    assert np.median(err / (M + 1e-300)) < 1e-5
+    assert np.abs(ref).max() > 1e-3
+
+
+def test_status_codes():
+    g = HashGrid(3, 16, 2, 1 << 19, 16, 2048, "f32", "f16")   # fp32 tables
+    lib = g._lib
+    assert lib.hashgrid_encode_mlp_fwd(g._h, 8, 4096, 4096, 4096, 4096, 4096, 1, 4096, None) == 2
+    g = HashGrid(3, 16, 8, 1 << 19, 16, 2048)                 # 128 inputs
+    assert lib.hashgrid_encode_mlp_fwd(g._h, 8, 4096, 4096, 4096, 4096, 4096, 1, 4096, None) == 2
+    g = HashGrid(3, 16, 2, 1 << 19, 16, 2048)
+    assert lib.hashgrid_encode_mlp_fwd(g._h, 8, 4096, 4096, 4096, 4096, 4096, 33, 4096, None) == 2
+    assert lib.hashgrid_encode_mlp_fwd(g._h, 8, 4096, 4096, 4096, 4096, 4096, 0, 4096, None) == 1
+    assert lib.hashgrid_encode_mlp_fwd(g._h, 8, None, 4096, 4096, 4096, 4096, 1, 4096, None) == 1
+    assert lib.hashgrid_encode_mlp_fwd(g._h, 0, None, None, None, None, None, 1, None, None) == 0
