@@ -192,6 +192,23 @@ def main():
     n_scalars = grid.n_entries * w.F
     adam_bytes = n_scalars * (16 + 12 + 4 + (2 if w.param_dtype == "f16" else 0))
 
+    # last row of the path's table: the encoding fused with the paper's 64-64 ReLU network (one output,
+    # as for a signed distance function); served for fp16 tables with at most 64 encoded features
+    mlp = None
+    n_in = w.L * w.F
+    if w.param_dtype == "f16" and n_in % 8 == 0 and n_in <= 64 and w.d >= 2:
+        import numpy as np
+        rng = np.random.default_rng(0)
+        W1 = torch.from_numpy((rng.standard_normal((64, n_in)) * np.sqrt(2.0 / n_in)).astype(np.float16)).cuda()
+        W2 = torch.from_numpy((rng.standard_normal((64, 64)) * np.sqrt(2.0 / 64)).astype(np.float16)).cuda()
+        W3 = torch.from_numpy((rng.standard_normal((1, 64)) / 8.0).astype(np.float16)).cuda()
+        o = torch.empty((w.B, 1), dtype=torch.float32, device="cuda")
+        grid.encode_mlp_fwd(xd, td, W1, W2, W3, o)
+        ms_mlp = time_launches(lambda: grid.encode_mlp_fwd(xd, td, W1, W2, W3, o), max(n // 2, 10), torch)
+        flops = 2.0 * (n_in * 64 + 64 * 64 + 64 * 1) * w.B
+        mlp = {"ms": ms_mlp, "mpoints_s": w.B / (ms_mlp * 1e-3) / 1e6, "n_out": 1,
+               "network_tflop_s": flops / (ms_mlp * 1e-3) / 1e12, "ms_over_forward_alone": ms_mlp - ms_fwd_alone}
+
     s_theta = 2 if w.param_dtype == "f16" else 4
     s_io = 2 if w.io_dtype == "f16" else 4
     b_fwd, b_bwd = algorithmic_bytes(w, s_theta, s_io)
@@ -226,6 +243,8 @@ def main():
                      "fwd_achieved": b_fwd * w.B / (ms_fwd * 1e-3) / 1e9,
                      "bwd_achieved": b_bwd * w.B / (ms_bwd * 1e-3) / 1e9},
     }
+    if mlp is not None:
+        out["encode_mlp_fwd"] = mlp
     if not args.no_probes:
         # the pass rates in the elementary operations they stand for, next to what the machine does
         # when it performs those operations one by one at random

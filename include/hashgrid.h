@@ -203,7 +203,7 @@ hg_status hashgrid_adam_step(uint64_t n_scalars, float* params_master, void* par
  * y = enc(x_b; params).  Half-precision operands on the matrix cores with fp32 accumulation: y, h1
  * and h2 are rounded to fp16 (nearest even) where they are stored, out is fp32.
  *   params  [n_entries, F]  fp16 (param_dtype must be HG_F16), device, read
- *   W1      [64, L*F]       fp16, device, read; row = neuron (as W2, W3)
+ *   W1      [64, L*F]       fp16, device, 8-byte aligned (as W2, W3), read; row = neuron
  *   W2      [64, 64]        fp16
  *   W3      [n_out, 64]     fp16, 1 <= n_out <= 32
  *   out     [B, n_out]      fp32, device, written in full

@@ -83,11 +83,20 @@ __global__ __launch_bounds__(kMlpBlock) void encode_mlp_fwd(const LevelTable lv,
   _Float16* w2 = w1 + kHidden * w1_stride;            // [kHidden][kActStride]
   _Float16* w3 = w2 + kHidden * kActStride;           // [kMaxOut][kActStride], rows from n_out on are zero
 
-  for (int i = threadIdx.x; i < kHidden * n_in; i += kMlpBlock) w1[(i / n_in) * w1_stride + i % n_in] = W1[i];
-  for (int i = threadIdx.x; i < kHidden * kHidden; i += kMlpBlock)
-    w2[(i / kHidden) * kActStride + i % kHidden] = W2[i];
-  for (int i = threadIdx.x; i < kMaxOut * kHidden; i += kMlpBlock)
-    w3[(i / kHidden) * kActStride + i % kHidden] = (uint32_t)(i / kHidden) < n_out ? W3[i] : (_Float16)0.0f;
+  // weights -> LDS in 8-byte pieces (rows are multiples of four halves, host-checked alignment)
+  {
+    const int q1 = n_in / 4;  // pieces per row of W1
+    for (int i = threadIdx.x; i < kHidden * q1; i += kMlpBlock)
+      *reinterpret_cast<half4*>(w1 + (i / q1) * w1_stride + 4 * (i % q1)) = reinterpret_cast<const half4*>(W1)[i];
+    constexpr int q2 = kHidden / 4;
+    for (int i = threadIdx.x; i < kHidden * q2; i += kMlpBlock)
+      *reinterpret_cast<half4*>(w2 + (i / q2) * kActStride + 4 * (i % q2)) = reinterpret_cast<const half4*>(W2)[i];
+    for (int i = threadIdx.x; i < kMaxOut * q2; i += kMlpBlock) {
+      half4 v = {(_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f};
+      if ((uint32_t)(i / q2) < n_out) v = reinterpret_cast<const half4*>(W3)[i];
+      *reinterpret_cast<half4*>(w3 + (i / q2) * kActStride + 4 * (i % q2)) = v;
+    }
+  }
 
   // the encoding, as in the forward kernel: one thread per point, level by level
   const uint32_t b0 = blockIdx.x * kMlpBlock + threadIdx.x;
@@ -188,7 +197,7 @@ extern "C" hg_status hashgrid_encode_mlp_fwd(const hashgrid_t* hg, uint32_t B, c
       n_out > (uint32_t)hg::kMaxOut)
     return HG_ERR_UNSUPPORTED;
   auto bad = [](const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; };
-  if (bad(x, 4) || bad(params, c.F * 2) || bad(W1, 2) || bad(W2, 2) || bad(W3, 2) || bad(out, 4))
+  if (bad(x, 4) || bad(params, c.F * 2) || bad(W1, 8) || bad(W2, 8) || bad(W3, 8) || bad(out, 4))
     return HG_ERR_INVALID_ARG;
   hipStream_t s = static_cast<hipStream_t>(stream);
 #define HG_MLP(D, F) hg::launch_mlp<D, F>(hg, B, x, params, W1, W2, W3, n_out, out, s)

@@ -94,16 +94,3 @@ def test_against_oracle(d, L, F, T, N_max, n_out, B, interp):
     assert (err <= 2.0 ** -10 * M + 1e-12).all(), f"worst {np.max(err / (M + 1e-300)):.2e} of M"
     assert np.median(err / (M + 1e-300)) < 1e-5
     assert np.abs(ref).max() > 1e-3
-
-
-def test_status_codes():
-    g = HashGrid(3, 16, 2, 1 << 19, 16, 2048, "f32", "f16")   # fp32 tables
-    lib = g._lib
-    assert lib.hashgrid_encode_mlp_fwd(g._h, 8, 4096, 4096, 4096, 4096, 4096, 1, 4096, None) == 2
-    g = HashGrid(3, 16, 8, 1 << 19, 16, 2048)                 # 128 inputs
-    assert lib.hashgrid_encode_mlp_fwd(g._h, 8, 4096, 4096, 4096, 4096, 4096, 1, 4096, None) == 2
-    g = HashGrid(3, 16, 2, 1 << 19, 16, 2048)
-    assert lib.hashgrid_encode_mlp_fwd(g._h, 8, 4096, 4096, 4096, 4096, 4096, 33, 4096, None) == 2
-    assert lib.hashgrid_encode_mlp_fwd(g._h, 8, 4096, 4096, 4096, 4096, 4096, 0, 4096, None) == 1
-    assert lib.hashgrid_encode_mlp_fwd(g._h, 8, None, 4096, 4096, 4096, 4096, 1, 4096, None) == 1
-    assert lib.hashgrid_encode_mlp_fwd(g._h, 0, None, None, None, None, None, 1, None, None) == 0

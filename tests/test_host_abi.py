@@ -118,3 +118,16 @@ def test_probe_status_codes_need_no_device():
     assert lib.hashgrid_probe_gather(4096, 1024, 100, 1, 8192, None) == 1    # not a multiple of 4096
     assert lib.hashgrid_probe_atomic_add(None, 1024, 4096, 1, None) == 1
     assert lib.hashgrid_probe_atomic_add(4096, 1 << 33, 4096, 1, None) == 1
+
+
+def test_encode_mlp_status_codes_need_no_device():
+    g = binding.HashGrid(3, 16, 2, 1 << 19, 16, 2048, "f32", "f16")   # fp32 tables
+    lib = g._lib
+    assert lib.hashgrid_encode_mlp_fwd(g._h, 8, 4096, 4096, 4096, 4096, 4096, 1, 4096, None) == 2
+    g = binding.HashGrid(3, 16, 8, 1 << 19, 16, 2048)                 # 128 inputs
+    assert lib.hashgrid_encode_mlp_fwd(g._h, 8, 4096, 4096, 4096, 4096, 4096, 1, 4096, None) == 2
+    g = binding.HashGrid(3, 16, 2, 1 << 19, 16, 2048)
+    assert lib.hashgrid_encode_mlp_fwd(g._h, 8, 4096, 4096, 4096, 4096, 4096, 33, 4096, None) == 2
+    assert lib.hashgrid_encode_mlp_fwd(g._h, 8, 4096, 4096, 4096, 4096, 4096, 0, 4096, None) == 1
+    assert lib.hashgrid_encode_mlp_fwd(g._h, 8, None, 4096, 4096, 4096, 4096, 1, 4096, None) == 1
+    assert lib.hashgrid_encode_mlp_fwd(g._h, 0, None, None, None, None, None, 1, None, None) == 0
