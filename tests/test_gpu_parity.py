@@ -232,6 +232,33 @@ def test_sweep_of_shapes_and_dtypes(d, L, F, T, N_min, N_max, pdt, iot, interp, 
     run_case(d, L, F, T, N_min, N_max, pdt, iot, interp, x, theta, dy)
 
 
+def _random_case(seed):
+    rng = np.random.default_rng(1000 + seed)
+    d = int(rng.integers(1, 4))
+    F = int(rng.choice([1, 2, 4, 8]))
+    L = int(rng.integers(1, 13))
+    T = int(rng.choice([1 << int(rng.integers(0, 18)), int(rng.integers(1, 100000))], p=[0.8, 0.2]))
+    N_min = int(rng.integers(1, 40))
+    N_max = int(N_min * rng.choice([1, 2, 7, 100, 3000]) + rng.integers(0, 5))
+    pdt, iot = (str(rng.choice(["f16", "f32"])) for _ in range(2))
+    interp = int(rng.integers(0, 2))
+    B = int(rng.choice([1, 63, 512, 513, int(rng.integers(2, 3000))]))
+    return d, L, F, T, N_min, N_max, pdt, iot, interp, B
+
+
+@pytest.mark.parametrize("seed", range(32))
+def test_random_configurations(seed):
+    # seeded draws over every parameter of the configuration, including tables smaller than a chunk,
+    # resolutions beyond 4096, single levels and single points: every entry point against the oracle
+    d, L, F, T, N_min, N_max, pdt, iot, interp, B = _random_case(seed)
+    lv = orc.levels(orc.OracleConfig(d, L, F, T, N_min, N_max, interp))
+    rng = np.random.default_rng(5000 + seed)
+    x = synth.points_uniform(rng, B, d)
+    theta = synth.make_tables(rng, lv.total, F, pdt, 1.0)
+    dy = synth.make_dy(rng, B, L * F, iot)
+    run_case(d, L, F, T, N_min, N_max, pdt, iot, interp, x, theta, dy)
+
+
 def test_edge_positions_and_grid_vertices():
     # exact 0, the largest fp32 below 1, grid vertices of every level and their fp32 neighbours
     d, L, F, T, N_min, N_max = 3, 8, 2, 1 << 12, 4, 512
