@@ -382,6 +382,40 @@ def test_counting_forward_gives_the_counts_of_the_count_pass():
         assert torch.equal(g0[lo:], g2[lo:])
 
 
+def test_step_replays_from_a_hip_graph():
+    # the library launches kernels only (no allocation, no memset, no synchronisation), so a step can
+    # be captured once and replayed; replays interleaved with eager work must reproduce the eager result
+    w = synth.WORKLOADS["sdf3d"]
+    grid = HashGrid(w.d, w.L, w.F, w.T, w.N_min, w.N_max, w.param_dtype, w.io_dtype)
+    B = 40000
+    x, theta, dy = synth.make_inputs(w, grid.n_entries, B=B, table_scale=1.0)
+    xd, td, gd = dev(x), dev(theta), dev(dy)
+    y_ref = grid.encode_fwd(xd, td, count_for_bwd="always")       # also allocates the scratch buffer
+    g_ref = grid.encode_bwd(xd, gd)
+    y = torch.zeros_like(y_ref)
+    grad = torch.zeros_like(g_ref)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            grad.fill_(0.0)                                       # a fill kernel, not a memset node
+            grid.encode_fwd(xd, td, y, count_for_bwd="always")
+            grid.encode_bwd(xd, gd, grad)
+    torch.cuda.current_stream().wait_stream(side)
+    hashed_from = [i for i in grid.levels() if not i.is_dense][0].entry_offset
+    for k in range(4):
+        y.zero_()
+        grad.fill_(float(k))                                      # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        same_forward(y, y_ref, w.io_dtype)
+        assert torch.equal(grad[hashed_from:], g_ref[hashed_from:])
+        torch.testing.assert_close(grad[:hashed_from], g_ref[:hashed_from], rtol=1e-4,
+                                   atol=1e-4 * float(g_ref.abs().max()))
+
+
 def test_binding_picks_the_backward_pass_by_batch_size():
     grid = HashGrid(3, 16, 2, 1 << 19, 16, 2048)
     assert not grid.bwd_ws_pays(1024) and grid.bwd_ws_pays(1 << 16)
