@@ -849,6 +849,26 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
   }
 }
 
+// The count pass by itself: counts[tile][bin] for the B points (x only).
+static hg_status launch_count(const hashgrid* h, uint32_t B, const float* x, const Workspace& ws, hipStream_t s) {
+  const BinPlan& bp = h->bp;
+  const uint32_t L = h->lv.L, cparts = bp.count_parts;
+  uint32_t max_bins = 0;
+  for (uint32_t p = 0; p < cparts; ++p) {
+    const uint32_t nbp = bp.bin_base[(p + 1) * L / cparts] - bp.bin_base[p * L / cparts];
+    max_bins = nbp > max_bins ? nbp : max_bins;
+  }
+  const bool smooth = h->cfg.interp == HG_INTERP_SMOOTHSTEP;
+  const dim3 grid((ws.n_tiles + 7u) / 8u * 8u, cparts);  // see tile_of_workgroup
+  if (h->cfg.d == 3)
+    hipLaunchKernelGGL((bin_count<3>), grid, dim3(kBinThreads), (size_t)max_bins * 4, s, h->lv, bp, smooth, B, x,
+                       ws.counts, ws.n_bins, ws.n_tiles);
+  else
+    hipLaunchKernelGGL((bin_count<2>), grid, dim3(kBinThreads), (size_t)max_bins * 4, s, h->lv, bp, smooth, B, x,
+                       ws.counts, ws.n_bins, ws.n_tiles);
+  return hipGetLastError() == hipSuccess ? HG_OK : HG_ERR_DEVICE;
+}
+
 template <int D, typename IT, int F>
 static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, const void* dy, float* grad,
                                const Workspace& ws, const bool counted, hipStream_t s) {
@@ -858,7 +878,7 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
   plan_slices(bp, h->lv, B);
   const bool smooth = h->cfg.interp == HG_INTERP_SMOOTHSTEP;
   const uint32_t n_records = B * h->lv.L * bp.rec_per_point;
-  const uint32_t L = h->lv.L, parts = bp.scatter_parts, cparts = bp.count_parts;
+  const uint32_t L = h->lv.L, parts = bp.scatter_parts;
   auto max_part_bins = [&](uint32_t np) {
     uint32_t m = 0;
     for (uint32_t p = 0; p < np; ++p) {
@@ -886,12 +906,9 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
     return e;
   }();
   if (lds_ok != hipSuccess) return HG_ERR_DEVICE;
-  const size_t lds_count = (size_t)max_part_bins(cparts) * 4;
   const size_t lds_scatter = kStagingBytes + (3 * (size_t)max_part_bins(parts) + 1) * 4;
   const uint32_t tile_wgs = (ws.n_tiles + 7u) / 8u * 8u;  // see tile_of_workgroup
-  if (!counted)
-    hipLaunchKernelGGL((bin_count<D>), dim3(tile_wgs, cparts), dim3(kBinThreads), lds_count, s, h->lv, bp, smooth, B,
-                       x, ws.counts, ws.n_bins, ws.n_tiles);
+  if (!counted && launch_count(h, B, x, ws, s) != HG_OK) return HG_ERR_DEVICE;
   hipLaunchKernelGGL(bin_scan, dim3((ws.n_bins + kScanBins - 1) / kScanBins), dim3(kScanThreads), 0, s, ws.n_tiles,
                      ws.n_bins, ws.counts, ws.bin_total, ws.item_counter);
   hipLaunchKernelGGL((bin_scatter<D, IT, F>), dim3(tile_wgs, parts), dim3(kBinThreads), lds_scatter, s, h->lv, bp,
@@ -965,8 +982,15 @@ hg_status hashgrid_encode_fwd_ws(const hashgrid_t* hg, uint32_t B, const float* 
   if (!x || !params || !y || (reinterpret_cast<uintptr_t>(x) & 3)) return HG_ERR_INVALID_ARG;
   hg::Workspace ws;
   hg::carve(hg, B, static_cast<uint8_t*>(workspace), &ws);
-  return hg::launch_fwd_counting(hg, B, x, params, y, ws.counts, ws.n_bins, ws.n_tiles,
-                                 static_cast<hipStream_t>(stream));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // The counting kernel runs full workgroups (they cover whole tiles), which is slow for a batch that
+  // cannot give every CU one: there the plain forward in small workgroups plus the count pass is
+  // faster and leaves the workspace in the same state.
+  if (hg::point_major_block(B) < 1024u) {
+    const hg_status st = hashgrid_encode_fwd(hg, B, x, params, y, stream);
+    return st != HG_OK ? st : hg::launch_count(hg, B, x, ws, s);
+  }
+  return hg::launch_fwd_counting(hg, B, x, params, y, ws.counts, ws.n_bins, ws.n_tiles, s);
 }
 
 hg_status hashgrid_encode_bwd_ws(const hashgrid_t* hg, uint32_t B, const float* x, const void* dLdy,

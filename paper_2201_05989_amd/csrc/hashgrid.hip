@@ -116,6 +116,22 @@ __global__ __launch_bounds__(kBlock) void fwd_general(const LevelTable lv, const
 // keeps the 16 waves of a workgroup on the same slice, which holds the L2 hit
 // rate at that of the level-major grid.
 constexpr int kPmBlock = 1024;
+// A batch that does not fill every CU with a full workgroup is cut into smaller ones: the kernels
+// are bound by what one CU's texture path and L1 deliver, so 2^14 points in sixteen workgroups
+// take as long as 2^18 in 256.  (The counting variant always runs full workgroups: they cover
+// whole tiles of the backward pass.)
+uint32_t point_major_block(uint32_t B) {
+  static const uint32_t cus = [] {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+      n = 256;
+    return (uint32_t)n;
+  }();
+  uint32_t block = kPmBlock;
+  while (block > 64 && (uint64_t)block * cus * 3 / 4 > B) block >>= 1;  // a few idle CUs beat half-size workgroups
+  return block;
+}
 constexpr size_t kMaxCountingLds = 128 * 1024;  // histograms of a counting forward workgroup (one workgroup per CU)
 
 // Levels whose outputs fill one store: 16 bytes, or one level when a level's F outputs are wider.
@@ -152,7 +168,7 @@ __global__ __launch_bounds__(kPmBlock) void fwd_point_major(const LevelTable lv,
     for (uint32_t i = threadIdx.x; i < kTiles * ca.n_bins; i += kPmBlock) hist[i] = 0;
     __syncthreads();
   }
-  const uint32_t b0 = blockIdx.x * kPmBlock + threadIdx.x;
+  const uint32_t b0 = blockIdx.x * blockDim.x + threadIdx.x;  // blockDim.x = kPmBlock with COUNT
   const bool valid = b0 < B;
   const uint32_t b = valid ? b0 : B - 1;  // idle lanes of the last workgroup shadow the last point
   float xp[D];
@@ -231,7 +247,7 @@ __global__ __launch_bounds__(kPmBlock) void bwd_input_point_major(const LevelTab
                                                                   const IT* __restrict__ dy, float* __restrict__ dx) {
   using Piece = OutPiece<F, IT>;
   constexpr int G = Piece::kLevels;
-  const uint32_t b0 = blockIdx.x * kPmBlock + threadIdx.x;
+  const uint32_t b0 = blockIdx.x * blockDim.x + threadIdx.x;
   const bool valid = b0 < B;
   const uint32_t b = valid ? b0 : B - 1;
   float xp[D];
@@ -447,13 +463,14 @@ static hg_status launch_fwd(const hashgrid* h, uint32_t B, const float* x, const
   {
     constexpr uint32_t G = OutPiece<F, IT>::kLevels;
     if (h->lv.L % G == 0 && !misaligned(y, 16) && !misaligned(params, F * sizeof(PT) > 16 ? 16 : F * sizeof(PT))) {
-      const dim3 grid((B + kPmBlock - 1) / kPmBlock);
+      const uint32_t block = point_major_block(B);
+      const dim3 grid((B + block - 1) / block);
       const bool smooth = h->cfg.interp == HG_INTERP_SMOOTHSTEP;
       if (h->lv.T_is_pow2)
-        hipLaunchKernelGGL((fwd_point_major<D, F, PT, IT, true, false>), grid, dim3(kPmBlock), 0, s, h->lv, smooth, B,
+        hipLaunchKernelGGL((fwd_point_major<D, F, PT, IT, true, false>), grid, dim3(block), 0, s, h->lv, smooth, B,
                            x, static_cast<const PT*>(params), static_cast<IT*>(y), NoCount{});
       else
-        hipLaunchKernelGGL((fwd_point_major<D, F, PT, IT, false, false>), grid, dim3(kPmBlock), 0, s, h->lv, smooth,
+        hipLaunchKernelGGL((fwd_point_major<D, F, PT, IT, false, false>), grid, dim3(block), 0, s, h->lv, smooth,
                            B, x, static_cast<const PT*>(params), static_cast<IT*>(y), NoCount{});
       return launched();
     }
@@ -471,13 +488,14 @@ static hg_status launch_bwd_input(const hashgrid* h, uint32_t B, const float* x,
   {
     constexpr uint32_t G = OutPiece<F, IT>::kLevels;
     if (h->lv.L % G == 0 && !misaligned(dy, 16) && !misaligned(params, F * sizeof(PT) > 16 ? 16 : F * sizeof(PT))) {
-      const dim3 pm_grid((B + kPmBlock - 1) / kPmBlock);
+      const uint32_t block = point_major_block(B);
+      const dim3 pm_grid((B + block - 1) / block);
       const bool smooth = h->cfg.interp == HG_INTERP_SMOOTHSTEP;
       if (h->lv.T_is_pow2)
-        hipLaunchKernelGGL((bwd_input_point_major<D, F, PT, IT, true>), pm_grid, dim3(kPmBlock), 0, s, h->lv, smooth,
+        hipLaunchKernelGGL((bwd_input_point_major<D, F, PT, IT, true>), pm_grid, dim3(block), 0, s, h->lv, smooth,
                            B, x, static_cast<const PT*>(params), static_cast<const IT*>(dy), dx);
       else
-        hipLaunchKernelGGL((bwd_input_point_major<D, F, PT, IT, false>), pm_grid, dim3(kPmBlock), 0, s, h->lv, smooth,
+        hipLaunchKernelGGL((bwd_input_point_major<D, F, PT, IT, false>), pm_grid, dim3(block), 0, s, h->lv, smooth,
                            B, x, static_cast<const PT*>(params), static_cast<const IT*>(dy), dx);
       return launched();
     }

@@ -30,6 +30,8 @@ struct hashgrid {
 
 namespace hg {
 void build_bin_plan(hashgrid* h);
+// hashgrid.hip: threads (= points) per workgroup of the point-major kernels for a batch of B points
+uint32_t point_major_block(uint32_t B);
 // hashgrid.hip: forward pass that also fills counts[n_tiles][n_bins] of the binned backward pass
 hg_status launch_fwd_counting(const hashgrid* h, uint32_t B, const float* x, const void* params, void* y,
                               uint32_t* counts, uint32_t n_bins, uint32_t n_tiles, hipStream_t s);

@@ -25,7 +25,7 @@
 
 namespace hg {
 
-constexpr int kMlpBlock = 1024;   // threads = points of a workgroup
+constexpr int kMlpBlock = 1024;   // threads = points of a workgroup, at most (fewer for small batches)
 constexpr int kHidden = 64;       // neurons of a hidden layer
 constexpr int kRowPad = 4;        // halves of padding per LDS row
 constexpr int kActStride = kHidden + kRowPad;
@@ -78,20 +78,21 @@ __global__ __launch_bounds__(kMlpBlock) void encode_mlp_fwd(const LevelTable lv,
   extern __shared__ _Float16 lds[];
   const int n_in = (int)lv.L * F;  // a multiple of 8, at most 64 (checked on the host)
   const int w1_stride = n_in + kRowPad;
-  _Float16* act = lds;                                // [kMlpBlock][kActStride]
-  _Float16* w1 = act + kMlpBlock * kActStride;        // [kHidden][n_in + pad]
+  const int block = (int)blockDim.x;
+  _Float16* act = lds;                                // [block][kActStride]
+  _Float16* w1 = act + block * kActStride;            // [kHidden][n_in + pad]
   _Float16* w2 = w1 + kHidden * w1_stride;            // [kHidden][kActStride]
   _Float16* w3 = w2 + kHidden * kActStride;           // [kMaxOut][kActStride], rows from n_out on are zero
 
   // weights -> LDS in 8-byte pieces (rows are multiples of four halves, host-checked alignment)
   {
     const int q1 = n_in / 4;  // pieces per row of W1
-    for (int i = threadIdx.x; i < kHidden * q1; i += kMlpBlock)
+    for (int i = threadIdx.x; i < kHidden * q1; i += block)
       *reinterpret_cast<half4*>(w1 + (i / q1) * w1_stride + 4 * (i % q1)) = reinterpret_cast<const half4*>(W1)[i];
     constexpr int q2 = kHidden / 4;
-    for (int i = threadIdx.x; i < kHidden * q2; i += kMlpBlock)
+    for (int i = threadIdx.x; i < kHidden * q2; i += block)
       *reinterpret_cast<half4*>(w2 + (i / q2) * kActStride + 4 * (i % q2)) = reinterpret_cast<const half4*>(W2)[i];
-    for (int i = threadIdx.x; i < kMaxOut * q2; i += kMlpBlock) {
+    for (int i = threadIdx.x; i < kMaxOut * q2; i += block) {
       half4 v = {(_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f};
       if ((uint32_t)(i / q2) < n_out) v = reinterpret_cast<const half4*>(W3)[i];
       *reinterpret_cast<half4*>(w3 + (i / q2) * kActStride + 4 * (i % q2)) = v;
@@ -99,7 +100,7 @@ __global__ __launch_bounds__(kMlpBlock) void encode_mlp_fwd(const LevelTable lv,
   }
 
   // the encoding, as in the forward kernel: one thread per point, level by level
-  const uint32_t b0 = blockIdx.x * kMlpBlock + threadIdx.x;
+  const uint32_t b0 = blockIdx.x * block + threadIdx.x;
   const uint32_t b = b0 < B ? b0 : B - 1;  // idle lanes of the last workgroup shadow the last point
   float xp[D];
 #pragma unroll
@@ -155,7 +156,7 @@ __global__ __launch_bounds__(kMlpBlock) void encode_mlp_fwd(const LevelTable lv,
 #pragma unroll
   for (int half = 0; half < 2; ++half) {
     const float16v o = block_product<kHidden>(w3, kActStride, 0, act, p0 + 32 * half);
-    const uint64_t point = (uint64_t)blockIdx.x * kMlpBlock + p0 + 32 * half + (lane & 31);
+    const uint64_t point = (uint64_t)blockIdx.x * block + p0 + 32 * half + (lane & 31);
     if (point < B) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
@@ -170,12 +171,13 @@ template <int D, int F>
 static hg_status launch_mlp(const hashgrid* h, uint32_t B, const float* x, const void* params, const void* W1,
                             const void* W2, const void* W3, uint32_t n_out, float* out, hipStream_t s) {
   const int n_in = (int)h->lv.L * F;
-  const size_t lds = ((size_t)kMlpBlock * kActStride + (size_t)kHidden * (n_in + kRowPad) +
+  const uint32_t block = point_major_block(B);
+  const size_t lds = ((size_t)block * kActStride + (size_t)kHidden * (n_in + kRowPad) +
                       (size_t)(kHidden + kMaxOut) * kActStride) * sizeof(_Float16);
   static const hipError_t lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(encode_mlp_fwd<D, F>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
   if (lds_ok != hipSuccess) return HG_ERR_DEVICE;
-  hipLaunchKernelGGL((encode_mlp_fwd<D, F>), dim3((B + kMlpBlock - 1) / kMlpBlock), dim3(kMlpBlock), lds, s, h->lv,
+  hipLaunchKernelGGL((encode_mlp_fwd<D, F>), dim3((B + block - 1) / block), dim3(block), lds, s, h->lv,
                      h->cfg.interp == HG_INTERP_SMOOTHSTEP, B, x, static_cast<const _Float16*>(params),
                      static_cast<const _Float16*>(W1), static_cast<const _Float16*>(W2),
                      static_cast<const _Float16*>(W3), n_out, out);
