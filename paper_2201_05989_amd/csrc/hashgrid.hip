@@ -116,10 +116,12 @@ __global__ __launch_bounds__(kBlock) void fwd_general(const LevelTable lv, const
 // keeps the 16 waves of a workgroup on the same slice, which holds the L2 hit
 // rate at that of the level-major grid.
 constexpr int kPmBlock = 1024;
-// A batch that does not fill every CU with a full workgroup is cut into smaller ones: the kernels
-// are bound by what one CU's texture path and L1 deliver, so 2^14 points in sixteen workgroups
-// take as long as 2^18 in 256.  (The counting variant always runs full workgroups: they cover
-// whole tiles of the backward pass.)
+// Threads (= points) per workgroup of the point-major kernels.  One workgroup's time does not
+// depend on how many others run - the kernels are bound by what one CU's texture path and L1
+// deliver - so 2^14 points in sixteen full workgroups take as long as 2^18 in 256, and 300 K points
+// in 293 as long as 2^19.  The batch is therefore spread evenly: k = number of rounds the batch
+// needs at full size, then B / (k * CUs) points per workgroup, rounded up to whole waves.  (The
+// counting variant always runs full workgroups: they cover whole tiles of the backward pass.)
 uint32_t point_major_block(uint32_t B) {
   static const uint32_t cus = [] {
     int dev = 0, n = 0;
@@ -128,9 +130,11 @@ uint32_t point_major_block(uint32_t B) {
       n = 256;
     return (uint32_t)n;
   }();
-  uint32_t block = kPmBlock;
-  while (block > 64 && (uint64_t)block * cus * 3 / 4 > B) block >>= 1;  // a few idle CUs beat half-size workgroups
-  return block;
+  const uint64_t per_round = (uint64_t)kPmBlock * cus;
+  const uint64_t rounds = (B + per_round - 1) / per_round;
+  const uint64_t per_wg = (B + rounds * cus - 1) / (rounds * cus);
+  const uint32_t block = (uint32_t)((per_wg + 63) / 64 * 64);
+  return block < 64 ? 64 : (block > (uint32_t)kPmBlock ? (uint32_t)kPmBlock : block);
 }
 constexpr size_t kMaxCountingLds = 128 * 1024;  // histograms of a counting forward workgroup (one workgroup per CU)
 
