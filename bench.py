@@ -94,8 +94,19 @@ def cpu_baseline(w, x, theta, dy, budget_s=10.0):
         el = time.perf_counter() - t0
         if el >= budget_s or reps >= 1024:
             break
-    return {"value": nb * reps / el / 1e6, "unit": "Mpoints/s", "cores": orc.num_threads(), "kind": "oracle",
-            "sample": f"{reps} fwd+bwd passes over the first {nb} points of the workload, {el:.1f} s"}
+    cores = orc.num_threads()
+    # one core, on a smaller sample of the same points (a few seconds)
+    n1 = min(nb, 1 << 15)
+    orc.set_num_threads(1)
+    t1 = time.perf_counter()
+    orc.encode_fwd(cfg, xs[:n1], th)
+    orc.encode_bwd(cfg, xs[:n1], dys[:n1])
+    el1 = time.perf_counter() - t1
+    orc.set_num_threads(cores)
+    return {"value": nb * reps / el / 1e6, "unit": "Mpoints/s", "cores": cores, "kind": "oracle",
+            "sample": f"{reps} fwd+bwd passes over the first {nb} points of the workload, {el:.1f} s",
+            "one_core_value": n1 / el1 / 1e6,
+            "one_core_sample": f"1 fwd+bwd pass over the first {n1} points, {el1:.1f} s"}
 
 
 def main():

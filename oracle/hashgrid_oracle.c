@@ -86,6 +86,15 @@ int hgo_num_threads(void) {
 #endif
 }
 
+/* Threads the following calls may use (timing on one core next to all cores); no effect on results. */
+void hgo_set_num_threads(int n) {
+#ifdef _OPENMP
+  if (n >= 1) omp_set_num_threads(n);
+#else
+  (void)n;
+#endif
+}
+
 /* Eq. 2-3 and the dense criterion of Section 3.  Returns 0, or -1 on a bad config. */
 int hgo_levels(const hgo_config* c, hgo_levels_t* out) {
   if (!c || !out) return -1;

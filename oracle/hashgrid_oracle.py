@@ -62,6 +62,8 @@ def _load():
         vp, u64, u32 = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32
         cfgp = ctypes.POINTER(_Config)
         lib.hgo_num_threads.restype = ctypes.c_int
+        lib.hgo_set_num_threads.argtypes = [ctypes.c_int]
+        lib.hgo_set_num_threads.restype = None
         lib.hgo_levels.argtypes = [cfgp, ctypes.POINTER(_Levels)]
         lib.hgo_index.argtypes = [u32, u32, u32, ctypes.c_int, vp]
         lib.hgo_index.restype = u32
@@ -103,6 +105,11 @@ class OracleConfig:
 
 def num_threads() -> int:
     return int(_load().hgo_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    """Threads the following calls may use (for timing on one core); results do not depend on it."""
+    _load().hgo_set_num_threads(int(n))
 
 
 def levels(cfg: OracleConfig) -> LevelTable:
