@@ -121,7 +121,9 @@ uint64_t hashgrid_bwd_workspace_bytes(const hashgrid_t* hg, uint32_t B);
 
 /* 1 when hashgrid_encode_bwd_ws serves this configuration and batch and is expected to be the
  * faster of the two backward passes, else 0: it visits every chunk of the gradient whatever the
- * batch, so below some ten thousand points (at Table 1's sizes) the atomic pass wins. */
+ * batch, so below some ten thousand points (at Table 1's sizes) the atomic pass wins, except
+ * where a level is so small that the atomic requests of the batch queue up on a few of its
+ * entries (a host-side estimate from sizes alone; points are taken as evenly spread). */
 int hashgrid_bwd_ws_pays(const hashgrid_t* hg, uint32_t B);
 
 /* Backward pass to the tables, same result as hashgrid_encode_bwd (Fig. 3

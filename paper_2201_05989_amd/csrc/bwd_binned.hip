@@ -958,11 +958,20 @@ uint64_t hashgrid_bwd_workspace_bytes(const hashgrid_t* hg, uint32_t B) {
 
 int hashgrid_bwd_ws_pays(const hashgrid_t* hg, uint32_t B) {
   if (hashgrid_bwd_workspace_bytes(hg, B) == 0) return 0;
-  // Measured on an MI355X: the sorted pass costs about 20 us of launches plus 0.027 us per chunk
-  // (every chunk of the gradient is visited) and then ~200 K corner pairs per us; the atomic pass
-  // about 13 K pairs per us from the first pair on.
-  const uint64_t pairs = (uint64_t)B * hg->lv.L * hg->bp.rec_per_point;
-  return pairs > 258000ull + 348ull * hg->bp.bin_base[hg->lv.L] ? 1 : 0;
+  // Both passes in microseconds, from measurements on an MI355X.  Sorted pass: about 20 us of
+  // launches, 0.027 us per chunk (every chunk of the gradient is visited), then ~300 K corner pairs
+  // per us.  Atomic pass: ~6 us, then ~14.5 K pairs per us, unless one 64-byte block of the gradient
+  // draws so many requests that they queue up behind each other (~0.02 us each): the smallest level
+  // decides that, taking the points as spread evenly over its entries.
+  const double pairs = (double)B * hg->lv.L * hg->bp.rec_per_point;
+  double per_block = 0.0;
+  for (uint32_t l = 0; l < hg->lv.L; ++l) {
+    const double blocks = ceil((double)hg->lv.size[l] * hg->cfg.F * sizeof(float) / 64.0);
+    per_block = fmax(per_block, (double)B * hg->bp.rec_per_point / blocks);
+  }
+  const double sorted_us = 20.0 + 0.027 * hg->bp.bin_base[hg->lv.L] + pairs / 300e3;
+  const double atomic_us = 6.0 + fmax(pairs / 14.5e3, 0.02 * per_block);
+  return atomic_us > sorted_us ? 1 : 0;
 }
 
 // shared argument checks of the two entry points that take the scratch buffer

@@ -131,3 +131,17 @@ def test_encode_mlp_status_codes_need_no_device():
     assert lib.hashgrid_encode_mlp_fwd(g._h, 8, 4096, 4096, 4096, 4096, 4096, 0, 4096, None) == 1
     assert lib.hashgrid_encode_mlp_fwd(g._h, 8, None, 4096, 4096, 4096, 4096, 1, 4096, None) == 1
     assert lib.hashgrid_encode_mlp_fwd(g._h, 0, None, None, None, None, None, 1, None, None) == 0
+
+
+def test_choice_between_the_backward_passes_needs_no_device():
+    """hashgrid_bwd_ws_pays is host arithmetic on sizes: the sort for large batches, atomics for small
+    ones, and the sort again where a small batch would queue its atomics on a handful of entries."""
+    table1 = binding.HashGrid(3, 16, 2, 1 << 19, 16, 2048)
+    assert not table1.bwd_ws_pays(1024) and not table1.bwd_ws_pays(4096)
+    assert table1.bwd_ws_pays(1 << 14) and table1.bwd_ws_pays(1 << 18)
+    small_levels = binding.HashGrid(2, 4, 2, 1 << 10, 4, 32, "f32", "f32")  # level 0 has 25 entries
+    assert not small_levels.bwd_ws_pays(512) and small_levels.bwd_ws_pays(4096)
+    assert not binding.HashGrid(3, 16, 2, 1000003, 16, 2048).bwd_ws_pays(1 << 20)  # not served: T not 2^k
+    for grid in (table1, small_levels):  # once it pays it keeps paying
+        flags = [grid.bwd_ws_pays(1 << k) for k in range(6, 22)]
+        assert flags == sorted(flags)
