@@ -116,7 +116,8 @@ hg_status hashgrid_encode_bwd(const hashgrid_t* hg, uint32_t B, const float* x, 
  * 4096, or 2048, entries per level), at most 4096 (2048) vertices per axis on 1:1 levels
  * and B*L*2^(d-1) < 2^32).  The buffer holds 8 + F * sizeof(dLdy scalar) bytes (rounded up
  * to 4) per pair of corners, B*L*2^(d-1) of them, plus 4 bytes per (tile of 512 points,
- * chunk): 195 MiB at Table 1's sizes with 2^18 points, 2.3 GiB at T = 2^24 with 2^21. */
+ * chunk), tiles of 4096 points where there are more than 16384 chunks in all: 195 MiB at
+ * Table 1's sizes with 2^18 points, 1.6 GiB at T = 2^24 with 2^21. */
 uint64_t hashgrid_bwd_workspace_bytes(const hashgrid_t* hg, uint32_t B);
 
 /* 1 when hashgrid_encode_bwd_ws serves this configuration and batch and is expected to be the

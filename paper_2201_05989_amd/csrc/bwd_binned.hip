@@ -57,6 +57,9 @@ constexpr uint32_t kCountParts = 2;              // ... of the count grid (its w
 // Level parts are doubled (up to one level per part) until one part's bins fit these bounds: a count
 // workgroup keeps one LDS word per bin of its part, a scatter workgroup three, next to its staging area.
 constexpr uint32_t kMaxCountPartBins = 4096, kMaxScatterPartBins = 4096;
+// Beyond this many chunks in all, a tile is kBigTileMult * 512 points and the scatter pass does not
+// stage (bin_scatter_direct, one LDS word per bin of its part).
+constexpr uint32_t kMaxStagedBins = 16384, kBigTileMult = 8, kMaxDirectPartBins = 8192;
 // A level may have this many chunks (one level is the smallest part): T up to 2^24 at 4096 entries per chunk.
 constexpr uint32_t kMaxLevelBins = 4096;
 
@@ -139,10 +142,14 @@ struct Workspace {
 
 static inline uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 
-static uint32_t tiles_for(uint32_t B) { return (B + kBinThreads - 1) / kBinThreads; }  // one workgroup each
+// one count / scatter workgroup per tile and level part
+static uint32_t tiles_for(const BinPlan& bp, uint32_t B) {
+  const uint32_t points = kBinThreads * bp.tile_mult;
+  return (uint32_t)(((uint64_t)B + points - 1) / points);
+}
 
 static uint64_t carve(const hashgrid* h, uint32_t B, uint8_t* base, Workspace* ws) {
-  const uint32_t nt = tiles_for(B), nb = h->bp.bin_base[h->lv.L];
+  const uint32_t nt = tiles_for(h->bp, B), nb = h->bp.bin_base[h->lv.L];
   uint64_t off = 0;
   auto take = [&](uint64_t bytes) {
     uint64_t o = off;
@@ -216,7 +223,11 @@ void build_bin_plan(hashgrid* h) {
     return max_part_bins(np) <= limit ? np : 0u;
   };
   bp.count_parts = parts_for(kCountParts, kMaxCountPartBins);
-  bp.scatter_parts = parts_for(kMaxParts, kMaxScatterPartBins);
+  // With very many chunks a tile of 512 points leaves less than a record per chunk and level: the
+  // per-chunk work of every count / scatter workgroup (and the count table) then outweighs the
+  // records, and staging them for whole-line writes gains nothing.  Larger tiles, no staging.
+  bp.tile_mult = bins > kMaxStagedBins ? kBigTileMult : 1u;
+  bp.scatter_parts = bp.tile_mult > 1 ? parts_for(kMaxParts, kMaxDirectPartBins) : parts_for(kMaxParts, kMaxScatterPartBins);
   if (!bp.count_parts || !bp.scatter_parts) return;
   bp.supported = 1;
 }
@@ -319,8 +330,9 @@ __global__ __launch_bounds__(kBinThreads) void bin_count(const LevelTable lv, co
   const uint32_t gb_a = bp.bin_base[l0], nbp = bp.bin_base[l1] - gb_a;
   for (uint32_t i = threadIdx.x; i < nbp; i += kBinThreads) hist[i] = 0;
   __syncthreads();
-  const uint64_t b64 = (uint64_t)tile * kBinThreads + threadIdx.x;
-  if (b64 < B) {
+  for (uint32_t sub = 0; sub < bp.tile_mult; ++sub) {
+    const uint64_t b64 = ((uint64_t)tile * bp.tile_mult + sub) * kBinThreads + threadIdx.x;
+    if (b64 >= B) break;
     const uint32_t b = (uint32_t)b64;
     float xp[D];
     load_x<D>(x, b, xp);
@@ -576,6 +588,97 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, 
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) gmax = nan_max(gmax, __shfl_xor(gmax, o));
   float* wave_max = reinterpret_cast<float*>(scan_tmp);  // free since the prologue
+  if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = gmax;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float t = wave_max[0];
+    for (int i = 1; i < kBinThreads / 64; ++i) t = nan_max(t, wave_max[i]);
+    tile_max[tile * gridDim.y + blockIdx.y] = t;
+  }
+}
+
+// scatter without staging, for plans of very many bins (BinPlan::tile_mult > 1): a tile is
+// tile_mult * 512 points, which the workgroup walks 512 at a time, and every record goes
+// straight to its slot.  The runs a tile writes are a few records long at best, so sorting them
+// in LDS first would not make whole lines of them; what merges partial lines here is the L2,
+// which keeps the tile's open runs (a few bytes per bin of the part) while the workgroup lasts.
+// LDS: slot[nbp], the next free record slot of each bin of this part for this tile.
+template <int D, typename IT, int F>
+__global__ __launch_bounds__(kBinThreads) void bin_scatter_direct(
+    const LevelTable lv, const BinPlan bp, const bool smooth, const uint32_t B, const float* __restrict__ x,
+    const IT* __restrict__ dy, const uint32_t* __restrict__ counts, const uint32_t* __restrict__ bin_total,
+    uint32_t* __restrict__ bin_start, uint32_t* __restrict__ records, const uint32_t n_bins, const uint32_t n_records,
+    const uint32_t n_tiles, float* __restrict__ tile_max, float* __restrict__ grad) {
+  constexpr uint32_t R = 1u << (D - 1);
+  using Rec = Record<IT, F>;
+  using Stored = typename Rec::Stored;
+  Stored* out = reinterpret_cast<Stored*>(records);
+  __shared__ uint32_t scan_tmp[kBinThreads / 64];
+  extern __shared__ uint32_t slot[];
+
+  const uint32_t tile = tile_of_workgroup(blockIdx.x, n_tiles);
+  if (tile >= n_tiles) return;  // uniform: a surplus workgroup of the rounded-up grid
+  uint32_t l0, l1;
+  part_levels(lv.L, l0, l1);
+  const uint32_t gb_a = bp.bin_base[l0], nbp = bp.bin_base[l1] - gb_a;
+
+  // first record of each bin = records of all bins before it; then the records of the tiles before this one
+  uint32_t before = 0;
+  for (uint32_t i = threadIdx.x; i < gb_a; i += kBinThreads) before += bin_total[i];
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) before += __shfl_xor(before, o);
+  if ((threadIdx.x & 63) == 0) scan_tmp[threadIdx.x >> 6] = before;
+  for (uint32_t i = threadIdx.x; i < nbp; i += kBinThreads) slot[i] = bin_total[gb_a + i];
+  __syncthreads();
+  before = 0;
+  for (int i = 0; i < kBinThreads / 64; ++i) before += scan_tmp[i];
+  __syncthreads();
+  block_exclusive_scan<kBinThreads>(slot, nbp, scan_tmp);
+  const uint32_t* row0 = counts + (uint64_t)tile * n_bins + gb_a;  // prefix over the tiles before this one
+  for (uint32_t i = threadIdx.x; i < nbp; i += kBinThreads) {
+    const uint32_t f = before + slot[i];
+    if (tile == 0) bin_start[gb_a + i] = f;
+    slot[i] = f + row0[i];
+  }
+  __syncthreads();
+
+  float gmax = 0.0f;  // largest |dL/dy| this workgroup sees
+  for (uint32_t sub = 0; sub < bp.tile_mult; ++sub) {
+    const uint64_t b64 = ((uint64_t)tile * bp.tile_mult + sub) * kBinThreads + threadIdx.x;
+    if (b64 >= B) break;  // no barrier inside this loop
+    const uint32_t b = (uint32_t)b64;
+    float xp[D];
+    load_x<D>(x, b, xp);
+    const IT* row = dy + (uint64_t)b * lv.L * F;
+    for (uint32_t l = l0; l < l1; ++l) {
+      IT g[F];
+      float gf[F];
+#pragma unroll
+      for (int f = 0; f < F; ++f) {
+        g[f] = row[(uint64_t)l * F + f];
+        gf[f] = (float)g[f];
+        gmax = nan_max(gmax, fabsf(gf[f]));
+      }
+      Rows<D> rw;
+      rows_of<D, false>(lv, bp, l, smooth, xp, rw);
+      if (rw.cross) {
+        add_crossing_pairs<D, F>(lv, l, smooth, xp, gf, grad);
+        continue;
+      }
+#pragma unroll
+      for (uint32_t r = 0; r < R; ++r) {
+        const uint32_t d =
+            __hip_atomic_fetch_add(&slot[rw.bin[r] - gb_a], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        // the count pass saw the same inputs, so d < n_records; the check only keeps a caller
+        // who changed x in between from writing out of bounds
+        if (d < n_records) out[d] = Rec::make(rw.la[r], rw.k, rw.wf0, rw.wrow[r], g);
+      }
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) gmax = nan_max(gmax, __shfl_xor(gmax, o));
+  __syncthreads();  // scan_tmp is free again
+  float* wave_max = reinterpret_cast<float*>(scan_tmp);
   if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = gmax;
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -911,9 +1014,15 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
   if (!counted && launch_count(h, B, x, ws, s) != HG_OK) return HG_ERR_DEVICE;
   hipLaunchKernelGGL(bin_scan, dim3((ws.n_bins + kScanBins - 1) / kScanBins), dim3(kScanThreads), 0, s, ws.n_tiles,
                      ws.n_bins, ws.counts, ws.bin_total, ws.item_counter);
-  hipLaunchKernelGGL((bin_scatter<D, IT, F>), dim3(tile_wgs, parts), dim3(kBinThreads), lds_scatter, s, h->lv, bp,
-                     smooth, B, x, static_cast<const IT*>(dy), ws.counts, ws.bin_total, ws.bin_start,
-                     ws.records, ws.n_bins, n_records, ws.n_tiles, ws.tile_max, grad);
+  if (bp.tile_mult > 1)
+    hipLaunchKernelGGL((bin_scatter_direct<D, IT, F>), dim3(tile_wgs, parts), dim3(kBinThreads),
+                       (size_t)max_part_bins(parts) * 4, s, h->lv, bp, smooth, B, x, static_cast<const IT*>(dy),
+                       ws.counts, ws.bin_total, ws.bin_start, ws.records, ws.n_bins, n_records, ws.n_tiles,
+                       ws.tile_max, grad);
+  else
+    hipLaunchKernelGGL((bin_scatter<D, IT, F>), dim3(tile_wgs, parts), dim3(kBinThreads), lds_scatter, s, h->lv, bp,
+                       smooth, B, x, static_cast<const IT*>(dy), ws.counts, ws.bin_total, ws.bin_start,
+                       ws.records, ws.n_bins, n_records, ws.n_tiles, ws.tile_max, grad);
   const uint32_t n_items = bp.wg_base[h->lv.L];
   static const uint32_t acc_slots = [] {  // its registers let one 1024-thread workgroup run per CU; more would queue
     int dev = 0, cus = 0;

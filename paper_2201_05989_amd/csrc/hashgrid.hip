@@ -531,7 +531,7 @@ static hg_status launch_fwd_counting_t(const hashgrid* h, uint32_t B, const floa
   constexpr uint32_t G = OutPiece<F, IT>::kLevels;
   const size_t lds = (size_t)(kPmBlock / kBinThreads) * n_bins * 4;
   if (h->lv.L % G != 0 || misaligned(y, 16) || misaligned(params, F * sizeof(PT) > 16 ? 16 : F * sizeof(PT)) ||
-      !h->lv.T_is_pow2 || lds > kMaxCountingLds)
+      !h->lv.T_is_pow2 || lds > kMaxCountingLds || h->bp.tile_mult != 1)  // (its tiles are 512 points)
     return HG_ERR_UNSUPPORTED;
   if (lds > 64 * 1024) {  // more dynamic LDS than the default limit: opt in once per kernel
     static const hipError_t lds_ok =

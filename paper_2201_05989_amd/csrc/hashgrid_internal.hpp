@@ -16,6 +16,7 @@ struct BinPlan {
   uint32_t chunk_log2;                   // log2 of the entries a chunk can hold
   uint32_t rec_per_point;                // records per (point, level): 2^(d-1)
   uint32_t count_parts, scatter_parts;   // level parts (gridDim.y) of the count and scatter grids
+  uint32_t tile_mult;                    // a tile of the sort = tile_mult * 512 points; above 1: no staging (bin_scatter_direct)
   uint32_t supported;                    // 0: configuration not served by the binned path
 };
 

@@ -187,18 +187,24 @@ def test_large3d_full_size_sampled_forward_and_prefix_backward():
     rows = np.random.default_rng(0).choice(w.B, 1 << 16, replace=False)
     rows.sort()
     check_fwd(y[rows], orc.encode_fwd(cfg, x[rows], theta), 1.0, w.io_dtype)
-    nb = 1 << 18
+    nb = 260000  # ends inside a tile of the sorted pass (here 4096 points) and inside one of its 512-point steps
     xs, dys = x[:nb], dy[:nb]
     g_ref = orc.encode_bwd(cfg, xs, dys)
     g_abs = orc.encode_bwd(cfg, xs, np.abs(dys.astype(np.float64)))
     g = grid.encode_bwd(dev(xs), dev(dys), use_workspace=False).cpu().numpy()  # atomics
     check_bwd(g, g_ref, g_abs)
     del g
-    # the sorted pass: 49 K chunks, less than one pair of corners per tile and chunk
+    # the sorted pass: 49 K chunks, so it takes tiles of 4096 points and writes its records unstaged
     assert grid.bwd_workspace_bytes(nb) > 0
     floor = ws_floor(dys, nb) + 2.0 ** -23 * corner_abs_sum(cfg, lv, xs, dys)
     g = grid.encode_bwd(dev(xs), dev(dys), use_workspace=True).cpu().numpy()
     check_bwd(g, g_ref, g_abs, floor)
+    del g, g_ref, g_abs
+    # a batch smaller than one tile, against the atomic pass (checked above)
+    few = 300
+    ga = grid.encode_bwd(dev(x[:few]), dev(dy[:few]), use_workspace=False)
+    gb = grid.encode_bwd(dev(x[:few]), dev(dy[:few]), use_workspace=True)
+    torch.testing.assert_close(gb, ga, rtol=1e-5, atol=1e-5 * float(ga.abs().max()))
 
 
 SWEEP = [
@@ -298,6 +304,23 @@ def test_workspace_backward_when_pairs_straddle_two_chunks(d, iot):
     theta = synth.make_tables(rng, lv.total, F, "f16", 1.0)
     dy = synth.make_dy(rng, B, L * F, iot)
     grid = run_case(d, L, F, T, N_min, N_max, "f16", iot, 0, x, theta, dy, do_dx=False)
+    assert grid.bwd_workspace_bytes(B) > 0
+
+
+@pytest.mark.parametrize("d,F,iot,interp,B", [(2, 1, "f32", 1, 9000), (3, 2, "f16", 0, 4096 + 513)])
+def test_workspace_backward_with_very_many_chunks(d, F, iot, interp, B):
+    # more than 16 K chunks in all: the sorted pass takes tiles of 4096 points and writes its records
+    # unstaged.  Five hashed levels of 2^24 entries, resolutions of 4096 and more (pairs that straddle
+    # two chunks occur too); the batch ends inside a tile and inside one of its 512-point steps.
+    L, T, N_min, N_max = 5, 1 << 24, 8192, 65536
+    lv = orc.levels(orc.OracleConfig(d, L, F, T, N_min, N_max, interp))
+    assert not lv.dense.any()
+    rng = np.random.default_rng(78)
+    x = synth.points_uniform(rng, B, d)
+    x[: B // 4, 0] = ((4095.75 + 4096.0 * rng.integers(0, 2, B // 4)) / 8192.0).astype(np.float32)
+    theta = synth.make_tables(rng, lv.total, F, "f16", 1.0)
+    dy = synth.make_dy(rng, B, L * F, iot)
+    grid = run_case(d, L, F, T, N_min, N_max, "f16", iot, interp, x, theta, dy, do_dx=False, do_indices=False)
     assert grid.bwd_workspace_bytes(B) > 0
 
 
