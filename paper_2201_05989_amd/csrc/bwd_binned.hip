@@ -738,6 +738,7 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
   const int H = 3 + (32 - __builtin_clz(B > 1 ? B - 1 : 1));
   const int S = (62 - H < kFixedBits ? 62 - H : kFixedBits) - E;  // |summand| * 2^S < 2^min(62-H, 51)
   const double scale = ldexp(1.0, S), inv_scale = ldexp(1.0, -S);
+  const uint32_t n_records = B * lv.L * bp.rec_per_point;  // < 2^32 (hashgrid_bwd_workspace_bytes)
   constexpr int kPer = (int)cap / kAccThreads;  // entries per lane
   struct alignas(F * 4 > 16 ? 16 : F * 4) Entry {
     float v[F];
@@ -783,6 +784,10 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
     const uint32_t per = (total + it.n_sl - 1) / it.n_sl;
     it.r0 = start + slice * per;
     it.r1 = (slice * per + per < total) ? it.r0 + per : start + total;
+    // true for counts that belong to these points; keeps a caller who passed HG_BWD_COUNTED over
+    // the counts of another batch from reading outside the records
+    it.r0 = it.r0 < n_records ? it.r0 : n_records;
+    it.r1 = it.r1 < n_records ? it.r1 : n_records;
     it.live = item < n_items && slice * per < total;
     uint32_t e0, e1;  // entries of this chunk in the level's slice
     it.dense = (lv.dense_mask >> l) & 1u;
