@@ -265,6 +265,29 @@ def test_random_configurations(seed):
     run_case(d, L, F, T, N_min, N_max, pdt, iot, interp, x, theta, dy)
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_random_larger_configurations(seed):
+    # seeded draws with batches of many tiles (5 K to 150 K points, uniform or near a surface), tables
+    # of up to 2^21 entries per level and up to 16 levels: the sorted backward pass with several
+    # slices per chunk, level parts and ragged last tiles, against the oracle
+    rng = np.random.default_rng(9000 + seed)
+    d = int(rng.integers(2, 4))
+    F = int(rng.choice([1, 2, 4, 8]))
+    L = int(rng.choice([2, 4, 8, 16]))
+    T = 1 << int(rng.integers(10, 22))
+    N_min = int(rng.integers(2, 40))
+    N_max = int(N_min * rng.choice([2, 16, 128, 1000]) + rng.integers(0, 5))
+    pdt, iot = (str(rng.choice(["f16", "f32"])) for _ in range(2))
+    interp = int(rng.integers(0, 2))
+    B = int(rng.integers(5000, 150000))
+    lv = orc.levels(orc.OracleConfig(d, L, F, T, N_min, N_max, interp))
+    kind = str(rng.choice(["uniform", "sdf"])) if d == 3 else "uniform"
+    x = synth.points_uniform(rng, B, d) if kind == "uniform" else synth.points_sdf(rng, B)
+    theta = synth.make_tables(rng, lv.total, F, pdt, 1.0)
+    dy = synth.make_dy(rng, B, L * F, iot)
+    run_case(d, L, F, T, N_min, N_max, pdt, iot, interp, x, theta, dy, do_indices=False)
+
+
 def test_edge_positions_and_grid_vertices():
     # exact 0, the largest fp32 below 1, grid vertices of every level and their fp32 neighbours
     d, L, F, T, N_min, N_max = 3, 8, 2, 1 << 12, 4, 512
