@@ -183,6 +183,16 @@ def main():
     ms_bwd = sum(eb.elapsed_time(ec) for _, eb, ec in marks) / n
     ms_zero = time_launches(lambda: grad.zero_(), 20, torch)
 
+    # the same step when the backward pass replaces the gradient instead of adding to it
+    # (HG_BWD_OVERWRITE: no clearing pass before it, no reading of the old values in it)
+    def step_overwrite():
+        fwd_counting()
+        grid.encode_bwd(xd, gd, grad, overwrite=True)
+
+    ms_bwd_ow = time_launches(lambda: grid.encode_bwd(xd, gd, grad, overwrite=True), n, torch)
+    ms_step_ow = time_launches(step_overwrite, n, torch)
+    grad.zero_()
+
     # next row of the path: the optimiser step on the tables (fp32 master + fp16 working copy,
     # clears the gradient).  Timed as (backward + optimiser) minus backward, because the step
     # skips entries whose gradient is zero and clears the ones it uses.
@@ -243,6 +253,7 @@ def main():
         "bwd_mpoints_s": w.B / (ms_bwd * 1e-3) / 1e6,
         "ms_fwd": ms_fwd, "ms_bwd": ms_bwd, "ms_grad_zero": ms_zero,
         "ms_fwd_alone": ms_fwd_alone, "ms_bwd_alone": ms_bwd_alone,
+        "overwrite": {"ms_bwd_alone": ms_bwd_ow, "ms_step": ms_step_ow, "mpoints_s": w.B / (ms_step_ow * 1e-3) / 1e6},
         "adam": {"ms": ms_adam, "scalars": n_scalars, "algorithmic_bytes": adam_bytes,
                  "achieved_gb_s": adam_bytes / (ms_adam * 1e-3) / 1e9 if ms_adam > 0 else None,
                  "train_step_ms": ms_fwd + ms_bwd + ms_adam,

@@ -59,7 +59,8 @@ typedef enum {
 } hg_interp;
 
 typedef enum {
-  HG_BWD_COUNTED = 1 /* the workspace already holds the counts of these points (hashgrid_encode_fwd_ws) */
+  HG_BWD_COUNTED = 1,  /* the workspace already holds the counts of these points (hashgrid_encode_fwd_ws) */
+  HG_BWD_OVERWRITE = 2 /* grad_params = the gradient of this batch, not += (no need to clear it first)   */
 } hg_bwd_flags;
 
 typedef struct {
@@ -142,8 +143,11 @@ int hashgrid_bwd_ws_pays(const hashgrid_t* hg, uint32_t B);
  *              bytes, owned by the caller; contents are scratch: undefined on
  *              entry and on exit.  Calls that overlap in time need separate
  *              workspaces.
- *   flags      0, or HG_BWD_COUNTED when hashgrid_encode_fwd_ws has just run on the same hg,
- *              B, x and workspace (see there).
+ *   flags      0, or any of: HG_BWD_COUNTED when hashgrid_encode_fwd_ws has just run on the same
+ *              hg, B, x and workspace (see there); HG_BWD_OVERWRITE to have every entry of
+ *              grad_params written with what the call without this flag leaves in a buffer of
+ *              zeros (untouched entries become 0), which spares the caller the clearing pass
+ *              and this call the reading of the old values.
  * Returns HG_ERR_UNSUPPORTED when hashgrid_bwd_workspace_bytes is 0 and
  * HG_ERR_INVALID_ARG when the buffer is missing, misaligned or too small or a flag is
  * unknown.  x and dLdy must not be written while the call is in flight. */

@@ -20,6 +20,7 @@ HG_F32, HG_F16 = 0, 1
 HG_INTERP_LINEAR, HG_INTERP_SMOOTHSTEP = 0, 1
 HG_MAX_LEVELS = 32
 HG_BWD_COUNTED = 1
+HG_BWD_OVERWRITE = 2
 HG_ERR_UNSUPPORTED = 2
 
 _DTYPES = {"f32": HG_F32, "f16": HG_F16, torch.float32: HG_F32, torch.float16: HG_F16}
@@ -203,12 +204,16 @@ class HashGrid:
         return int(self._lib.hashgrid_bwd_workspace_bytes(self._h, B))
 
     def encode_bwd(self, x: torch.Tensor, dLdy: torch.Tensor, grad_params: torch.Tensor | None = None,
-                   stream=None, workspace: torch.Tensor | None = None, use_workspace: bool | None = None):
+                   stream=None, workspace: torch.Tensor | None = None, use_workspace: bool | None = None,
+                   overwrite: bool = False):
         """hashgrid_encode_bwd_ws (the scratch buffer is `workspace` or one kept on this object) or
         hashgrid_encode_bwd.  use_workspace: True = the former wherever the configuration is served
-        by it, False = the latter, None = whichever hashgrid_bwd_ws_pays expects to be faster."""
+        by it, False = the latter, None = whichever hashgrid_bwd_ws_pays expects to be faster.
+        overwrite: grad_params becomes the gradient of this batch instead of growing by it
+        (HG_BWD_OVERWRITE; where the atomic pass runs, the buffer is cleared on the stream first)."""
         B = x.shape[0]
-        if grad_params is None:
+        fresh = grad_params is None
+        if fresh:
             grad_params = torch.zeros((self.n_entries, self.F), dtype=torch.float32, device=x.device)
         if use_workspace is None:
             use_workspace = self._counted is not None or self.bwd_ws_pays(B)
@@ -218,6 +223,8 @@ class HashGrid:
             if workspace is None:
                 workspace = self._workspace(need, x.device)
             flags = HG_BWD_COUNTED if counted == (x.data_ptr(), B, workspace.data_ptr()) else 0
+            if overwrite and not fresh:
+                flags |= HG_BWD_OVERWRITE
             _check(self._lib.hashgrid_encode_bwd_ws(
                 self._h, B, _dev(x, torch.float32, (B, self.d), "x"),
                 _dev(dLdy, self.io_dtype, (B, self.L * self.F), "dLdy"),
@@ -225,6 +232,10 @@ class HashGrid:
                 workspace.data_ptr(), workspace.numel() * workspace.element_size(), flags, _stream_ptr(stream)),
                 "hashgrid_encode_bwd_ws")
             return grad_params
+        if overwrite and not fresh:  # the atomic pass only adds: clear first, on the same stream
+            _dev(grad_params, torch.float32, (self.n_entries, self.F), "grad_params")
+            with torch.cuda.stream(torch.cuda.current_stream() if stream is None else stream):
+                grad_params.zero_()
         _check(self._lib.hashgrid_encode_bwd(
             self._h, B, _dev(x, torch.float32, (B, self.d), "x"),
             _dev(dLdy, self.io_dtype, (B, self.L * self.F), "dLdy"),

@@ -38,6 +38,8 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "hashgrid.h"
 #include "hashgrid_common.hpp"
 #include "hashgrid_internal.hpp"
@@ -384,12 +386,23 @@ __device__ __forceinline__ void block_exclusive_scan(uint32_t* a, uint32_t n, ui
 // counts[tile][bin] into the exclusive prefix over tiles; it also writes the
 // bin's record count.  Workgroup 0 clears the work counter of the accumulate pass.
 constexpr int kScanBins = 32;  // 128-byte rows of the count table per load (16, 8: slower; 64: the same)
+// With HG_BWD_OVERWRITE it also clears the gradient of the levels in zero_mask (those that the
+// later passes add into, see launch_binned): it is the first kernel of the call to run.
 __global__ __launch_bounds__(kScanThreads) void bin_scan(const uint32_t n_tiles, const uint32_t n_bins,
                                                          uint32_t* __restrict__ counts,
                                                          uint32_t* __restrict__ bin_total,
-                                                         uint32_t* __restrict__ item_counter) {
+                                                         uint32_t* __restrict__ item_counter, const LevelTable lv,
+                                                         const uint32_t zero_mask, const uint32_t F,
+                                                         float* __restrict__ grad) {
   __shared__ uint32_t seg_sum[kScanThreads];
   if (blockIdx.x == 0 && threadIdx.x == 0) item_counter[0] = 0;  // the accumulate pass draws its work items from here
+  for (uint32_t l = 0; zero_mask >> l; ++l) {  // uniform
+    if (!((zero_mask >> l) & 1u)) continue;
+    float* g = grad + lv.offset[l] * F;
+    const uint64_t n = (uint64_t)lv.size[l] * F;
+    for (uint64_t i = (uint64_t)blockIdx.x * kScanThreads + threadIdx.x; i < n; i += (uint64_t)gridDim.x * kScanThreads)
+      g[i] = 0.0f;
+  }
   constexpr uint32_t segs = kScanThreads / kScanBins;
   const uint32_t bin_in = threadIdx.x % kScanBins, seg = threadIdx.x / kScanBins;
   const uint32_t gb = blockIdx.x * kScanBins + bin_in;
@@ -456,7 +469,7 @@ __global__ __launch_bounds__(kScanThreads) void bin_scan(const uint32_t n_tiles,
 // local[nbp + 1] exclusive prefix of this tile's counts (where a bin's records
 // sit in the tile's sorted order), cur[nbp] the same, advanced as records are
 // placed, delta[nbp] = global slot minus tile-local position.
-template <int D, typename IT, int F>
+template <int D, typename IT, int F, bool CROSS>  // CROSS: this pass adds the pairs that straddle two chunks
 __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, const BinPlan bp, const bool smooth,
                                                            const uint32_t B, const float* __restrict__ x,
                                                            const IT* __restrict__ dy,
@@ -563,7 +576,7 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, 
     if (valid) {
       Rows<D> rw;
       rows_of<D, false>(lv, bp, l, smooth, xp, rw);
-      if (rw.cross) add_crossing_pairs<D, F>(lv, l, smooth, xp, gf, grad);
+      if (CROSS && rw.cross) add_crossing_pairs<D, F>(lv, l, smooth, xp, gf, grad);
 #pragma unroll
       for (uint32_t r = 0; r < R && !rw.cross; ++r) {
         const uint32_t rb = rw.bin[r] - gb_a;
@@ -603,7 +616,7 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, 
 // in LDS first would not make whole lines of them; what merges partial lines here is the L2,
 // which keeps the tile's open runs (a few bytes per bin of the part) while the workgroup lasts.
 // LDS: slot[nbp], the next free record slot of each bin of this part for this tile.
-template <int D, typename IT, int F>
+template <int D, typename IT, int F, bool CROSS>
 __global__ __launch_bounds__(kBinThreads) void bin_scatter_direct(
     const LevelTable lv, const BinPlan bp, const bool smooth, const uint32_t B, const float* __restrict__ x,
     const IT* __restrict__ dy, const uint32_t* __restrict__ counts, const uint32_t* __restrict__ bin_total,
@@ -662,7 +675,7 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter_direct(
       Rows<D> rw;
       rows_of<D, false>(lv, bp, l, smooth, xp, rw);
       if (rw.cross) {
-        add_crossing_pairs<D, F>(lv, l, smooth, xp, gf, grad);
+        if (CROSS) add_crossing_pairs<D, F>(lv, l, smooth, xp, gf, grad);
         continue;
       }
 #pragma unroll
@@ -685,6 +698,31 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter_direct(
     float t = wave_max[0];
     for (int i = 1; i < kBinThreads / 64; ++i) t = nan_max(t, wave_max[i]);
     tile_max[tile * gridDim.y + blockIdx.y] = t;
+  }
+}
+
+// The pairs that straddle two chunks (add_crossing_pairs), as a pass of its own after the accumulate
+// pass: with HG_BWD_OVERWRITE the owners of the chunks store their sums, so these atomic adds
+// must come after them.  Only the levels in level_mask can have such pairs; one thread per point.
+template <int D, typename IT, int F>
+__global__ __launch_bounds__(kBinThreads) void bin_crossing(const LevelTable lv, const BinPlan bp, const bool smooth,
+                                                            const uint32_t B, const float* __restrict__ x,
+                                                            const IT* __restrict__ dy, const uint32_t level_mask,
+                                                            float* __restrict__ grad) {
+  const uint64_t b64 = (uint64_t)blockIdx.x * kBinThreads + threadIdx.x;
+  if (b64 >= B) return;
+  const uint32_t b = (uint32_t)b64;
+  float xp[D];
+  load_x<D>(x, b, xp);
+  for (uint32_t l = 0; level_mask >> l; ++l) {  // uniform
+    if (!((level_mask >> l) & 1u)) continue;
+    Rows<D> rw;
+    rows_of<D, true>(lv, bp, l, smooth, xp, rw);
+    if (!rw.cross) continue;
+    float gf[F];
+#pragma unroll
+    for (int f = 0; f < F; ++f) gf[f] = (float)dy[((uint64_t)b * lv.L + l) * F + f];
+    add_crossing_pairs<D, F>(lv, l, smooth, xp, gf, grad);
   }
 }
 
@@ -714,7 +752,9 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
                                                               const uint32_t n_max,
                                                               const uint32_t* __restrict__ records,
                                                               uint32_t* __restrict__ item_counter,
-                                                              float* __restrict__ grad) {
+                                                              float* __restrict__ grad, const uint32_t overwrite_mask) {
+  // bit l of overwrite_mask: the owner of a chunk of level l stores its sums (HG_BWD_OVERWRITE, one
+  // slice per chunk, no pairs that straddle chunks) instead of adding them to what is there
   __shared__ uint32_t s_ticket;
   extern __shared__ unsigned long long acc[];  // [F][2^chunk_log2] fixed point: feature 0 of every entry, then
                                                // feature 1 ..., so that consecutive entries map to consecutive banks
@@ -729,7 +769,7 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
   m = red[0];
 #pragma unroll
   for (int i = 1; i < kAccThreads / 64; ++i) m = nan_max(m, red[i]);
-  if (m == 0.0f) return;  // every summand is zero (uniform: all lanes hold the same m)
+  if (m == 0.0f && overwrite_mask == 0) return;  // every summand is zero (uniform: all lanes hold the same m)
   const bool finite = m < INFINITY;
   constexpr uint32_t cl = chunk_log2_of(F), cap = 1u << cl, cmask = cap - 1u;
   // fixed-point scale: |summand| <= m < 2^E, at most 8B summands per entry
@@ -813,8 +853,9 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
       if (i < it.r1) pre[j] = Rec::load(records, i);
     }
   };
+  auto overwrites = [&](const Item& it) { return ((overwrite_mask >> it.l) & 1u) != 0; };  // uniform
   auto request_chunk = [&](const Item& it, Entry (&cur)[kPer]) {
-    if (!kChunkAhead || !it.live || !finite) return;
+    if (!kChunkAhead || !it.live || !finite || overwrites(it)) return;
     if (it.n_sl == 1) {
 #pragma unroll
       for (int j = 0; j < kPer; ++j) {
@@ -849,7 +890,16 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
     Item it_n;
     it_n.live = false;
     Entry cur_n[kPer];
+    // HG_BWD_OVERWRITE: a chunk that gets no sums stored below is cleared by its owner
+    auto clear_chunk = [&](const Item& c) {
+      for (uint32_t q = threadIdx.x; q < c.n_e * F; q += kAccThreads) c.gl[q] = 0.0f;
+    };
     if (it.live && !finite) {
+      if (overwrites(it)) {  // uniform
+        clear_chunk(it);
+        __threadfence();  // the zeros reach the L2 before any lane's atomics below
+        __syncthreads();
+      }
       // inf or NaN upstream: keep IEEE semantics with direct fp32 atomics (slow, rare)
       for (uint32_t i = it.r0 + threadIdx.x; i < it.r1; i += kAccThreads) {
         uint32_t la, lb;
@@ -867,6 +917,7 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
       }
       it_n = describe(next, start_n, total_n, l_n, bin_n, slice_n);
     } else if (!it.live) {
+      if (overwrites(it)) clear_chunk(it);  // no records for this chunk (item < n_items inside the loop)
       it_n = describe(next, start_n, total_n, l_n, bin_n, slice_n);
       request_records(it_n, pre, 0, kPre);
       request_chunk(it_n, cur_n);
@@ -925,11 +976,17 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
             acc[f * cap + e] = 0ull;  // ready for the next item
           }
           if (e >= it.n_e) continue;
-          if (!kChunkAhead) cur[j] = reinterpret_cast<const Entry*>(it.gl)[e];
-          // an entry no record reached gets -0.0f added, which leaves every float (either zero,
-          // NaNs included) exactly as it was; storing it anyway keeps the stores of a wave contiguous
+          if (overwrites(it)) {
+            // what adding to a cleared entry would leave
 #pragma unroll
-          for (int f = 0; f < F; ++f) cur[j].v[f] += a[f] ? (float)((double)a[f] * inv_scale) : -0.0f;
+            for (int f = 0; f < F; ++f) cur[j].v[f] = 0.0f + (a[f] ? (float)((double)a[f] * inv_scale) : 0.0f);
+          } else {
+            if (!kChunkAhead) cur[j] = reinterpret_cast<const Entry*>(it.gl)[e];
+            // an entry no record reached gets -0.0f added, which leaves every float (either zero,
+            // NaNs included) exactly as it was; storing it anyway keeps the stores of a wave contiguous
+#pragma unroll
+            for (int f = 0; f < F; ++f) cur[j].v[f] += a[f] ? (float)((double)a[f] * inv_scale) : -0.0f;
+          }
           reinterpret_cast<Entry*>(it.gl)[e] = cur[j];
         }
       } else {
@@ -979,7 +1036,7 @@ static hg_status launch_count(const hashgrid* h, uint32_t B, const float* x, con
 
 template <int D, typename IT, int F>
 static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, const void* dy, float* grad,
-                               const Workspace& ws, const bool counted, hipStream_t s) {
+                               const Workspace& ws, const bool counted, const bool overwrite, hipStream_t s) {
   using Rec = Record<IT, F>;
   constexpr uint32_t R = 1u << (D - 1);
   BinPlan bp = h->bp;
@@ -1003,7 +1060,10 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
   static const hipError_t lds_ok = [] {
     hipError_t e = hipSuccess;
     if (kScatterLdsMax > 64 * 1024)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_scatter<D, IT, F>),
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_scatter<D, IT, F, true>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kScatterLdsMax);
+    if (e == hipSuccess && kScatterLdsMax > 64 * 1024)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_scatter<D, IT, F, false>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kScatterLdsMax);
     if (e == hipSuccess && kAccLds > 48 * 1024)
       e = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_accumulate<IT, F, false>),
@@ -1017,17 +1077,37 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
   const size_t lds_scatter = kStagingBytes + (3 * (size_t)max_part_bins(parts) + 1) * 4;
   const uint32_t tile_wgs = (ws.n_tiles + 7u) / 8u * 8u;  // see tile_of_workgroup
   if (!counted && launch_count(h, B, x, ws, s) != HG_OK) return HG_ERR_DEVICE;
+  // HG_BWD_OVERWRITE: the owner of a chunk stores its sums, except on levels whose chunks are summed
+  // by several workgroups; those levels are cleared first and added into as usual.  Pairs that
+  // straddle two chunks (hashed levels of resolution 2^chunk_log2 or more) get their atomic adds
+  // from a pass after the owners have stored.
+  uint32_t add_mask = 0, cross_mask = 0;
+  for (uint32_t l = 0; l < L; ++l) {
+    const bool hashed = !((h->lv.dense_mask >> l) & 1u);
+    if (bp.slices[l] > 1) add_mask |= 1u << l;
+    if (hashed && h->lv.N[l] + 1u >= (1u << bp.chunk_log2)) cross_mask |= 1u << l;
+  }
+  const uint32_t all_levels = L == 32 ? 0xffffffffu : (1u << L) - 1u;
+  const uint32_t zero_mask = overwrite ? add_mask : 0u, overwrite_mask = overwrite ? all_levels & ~add_mask : 0u;
+  const bool defer_cross = overwrite && cross_mask != 0;  // those atomic adds then follow the accumulate pass
   hipLaunchKernelGGL(bin_scan, dim3((ws.n_bins + kScanBins - 1) / kScanBins), dim3(kScanThreads), 0, s, ws.n_tiles,
-                     ws.n_bins, ws.counts, ws.bin_total, ws.item_counter);
-  if (bp.tile_mult > 1)
-    hipLaunchKernelGGL((bin_scatter_direct<D, IT, F>), dim3(tile_wgs, parts), dim3(kBinThreads),
-                       (size_t)max_part_bins(parts) * 4, s, h->lv, bp, smooth, B, x, static_cast<const IT*>(dy),
-                       ws.counts, ws.bin_total, ws.bin_start, ws.records, ws.n_bins, n_records, ws.n_tiles,
-                       ws.tile_max, grad);
+                     ws.n_bins, ws.counts, ws.bin_total, ws.item_counter, h->lv, zero_mask, (uint32_t)F, grad);
+  auto scatter = [&](auto cross) {
+    constexpr bool kCross = decltype(cross)::value;
+    if (bp.tile_mult > 1)
+      hipLaunchKernelGGL((bin_scatter_direct<D, IT, F, kCross>), dim3(tile_wgs, parts), dim3(kBinThreads),
+                         (size_t)max_part_bins(parts) * 4, s, h->lv, bp, smooth, B, x, static_cast<const IT*>(dy),
+                         ws.counts, ws.bin_total, ws.bin_start, ws.records, ws.n_bins, n_records, ws.n_tiles,
+                         ws.tile_max, grad);
+    else
+      hipLaunchKernelGGL((bin_scatter<D, IT, F, kCross>), dim3(tile_wgs, parts), dim3(kBinThreads), lds_scatter, s,
+                         h->lv, bp, smooth, B, x, static_cast<const IT*>(dy), ws.counts, ws.bin_total, ws.bin_start,
+                         ws.records, ws.n_bins, n_records, ws.n_tiles, ws.tile_max, grad);
+  };
+  if (defer_cross || cross_mask == 0)  // no such pairs at these resolutions, or bin_crossing takes them
+    scatter(std::false_type{});
   else
-    hipLaunchKernelGGL((bin_scatter<D, IT, F>), dim3(tile_wgs, parts), dim3(kBinThreads), lds_scatter, s, h->lv, bp,
-                       smooth, B, x, static_cast<const IT*>(dy), ws.counts, ws.bin_total, ws.bin_start,
-                       ws.records, ws.n_bins, n_records, ws.n_tiles, ws.tile_max, grad);
+    scatter(std::true_type{});
   const uint32_t n_items = bp.wg_base[h->lv.L];
   static const uint32_t acc_slots = [] {  // its registers let one 1024-thread workgroup run per CU; more would queue
     int dev = 0, cus = 0;
@@ -1040,22 +1120,25 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
   if (smooth)
     hipLaunchKernelGGL((bin_accumulate<IT, F, true>), acc_grid, dim3(kAccThreads), kAccLds, s, h->lv, bp, B, n_items,
                        ws.bin_start, ws.bin_total, ws.tile_max, ws.n_tiles * parts, ws.records, ws.item_counter,
-                       grad);
+                       grad, overwrite_mask);
   else
     hipLaunchKernelGGL((bin_accumulate<IT, F, false>), acc_grid, dim3(kAccThreads), kAccLds, s, h->lv, bp, B, n_items,
                        ws.bin_start, ws.bin_total, ws.tile_max, ws.n_tiles * parts, ws.records, ws.item_counter,
-                       grad);
+                       grad, overwrite_mask);
+  if (defer_cross)
+    hipLaunchKernelGGL((bin_crossing<D, IT, F>), dim3((B + kBinThreads - 1) / kBinThreads), dim3(kBinThreads), 0, s,
+                       h->lv, bp, smooth, B, x, static_cast<const IT*>(dy), cross_mask, grad);
   return hipGetLastError() == hipSuccess ? HG_OK : HG_ERR_DEVICE;
 }
 
 template <int D, typename IT>
 static hg_status launch_binned_f(const hashgrid* h, uint32_t B, const float* x, const void* dy, float* grad,
-                                 const Workspace& ws, const bool counted, hipStream_t s) {
+                                 const Workspace& ws, const bool counted, const bool overwrite, hipStream_t s) {
   switch (h->cfg.F) {
-    case 1: return launch_binned<D, IT, 1>(h, B, x, dy, grad, ws, counted, s);
-    case 2: return launch_binned<D, IT, 2>(h, B, x, dy, grad, ws, counted, s);
-    case 4: return launch_binned<D, IT, 4>(h, B, x, dy, grad, ws, counted, s);
-    case 8: return launch_binned<D, IT, 8>(h, B, x, dy, grad, ws, counted, s);
+    case 1: return launch_binned<D, IT, 1>(h, B, x, dy, grad, ws, counted, overwrite, s);
+    case 2: return launch_binned<D, IT, 2>(h, B, x, dy, grad, ws, counted, overwrite, s);
+    case 4: return launch_binned<D, IT, 4>(h, B, x, dy, grad, ws, counted, overwrite, s);
+    case 8: return launch_binned<D, IT, 8>(h, B, x, dy, grad, ws, counted, overwrite, s);
     default: return HG_ERR_UNSUPPORTED;
   }
 }
@@ -1119,7 +1202,7 @@ hg_status hashgrid_encode_fwd_ws(const hashgrid_t* hg, uint32_t B, const float* 
 hg_status hashgrid_encode_bwd_ws(const hashgrid_t* hg, uint32_t B, const float* x, const void* dLdy,
                                  float* grad_params, void* workspace, uint64_t workspace_bytes, uint32_t flags,
                                  void* stream) {
-  if (!hg || (flags & ~(uint32_t)HG_BWD_COUNTED)) return HG_ERR_INVALID_ARG;
+  if (!hg || (flags & ~(uint32_t)(HG_BWD_COUNTED | HG_BWD_OVERWRITE))) return HG_ERR_INVALID_ARG;
   if (B == 0) return HG_OK;
   const hg_status ok = check_workspace(hg, B, workspace, workspace_bytes);
   if (ok != HG_OK) return ok;
@@ -1132,12 +1215,12 @@ hg_status hashgrid_encode_bwd_ws(const hashgrid_t* hg, uint32_t B, const float* 
   hg::Workspace ws;
   hg::carve(hg, B, static_cast<uint8_t*>(workspace), &ws);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const bool i16 = hg->cfg.io_dtype == HG_F16, counted = flags & HG_BWD_COUNTED;
+  const bool i16 = hg->cfg.io_dtype == HG_F16, counted = flags & HG_BWD_COUNTED, ow = flags & HG_BWD_OVERWRITE;
   if (hg->cfg.d == 3)
-    return i16 ? hg::launch_binned_f<3, _Float16>(hg, B, x, dLdy, grad_params, ws, counted, s)
-               : hg::launch_binned_f<3, float>(hg, B, x, dLdy, grad_params, ws, counted, s);
-  return i16 ? hg::launch_binned_f<2, _Float16>(hg, B, x, dLdy, grad_params, ws, counted, s)
-             : hg::launch_binned_f<2, float>(hg, B, x, dLdy, grad_params, ws, counted, s);
+    return i16 ? hg::launch_binned_f<3, _Float16>(hg, B, x, dLdy, grad_params, ws, counted, ow, s)
+               : hg::launch_binned_f<3, float>(hg, B, x, dLdy, grad_params, ws, counted, ow, s);
+  return i16 ? hg::launch_binned_f<2, _Float16>(hg, B, x, dLdy, grad_params, ws, counted, ow, s)
+             : hg::launch_binned_f<2, float>(hg, B, x, dLdy, grad_params, ws, counted, ow, s);
 }
 
 }  // extern "C"

@@ -118,6 +118,9 @@ def run_case(d, L, F, T, N_min, N_max, pdt, iot, interp, x, theta, dy, do_indice
         check_bwd(gw.cpu().numpy(), g_ref, g_abs, floor)
         gw2 = grid.encode_bwd(xd, gd, gw.clone(), use_workspace=True)
         check_bwd(gw2.cpu().numpy(), 2 * g_ref, 2 * g_abs, 2 * floor)
+        # HG_BWD_OVERWRITE: the same gradient whatever the buffer held (here NaN), untouched entries 0
+        go = grid.encode_bwd(xd, gd, torch.full_like(gw, float("nan")), use_workspace=True, overwrite=True)
+        check_bwd(go.cpu().numpy(), g_ref, g_abs, floor)
         # hashgrid_encode_fwd_ws: the same y, and its counts serve the backward pass
         yc = grid.encode_fwd(xd, td, count_for_bwd="always")
         same_forward(yc, y, iot)
@@ -516,9 +519,34 @@ def test_workspace_backward_with_non_finite_upstream_gradient():
     dy[99, 8] = np.nan
     with np.errstate(invalid="ignore"):
         ref = orc.encode_bwd(cfg, x, dy)
-    for use_ws in (False, True):
-        g = grid.encode_bwd(dev(x), dev(dy), use_workspace=use_ws).cpu().numpy()
+    for use_ws, overwrite in ((False, False), (True, False), (True, True)):
+        old = torch.full((grid.n_entries, F), 7.0, device="cuda") if overwrite else None
+        g = grid.encode_bwd(dev(x), dev(dy), old, use_workspace=use_ws, overwrite=overwrite).cpu().numpy()
         assert (np.isfinite(g) == np.isfinite(ref)).all()
         assert (np.isnan(g) == np.isnan(ref)).all()
         fin = np.isfinite(ref)
         np.testing.assert_allclose(g[fin], ref[fin], rtol=1e-4, atol=1e-5)
+
+
+def test_overwriting_backward():
+    # HG_BWD_OVERWRITE at the headline shape (several slices per chunk on the coarse levels), with
+    # the counts of the forward pass, on a buffer full of other values: equal to the adding call on
+    # zeros where one workgroup owns a chunk, and within rounding of it where several add up;
+    # a batch of zeros clears the buffer; the atomic pass behind the same option of the binding.
+    w = synth.WORKLOADS["sdf3d"]
+    grid = HashGrid(w.d, w.L, w.F, w.T, w.N_min, w.N_max, w.param_dtype, w.io_dtype)
+    x, theta, dy = synth.make_inputs(w, grid.n_entries, B=50000, table_scale=1.0)
+    xd, td, gd = dev(x), dev(theta), dev(dy)
+    g_add = grid.encode_bwd(xd, gd, use_workspace=True)
+    junk = torch.randn((grid.n_entries, w.F), device="cuda")
+    grid.encode_fwd(xd, td, count_for_bwd="always")
+    g_ow = grid.encode_bwd(xd, gd, junk.clone(), overwrite=True)
+    hashed_from = [i for i in grid.levels() if not i.is_dense][0].entry_offset
+    assert torch.equal(g_ow[hashed_from:], g_add[hashed_from:])
+    torch.testing.assert_close(g_ow[:hashed_from], g_add[:hashed_from], rtol=1e-4,
+                               atol=1e-4 * float(g_add.abs().max()))
+    g0 = grid.encode_bwd(xd, torch.zeros_like(gd), junk.clone(), use_workspace=True, overwrite=True)
+    assert not g0.any()
+    ga = grid.encode_bwd(xd[:1000], gd[:1000], junk.clone(), use_workspace=False, overwrite=True)
+    gb = grid.encode_bwd(xd[:1000], gd[:1000], use_workspace=False)
+    torch.testing.assert_close(ga, gb, rtol=1e-4, atol=1e-4 * float(gb.abs().max()))
