@@ -34,6 +34,15 @@
 //              the sum is exact and independent of the order of the records;
 //              each summand is rounded once to 2^-min(62-H, 51) of the power of
 //              two above that largest value (H = ceil(log2(8B))).
+//
+// Variants of the same plan: the forward pass can do the counting (hashgrid.hip,
+// HG_BWD_COUNTED); plans with more than kMaxStagedBins chunks use tiles of
+// kBigTileMult * 512 points and write their records unstaged (bin_scatter_direct);
+// pairs whose corners lie in two chunks (hashed levels of resolution 2^chunk_log2
+// or more) bypass the sort and are added with device atomics; with
+// HG_BWD_OVERWRITE the owners store their sums instead of adding them, the scan
+// kernel clears the levels that several workgroups share, and the atomics for the
+// straddling pairs run as a last pass (bin_crossing).
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
