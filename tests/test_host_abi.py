@@ -145,3 +145,27 @@ def test_choice_between_the_backward_passes_needs_no_device():
     for grid in (table1, small_levels):  # once it pays it keeps paying
         flags = [grid.bwd_ws_pays(1 << k) for k in range(6, 22)]
         assert flags == sorted(flags)
+
+
+def test_workspace_size_of_the_sorted_backward_needs_no_device():
+    """hashgrid_bwd_workspace_bytes is host arithmetic: 8 + F * sizeof(dL/dy scalar) bytes per pair of
+    corners plus one count per (tile, chunk); 0 where the pass is not served."""
+    B = 1 << 18
+    table1 = binding.HashGrid(3, 16, 2, 1 << 19, 16, 2048, "f16", "f16")
+    pairs = B * 16 * 4
+    chunks = sum(-(-lv.n_entries // 4096) if not lv.is_dense else 0 for lv in table1.levels())
+    assert chunks == 11 * 128
+    need = table1.bwd_workspace_bytes(B)
+    assert pairs * 12 + (B // 512) * chunks * 4 < need < pairs * 12 + (B // 512 + 2) * (chunks + 200) * 4 + (1 << 16)
+    assert binding.HashGrid(3, 16, 2, 1 << 19, 16, 2048, "f16", "f32").bwd_workspace_bytes(B) - need == pairs * 4
+    assert binding.HashGrid(3, 16, 8, 1 << 19, 16, 2048, "f16", "f16").bwd_workspace_bytes(B) > pairs * 24
+    # more than 16384 chunks: tiles of 4096 points, an eighth of the count rows
+    large = binding.HashGrid(3, 16, 2, 1 << 24, 16, 1 << 19, "f16", "f16")
+    need = large.bwd_workspace_bytes(1 << 21)
+    assert (1 << 21) * 16 * 4 * 12 < need < (1 << 21) * 16 * 4 * 12 + 600 * 50000 * 4
+    # not served: one dimension, T not a power of two, T beyond 2^24, too many pairs for 32-bit slots
+    assert binding.HashGrid(1, 4, 2, 1 << 10, 4, 64).bwd_workspace_bytes(1000) == 0
+    assert binding.HashGrid(3, 16, 2, 1000003, 16, 2048).bwd_workspace_bytes(1000) == 0
+    assert binding.HashGrid(3, 2, 2, 1 << 25, 16, 2048).bwd_workspace_bytes(1000) == 0
+    assert table1.bwd_workspace_bytes(1 << 27) == 0
+    assert table1.bwd_workspace_bytes(0) == 0
