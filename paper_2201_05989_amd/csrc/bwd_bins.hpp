@@ -23,8 +23,9 @@ struct Rows {
   bool cross;                    // hashed level: the pair's corners fall into different chunks (no record)
 };
 
+// (also compiled for the host: the plan's invariants are checked there, point by point, without a GPU)
 template <int D, bool COUNT_ONLY>
-__device__ __forceinline__ void rows_of(const LevelTable& lv, const BinPlan& bp, uint32_t l, bool smooth,
+__host__ __device__ __forceinline__ void rows_of(const LevelTable& lv, const BinPlan& bp, uint32_t l, bool smooth,
                                         const float (&xp)[D], Rows<D>& out) {
   const uint32_t N = lv.N[l], verts = lv.verts[l];
   const bool dense = (lv.dense_mask >> l) & 1u;

@@ -25,7 +25,7 @@ struct LevelTable {
 };
 
 // Eq. 4: pi_1 = 1, pi_2 = 2654435761, pi_3 = 805459861.
-__device__ __forceinline__ constexpr uint32_t prime(int i) {
+__host__ __device__ __forceinline__ constexpr uint32_t prime(int i) {
   return i == 0 ? 1u : (i == 1 ? 2654435761u : 805459861u);
 }
 
@@ -34,7 +34,7 @@ __device__ __forceinline__ constexpr uint32_t prime(int i) {
 // offset of Appendix A (0 or 0.5).  The corner is clamped to [0, cmax] so that a
 // coordinate outside [0,1) (a violated precondition) can never index outside a
 // 1:1 level; for valid input the clamp is the identity.
-__device__ __forceinline__ void split(float x, float Nf, float shift, float cmaxf, uint32_t& c0, float& w) {
+__host__ __device__ __forceinline__ void split(float x, float Nf, float shift, float cmaxf, uint32_t& c0, float& w) {
   float p = x * Nf;
   p = p + shift;  // the file is compiled with fp contraction off: two roundings
   float fl = floorf(p);
@@ -79,7 +79,7 @@ __device__ __forceinline__ uint32_t corner_index(const CornerTerms<D>& ct, uint3
 }
 
 // Appendix A: S(w) = w^2 (3 - 2w), S'(w) = 6 w (1 - w).
-__device__ __forceinline__ float smoothstep(float w) { return w * w * (3.0f - 2.0f * w); }
+__host__ __device__ __forceinline__ float smoothstep(float w) { return w * w * (3.0f - 2.0f * w); }
 __device__ __forceinline__ float dsmoothstep(float w) { return 6.0f * w * (1.0f - w); }
 
 // F scalars of one table entry / one output fragment, loaded and stored as one
