@@ -350,6 +350,50 @@ def test_workspace_backward_with_very_many_chunks(d, F, iot, interp, B):
     assert grid.bwd_workspace_bytes(B) > 0
 
 
+@pytest.mark.parametrize("F,pdt,iot", [(2, "f16", "f16"), (1, "f32", "f16"), (4, "f16", "f32")])
+def test_buffers_aligned_to_one_entry_only(F, pdt, iot):
+    # every array starts one table entry (one level's outputs) past a 256-byte boundary: allowed by
+    # the interface, but not the 16-byte alignment the vector paths of the kernels want
+    d, L, T, N_min, N_max, B = 3, 8, 1 << 12, 4, 128, 3000
+    cfg = orc.OracleConfig(d, L, F, T, N_min, N_max)
+    lv = orc.levels(cfg)
+    rng = np.random.default_rng(31)
+    x = synth.points_uniform(rng, B, d)
+    theta = synth.make_tables(rng, lv.total, F, pdt, 1.0)
+    dy = synth.make_dy(rng, B, L * F, iot)
+    grid = HashGrid(d, L, F, T, N_min, N_max, pdt, iot)
+
+    def shifted(a, fill=None):
+        t = torch.empty(a.size + F, dtype=torch.from_numpy(a[:0]).dtype, device="cuda")
+        v = t[F:].view(a.shape)
+        assert v.data_ptr() % 16 != 0 or F * a.itemsize >= 16
+        v.copy_(dev(a)) if fill is None else v.fill_(fill)
+        return v
+
+    td, gd = shifted(theta), shifted(dy)
+    xd = dev(x)
+    y = shifted(np.empty((B, L * F), NP[iot]), fill=0.0)
+    grid.encode_fwd(xd, td, y)
+    check_fwd(y.cpu().numpy(), orc.encode_fwd(cfg, x, theta), 1.0, iot)
+    g_ref = orc.encode_bwd(cfg, x, dy)
+    g_abs = orc.encode_bwd(cfg, x, np.abs(dy.astype(np.float64)))
+    floor = ws_floor(dy, B) + 2.0 ** -23 * corner_abs_sum(cfg, lv, x, dy)
+    for use_ws, ow in ((False, False), (True, False), (True, True)):
+        g = shifted(np.empty((lv.total, F), np.float32), fill=0.0)
+        grid.encode_bwd(xd, gd, g, use_workspace=use_ws, overwrite=ow)
+        check_bwd(g.cpu().numpy(), g_ref, g_abs, floor if use_ws else 0.0)
+    y2 = shifted(np.empty((B, L * F), NP[iot]), fill=0.0)
+    grid.encode_fwd(xd, td, y2, count_for_bwd="always")
+    same_forward(y2, y, iot)
+    g = shifted(np.empty((lv.total, F), np.float32), fill=0.0)
+    grid.encode_bwd(xd, gd, g)
+    check_bwd(g.cpu().numpy(), g_ref, g_abs, floor)
+    dx = grid.encode_bwd_input(xd, td, gd).cpu().numpy().astype(np.float64)
+    dx_ref = orc.encode_bwd_input(cfg, x, theta, dy)
+    scale = np.abs(dy.astype(np.float64)).reshape(B, L, F).sum(axis=2) @ lv.N.astype(np.float64) * 3.0
+    assert (np.abs(dx - dx_ref) <= 2e-6 * scale[:, None] + 1e-30).all()
+
+
 def test_empty_batch_is_a_no_op():
     grid = HashGrid(3, 16, 2, 1 << 19, 16, 2048)
     x = torch.empty((0, 3), dtype=torch.float32, device="cuda")
