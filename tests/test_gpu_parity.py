@@ -433,6 +433,31 @@ def test_non_default_stream():
     check_fwd(y.cpu().numpy(), orc.encode_fwd(cfg, x, theta), 1.0, "f32")
 
 
+def test_two_streams_share_a_handle_with_a_workspace_each():
+    # the handle is read-only; calls that overlap in time need their own scratch buffers
+    w = synth.WORKLOADS["sdf3d"]
+    grid = HashGrid(w.d, w.L, w.F, w.T, w.N_min, w.N_max, w.param_dtype, w.io_dtype)
+    B = 40000
+    x, theta, dy = synth.make_inputs(w, grid.n_entries, B=2 * B, table_scale=1.0)
+    xs, dys = [dev(x[:B]), dev(x[B:])], [dev(dy[:B]), dev(dy[B:])]
+    ref = [grid.encode_bwd(xs[i], dys[i], use_workspace=True) for i in range(2)]
+    need = grid.bwd_workspace_bytes(B)
+    spaces = [torch.empty(need, dtype=torch.uint8, device="cuda") for _ in range(2)]
+    grads = [torch.zeros_like(ref[0]) for _ in range(2)]
+    streams = [torch.cuda.Stream() for _ in range(2)]
+    torch.cuda.synchronize()
+    for _ in range(3):  # several rounds in flight on both streams at once
+        for i in range(2):
+            grid.encode_bwd(xs[i], dys[i], grads[i], stream=streams[i], workspace=spaces[i], use_workspace=True,
+                            overwrite=True)
+    torch.cuda.synchronize()
+    hashed_from = [i for i in grid.levels() if not i.is_dense][0].entry_offset
+    for i in range(2):
+        assert torch.equal(grads[i][hashed_from:], ref[i][hashed_from:])
+        torch.testing.assert_close(grads[i][:hashed_from], ref[i][:hashed_from], rtol=1e-4,
+                                   atol=1e-4 * float(ref[i].abs().max()))
+
+
 def test_workspace_backward_is_reproducible_and_keeps_untouched_entries():
     w = synth.WORKLOADS["sdf3d"]
     grid = HashGrid(w.d, w.L, w.F, w.T, w.N_min, w.N_max, w.param_dtype, w.io_dtype)
