@@ -117,6 +117,9 @@ def main():
     ap.add_argument("--workload", default="sdf3d")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probes", action="store_true", help="skip the machine probes (copy, gather, atomic rates)")
+    ap.add_argument("--step-only", action="store_true",
+                    help="only the step and its two passes (what the profiles are taken of): no stand-alone "
+                         "calls, other entry points, probes or CPU baseline")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a 1 GiB device-to-device copy (20 times): the known-size kernel that "
                          "FETCH_SIZE / WRITE_SIZE counter readings are scaled by")
@@ -168,8 +171,6 @@ def main():
     ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
 
     n = max(args.steps, 20)
-    ms_fwd_alone = time_launches(fwd, n, torch)
-    ms_bwd_alone = time_launches(bwd, n, torch)
     # the two passes as the step runs them, each bracketed by HIP events on the launch stream
     marks = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n)]
     for ea, eb, ec in marks:
@@ -181,66 +182,82 @@ def main():
     torch.cuda.synchronize()
     ms_fwd = sum(ea.elapsed_time(eb) for ea, eb, _ in marks) / n
     ms_bwd = sum(eb.elapsed_time(ec) for _, eb, ec in marks) / n
-    ms_zero = time_launches(lambda: grad.zero_(), 20, torch)
+    extras = {}
+    if not args.step_only:
+        ms_fwd_alone = time_launches(fwd, n, torch)
+        ms_bwd_alone = time_launches(bwd, n, torch)
+        ms_zero = time_launches(lambda: grad.zero_(), 20, torch)
 
-    # the same step when the backward pass replaces the gradient instead of adding to it
-    # (HG_BWD_OVERWRITE: no clearing pass before it, no reading of the old values in it)
-    def step_overwrite():
-        fwd_counting()
-        grid.encode_bwd(xd, gd, grad, overwrite=True)
+        # the same step when the backward pass replaces the gradient instead of adding to it
+        # (HG_BWD_OVERWRITE: no clearing pass before it, no reading of the old values in it)
+        def step_overwrite():
+            fwd_counting()
+            grid.encode_bwd(xd, gd, grad, overwrite=True)
 
-    ms_bwd_ow = time_launches(lambda: grid.encode_bwd(xd, gd, grad, overwrite=True), n, torch)
-    ms_step_ow = time_launches(step_overwrite, n, torch)
-    grad.zero_()
+        ms_bwd_ow = time_launches(lambda: grid.encode_bwd(xd, gd, grad, overwrite=True), n, torch)
+        ms_step_ow = time_launches(step_overwrite, n, torch)
+        grad.zero_()
 
-    # next row of the path: the optimiser step on the tables (fp32 master + fp16 working copy,
-    # clears the gradient).  Timed as (backward + optimiser) minus backward, because the step
-    # skips entries whose gradient is zero and clears the ones it uses.
-    from paper_2201_05989_amd import adam_step
-    master = td.float()
-    m1, m2 = torch.zeros_like(master), torch.zeros_like(master)
-    counter = [0]
+        # next row of the path: the optimiser step on the tables (fp32 master + fp16 working copy,
+        # clears the gradient).  Timed as (backward + optimiser) minus backward, because the step
+        # skips entries whose gradient is zero and clears the ones it uses.
+        from paper_2201_05989_amd import adam_step
+        master = td.float()
+        m1, m2 = torch.zeros_like(master), torch.zeros_like(master)
+        counter = [0]
 
-    def bwd_adam():
-        bwd()
-        counter[0] += 1
-        adam_step(master, grad, m1, m2, counter[0], lr=1e-2, params_half=td if w.param_dtype == "f16" else None)
+        def bwd_adam():
+            bwd()
+            counter[0] += 1
+            adam_step(master, grad, m1, m2, counter[0], lr=1e-2, params_half=td if w.param_dtype == "f16" else None)
 
-    grad.zero_()
-    ms_bwd_adam = time_launches(bwd_adam, max(args.steps // 2, 10), torch)
-    grad.zero_()
-    ms_adam = ms_bwd_adam - ms_bwd_alone
+        grad.zero_()
+        ms_bwd_adam = time_launches(bwd_adam, max(args.steps // 2, 10), torch)
+        grad.zero_()
+        ms_adam = ms_bwd_adam - ms_bwd_alone
 
-    # the whole table-training step when the backward pass replaces the gradient: the optimiser
-    # then has nothing to clear
-    def train_overwrite():
-        fwd_counting()
-        grid.encode_bwd(xd, gd, grad, overwrite=True)
-        counter[0] += 1
-        adam_step(master, grad, m1, m2, counter[0], lr=1e-2, params_half=td if w.param_dtype == "f16" else None,
-                  zero_grad=False)
+        # the whole table-training step when the backward pass replaces the gradient: the optimiser
+        # then has nothing to clear
+        def train_overwrite():
+            fwd_counting()
+            grid.encode_bwd(xd, gd, grad, overwrite=True)
+            counter[0] += 1
+            adam_step(master, grad, m1, m2, counter[0], lr=1e-2, params_half=td if w.param_dtype == "f16" else None,
+                      zero_grad=False)
 
-    ms_train_ow = time_launches(train_overwrite, max(args.steps // 2, 10), torch)
-    grad.zero_()
-    n_scalars = grid.n_entries * w.F
-    adam_bytes = n_scalars * (16 + 12 + 4 + (2 if w.param_dtype == "f16" else 0))
+        ms_train_ow = time_launches(train_overwrite, max(args.steps // 2, 10), torch)
+        grad.zero_()
+        n_scalars = grid.n_entries * w.F
+        adam_bytes = n_scalars * (16 + 12 + 4 + (2 if w.param_dtype == "f16" else 0))
 
-    # last row of the path's table: the encoding fused with the paper's 64-64 ReLU network (one output,
-    # as for a signed distance function); served for fp16 tables with at most 64 encoded features
-    mlp = None
-    n_in = w.L * w.F
-    if w.param_dtype == "f16" and n_in % 8 == 0 and n_in <= 64 and w.d >= 2:
-        import numpy as np
-        rng = np.random.default_rng(0)
-        W1 = torch.from_numpy((rng.standard_normal((64, n_in)) * np.sqrt(2.0 / n_in)).astype(np.float16)).cuda()
-        W2 = torch.from_numpy((rng.standard_normal((64, 64)) * np.sqrt(2.0 / 64)).astype(np.float16)).cuda()
-        W3 = torch.from_numpy((rng.standard_normal((1, 64)) / 8.0).astype(np.float16)).cuda()
-        o = torch.empty((w.B, 1), dtype=torch.float32, device="cuda")
-        grid.encode_mlp_fwd(xd, td, W1, W2, W3, o)
-        ms_mlp = time_launches(lambda: grid.encode_mlp_fwd(xd, td, W1, W2, W3, o), max(n // 2, 10), torch)
-        flops = 2.0 * (n_in * 64 + 64 * 64 + 64 * 1) * w.B
-        mlp = {"ms": ms_mlp, "mpoints_s": w.B / (ms_mlp * 1e-3) / 1e6, "n_out": 1,
-               "network_tflop_s": flops / (ms_mlp * 1e-3) / 1e12, "ms_over_forward_alone": ms_mlp - ms_fwd_alone}
+        # last row of the path's table: the encoding fused with the paper's 64-64 ReLU network (one output,
+        # as for a signed distance function); served for fp16 tables with at most 64 encoded features
+        mlp = None
+        n_in = w.L * w.F
+        if w.param_dtype == "f16" and n_in % 8 == 0 and n_in <= 64 and w.d >= 2:
+            import numpy as np
+            rng = np.random.default_rng(0)
+            W1 = torch.from_numpy((rng.standard_normal((64, n_in)) * np.sqrt(2.0 / n_in)).astype(np.float16)).cuda()
+            W2 = torch.from_numpy((rng.standard_normal((64, 64)) * np.sqrt(2.0 / 64)).astype(np.float16)).cuda()
+            W3 = torch.from_numpy((rng.standard_normal((1, 64)) / 8.0).astype(np.float16)).cuda()
+            o = torch.empty((w.B, 1), dtype=torch.float32, device="cuda")
+            grid.encode_mlp_fwd(xd, td, W1, W2, W3, o)
+            ms_mlp = time_launches(lambda: grid.encode_mlp_fwd(xd, td, W1, W2, W3, o), max(n // 2, 10), torch)
+            flops = 2.0 * (n_in * 64 + 64 * 64 + 64 * 1) * w.B
+            mlp = {"ms": ms_mlp, "mpoints_s": w.B / (ms_mlp * 1e-3) / 1e6, "n_out": 1,
+                   "network_tflop_s": flops / (ms_mlp * 1e-3) / 1e12, "ms_over_forward_alone": ms_mlp - ms_fwd_alone}
+        extras = {
+            "ms_grad_zero": ms_zero, "ms_fwd_alone": ms_fwd_alone, "ms_bwd_alone": ms_bwd_alone,
+            "overwrite": {"ms_bwd_alone": ms_bwd_ow, "ms_step": ms_step_ow,
+                          "mpoints_s": w.B / (ms_step_ow * 1e-3) / 1e6, "train_step_ms": ms_train_ow,
+                          "train_step_mpoints_s": w.B / (ms_train_ow * 1e-3) / 1e6},
+            "adam": {"ms": ms_adam, "scalars": n_scalars, "algorithmic_bytes": adam_bytes,
+                     "achieved_gb_s": adam_bytes / (ms_adam * 1e-3) / 1e9 if ms_adam > 0 else None,
+                     "train_step_ms": ms_fwd + ms_bwd + ms_adam,
+                     "train_step_mpoints_s": w.B / ((ms_fwd + ms_bwd + ms_adam) * 1e-3) / 1e6},
+        }
+        if mlp is not None:
+            extras["encode_mlp_fwd"] = mlp
 
     s_theta = 2 if w.param_dtype == "f16" else 4
     s_io = 2 if w.io_dtype == "f16" else 4
@@ -263,14 +280,7 @@ def main():
                    "param_dtype": w.param_dtype, "io_dtype": w.io_dtype, "grad_dtype": "f32"},
         "fwd_mpoints_s": w.B / (ms_fwd * 1e-3) / 1e6,
         "bwd_mpoints_s": w.B / (ms_bwd * 1e-3) / 1e6,
-        "ms_fwd": ms_fwd, "ms_bwd": ms_bwd, "ms_grad_zero": ms_zero,
-        "ms_fwd_alone": ms_fwd_alone, "ms_bwd_alone": ms_bwd_alone,
-        "overwrite": {"ms_bwd_alone": ms_bwd_ow, "ms_step": ms_step_ow, "mpoints_s": w.B / (ms_step_ow * 1e-3) / 1e6,
-                      "train_step_ms": ms_train_ow, "train_step_mpoints_s": w.B / (ms_train_ow * 1e-3) / 1e6},
-        "adam": {"ms": ms_adam, "scalars": n_scalars, "algorithmic_bytes": adam_bytes,
-                 "achieved_gb_s": adam_bytes / (ms_adam * 1e-3) / 1e9 if ms_adam > 0 else None,
-                 "train_step_ms": ms_fwd + ms_bwd + ms_adam,
-                 "train_step_mpoints_s": w.B / ((ms_fwd + ms_bwd + ms_adam) * 1e-3) / 1e6},
+        "ms_fwd": ms_fwd, "ms_bwd": ms_bwd,
         "roofline": {"bound": "hbm", "kernel": kernels[dom[0]] if grid.bwd_workspace_bytes(w.B) else dom[0],
                      "pass": dom[0], "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
@@ -278,9 +288,8 @@ def main():
                      "fwd_achieved": b_fwd * w.B / (ms_fwd * 1e-3) / 1e9,
                      "bwd_achieved": b_bwd * w.B / (ms_bwd * 1e-3) / 1e9},
     }
-    if mlp is not None:
-        out["encode_mlp_fwd"] = mlp
-    if not args.no_probes:
+    out.update(extras)
+    if not args.no_probes and not args.step_only:
         # the pass rates in the elementary operations they stand for, next to what the machine does
         # when it performs those operations one by one at random
         corners = (1 << w.d) * w.L
@@ -294,7 +303,7 @@ def main():
             / probes["atomic_add_f32_4MiB_g_per_s"],
             "hbm_frac_of_copy": achieved / probes["copy_1GiB_gb_s"],
         }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.step_only:
         out["cpu_baseline"] = cpu_baseline(w, x, theta, dy)
     print(json.dumps(out))
 
