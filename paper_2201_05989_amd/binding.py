@@ -175,8 +175,8 @@ class HashGrid:
                    count_for_bwd=False, workspace: torch.Tensor | None = None):
         """hashgrid_encode_fwd; with count_for_bwd, hashgrid_encode_fwd_ws where the configuration
         is served by it and the batch is large enough for the sorted backward pass to pay
-        (count_for_bwd="always": whatever the batch): the next encode_bwd on the same x and workspace
-        then skips its counting pass."""
+        (count_for_bwd="always": whatever the batch): the next encode_bwd on the same, unmodified x and
+        the same workspace then skips its counting pass."""
         B = x.shape[0]
         if y is None:
             y = torch.empty((B, self.L * self.F), dtype=self.io_dtype, device=x.device)
@@ -192,7 +192,7 @@ class HashGrid:
                 _stream_ptr(stream))
             if st != HG_ERR_UNSUPPORTED:
                 _check(st, "hashgrid_encode_fwd_ws")
-                self._counted = (x.data_ptr(), B, ws.data_ptr())
+                self._counted = (x.data_ptr(), B, ws.data_ptr(), x._version)  # x unchanged since, as far as torch knows
                 return y
         _check(self._lib.hashgrid_encode_fwd(
             self._h, B, _dev(x, torch.float32, (B, self.d), "x"),
@@ -222,7 +222,7 @@ class HashGrid:
         if need:
             if workspace is None:
                 workspace = self._workspace(need, x.device)
-            flags = HG_BWD_COUNTED if counted == (x.data_ptr(), B, workspace.data_ptr()) else 0
+            flags = HG_BWD_COUNTED if counted == (x.data_ptr(), B, workspace.data_ptr(), x._version) else 0
             if overwrite and not fresh:
                 flags |= HG_BWD_OVERWRITE
             _check(self._lib.hashgrid_encode_bwd_ws(

@@ -498,6 +498,15 @@ def test_counting_forward_gives_the_counts_of_the_count_pass():
         # the counts are consumed: a second backward counts for itself and agrees
         g2 = grid.encode_bwd(xd, gd, use_workspace=True)
         assert torch.equal(g0[lo:], g2[lo:])
+        # points changed in place after the forward pass: the binding drops the counts (they belong to
+        # the old points) and the backward pass counts for itself
+        grid.encode_fwd(xd, td, count_for_bwd="always")
+        xd2 = xd.clone()
+        xd.copy_(xd.flip(0))
+        g3 = grid.encode_bwd(xd, gd, use_workspace=True)
+        g4 = grid.encode_bwd(xd.clone(), gd, use_workspace=True)
+        assert torch.equal(g3[lo:], g4[lo:])
+        xd.copy_(xd2)
 
 
 def test_step_replays_from_a_hip_graph():
