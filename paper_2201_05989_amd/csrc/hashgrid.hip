@@ -122,7 +122,7 @@ constexpr int kPmBlock = 1024;
 // in 293 as long as 2^19.  The batch is therefore spread evenly: k = number of rounds the batch
 // needs at full size, then B / (k * CUs) points per workgroup, rounded up to whole waves.  (The
 // counting variant always runs full workgroups: they cover whole tiles of the backward pass.)
-uint32_t point_major_block(uint32_t B) {
+static uint32_t cu_count() {
   static const uint32_t cus = [] {
     int dev = 0, n = 0;
     if (hipGetDevice(&dev) != hipSuccess ||
@@ -130,6 +130,10 @@ uint32_t point_major_block(uint32_t B) {
       n = 256;
     return (uint32_t)n;
   }();
+  return cus;
+}
+uint32_t point_major_block(uint32_t B) {
+  const uint32_t cus = cu_count();
   const uint64_t per_round = (uint64_t)kPmBlock * cus;
   const uint64_t rounds = (B + per_round - 1) / per_round;
   const uint64_t per_wg = (B + rounds * cus - 1) / (rounds * cus);
@@ -158,74 +162,92 @@ struct CountArgs {
 };
 struct NoCount {};
 
-template <int D, int F, typename PT, typename IT, bool POW2, bool COUNT>
+// SB: points per thread.  A workgroup then walks SB blocks of blockDim.x points level by level,
+// so that a level's slice, once in the XCD's L2, serves SB times the points before the next
+// level replaces it (for batches of several rounds of workgroups per CU).
+template <int D, int F, typename PT, typename IT, bool POW2, bool COUNT, int SB = 1>
 __global__ __launch_bounds__(kPmBlock) void fwd_point_major(const LevelTable lv, const bool smooth, const uint32_t B,
                                                             const float* __restrict__ x,
                                                             const PT* __restrict__ theta, IT* __restrict__ y,
                                                             const typename std::conditional<COUNT, CountArgs, NoCount>::type ca) {
   using Piece = OutPiece<F, IT>;
   constexpr int G = Piece::kLevels;
-  constexpr uint32_t kTiles = kPmBlock / kBinThreads;  // tiles of the backward pass per workgroup
+  constexpr uint32_t kTiles = SB * kPmBlock / kBinThreads;  // tiles of the backward pass per workgroup
   static_assert(kPmBlock % kBinThreads == 0, "a forward workgroup covers whole tiles");
   extern __shared__ uint32_t hist[];  // COUNT: [kTiles][n_bins]
   if constexpr (COUNT) {
     for (uint32_t i = threadIdx.x; i < kTiles * ca.n_bins; i += kPmBlock) hist[i] = 0;
     __syncthreads();
   }
-  const uint32_t b0 = blockIdx.x * blockDim.x + threadIdx.x;  // blockDim.x = kPmBlock with COUNT
-  const bool valid = b0 < B;
-  const uint32_t b = valid ? b0 : B - 1;  // idle lanes of the last workgroup shadow the last point
-  float xp[D];
-  load_point<D>(x, b, xp);
-  Vec<IT, F * G>* yrow = reinterpret_cast<Vec<IT, F * G>*>(y + (uint64_t)b * lv.L * F);
+  bool valid[SB];
+  float xp[SB][D];
+  Vec<IT, F * G>* yrow[SB];
+#pragma unroll
+  for (int q = 0; q < SB; ++q) {
+    const uint64_t b0 = ((uint64_t)blockIdx.x * SB + q) * blockDim.x + threadIdx.x;  // blockDim.x = kPmBlock with COUNT
+    valid[q] = b0 < B;
+    const uint32_t b = valid[q] ? (uint32_t)b0 : B - 1;  // idle lanes shadow the last point
+    load_point<D>(x, b, xp[q]);
+    yrow[q] = reinterpret_cast<Vec<IT, F * G>*>(y + (uint64_t)b * lv.L * F);
+  }
   // 16-byte pieces are stored two at a time so that a 32-byte sector of the row is written
   // once, not twice
-  Vec<IT, F * G> held;
+  Vec<IT, F * G> held[SB];
   for (uint32_t l0 = 0; l0 < lv.L; l0 += G) {
-    Vec<IT, F * G> out;
+    Vec<IT, F * G> out[SB];
 #pragma unroll
     for (int j = 0; j < G; ++j) {
       const uint32_t l = l0 + j;
-      uint32_t idx[1 << D];
-      float wr[1 << (D - 1)], w0, u0;
-      level_corners<D, POW2>(lv, l, smooth, xp, idx, wr, w0, u0);
       const Vec<PT, F>* tab = reinterpret_cast<const Vec<PT, F>*>(theta) + lv.offset[l];
-      Vec<PT, F> e[1 << D];
+      Vec<PT, F> e[SB][1 << D];
+      float wr[SB][1 << (D - 1)], w0[SB], u0[SB];
 #pragma unroll
-      for (uint32_t m = 0; m < (1u << D); ++m) e[m] = tab[idx[m]];
-      float acc[F];
+      for (int q = 0; q < SB; ++q) {
+        uint32_t idx[1 << D];
+        level_corners<D, POW2>(lv, l, smooth, xp[q], idx, wr[q], w0[q], u0[q]);
 #pragma unroll
-      for (int f = 0; f < F; ++f) acc[f] = 0.0f;
-#pragma unroll
-      for (uint32_t m = 0; m < (1u << D); ++m) {
-        const float wt = wr[m >> 1] * ((m & 1u) ? w0 : u0);
-#pragma unroll
-        for (int f = 0; f < F; ++f) acc[f] = fmaf(wt, (float)e[m].v[f], acc[f]);
+        for (uint32_t m = 0; m < (1u << D); ++m) e[q][m] = tab[idx[m]];
       }
 #pragma unroll
-      // (the compiler folds this conversion into the last multiply-add in some instantiations and
-      // not in others - one rounding instead of two - so two variants of the kernel may differ in
-      // the last bit of an fp16 output that is an exact tie)
-      for (int f = 0; f < F; ++f) out.v[F * j + f] = (IT)acc[f];
-      if constexpr (COUNT) {
-        if (valid) {
-          Rows<D> rw;
-          rows_of<D, true>(lv, ca.bp, l, smooth, xp, rw);
-          uint32_t* h = hist + (threadIdx.x / kBinThreads) * ca.n_bins;
+      for (int q = 0; q < SB; ++q) {
+        float acc[F];
 #pragma unroll
-          for (uint32_t r = 0; r < (1u << (D - 1)); ++r)
-            if (!rw.cross) __hip_atomic_fetch_add(&h[rw.bin[r]], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        for (int f = 0; f < F; ++f) acc[f] = 0.0f;
+#pragma unroll
+        for (uint32_t m = 0; m < (1u << D); ++m) {
+          const float wt = wr[q][m >> 1] * ((m & 1u) ? w0[q] : u0[q]);
+#pragma unroll
+          for (int f = 0; f < F; ++f) acc[f] = fmaf(wt, (float)e[q][m].v[f], acc[f]);
+        }
+#pragma unroll
+        // (the compiler folds this conversion into the last multiply-add in some instantiations and
+        // not in others - one rounding instead of two - so two variants of the kernel may differ in
+        // the last bit of an fp16 output that is an exact tie)
+        for (int f = 0; f < F; ++f) out[q].v[F * j + f] = (IT)acc[f];
+        if constexpr (COUNT) {
+          if (valid[q]) {
+            Rows<D> rw;
+            rows_of<D, true>(lv, ca.bp, l, smooth, xp[q], rw);
+            uint32_t* h = hist + (q * (kPmBlock / kBinThreads) + threadIdx.x / kBinThreads) * ca.n_bins;
+#pragma unroll
+            for (uint32_t r = 0; r < (1u << (D - 1)); ++r)
+              if (!rw.cross)
+                __hip_atomic_fetch_add(&h[rw.bin[r]], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+          }
         }
       }
       asm volatile("" ::: "memory");  // keep the gathers of one level together
       __syncthreads();
     }
     const uint32_t piece = l0 / G;
-    if (Piece::kPair && (piece & 1u) == 0 && l0 + G < lv.L) {
-      held = out;  // even piece with a partner: keep it until the partner is ready
-    } else if (valid) {
-      if (Piece::kPair && (piece & 1u)) yrow[piece - 1] = held;
-      yrow[piece] = out;
+#pragma unroll
+    for (int q = 0; q < SB; ++q) {
+      if (Piece::kPair && (piece & 1u) == 0 && l0 + G < lv.L) {
+        held[q] = out[q];  // even piece with a partner: keep it until the partner is ready
+      } else if (valid[q]) {
+        if (Piece::kPair && (piece & 1u)) yrow[q][piece - 1] = held[q];
+        yrow[q][piece] = out[q];
+      }
     }
   }
   if constexpr (COUNT) {  // the last level's barrier has passed: the histograms are complete
@@ -461,6 +483,9 @@ static inline size_t dtype_size(uint32_t t) { return t == HG_F16 ? 2 : 4; }
 
 static hg_status launched() { return hipGetLastError() == hipSuccess ? HG_OK : HG_ERR_DEVICE; }
 
+// Two points per thread once the batch needs two or more rounds of full workgroups per CU
+static bool fwd_two_points_per_thread(uint32_t B) { return (uint64_t)B >= 2ull * kPmBlock * cu_count(); }
+
 template <int D, int F, typename PT, typename IT>
 static hg_status launch_fwd(const hashgrid* h, uint32_t B, const float* x, const void* params, void* y,
                             hipStream_t s) {
@@ -470,7 +495,11 @@ static hg_status launch_fwd(const hashgrid* h, uint32_t B, const float* x, const
       const uint32_t block = point_major_block(B);
       const dim3 grid((B + block - 1) / block);
       const bool smooth = h->cfg.interp == HG_INTERP_SMOOTHSTEP;
-      if (h->lv.T_is_pow2)
+      if (h->lv.T_is_pow2 && fwd_two_points_per_thread(B))
+        hipLaunchKernelGGL((fwd_point_major<D, F, PT, IT, true, false, 2>), dim3((B + 2 * kPmBlock - 1) / (2 * kPmBlock)),
+                           dim3(kPmBlock), 0, s, h->lv, smooth, B, x, static_cast<const PT*>(params),
+                           static_cast<IT*>(y), NoCount{});
+      else if (h->lv.T_is_pow2)
         hipLaunchKernelGGL((fwd_point_major<D, F, PT, IT, true, false>), grid, dim3(block), 0, s, h->lv, smooth, B,
                            x, static_cast<const PT*>(params), static_cast<IT*>(y), NoCount{});
       else
@@ -529,7 +558,8 @@ template <int D, int F, typename PT, typename IT>
 static hg_status launch_fwd_counting_t(const hashgrid* h, uint32_t B, const float* x, const void* params, void* y,
                                        uint32_t* counts, uint32_t n_bins, uint32_t n_tiles, hipStream_t s) {
   constexpr uint32_t G = OutPiece<F, IT>::kLevels;
-  const size_t lds = (size_t)(kPmBlock / kBinThreads) * n_bins * 4;
+  const bool two = fwd_two_points_per_thread(B) && (size_t)(2 * kPmBlock / kBinThreads) * n_bins * 4 <= 64 * 1024;
+  const size_t lds = (size_t)((two ? 2 : 1) * kPmBlock / kBinThreads) * n_bins * 4;
   if (h->lv.L % G != 0 || misaligned(y, 16) || misaligned(params, F * sizeof(PT) > 16 ? 16 : F * sizeof(PT)) ||
       !h->lv.T_is_pow2 || lds > kMaxCountingLds || h->bp.tile_mult != 1)  // (its tiles are 512 points)
     return HG_ERR_UNSUPPORTED;
@@ -544,9 +574,14 @@ static hg_status launch_fwd_counting_t(const hashgrid* h, uint32_t B, const floa
   ca.counts = counts;
   ca.n_bins = n_bins;
   ca.n_tiles = n_tiles;
-  hipLaunchKernelGGL((fwd_point_major<D, F, PT, IT, true, true>), dim3((B + kPmBlock - 1) / kPmBlock), dim3(kPmBlock),
-                     lds, s, h->lv, h->cfg.interp == HG_INTERP_SMOOTHSTEP, B, x, static_cast<const PT*>(params),
-                     static_cast<IT*>(y), ca);
+  if (two)
+    hipLaunchKernelGGL((fwd_point_major<D, F, PT, IT, true, true, 2>), dim3((B + 2 * kPmBlock - 1) / (2 * kPmBlock)),
+                       dim3(kPmBlock), lds, s, h->lv, h->cfg.interp == HG_INTERP_SMOOTHSTEP, B, x,
+                       static_cast<const PT*>(params), static_cast<IT*>(y), ca);
+  else
+    hipLaunchKernelGGL((fwd_point_major<D, F, PT, IT, true, true>), dim3((B + kPmBlock - 1) / kPmBlock), dim3(kPmBlock),
+                       lds, s, h->lv, h->cfg.interp == HG_INTERP_SMOOTHSTEP, B, x, static_cast<const PT*>(params),
+                       static_cast<IT*>(y), ca);
   return launched();
 }
 

@@ -169,6 +169,12 @@ def test_headline_shape_with_other_feature_counts(F):
     assert grid.bwd_workspace_bytes(len(x)) > 0
 
 
+def test_two_rounds_of_workgroups_with_a_ragged_end():
+    # from 2^19 points on the forward kernel gives every thread two points; the batch ends inside
+    # a workgroup and inside a tile
+    workload_case("sdf3d", B=(1 << 19) + 1531, table_scale=1.0, do_indices=False)
+
+
 def test_nerf3d_full_size():
     workload_case("nerf3d", table_scale=1.0, do_indices=False)
 
