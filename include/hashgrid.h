@@ -182,6 +182,13 @@ hg_status hashgrid_encode_bwd_input(const hashgrid_t* hg, uint32_t B, const floa
 hg_status hashgrid_debug_indices(const hashgrid_t* hg, uint32_t B, const float* x, uint32_t level, uint32_t* idx,
                                  float* w, void* stream);
 
+/* The precondition of every call above, checked on request (Appendix E.1 bounds scenes to the unit
+ * cube; the kernels clamp instead of checking): adds to *count the number of coordinates of x that
+ * are not in [0,1), NaN and infinities included.
+ *   count  one uint32, device, 4-byte aligned, ADDED TO (clear it first) */
+hg_status hashgrid_debug_count_outside(const hashgrid_t* hg, uint32_t B, const float* x, uint32_t* count,
+                                       void* stream);
+
 /* Hyper-parameters of the optimiser step below (paper Section 4, "Training": Adam with
  * beta1 = 0.9, beta2 = 0.99, eps = 1e-15; learning rate 1e-2, 1e-4 for signed distance
  * functions; no weight decay on table entries). */

@@ -28,7 +28,7 @@ _TORCH = {HG_F32: torch.float32, HG_F16: torch.float16}
 
 EXPORTS = ("hashgrid_create", "hashgrid_destroy", "hashgrid_n_entries", "hashgrid_level_info",
            "hashgrid_encode_fwd", "hashgrid_encode_bwd", "hashgrid_encode_bwd_input",
-           "hashgrid_debug_indices", "hashgrid_strerror", "hashgrid_bwd_workspace_bytes",
+           "hashgrid_debug_indices", "hashgrid_debug_count_outside", "hashgrid_strerror", "hashgrid_bwd_workspace_bytes",
            "hashgrid_encode_bwd_ws", "hashgrid_encode_fwd_ws", "hashgrid_bwd_ws_pays", "hashgrid_adam_step",
            "hashgrid_encode_mlp_fwd", "hashgrid_probe_copy", "hashgrid_probe_gather",
            "hashgrid_probe_atomic_add")
@@ -77,6 +77,8 @@ def load_library() -> ctypes.CDLL:
     lib.hashgrid_encode_bwd_input.restype = ctypes.c_int
     lib.hashgrid_debug_indices.argtypes = [vp, u32, vp, u32, vp, vp, vp]
     lib.hashgrid_debug_indices.restype = ctypes.c_int
+    lib.hashgrid_debug_count_outside.argtypes = [vp, u32, vp, vp, vp]
+    lib.hashgrid_debug_count_outside.restype = ctypes.c_int
     lib.hashgrid_bwd_workspace_bytes.argtypes = [vp, u32]
     lib.hashgrid_bwd_workspace_bytes.restype = u64
     lib.hashgrid_encode_bwd_ws.argtypes = [vp, u32, vp, vp, vp, vp, u64, u32, vp]
@@ -269,6 +271,15 @@ class HashGrid:
             _dev(W3, torch.float16, (n_out, 64), "W3"), n_out, _dev(out, torch.float32, (B, n_out), "out"),
             _stream_ptr(stream)), "hashgrid_encode_mlp_fwd")
         return out
+
+    def debug_count_outside(self, x: torch.Tensor, stream=None) -> int:
+        """hashgrid_debug_count_outside: coordinates of x that are not in [0,1) (synchronises)."""
+        B = x.shape[0]
+        count = torch.zeros(1, dtype=torch.int32, device=x.device)
+        _check(self._lib.hashgrid_debug_count_outside(
+            self._h, B, _dev(x, torch.float32, (B, self.d), "x"), count.data_ptr(), _stream_ptr(stream)),
+            "hashgrid_debug_count_outside")
+        return int(count.item())
 
     def debug_indices(self, x: torch.Tensor, level: int, stream=None):
         B = x.shape[0]

@@ -417,6 +417,20 @@ __global__ __launch_bounds__(kBlock) void bwd_input_general(const LevelTable lv,
 }
 
 // The fp32 decisions of one level, for bit-exact comparison.
+// Precondition check for callers: how many of the B * d coordinates are not in [0,1) (NaN and
+// infinities included).  One atomic per wave that found any.
+__global__ __launch_bounds__(kBlock) void count_outside_unit(const uint64_t n, const float* __restrict__ x,
+                                                             uint32_t* __restrict__ count) {
+  uint32_t bad = 0;
+  for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (uint64_t)gridDim.x * kBlock) {
+    const float v = x[i];
+    bad += !(v >= 0.0f && v < 1.0f);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) bad += __shfl_xor(bad, o);
+  if ((threadIdx.x & 63) == 0 && bad) atomicAdd(count, bad);
+}
+
 template <int D>
 __global__ __launch_bounds__(kBlock) void indices_general(const LevelTable lv, const bool smooth, const uint32_t B,
                                                           const float* __restrict__ x, const uint32_t l,
@@ -744,6 +758,19 @@ hg_status hashgrid_debug_indices(const hashgrid_t* hg, uint32_t B, const float* 
     case 3: hipLaunchKernelGGL((hg::indices_general<3>), grid, dim3(hg::kBlock), 0, s, hg->lv, smooth, B, x, level, idx, w); break;
     default: return HG_ERR_UNSUPPORTED;
   }
+  return hg::launched();
+}
+
+hg_status hashgrid_debug_count_outside(const hashgrid_t* hg, uint32_t B, const float* x, uint32_t* count,
+                                       void* stream) {
+  if (!hg || !count || hg::misaligned(count, 4)) return HG_ERR_INVALID_ARG;
+  if (B == 0) return HG_OK;
+  if (B > HG_MAX_BATCH) return HG_ERR_UNSUPPORTED;
+  if (!x || hg::misaligned(x, 4)) return HG_ERR_INVALID_ARG;
+  const uint64_t n = (uint64_t)B * hg->cfg.d;
+  const uint64_t wgs = (n + hg::kBlock - 1) / hg::kBlock;
+  hipLaunchKernelGGL(hg::count_outside_unit, dim3((uint32_t)(wgs < 4096 ? wgs : 4096)), dim3(hg::kBlock), 0,
+                     static_cast<hipStream_t>(stream), n, x, count);
   return hg::launched();
 }
 

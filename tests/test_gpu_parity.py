@@ -410,6 +410,17 @@ def test_empty_batch_is_a_no_op():
     assert float(g.abs().max()) == 0.0
 
 
+def test_precondition_check_counts_coordinates_outside_the_unit_interval():
+    grid = HashGrid(3, 4, 2, 1 << 12, 4, 64)
+    rng = np.random.default_rng(2)
+    x = synth.points_uniform(rng, 100003, 3)
+    assert grid.debug_count_outside(dev(x)) == 0
+    x[5, 0], x[77, 2], x[4000, 1], x[99999, 0], x[100002, 2] = 1.0, -1e-9, np.nan, np.inf, 7.0
+    x[10, 1] = np.float32(1 - 2.0 ** -24)   # the largest float below 1 is inside
+    x[11, 1] = -0.0                          # and so is a negative zero
+    assert grid.debug_count_outside(dev(x)) == 5
+
+
 def test_out_of_range_positions_stay_in_bounds():
     # a violated precondition must not fault: values are unspecified, memory safety is not
     grid = HashGrid(3, 16, 2, 1 << 19, 16, 2048, "f32", "f32")

@@ -94,6 +94,9 @@ def test_null_and_empty_batches_need_no_device():
     assert lib.hashgrid_level_info(g._h, 4, None, None, None, None) == 1   # level out of range
     assert lib.hashgrid_level_info(g._h, 3, None, None, None, None) == 0
     assert lib.hashgrid_debug_indices(g._h, 8, None, 9, None, None, None) == 1
+    assert lib.hashgrid_debug_count_outside(g._h, 8, 4096, None, None) == 1   # no counter
+    assert lib.hashgrid_debug_count_outside(g._h, 8, None, 4096, None) == 1   # no points
+    assert lib.hashgrid_debug_count_outside(g._h, 0, None, 4096, None) == 0   # B = 0
     # misaligned pointers are rejected before any launch (F*sizeof = 8-byte vectors here)
     assert lib.hashgrid_encode_fwd(g._h, 8, 4096, 4100, 4096, None) == 1
 
