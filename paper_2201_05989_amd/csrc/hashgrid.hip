@@ -266,83 +266,99 @@ __global__ __launch_bounds__(kPmBlock) void fwd_point_major(const LevelTable lv,
 // are first contracted with dL/dy (s_m = sum_f g_f theta_m,f); the derivative of the d-linear
 // blend of the s_m then follows dimension by dimension: along a dimension with weights (u, w)
 // and slope dw, a pair (lower a, upper b) becomes value u a + w b and derivative dw (b - a).
-template <int D, int F, typename PT, typename IT, bool POW2>
+template <int D, int F, typename PT, typename IT, bool POW2, int SB = 1>  // SB: points per thread, as in fwd_point_major
 __global__ __launch_bounds__(kPmBlock) void bwd_input_point_major(const LevelTable lv, const bool smooth,
                                                                   const uint32_t B, const float* __restrict__ x,
                                                                   const PT* __restrict__ theta,
                                                                   const IT* __restrict__ dy, float* __restrict__ dx) {
   using Piece = OutPiece<F, IT>;
   constexpr int G = Piece::kLevels;
-  const uint32_t b0 = blockIdx.x * blockDim.x + threadIdx.x;
-  const bool valid = b0 < B;
-  const uint32_t b = valid ? b0 : B - 1;
-  float xp[D];
-  load_point<D>(x, b, xp);
-  const Vec<IT, F * G>* grow = reinterpret_cast<const Vec<IT, F * G>*>(dy + (uint64_t)b * lv.L * F);
-  float gx[D];
+  bool valid[SB];
+  uint32_t b[SB];
+  float xp[SB][D], gx[SB][D];
+  const Vec<IT, F * G>* grow[SB];
 #pragma unroll
-  for (int j = 0; j < D; ++j) gx[j] = 0.0f;
+  for (int q = 0; q < SB; ++q) {
+    const uint64_t b0 = ((uint64_t)blockIdx.x * SB + q) * blockDim.x + threadIdx.x;
+    valid[q] = b0 < B;
+    b[q] = valid[q] ? (uint32_t)b0 : B - 1;
+    load_point<D>(x, b[q], xp[q]);
+    grow[q] = reinterpret_cast<const Vec<IT, F * G>*>(dy + (uint64_t)b[q] * lv.L * F);
+#pragma unroll
+    for (int j = 0; j < D; ++j) gx[q][j] = 0.0f;
+  }
   const float shift = smooth ? 0.5f : 0.0f;
   for (uint32_t l0 = 0; l0 < lv.L; l0 += G) {
-    const Vec<IT, F * G> g = grow[l0 / G];
+    Vec<IT, F * G> g[SB];
+#pragma unroll
+    for (int q = 0; q < SB; ++q) g[q] = grow[q][l0 / G];
 #pragma unroll
     for (int j = 0; j < G; ++j) {
       const uint32_t l = l0 + j;
       const float Nf = (float)lv.N[l];
       const float cmaxf = smooth ? Nf : Nf - 1.0f;
-      uint32_t c0[D], idx[1 << D];
-      float w[D], u[D], dw[D];
-#pragma unroll
-      for (int i = 0; i < D; ++i) {
-        float wf;
-        split(xp[i], Nf, shift, cmaxf, c0[i], wf);
-        w[i] = smooth ? smoothstep(wf) : wf;
-        u[i] = smooth ? smoothstep(1.0f - wf) : 1.0f - wf;
-        dw[i] = smooth ? dsmoothstep(wf) * Nf : Nf;
-      }
-      if ((lv.dense_mask >> l) & 1u) {  // uniform
-        corner_indices_uniform<D, true>(c0, lv.verts[l], 0u, idx);
-      } else if (POW2) {
-        corner_indices_uniform<D, false>(c0, 0u, lv.T - 1u, idx);
-      } else {
-        const CornerTerms<D> ct = corner_terms<D>(c0, false, 0u);
-#pragma unroll
-        for (uint32_t m = 0; m < (1u << D); ++m) idx[m] = corner_index<D>(ct, m, false, lv.T, false);
-      }
       const Vec<PT, F>* tab = reinterpret_cast<const Vec<PT, F>*>(theta) + lv.offset[l];
-      Vec<PT, F> e[1 << D];
+      Vec<PT, F> e[SB][1 << D];
+      float w[SB][D], u[SB][D], dw[SB][D];
 #pragma unroll
-      for (uint32_t m = 0; m < (1u << D); ++m) e[m] = tab[idx[m]];
-      // val[m]: blend over the dimensions folded so far; der[i][m]: its derivative along dimension i
-      float val[1 << D], der[D][1 << D];
+      for (int q = 0; q < SB; ++q) {
+        uint32_t c0[D], idx[1 << D];
 #pragma unroll
-      for (uint32_t m = 0; m < (1u << D); ++m) {
-        float sm = 0.0f;
+        for (int i = 0; i < D; ++i) {
+          float wf;
+          split(xp[q][i], Nf, shift, cmaxf, c0[i], wf);
+          w[q][i] = smooth ? smoothstep(wf) : wf;
+          u[q][i] = smooth ? smoothstep(1.0f - wf) : 1.0f - wf;
+          dw[q][i] = smooth ? dsmoothstep(wf) * Nf : Nf;
+        }
+        if ((lv.dense_mask >> l) & 1u) {  // uniform
+          corner_indices_uniform<D, true>(c0, lv.verts[l], 0u, idx);
+        } else if (POW2) {
+          corner_indices_uniform<D, false>(c0, 0u, lv.T - 1u, idx);
+        } else {
+          const CornerTerms<D> ct = corner_terms<D>(c0, false, 0u);
 #pragma unroll
-        for (int f = 0; f < F; ++f) sm = fmaf((float)g.v[F * j + f], (float)e[m].v[f], sm);
-        val[m] = sm;
+          for (uint32_t m = 0; m < (1u << D); ++m) idx[m] = corner_index<D>(ct, m, false, lv.T, false);
+        }
+#pragma unroll
+        for (uint32_t m = 0; m < (1u << D); ++m) e[q][m] = tab[idx[m]];
       }
 #pragma unroll
-      for (int i = 0; i < D; ++i) {        // fold dimension i: corners m (bit i clear) and m | 1<<i
+      for (int q = 0; q < SB; ++q) {
+        // val[m]: blend over the dimensions folded so far; der[i][m]: its derivative along dimension i
+        float val[1 << D], der[D][1 << D];
 #pragma unroll
         for (uint32_t m = 0; m < (1u << D); ++m) {
-          if (m & ((2u << i) - 1u)) continue;  // representatives: bits 0..i clear
-          const uint32_t hi = m | (1u << i);
+          float sm = 0.0f;
 #pragma unroll
-          for (int k = 0; k < i; ++k) der[k][m] = u[i] * der[k][m] + w[i] * der[k][hi];
-          der[i][m] = dw[i] * (val[hi] - val[m]);
-          val[m] = u[i] * val[m] + w[i] * val[hi];
+          for (int f = 0; f < F; ++f) sm = fmaf((float)g[q].v[F * j + f], (float)e[q][m].v[f], sm);
+          val[m] = sm;
         }
-      }
 #pragma unroll
-      for (int i = 0; i < D; ++i) gx[i] += der[i][0];
+        for (int i = 0; i < D; ++i) {        // fold dimension i: corners m (bit i clear) and m | 1<<i
+#pragma unroll
+          for (uint32_t m = 0; m < (1u << D); ++m) {
+            if (m & ((2u << i) - 1u)) continue;  // representatives: bits 0..i clear
+            const uint32_t hi = m | (1u << i);
+#pragma unroll
+            for (int k = 0; k < i; ++k) der[k][m] = u[q][i] * der[k][m] + w[q][i] * der[k][hi];
+            der[i][m] = dw[q][i] * (val[hi] - val[m]);
+            val[m] = u[q][i] * val[m] + w[q][i] * val[hi];
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < D; ++i) gx[q][i] += der[i][0];
+      }
       asm volatile("" ::: "memory");
       __syncthreads();
     }
   }
-  if (valid) {
 #pragma unroll
-    for (int i = 0; i < D; ++i) dx[(uint64_t)b * D + i] = gx[i];
+  for (int q = 0; q < SB; ++q) {
+    if (valid[q]) {
+#pragma unroll
+      for (int i = 0; i < D; ++i) dx[(uint64_t)b[q] * D + i] = gx[q][i];
+    }
   }
 }
 
@@ -538,7 +554,11 @@ static hg_status launch_bwd_input(const hashgrid* h, uint32_t B, const float* x,
       const uint32_t block = point_major_block(B);
       const dim3 pm_grid((B + block - 1) / block);
       const bool smooth = h->cfg.interp == HG_INTERP_SMOOTHSTEP;
-      if (h->lv.T_is_pow2)
+      if (h->lv.T_is_pow2 && fwd_two_points_per_thread(B))
+        hipLaunchKernelGGL((bwd_input_point_major<D, F, PT, IT, true, 2>),
+                           dim3((B + 2 * kPmBlock - 1) / (2 * kPmBlock)), dim3(kPmBlock), 0, s, h->lv, smooth, B, x,
+                           static_cast<const PT*>(params), static_cast<const IT*>(dy), dx);
+      else if (h->lv.T_is_pow2)
         hipLaunchKernelGGL((bwd_input_point_major<D, F, PT, IT, true>), pm_grid, dim3(block), 0, s, h->lv, smooth,
                            B, x, static_cast<const PT*>(params), static_cast<const IT*>(dy), dx);
       else
