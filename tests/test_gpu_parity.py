@@ -175,6 +175,20 @@ def test_two_rounds_of_workgroups_with_a_ragged_end():
     workload_case("sdf3d", B=(1 << 19) + 1531, table_scale=1.0, do_indices=False)
 
 
+def test_sixteen_million_points_on_small_tables():
+    # 2^24 + 3 points: 32 K tiles, 64 rounds of workgroups, every chunk shared by the maximum number
+    # of accumulate workgroups, 64-bit offsets into x and y
+    d, L, F, T, N_min, N_max = 2, 2, 2, 1 << 10, 4, 64
+    cfg = orc.OracleConfig(d, L, F, T, N_min, N_max)
+    lv = orc.levels(cfg)
+    rng = np.random.default_rng(12)
+    B = (1 << 24) + 3
+    x = synth.points_uniform(rng, B, d)
+    theta = synth.make_tables(rng, lv.total, F, "f32", 1.0)
+    dy = synth.make_dy(rng, B, L * F, "f32")
+    run_case(d, L, F, T, N_min, N_max, "f32", "f32", 0, x, theta, dy, do_indices=False)
+
+
 def test_nerf3d_full_size():
     workload_case("nerf3d", table_scale=1.0, do_indices=False)
 
