@@ -1085,7 +1085,7 @@ static hg_status launch_binned_f(const hashgrid* h, uint32_t B, const float* x, 
 extern "C" {
 
 uint64_t hashgrid_bwd_workspace_bytes(const hashgrid_t* hg, uint32_t B) {
-  if (!hg || !hg->bp.supported || B == 0) return 0;
+  if (!hg || !hg->bp.supported || B == 0 || B > HG_MAX_BATCH) return 0;
   if ((uint64_t)B * hg->lv.L * hg->bp.rec_per_point >= (1ull << 32)) return 0;
   return hg::carve(hg, B, nullptr, nullptr);
 }

@@ -97,6 +97,13 @@ def test_null_and_empty_batches_need_no_device():
     assert lib.hashgrid_debug_count_outside(g._h, 8, 4096, None, None) == 1   # no counter
     assert lib.hashgrid_debug_count_outside(g._h, 8, None, 4096, None) == 1   # no points
     assert lib.hashgrid_debug_count_outside(g._h, 0, None, 4096, None) == 0   # B = 0
+    # more than HG_MAX_BATCH (2^28) points per call: refused before anything is launched
+    big = (1 << 28) + 1
+    assert lib.hashgrid_encode_fwd(g._h, big, 4096, 4096, 4096, None) == 2
+    assert lib.hashgrid_encode_bwd(g._h, big, 4096, 4096, 4096, None) == 2
+    assert lib.hashgrid_encode_bwd_input(g._h, big, 4096, 4096, 4096, 4096, None) == 2
+    assert lib.hashgrid_debug_indices(g._h, big, 4096, 0, 4096, 4096, None) == 2
+    assert lib.hashgrid_bwd_workspace_bytes(g._h, big) == 0
     # misaligned pointers are rejected before any launch (F*sizeof = 8-byte vectors here)
     assert lib.hashgrid_encode_fwd(g._h, 8, 4096, 4100, 4096, None) == 1
 
