@@ -40,9 +40,12 @@
  *     dense stride use N_l + 2 in place of N_l + 1 for this variant.  (The
  *     appendix does not say how the shifted grid is indexed; this is the
  *     reading taken here.  The smoothstep weights and their derivative are
- *     pinned by closed forms; which entry a vertex of the shifted grid maps to
- *     on a 1:1 level is a choice nothing in the paper fixes: parity unpinned
- *     for that choice only.)
+ *     pinned by closed forms, and what this reading computes is pinned too
+ *     (vertex exactness at x = (k - 1/2)/N_l, the map being one-to-one onto
+ *     (N_l+2)^d entries, every corner's entry against the formula in integers).
+ *     That the paper means this map and not another 1:1 map of the shifted grid
+ *     is a choice nothing in the paper fixes: parity unpinned for that choice
+ *     only.)
  */
 #include <math.h>
 #include <stdint.h>
@@ -292,12 +295,12 @@ int hgo_indices(const hgo_config* c, uint64_t B, const float* x, uint32_t l, uin
   if (hgo_check_x(B * c->d, x)) return -2;
   const uint32_t d = c->d;
   for (uint64_t b = 0; b < B; ++b) {
-    uint32_t c0[HGO_MAX_D];
-    for (uint32_t i = 0; i < d; ++i) hgo_split(x[b * d + i], lv.N[l], c->interp, &c0[i], &w[b * d + i]);
-    for (uint32_t m = 0; m < (1u << d); ++m) {
-      uint32_t v[HGO_MAX_D];
-      for (uint32_t i = 0; i < d; ++i) v[i] = c0[i] + ((m >> i) & 1u);
-      idx[b * (1u << d) + m] = hgo_index(d, lv.verts[l], c->T, lv.dense[l], v);
+    /* the entries are the ones the forward and backward passes use: same routine */
+    double wt[1 << HGO_MAX_D];
+    hgo_corners(c, &lv, l, x + b * d, idx + b * (1u << d), wt, NULL);
+    for (uint32_t i = 0; i < d; ++i) {
+      uint32_t c0;
+      hgo_split(x[b * d + i], lv.N[l], c->interp, &c0, &w[b * d + i]);
     }
   }
   return 0;

@@ -407,3 +407,126 @@ def test_smoothstep_closed_forms():
     # and equals S'(1/2) * N * (difference) = 1.5 N (theta[k+1] - theta[k]) halfway
     dmid = orc.encode_bwd_input(cfg, xm.reshape(-1, 1), theta, np.ones((N - 1, 1)))[:, 0]
     np.testing.assert_allclose(dmid, 1.5 * N * (theta[2:N + 1, 0] - theta[1:N, 0]), rtol=1e-13)
+
+
+# ----------------------------------------------------------------------------- the entry every corner maps to
+
+_PRIMES = (1, 2654435761, 805459861)
+
+
+def _entry_bigint(v, verts, T, dense):
+    """Section 3 / Eq. 4 for one integer vertex, in Python integers: the 1:1 map
+    v_0 + v_1 V + v_2 V^2 on a coarse level, else XOR_i (v_i pi_i mod 2^32) mod T."""
+    if dense:
+        return sum(int(vi) * verts ** i for i, vi in enumerate(v))
+    h = 0
+    for i, vi in enumerate(v):
+        h ^= (int(vi) * _PRIMES[i]) & 0xFFFFFFFF
+    return h % T
+
+
+@pytest.mark.parametrize("interp", [0, 1])
+@pytest.mark.parametrize("d,L,T,N_min,N_max", [(1, 5, 40, 4, 300), (2, 6, 1 << 10, 4, 200), (3, 6, 1 << 12, 4, 100),
+                                               (2, 5, 1000, 3, 97), (3, 5, 12345, 5, 80), (3, 16, 1 << 19, 16, 2048)])
+def test_corner_entries_match_bigint_formulas_corner_by_corner(d, L, T, N_min, N_max, interp):
+    # corner m is the upper corner along dimension i exactly when bit i of m is set (the order the
+    # GPU library's debug call is compared in, bit for bit); the vertex it stands for is
+    # floor(p) + bits with p = x N_l (+ 1/2 for Appendix A), evaluated here in fp32 by numpy
+    cfg = OracleConfig(d, L, 2, T, N_min, N_max, interp)
+    lv = orc.levels(cfg)
+    assert lv.dense.any() and not lv.dense.all()
+    x = np.random.default_rng(20 + d + 10 * interp).random((300, d)).astype(np.float32)
+    for l in range(L):
+        N, V = int(lv.N[l]), int(lv.N[l]) + 1 + interp
+        assert int(lv.verts[l]) == V
+        p = x * np.float32(N)
+        if interp:
+            p = p + np.float32(0.5)
+        c0 = np.floor(p).astype(np.int64)
+        idx, w = orc.indices(cfg, x, l)
+        np.testing.assert_array_equal(w, p - np.floor(p))
+        for b in range(len(x)):
+            for m in range(1 << d):
+                v = [int(c0[b, i]) + ((m >> i) & 1) for i in range(d)]
+                assert int(idx[b, m]) == _entry_bigint(v, V, T, bool(lv.dense[l])), (l, b, m)
+        assert int(idx.max()) < int(lv.size[l])
+
+
+@pytest.mark.parametrize("interp", [0, 1])
+@pytest.mark.parametrize("d", [1, 2, 3])
+def test_forward_rebuilt_from_reported_entries_and_positions(d, interp):
+    # sum_m weight_m theta[idx_m], with idx_m and the fractional positions as the oracle reports them and
+    # the weights of Section 3 (Appendix A: S(w)) formed here, is the oracle's forward: the reported
+    # entries are the ones the passes use, in the documented corner order
+    cfg = OracleConfig(d, 5, 3, 1 << 9, 3, 150, interp)
+    lv, x, theta = _rand_cfg_inputs(cfg, 400, 30 + d)
+    y = orc.encode_fwd(cfg, x, theta)
+    for l in range(cfg.L):
+        idx, w = orc.indices(cfg, x, l)
+        w = w.astype(np.float64)
+        if interp:
+            w = w * w * (3.0 - 2.0 * w)
+        acc = np.zeros((len(x), cfg.F))
+        for m in range(1 << d):
+            wt = np.ones(len(x))
+            for i in range(d):
+                wt = wt * (w[:, i] if (m >> i) & 1 else 1.0 - w[:, i])
+            acc += wt[:, None] * theta[int(lv.offset[l]) + idx[:, m].astype(np.int64)]
+        np.testing.assert_allclose(y[:, l * cfg.F:(l + 1) * cfg.F], acc, rtol=0, atol=1e-14)
+
+
+# ----------------------------------------------------------------------------- Appendix A on 1:1 levels, d >= 2
+
+@pytest.mark.parametrize("d,N", [(2, 8), (3, 4), (3, 8)])
+def test_shifted_grid_vertex_exactness_and_one_to_one_map(d, N):
+    # Appendix A shifts every level by half a voxel: vertex k of the shifted grid sits at
+    # x = (k - 1/2)/N_l (exact in fp32 for a power-of-two N_l), k = 0 .. N_l+1.  At such a point the
+    # output is the table entry of that vertex (S(0) = 0), and on a 1:1 level the entry of vertex v is
+    # v_0 + v_1 (N_l+2) + v_2 (N_l+2)^2: every entry holds its own index here, so any other stride shows.
+    V = N + 2
+    cfg = OracleConfig(d, 1, 1, V ** d, N, N, 1)
+    lv = orc.levels(cfg)
+    assert lv.dense[0] and int(lv.size[0]) == V ** d and int(lv.verts[0]) == V
+    theta = np.arange(V ** d, dtype=np.float64).reshape(-1, 1)
+    grids = np.meshgrid(*[np.arange(1, N + 1)] * d, indexing="ij")  # vertices with x = (k - 1/2)/N in [0,1)
+    k = np.stack([g.ravel() for g in grids], axis=1)
+    x = ((k - 0.5) / N).astype(np.float32)
+    y = orc.encode_fwd(cfg, x, theta)[:, 0]
+    expect = sum(k[:, i] * V ** i for i in range(d))
+    np.testing.assert_array_equal(y, expect.astype(np.float64))
+    # every voxel of the shifted grid, one point each: the corners seen cover all (N+2)^d vertices and
+    # the map vertex -> entry is a bijection onto 0 .. (N+2)^d - 1
+    grids = np.meshgrid(*[np.arange(0, N + 1)] * d, indexing="ij")
+    c = np.stack([g.ravel() for g in grids], axis=1)
+    xv = np.where(c == 0, 0.1 / N, (c - 0.25) / N).astype(np.float32)  # p = x N + 1/2 lies inside voxel c
+    assert (xv < 1).all()
+    idx, w = orc.indices(cfg, xv, 0)
+    seen = {}
+    for b in range(len(c)):
+        for m in range(1 << d):
+            v = tuple(int(c[b, i]) + ((m >> i) & 1) for i in range(d))
+            assert seen.setdefault(v, int(idx[b, m])) == int(idx[b, m])
+    assert len(seen) == V ** d and sorted(seen.values()) == list(range(V ** d))
+    for v, e in seen.items():
+        assert e == sum(vi * V ** i for i, vi in enumerate(v))
+
+
+def test_shifted_grid_dense_criterion_uses_its_own_vertex_count():
+    # (N_l+2)^d <= T decides 1:1 for Appendix A's grid: N = 15, d = 2: 16^2 = 256 fits T = 256 without
+    # the shift, 17^2 = 289 does not with it
+    assert orc.levels(OracleConfig(2, 1, 1, 256, 15, 15, 0)).dense[0]
+    assert not orc.levels(OracleConfig(2, 1, 1, 256, 15, 15, 1)).dense[0]
+    assert orc.levels(OracleConfig(2, 1, 1, 289, 15, 15, 1)).dense[0]
+
+
+@pytest.mark.parametrize("d", [2, 3])
+def test_shifted_grid_backward_puts_unit_mass_on_the_vertex_entry(d):
+    # the backward pass of a point that sits on a vertex of the shifted grid adds dL/dy to that
+    # vertex's entry and to no other (weights 1 and 0)
+    N, V = 8, 10
+    cfg = OracleConfig(d, 1, 1, V ** d, N, N, 1)
+    k = np.array([[3, 7, 1][:d]])
+    x = ((k - 0.5) / N).astype(np.float32)
+    g = orc.encode_bwd(cfg, x, np.array([[2.5]]))
+    e = sum(int(k[0, i]) * V ** i for i in range(d))
+    assert g[e, 0] == 2.5 and np.count_nonzero(g) == 1
