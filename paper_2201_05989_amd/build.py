@@ -31,13 +31,28 @@ def hipcc() -> str:
 
 
 def build_library(verbose: bool = False, extra_flags=(), out: str | None = None) -> str:
-    srcs = [os.path.join(CSRC, s) for s in SOURCES]
+    """Compiles every source (one hipcc process each, side by side) and links the shared library."""
+    import tempfile
+    from concurrent.futures import ThreadPoolExecutor
+
     out = out or LIB_PATH
     tmp = out + f".tmp{os.getpid()}"
-    cmd = [hipcc(), *HIPCC_FLAGS, *extra_flags, f"-I{INCLUDE}", f"-I{CSRC}", "-o", tmp, *srcs]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    with tempfile.TemporaryDirectory(prefix="hashgrid_obj_") as objdir:
+        def compile_one(src):
+            obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
+            cmd = [hipcc(), *flags, *extra_flags, f"-I{INCLUDE}", f"-I{CSRC}", "-c", "-o", obj, os.path.join(CSRC, src)]
+            if verbose:
+                print(" ".join(cmd), flush=True)
+            subprocess.run(cmd, check=True)
+            return obj
+
+        with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 1)) as pool:
+            objs = list(pool.map(compile_one, SOURCES))
+        link = [hipcc(), "--offload-arch=gfx950", "-fPIC", "-shared", "-o", tmp, *objs]
+        if verbose:
+            print(" ".join(link), flush=True)
+        subprocess.run(link, check=True)
     os.replace(tmp, out)
     return out
 
