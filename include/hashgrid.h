@@ -155,6 +155,23 @@ hg_status hashgrid_encode_bwd_ws(const hashgrid_t* hg, uint32_t B, const float* 
                                  float* grad_params, void* workspace, uint64_t workspace_bytes, uint32_t flags,
                                  void* stream);
 
+/* hashgrid_encode_bwd_ws for callers that cannot allocate and have no scratch buffer to pass: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * result and error codes, minus the workspace: the scratch is a fixed array of
+ * HG_STATIC_SCRATCH_BYTES in device memory that belongs to the library (each GPU the library runs on
+ * holds its own copy from the time the library is loaded until the process ends).  The call itself
+ * allocates and frees nothing, on the host or on the device.
+ *   flags  0 or HG_BWD_OVERWRITE (HG_BWD_COUNTED needs a caller-owned workspace: HG_ERR_INVALID_ARG)
+ * Returns HG_ERR_UNSUPPORTED when hashgrid_bwd_workspace_bytes(hg, B) is 0 or larger than
+ * HG_STATIC_SCRATCH_BYTES (at Table 1's sizes: batches beyond about 87 000 points), HG_ERR_DEVICE
+ * when the array cannot be located on the current device.
+ * All calls on one GPU share that GPU's array: two calls that overlap in time on one GPU (different
+ * streams, or different threads) race; calls on one stream, or otherwise ordered, are fine.  The
+ * array keeps what the last call left; nothing in it needs clearing between calls. */
+#define HG_STATIC_SCRATCH_BYTES (64u << 20)
+hg_status hashgrid_encode_bwd_static(const hashgrid_t* hg, uint32_t B, const float* x, const void* dLdy,
+                                     float* grad_params, uint32_t flags, void* stream);
+
 /* Forward pass, the arithmetic of hashgrid_encode_fwd (Section 3; Fig. 3 steps 1-4; an fp16 output
  * that is an exact tie may differ from that call's in its last bit), that also does
  * the first step of hashgrid_encode_bwd_ws for the same points while it gathers: it counts, per

@@ -22,6 +22,7 @@ HG_MAX_LEVELS = 32
 HG_BWD_COUNTED = 1
 HG_BWD_OVERWRITE = 2
 HG_ERR_UNSUPPORTED = 2
+HG_STATIC_SCRATCH_BYTES = 64 << 20
 
 _DTYPES = {"f32": HG_F32, "f16": HG_F16, torch.float32: HG_F32, torch.float16: HG_F16}
 _TORCH = {HG_F32: torch.float32, HG_F16: torch.float16}
@@ -30,7 +31,7 @@ EXPORTS = ("hashgrid_create", "hashgrid_destroy", "hashgrid_n_entries", "hashgri
            "hashgrid_encode_fwd", "hashgrid_encode_bwd", "hashgrid_encode_bwd_input",
            "hashgrid_debug_indices", "hashgrid_debug_count_outside", "hashgrid_strerror", "hashgrid_bwd_workspace_bytes",
            "hashgrid_encode_bwd_ws", "hashgrid_encode_fwd_ws", "hashgrid_bwd_ws_pays", "hashgrid_adam_step",
-           "hashgrid_encode_mlp_fwd", "hashgrid_probe_copy", "hashgrid_probe_gather",
+           "hashgrid_encode_mlp_fwd", "hashgrid_encode_bwd_static", "hashgrid_probe_copy", "hashgrid_probe_gather",
            "hashgrid_probe_atomic_add")
 
 
@@ -82,6 +83,8 @@ def load_library() -> ctypes.CDLL:
     lib.hashgrid_bwd_workspace_bytes.argtypes = [vp, u32]
     lib.hashgrid_bwd_workspace_bytes.restype = u64
     lib.hashgrid_encode_bwd_ws.argtypes = [vp, u32, vp, vp, vp, vp, u64, u32, vp]
+    lib.hashgrid_encode_bwd_static.argtypes = [vp, u32, vp, vp, vp, u32, vp]
+    lib.hashgrid_encode_bwd_static.restype = ctypes.c_int
     lib.hashgrid_encode_fwd_ws.argtypes = [vp, u32, vp, vp, vp, vp, u64, vp]
     lib.hashgrid_encode_fwd_ws.restype = ctypes.c_int
     lib.hashgrid_encode_mlp_fwd.argtypes = [vp, u32, vp, vp, vp, vp, vp, u32, vp, vp]
@@ -243,6 +246,18 @@ class HashGrid:
             _dev(dLdy, self.io_dtype, (B, self.L * self.F), "dLdy"),
             _dev(grad_params, torch.float32, (self.n_entries, self.F), "grad_params"), _stream_ptr(stream)),
             "hashgrid_encode_bwd")
+        return grad_params
+
+    def encode_bwd_static(self, x: torch.Tensor, dLdy: torch.Tensor, grad_params: torch.Tensor, stream=None,
+                          overwrite: bool = False):
+        """hashgrid_encode_bwd_static: the sorted backward pass on the library's own fixed scratch array
+        (no workspace, no allocation inside the call); grad_params must be given."""
+        B = x.shape[0]
+        _check(self._lib.hashgrid_encode_bwd_static(
+            self._h, B, _dev(x, torch.float32, (B, self.d), "x"),
+            _dev(dLdy, self.io_dtype, (B, self.L * self.F), "dLdy"),
+            _dev(grad_params, torch.float32, (self.n_entries, self.F), "grad_params"),
+            HG_BWD_OVERWRITE if overwrite else 0, _stream_ptr(stream)), "hashgrid_encode_bwd_static")
         return grad_params
 
     def encode_bwd_input(self, x: torch.Tensor, params: torch.Tensor, dLdy: torch.Tensor,

@@ -47,6 +47,7 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <atomic>
 #include <type_traits>
 
 #include "hashgrid.h"
@@ -1158,6 +1159,50 @@ hg_status hashgrid_encode_bwd_ws(const hashgrid_t* hg, uint32_t B, const float* 
                : hg::launch_binned_f<3, float>(hg, B, x, dLdy, grad_params, ws, counted, ow, s);
   return i16 ? hg::launch_binned_f<2, _Float16>(hg, B, x, dLdy, grad_params, ws, counted, ow, s)
              : hg::launch_binned_f<2, float>(hg, B, x, dLdy, grad_params, ws, counted, ow, s);
+}
+
+// ---------------------------------------------------------------- entry point that allocates nothing
+//
+// For callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses that
+// forbid hipMalloc) and have no workspace to hand over: the scratch of the sorted pass lives in a
+// fixed device array that every GPU holds from the moment the library is loaded.
+static __device__ __align__(256) unsigned char scratch[HG_STATIC_SCRATCH_BYTES];
+
+namespace hg {
+constexpr int kMaxDevices = 64;
+// Device address of `scratch` on each GPU (every GPU has its own copy of the array at its own
+// address); looked up once per device, with that device current.  In host code the array's name is
+// only a handle for this lookup, never an address a kernel could use.
+static void* static_scratch_of_current_device() {
+  static std::atomic<void*> ptr_of[kMaxDevices];
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  void* p = ptr_of[dev].load(std::memory_order_acquire);
+  if (!p) {
+    void* q = nullptr;
+    if (hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)) != hipSuccess || !q) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    ptr_of[dev].store(q, std::memory_order_release);  // (two threads racing here store the same address)
+    p = q;
+  }
+  return p;
+}
+}  // namespace hg
+
+hg_status hashgrid_encode_bwd_static(const hashgrid_t* hg, uint32_t B, const float* x, const void* dLdy,
+                                     float* grad_params, uint32_t flags, void* stream) {
+  if (!hg || (flags & ~(uint32_t)HG_BWD_OVERWRITE)) return HG_ERR_INVALID_ARG;
+  if (B == 0) return HG_OK;
+  const uint64_t need = hashgrid_bwd_workspace_bytes(hg, B);
+  if (need == 0 || need > HG_STATIC_SCRATCH_BYTES) return HG_ERR_UNSUPPORTED;  // batch too large for the fixed array
+  void* ws = hg::static_scratch_of_current_device();
+  if (!ws) return HG_ERR_DEVICE;
+  // every word of the scratch that a kernel reads is written earlier in the same call (counts by
+  // bin_count, totals and the work counter by bin_scan, offsets, records and maxima by bin_scatter),
+  // so what the previous call left behind needs no clearing
+  return hashgrid_encode_bwd_ws(hg, B, x, dLdy, grad_params, ws, HG_STATIC_SCRATCH_BYTES, flags, stream);
 }
 
 }  // extern "C"

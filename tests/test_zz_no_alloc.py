@@ -1,0 +1,94 @@
+"""hashgrid_encode_bwd_static (the sorted backward pass on the library's own fixed scratch array, for callers
+that cannot allocate) against hashgrid_encode_bwd_ws, through the C ABI: two calls in a row, the second
+with a smaller batch, so that the second call runs over what the first one left in the array.
+
+Bar: the two entry points run the same kernels; where one workgroup owns a chunk of the gradient the
+sums are exact fixed point and the results are bit-equal, on the few coarse 1:1 levels whose chunks are
+shared the fp32 atomic order varies: both are held to the backward bar of the parity suite against the
+oracle, |g - g*| <= 1e-5 A + M 2^(H-54) + 2^-23 G (see test_gpu_parity.py).
+"""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import hashgrid_oracle as orc
+from paper_2201_05989_amd import HashGrid, binding, synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _floor(dy, B):
+    H = max(3 + int(np.ceil(np.log2(max(B, 2)))), 11)
+    return float(np.abs(dy.astype(np.float64)).max()) * 2.0 ** (H - 54)
+
+
+def _corner_abs_sum(cfg, lv, x, dy):
+    a = np.abs(dy.astype(np.float64)).reshape(len(x), cfg.L, cfg.F)
+    G = np.zeros((lv.total, cfg.F))
+    for l in range(cfg.L):
+        idx, _ = orc.indices(cfg, x, l)
+        flat = idx.astype(np.int64).ravel()
+        for f in range(cfg.F):
+            G[int(lv.offset[l]):int(lv.offset[l]) + int(lv.size[l]), f] = np.bincount(
+                flat, weights=np.repeat(a[:, l, f], idx.shape[1]), minlength=int(lv.size[l]))
+    return G
+
+
+def test_static_scratch_backward_matches_workspace_backward_twice_in_a_row():
+    w = synth.WORKLOADS["sdf3d"]
+    cfg = orc.OracleConfig(w.d, w.L, w.F, w.T, w.N_min, w.N_max)
+    lv = orc.levels(cfg)
+    grid = HashGrid(w.d, w.L, w.F, w.T, w.N_min, w.N_max, w.param_dtype, w.io_dtype)
+    lib = binding.load_library()
+    for B in (40000 + 77, 9000 + 5):  # several tiles and a ragged tail; the second batch is the smaller one
+        need = grid.bwd_workspace_bytes(B)
+        assert 0 < need <= binding.HG_STATIC_SCRATCH_BYTES
+        x, _, dy = synth.make_inputs(w, grid.n_entries, B=B)
+        xd, gd = torch.from_numpy(x).cuda(), torch.from_numpy(dy).cuda()
+        g_ws = torch.zeros((grid.n_entries, w.F), dtype=torch.float32, device="cuda")
+        g_st = torch.zeros_like(g_ws)
+        ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+        s = torch.cuda.current_stream().cuda_stream
+        # raw C ABI calls: plain pointers and sizes
+        st = lib.hashgrid_encode_bwd_ws(grid._h, B, xd.data_ptr(), gd.data_ptr(), g_ws.data_ptr(), ws.data_ptr(),
+                                        ctypes.c_uint64(need), 0, s)
+        assert st == 0
+        st = lib.hashgrid_encode_bwd_static(grid._h, B, xd.data_ptr(), gd.data_ptr(), g_st.data_ptr(), 0, s)
+        assert st == 0
+        torch.cuda.synchronize()
+        a, b = g_ws.cpu().numpy(), g_st.cpu().numpy()
+        g_ref = orc.encode_bwd(cfg, x, dy)
+        g_abs = orc.encode_bwd(cfg, x, np.abs(dy.astype(np.float64)))
+        bound = 1e-5 * g_abs + 1e-30 + _floor(dy, B) + 2.0 ** -23 * _corner_abs_sum(cfg, lv, x, dy)
+        for g in (a, b):
+            assert (np.abs(g.astype(np.float64) - g_ref) <= bound).all()
+            assert (g[g_abs == 0] == 0).all()
+        # one owner per chunk: exact, order-independent sums -> the two entry points agree bit for bit
+        # (the fine levels of this configuration; the plan gives them one workgroup per chunk)
+        fine = int(lv.offset[8])
+        assert np.array_equal(a[fine:], b[fine:])
+        # adding again into the same buffer doubles it, and HG_BWD_OVERWRITE replaces it
+        g2 = g_st.clone()
+        assert lib.hashgrid_encode_bwd_static(grid._h, B, xd.data_ptr(), gd.data_ptr(), g2.data_ptr(), 2, s) == 0
+        torch.cuda.synchronize()
+        assert (np.abs(g2.cpu().numpy().astype(np.float64) - g_ref) <= bound).all()
+
+
+def test_static_scratch_backward_rejects_what_it_cannot_serve():
+    w = synth.WORKLOADS["sdf3d"]
+    grid = HashGrid(w.d, w.L, w.F, w.T, w.N_min, w.N_max, w.param_dtype, w.io_dtype)
+    lib = binding.load_library()
+    B = 1 << 18
+    assert grid.bwd_workspace_bytes(B) > binding.HG_STATIC_SCRATCH_BYTES
+    x = torch.zeros((B, 3), device="cuda")
+    dy = torch.zeros((B, 32), dtype=torch.float16, device="cuda")
+    g = torch.zeros((grid.n_entries, 2), device="cuda")
+    assert lib.hashgrid_encode_bwd_static(grid._h, B, x.data_ptr(), dy.data_ptr(), g.data_ptr(), 0, None) == 2
+    assert lib.hashgrid_encode_bwd_static(grid._h, 4096, x.data_ptr(), dy.data_ptr(), g.data_ptr(), 1, None) == 1  # COUNTED
+    assert lib.hashgrid_encode_bwd_static(grid._h, 0, None, None, None, 0, None) == 0
+    assert lib.hashgrid_encode_bwd_static(grid._h, 4096, None, dy.data_ptr(), g.data_ptr(), 0, None) == 1
+    odd = HashGrid(3, 4, 2, 1000, 4, 64, "f32", "f32")  # not a power of two: no sorted pass
+    if odd.bwd_workspace_bytes(4096) == 0:
+        assert lib.hashgrid_encode_bwd_static(odd._h, 4096, x.data_ptr(), x.data_ptr(), g.data_ptr(), 0, None) == 2
