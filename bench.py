@@ -4,7 +4,8 @@ A step is one forward plus one backward pass of the encoding over one batch of
 synthetic points (inputs resident in HBM): hashgrid_encode_fwd_ws, which also
 counts for the backward pass, then hashgrid_encode_bwd_ws (where the
 configuration is not served by them: hashgrid_encode_fwd + hashgrid_encode_bwd).
-Prints one JSON line.
+Prints one JSON line: the headline workload first (the configuration the metric is
+quoted on), then the same step on the other workloads under "workloads".
 """
 import argparse
 import json
@@ -17,6 +18,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+# What the 256 compute units can take in from their XCDs' L2 caches: 64 bytes per clock each at 2.4 GHz.
+# A gather that misses the L1 moves one 128-byte line over this path, however few of its bytes are used.
+L2_FILL_PEAK_GBS = 256 * 64 * 2.4
+LINE_BYTES = 128
+INIT_STEPS = 30  # untimed steps before the warm-up steps: first-call set-up of the library, clocks
 
 
 def algorithmic_bytes(w, s_theta, s_io):
@@ -39,13 +45,26 @@ def time_launches(fn, n, torch):
     return e0.elapsed_time(e1) / n  # ms
 
 
-def measured_traffic(workload, which):
-    """HBM bytes per launch of the dominant pass, from the committed rocprofv3 counter summary
-    (FETCH_SIZE + WRITE_SIZE scaled by the copy calibration); None when no summary covers it."""
-    path = os.path.join(ROOT, "profiles", f"traffic_{workload}.txt")
+def time_each(before, fn, n, torch):
+    """Average duration of fn over n launches, each bracketed by its own pair of HIP events on the
+    launch stream; `before` runs ahead of every launch, outside the bracket."""
+    marks = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+    for e0, e1 in marks:
+        before()
+        e0.record()
+        fn()
+        e1.record()
+    torch.cuda.synchronize()
+    return sum(e0.elapsed_time(e1) for e0, e1 in marks) / n
+
+
+def profile_figure(name, key):
+    """A per-launch figure from a committed rocprofv3 counter summary under profiles/ (`key: value`
+    lines); None when no summary holds it."""
+    path = os.path.join(ROOT, "profiles", name)
     try:
         for line in open(path):
-            if line.startswith(f"{which}_hbm_bytes_per_launch:"):
+            if line.startswith(f"{key}:"):
                 return float(line.split(":")[1])
     except OSError:
         pass
@@ -53,9 +72,9 @@ def measured_traffic(workload, which):
 
 
 def machine_probes(torch):
-    """What this GPU delivers on three elementary access patterns (hashgrid_probe_*): the measured
+    """What this GPU delivers on elementary access patterns (libhashgrid_probes): the measured
     denominators next to the published 8 TB/s."""
-    from paper_2201_05989_amd import probe_atomic_add, probe_copy, probe_gather
+    from paper_2201_05989_amd import probe_atomic_add, probe_copy, probe_gather, probe_gather_lines
 
     out = {}
     a = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")  # 1 GiB
@@ -69,6 +88,13 @@ def machine_probes(torch):
         t = a[: mib << 18].view(torch.int32)
         probe_gather(t, n, sink)
         out[f"gather_4B_{mib}MiB_g_per_s"] = n / (time_launches(lambda: probe_gather(t, n, sink), 10, torch) * 1e-3) / 1e9
+    # the forward pass's own shape: 2^18 points, 16 levels, 4 lines (2 adjacent words each) per point and
+    # level, a barrier per level, a new 2 MiB slice every level
+    points, levels, words = 1 << 18, 16, 1 << 19
+    t = a[: levels * words].view(torch.int32)
+    probe_gather_lines(t, words, levels, points, levels, sink)
+    ms = time_launches(lambda: probe_gather_lines(t, words, levels, points, levels, sink), 10, torch)
+    out["gather_lines_16x2MiB_g_lines_per_s"] = points * levels * 4 / (ms * 1e-3) / 1e9
     n = 1 << 25
     for mib in (4, 128):
         t = a[: mib << 18]
@@ -109,6 +135,160 @@ def cpu_baseline(w, x, theta, dy, budget_s=10.0):
             "one_core_sample": f"1 fwd+bwd pass over the first {n1} points, {el1:.1f} s"}
 
 
+class Case:
+    """One workload resident on the GPU: inputs, outputs and the calls of a step."""
+
+    def __init__(self, w, torch):
+        from paper_2201_05989_amd import HashGrid, synth
+
+        self.w, self.torch = w, torch
+        self.grid = HashGrid(w.d, w.L, w.F, w.T, w.N_min, w.N_max, w.param_dtype, w.io_dtype)
+        self.host = synth.make_inputs(w, self.grid.n_entries)
+        self.xd, self.td, self.gd = (torch.from_numpy(a).cuda() for a in self.host)
+        self.y = torch.empty((w.B, w.L * w.F), dtype=self.grid.io_dtype, device="cuda")
+        self.grad = torch.zeros((self.grid.n_entries, w.F), dtype=torch.float32, device="cuda")
+        s_theta = 2 if w.param_dtype == "f16" else 4
+        s_io = 2 if w.io_dtype == "f16" else 4
+        self.b_fwd, self.b_bwd = algorithmic_bytes(w, s_theta, s_io)
+
+    def fwd(self):  # forward alone
+        self.grid.encode_fwd(self.xd, self.td, self.y)
+
+    def bwd(self):  # backward; skips its counting pass when the forward has just counted
+        self.grid.encode_bwd(self.xd, self.gd, self.grad)
+
+    def fwd_counting(self):
+        self.grid.encode_fwd(self.xd, self.td, self.y, count_for_bwd=True)
+
+    def step(self):
+        self.fwd_counting()
+        self.bwd()
+
+    def measure(self, steps, warmup, init=INIT_STEPS):
+        """Wall-clock time of `steps` steps after `init` + `warmup` untimed ones, then the two passes as the
+        step runs them, each bracketed by HIP events on the launch stream."""
+        torch = self.torch
+        for _ in range(init + warmup):
+            self.step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.step()
+        torch.cuda.synchronize()
+        ms_step = (time.perf_counter() - t0) * 1e3 / steps
+        n = max(steps, 20)
+        marks = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n)]
+        for ea, eb, ec in marks:
+            ea.record()
+            self.fwd_counting()
+            eb.record()
+            self.bwd()
+            ec.record()
+        torch.cuda.synchronize()
+        ms_fwd = sum(ea.elapsed_time(eb) for ea, eb, _ in marks) / n
+        ms_bwd = sum(eb.elapsed_time(ec) for _, eb, ec in marks) / n
+        return ms_step, ms_fwd, ms_bwd
+
+    def fractions(self, ms_step, ms_fwd, ms_bwd):
+        """Algorithmic bytes over time, as GB/s and as a fraction of the published HBM rate."""
+        B = self.w.B
+
+        def one(nbytes, ms):
+            gbs = nbytes * B / (ms * 1e-3) / 1e9
+            return {"achieved": gbs, "frac": gbs / HBM_PEAK_GBS}
+
+        return {"fwd": one(self.b_fwd, ms_fwd), "bwd": one(self.b_bwd, ms_bwd),
+                "step": one(self.b_fwd + self.b_bwd, ms_step)}
+
+    def describe(self):
+        w = self.w
+        return (f"{w.name}: d={w.d} L={w.L} F={w.F} T=2^{w.T.bit_length() - 1} "
+                f"N_min={w.N_min} N_max={w.N_max} B={w.B} points={w.points}")
+
+
+def headline_extras(c, ms_fwd, ms_bwd, n, steps, torch):
+    """Stand-alone calls, the replacing backward, the optimiser step and the fused network on the headline workload."""
+    w, grid, xd, td, gd, grad = c.w, c.grid, c.xd, c.td, c.gd, c.grad
+    ms_fwd_alone = time_launches(c.fwd, n, torch)
+    ms_bwd_alone = time_launches(c.bwd, n, torch)
+    ms_zero = time_launches(lambda: grad.zero_(), 20, torch)
+
+    # the same step when the backward pass replaces the gradient instead of adding to it
+    # (HG_BWD_OVERWRITE: no clearing pass before it, no reading of the old values in it)
+    def step_overwrite():
+        c.fwd_counting()
+        grid.encode_bwd(xd, gd, grad, overwrite=True)
+
+    ms_bwd_ow = time_launches(lambda: grid.encode_bwd(xd, gd, grad, overwrite=True), n, torch)
+    ms_step_ow = time_launches(step_overwrite, n, torch)
+    grad.zero_()
+
+    # next row of the path: the optimiser step on the tables (fp32 master + fp16 working copy, clears the
+    # gradient).  Every timed launch follows a backward pass, outside its bracket of events, so that it
+    # works on a real gradient (the step skips scalars whose gradient is zero and clears the ones it uses).
+    from paper_2201_05989_amd import adam_step
+    master = td.float()
+    m1, m2 = torch.zeros_like(master), torch.zeros_like(master)
+    counter = [0]
+    half = td if w.param_dtype == "f16" else None
+
+    def adam(zero_grad=True):
+        counter[0] += 1
+        adam_step(master, grad, m1, m2, counter[0], lr=1e-2, params_half=half, zero_grad=zero_grad)
+
+    grad.zero_()
+    ms_adam = time_each(c.bwd, adam, max(steps // 2, 50), torch)
+
+    def train():
+        c.step()
+        adam()
+
+    ms_train = time_launches(train, max(steps // 2, 10), torch)
+
+    # the whole table-training step when the backward pass replaces the gradient: the optimiser
+    # then has nothing to clear
+    def train_overwrite():
+        step_overwrite()
+        adam(zero_grad=False)
+
+    ms_train_ow = time_launches(train_overwrite, max(steps // 2, 10), torch)
+    grad.zero_()
+    n_scalars = grid.n_entries * w.F
+    per_scalar = 16 + 12 + 4 + (2 if w.param_dtype == "f16" else 0)
+    adam_bytes = n_scalars * per_scalar
+    footprint = n_scalars * (16 + (2 if w.param_dtype == "f16" else 0))
+
+    extras = {
+        "ms_grad_zero": ms_zero, "ms_fwd_alone": ms_fwd_alone, "ms_bwd_alone": ms_bwd_alone,
+        "overwrite": {"ms_bwd_alone": ms_bwd_ow, "ms_step": ms_step_ow,
+                      "mpoints_s": w.B / (ms_step_ow * 1e-3) / 1e6, "train_step_ms": ms_train_ow,
+                      "train_step_mpoints_s": w.B / (ms_train_ow * 1e-3) / 1e6},
+        "adam": {"ms": ms_adam, "timing": "HIP events around each of the launches, a backward pass before each",
+                 "scalars": n_scalars, "algorithmic_bytes": adam_bytes,
+                 "achieved_gb_s": adam_bytes / (ms_adam * 1e-3) / 1e9,
+                 "footprint_bytes": footprint,
+                 "cache_resident": footprint < 256e6,  # then the rate is the memory-side cache's, not HBM's
+                 "train_step_ms": ms_train, "train_step_mpoints_s": w.B / (ms_train * 1e-3) / 1e6},
+    }
+    # last row of the path's table: the encoding fused with the paper's 64-64 ReLU network (one output,
+    # as for a signed distance function); served for fp16 tables with at most 64 encoded features
+    n_in = w.L * w.F
+    if w.param_dtype == "f16" and n_in % 8 == 0 and n_in <= 64 and w.d >= 2:
+        import numpy as np
+        rng = np.random.default_rng(0)
+        W1 = torch.from_numpy((rng.standard_normal((64, n_in)) * np.sqrt(2.0 / n_in)).astype(np.float16)).cuda()
+        W2 = torch.from_numpy((rng.standard_normal((64, 64)) * np.sqrt(2.0 / 64)).astype(np.float16)).cuda()
+        W3 = torch.from_numpy((rng.standard_normal((1, 64)) / 8.0).astype(np.float16)).cuda()
+        o = torch.empty((w.B, 1), dtype=torch.float32, device="cuda")
+        grid.encode_mlp_fwd(xd, td, W1, W2, W3, o)
+        ms_mlp = time_launches(lambda: grid.encode_mlp_fwd(xd, td, W1, W2, W3, o), max(n // 2, 10), torch)
+        flops = 2.0 * (n_in * 64 + 64 * 64 + 64 * 1) * w.B
+        extras["encode_mlp_fwd"] = {"ms": ms_mlp, "mpoints_s": w.B / (ms_mlp * 1e-3) / 1e6, "n_out": 1,
+                                    "network_tflop_s": flops / (ms_mlp * 1e-3) / 1e12,
+                                    "ms_over_forward_alone": ms_mlp - ms_fwd_alone}
+    return extras
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -117,9 +297,11 @@ def main():
     ap.add_argument("--workload", default="sdf3d")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probes", action="store_true", help="skip the machine probes (copy, gather, atomic rates)")
+    ap.add_argument("--other-workloads", default="all",
+                    help="the workloads whose step is timed after the headline one: all, none, or names separated by commas")
     ap.add_argument("--step-only", action="store_true",
                     help="only the step and its two passes (what the profiles are taken of): no stand-alone "
-                         "calls, other entry points, probes or CPU baseline")
+                         "calls, other entry points, other workloads, probes or CPU baseline")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a 1 GiB device-to-device copy (20 times): the known-size kernel that "
                          "FETCH_SIZE / WRITE_SIZE counter readings are scaled by")
@@ -129,7 +311,7 @@ def main():
         sys.exit(2)
 
     import torch
-    from paper_2201_05989_amd import HashGrid, synth
+    from paper_2201_05989_amd import synth
 
     if args.calibrate_copy:
         a = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
@@ -141,133 +323,25 @@ def main():
         return
 
     w = synth.WORKLOADS[args.workload]
-    grid = HashGrid(w.d, w.L, w.F, w.T, w.N_min, w.N_max, w.param_dtype, w.io_dtype)
-    x, theta, dy = synth.make_inputs(w, grid.n_entries)
-    xd, td, gd = (torch.from_numpy(a).cuda() for a in (x, theta, dy))
-    y = torch.empty((w.B, w.L * w.F), dtype=grid.io_dtype, device="cuda")
-    grad = torch.zeros((grid.n_entries, w.F), dtype=torch.float32, device="cuda")
+    c = Case(w, torch)
+    ms_step, ms_fwd, ms_bwd = c.measure(args.steps, args.warmup)
+    passes = c.fractions(ms_step, ms_fwd, ms_bwd)
+    sorted_path = bool(c.grid.bwd_workspace_bytes(w.B))
 
-    def fwd():  # forward alone
-        grid.encode_fwd(xd, td, y)
-
-    def bwd():  # backward alone (does its own counting)
-        grid.encode_bwd(xd, gd, grad)
-
-    def fwd_counting():
-        grid.encode_fwd(xd, td, y, count_for_bwd=True)
-
-    def step():
-        fwd_counting()
-        bwd()  # skips its counting pass when the forward has done it
-
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
-
-    n = max(args.steps, 20)
-    # the two passes as the step runs them, each bracketed by HIP events on the launch stream
-    marks = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n)]
-    for ea, eb, ec in marks:
-        ea.record()
-        fwd_counting()
-        eb.record()
-        bwd()
-        ec.record()
-    torch.cuda.synchronize()
-    ms_fwd = sum(ea.elapsed_time(eb) for ea, eb, _ in marks) / n
-    ms_bwd = sum(eb.elapsed_time(ec) for _, eb, ec in marks) / n
-    extras = {}
-    if not args.step_only:
-        ms_fwd_alone = time_launches(fwd, n, torch)
-        ms_bwd_alone = time_launches(bwd, n, torch)
-        ms_zero = time_launches(lambda: grad.zero_(), 20, torch)
-
-        # the same step when the backward pass replaces the gradient instead of adding to it
-        # (HG_BWD_OVERWRITE: no clearing pass before it, no reading of the old values in it)
-        def step_overwrite():
-            fwd_counting()
-            grid.encode_bwd(xd, gd, grad, overwrite=True)
-
-        ms_bwd_ow = time_launches(lambda: grid.encode_bwd(xd, gd, grad, overwrite=True), n, torch)
-        ms_step_ow = time_launches(step_overwrite, n, torch)
-        grad.zero_()
-
-        # next row of the path: the optimiser step on the tables (fp32 master + fp16 working copy,
-        # clears the gradient).  Timed as (backward + optimiser) minus backward, because the step
-        # skips entries whose gradient is zero and clears the ones it uses.
-        from paper_2201_05989_amd import adam_step
-        master = td.float()
-        m1, m2 = torch.zeros_like(master), torch.zeros_like(master)
-        counter = [0]
-
-        def bwd_adam():
-            bwd()
-            counter[0] += 1
-            adam_step(master, grad, m1, m2, counter[0], lr=1e-2, params_half=td if w.param_dtype == "f16" else None)
-
-        grad.zero_()
-        ms_bwd_adam = time_launches(bwd_adam, max(args.steps // 2, 10), torch)
-        grad.zero_()
-        ms_adam = ms_bwd_adam - ms_bwd_alone
-
-        # the whole table-training step when the backward pass replaces the gradient: the optimiser
-        # then has nothing to clear
-        def train_overwrite():
-            fwd_counting()
-            grid.encode_bwd(xd, gd, grad, overwrite=True)
-            counter[0] += 1
-            adam_step(master, grad, m1, m2, counter[0], lr=1e-2, params_half=td if w.param_dtype == "f16" else None,
-                      zero_grad=False)
-
-        ms_train_ow = time_launches(train_overwrite, max(args.steps // 2, 10), torch)
-        grad.zero_()
-        n_scalars = grid.n_entries * w.F
-        adam_bytes = n_scalars * (16 + 12 + 4 + (2 if w.param_dtype == "f16" else 0))
-
-        # last row of the path's table: the encoding fused with the paper's 64-64 ReLU network (one output,
-        # as for a signed distance function); served for fp16 tables with at most 64 encoded features
-        mlp = None
-        n_in = w.L * w.F
-        if w.param_dtype == "f16" and n_in % 8 == 0 and n_in <= 64 and w.d >= 2:
-            import numpy as np
-            rng = np.random.default_rng(0)
-            W1 = torch.from_numpy((rng.standard_normal((64, n_in)) * np.sqrt(2.0 / n_in)).astype(np.float16)).cuda()
-            W2 = torch.from_numpy((rng.standard_normal((64, 64)) * np.sqrt(2.0 / 64)).astype(np.float16)).cuda()
-            W3 = torch.from_numpy((rng.standard_normal((1, 64)) / 8.0).astype(np.float16)).cuda()
-            o = torch.empty((w.B, 1), dtype=torch.float32, device="cuda")
-            grid.encode_mlp_fwd(xd, td, W1, W2, W3, o)
-            ms_mlp = time_launches(lambda: grid.encode_mlp_fwd(xd, td, W1, W2, W3, o), max(n // 2, 10), torch)
-            flops = 2.0 * (n_in * 64 + 64 * 64 + 64 * 1) * w.B
-            mlp = {"ms": ms_mlp, "mpoints_s": w.B / (ms_mlp * 1e-3) / 1e6, "n_out": 1,
-                   "network_tflop_s": flops / (ms_mlp * 1e-3) / 1e12, "ms_over_forward_alone": ms_mlp - ms_fwd_alone}
-        extras = {
-            "ms_grad_zero": ms_zero, "ms_fwd_alone": ms_fwd_alone, "ms_bwd_alone": ms_bwd_alone,
-            "overwrite": {"ms_bwd_alone": ms_bwd_ow, "ms_step": ms_step_ow,
-                          "mpoints_s": w.B / (ms_step_ow * 1e-3) / 1e6, "train_step_ms": ms_train_ow,
-                          "train_step_mpoints_s": w.B / (ms_train_ow * 1e-3) / 1e6},
-            "adam": {"ms": ms_adam, "scalars": n_scalars, "algorithmic_bytes": adam_bytes,
-                     "achieved_gb_s": adam_bytes / (ms_adam * 1e-3) / 1e9 if ms_adam > 0 else None,
-                     "train_step_ms": ms_fwd + ms_bwd + ms_adam,
-                     "train_step_mpoints_s": w.B / ((ms_fwd + ms_bwd + ms_adam) * 1e-3) / 1e6},
-        }
-        if mlp is not None:
-            extras["encode_mlp_fwd"] = mlp
-
-    s_theta = 2 if w.param_dtype == "f16" else 4
-    s_io = 2 if w.io_dtype == "f16" else 4
-    b_fwd, b_bwd = algorithmic_bytes(w, s_theta, s_io)
-    dom = ("bwd", ms_bwd, b_bwd) if ms_bwd >= ms_fwd else ("fwd", ms_fwd, b_fwd)
-    achieved = dom[2] * w.B / (dom[1] * 1e-3) / 1e9
-    kernels = {"fwd": "fwd_point_major (counting)", "bwd": "bin_scan+bin_scatter+bin_accumulate "
-                                                            "(one hashgrid_encode_bwd_ws call, counts from the forward)"}
-    traffic = measured_traffic(w.name, dom[0])
-
+    # The dominant kernel: the forward pass is one kernel per call; the backward call is three
+    # (bin_scan, bin_scatter, bin_accumulate), none of which takes as long as the forward kernel
+    # unless the whole call takes twice as long.
+    fwd_dominant = not sorted_path or ms_fwd >= 0.5 * ms_bwd
+    dom = "fwd" if fwd_dominant else "bwd"
+    kernels = {"fwd": "fwd_point_major (counting variant)" if sorted_path else "fwd_point_major",
+               "bwd": "bin_scan+bin_scatter+bin_accumulate (one hashgrid_encode_bwd_ws call)" if sorted_path
+               else "bwd_general"}
+    traffic = {p: profile_figure(f"traffic_{w.name}.txt", f"{p}_hbm_bytes_per_launch") for p in ("fwd", "bwd")}
+    roofline = {"bound": "hbm", "kernel": kernels[dom], "pass": dom, "achieved": passes[dom]["achieved"],
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": passes[dom]["frac"], "traffic": traffic[dom],
+                "algorithmic_bytes_per_point": {"fwd": c.b_fwd, "bwd": c.b_bwd},
+                "duration_ms": ms_fwd if dom == "fwd" else ms_bwd,
+                "passes": {p: dict(passes[p], traffic=traffic.get(p)) for p in passes}}
     out = {
         "metric": "hash-grid encoding fwd+bwd throughput",
         "value": w.B / (ms_step * 1e-3) / 1e6,
@@ -275,20 +349,23 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{w.name}: d={w.d} L={w.L} F={w.F} T=2^{w.T.bit_length() - 1} "
-                               f"N_min={w.N_min} N_max={w.N_max} B={w.B} points={w.points}",
-                   "param_dtype": w.param_dtype, "io_dtype": w.io_dtype, "grad_dtype": "f32"},
+        "config": {"workload": c.describe(), "param_dtype": w.param_dtype, "io_dtype": w.io_dtype, "grad_dtype": "f32",
+                   "untimed_steps_before_warmup": INIT_STEPS},
         "fwd_mpoints_s": w.B / (ms_fwd * 1e-3) / 1e6,
         "bwd_mpoints_s": w.B / (ms_bwd * 1e-3) / 1e6,
         "ms_fwd": ms_fwd, "ms_bwd": ms_bwd,
-        "roofline": {"bound": "hbm", "kernel": kernels[dom[0]] if grid.bwd_workspace_bytes(w.B) else dom[0],
-                     "pass": dom[0], "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "algorithmic_bytes_per_point": {"fwd": b_fwd, "bwd": b_bwd},
-                     "fwd_achieved": b_fwd * w.B / (ms_fwd * 1e-3) / 1e9,
-                     "bwd_achieved": b_bwd * w.B / (ms_bwd * 1e-3) / 1e9},
+        "roofline": roofline,
     }
-    out.update(extras)
+    # The forward kernel's gathers are served by the L2, not by HBM: its own roofline is the path from the
+    # L2 caches into the compute units.  Lines per launch = TCP_TCC_READ_REQ of the committed counter summary.
+    lines = profile_figure(f"ta_tcp_counters_{w.name}.txt", "fwd_l2_read_requests_per_launch")
+    if lines is not None:
+        gbs = lines * LINE_BYTES / (ms_fwd * 1e-3) / 1e9
+        out["roofline_l2"] = {"bound": "l2_fill", "kernel": kernels["fwd"], "lines_per_launch": lines,
+                              "line_bytes": LINE_BYTES, "achieved": gbs, "peak": L2_FILL_PEAK_GBS, "unit": "GB/s",
+                              "frac": gbs / L2_FILL_PEAK_GBS, "achieved_g_lines_per_s": lines / (ms_fwd * 1e-3) / 1e9}
+    if not args.step_only:
+        out.update(headline_extras(c, ms_fwd, ms_bwd, max(args.steps, 20), args.steps, torch))
     if not args.no_probes and not args.step_only:
         # the pass rates in the elementary operations they stand for, next to what the machine does
         # when it performs those operations one by one at random
@@ -297,14 +374,38 @@ def main():
         out["measured_peaks"] = probes
         out["vs_measured"] = {
             "fwd_gathers_g_per_s": corners * w.B / (ms_fwd * 1e-3) / 1e9,
-            "fwd_over_gather_2MiB": corners * w.B / (ms_fwd * 1e-3) / 1e9 / probes["gather_4B_2MiB_g_per_s"],
             "bwd_scalar_adds_g_per_s": corners * w.F * w.B / (ms_bwd * 1e-3) / 1e9,
             "bwd_over_atomic_add_4MiB": corners * w.F * w.B / (ms_bwd * 1e-3) / 1e9
             / probes["atomic_add_f32_4MiB_g_per_s"],
-            "hbm_frac_of_copy": achieved / probes["copy_1GiB_gb_s"],
+            "step_hbm_frac_of_copy": passes["step"]["achieved"] / probes["copy_1GiB_gb_s"],
         }
+        if "roofline_l2" in out:  # the same line fetches, issued in the forward's shape with nothing else to do
+            out["roofline_l2"]["probe_g_lines_per_s"] = probes["gather_lines_16x2MiB_g_lines_per_s"]
+            out["roofline_l2"]["frac_of_probe"] = (out["roofline_l2"]["achieved_g_lines_per_s"]
+                                                   / probes["gather_lines_16x2MiB_g_lines_per_s"])
+    host = c.host
+    other_names = [n for n in synth.WORKLOADS if n != w.name and args.other_workloads != "none"
+                   and (args.other_workloads == "all" or n in args.other_workloads.split(","))]
+    if not args.step_only and other_names:
+        # the other workloads: the same step, GPU side only, a shorter run each
+        del c
+        torch.cuda.empty_cache()
+        others = []
+        for name in other_names:
+            o = Case(synth.WORKLOADS[name], torch)
+            steps = 100 if o.w.B <= (1 << 18) else 20
+            s, f, b = o.measure(steps, 5, init=10)
+            fr = o.fractions(s, f, b)
+            others.append({"name": name, "workload": o.describe(), "B": o.w.B, "steps": steps, "ms_step": s,
+                           "mpoints_s": o.w.B / (s * 1e-3) / 1e6, "ms_fwd": f, "ms_bwd": b,
+                           "sorted_backward": bool(o.grid.bwd_workspace_bytes(o.w.B)),
+                           "frac": fr["step"]["frac"], "fwd_frac": fr["fwd"]["frac"], "bwd_frac": fr["bwd"]["frac"],
+                           "algorithmic_bytes_per_point": {"fwd": o.b_fwd, "bwd": o.b_bwd}})
+            del o
+            torch.cuda.empty_cache()
+        out["workloads"] = others
     if not args.no_cpu_baseline and not args.step_only:
-        out["cpu_baseline"] = cpu_baseline(w, x, theta, dy)
+        out["cpu_baseline"] = cpu_baseline(w, *host)
     print(json.dumps(out))
 
 

@@ -26,6 +26,9 @@
  *   - y and dL/dy are row-major [B, L*F] of `io_dtype`, level-major inside a row
  *     (the concatenation of Fig. 3, step 4).
  *   - Table gradients are always fp32, same shape as theta.
+ *   - Alignment: x 4 bytes; tables, y, dL/dy and gradients one entry (F scalars of their type) or
+ *     16 bytes, whichever is smaller; anything less is HG_ERR_INVALID_ARG.  The fastest kernels
+ *     want 16 bytes and rows of y that are a multiple of 16 bytes; other cases take a slower path.
  *   - Errors are returned as status codes; nothing aborts or throws.  B = 0 is
  *     HG_OK and launches nothing.
  */
@@ -243,23 +246,6 @@ hg_status hashgrid_adam_step(uint64_t n_scalars, float* params_master, void* par
 hg_status hashgrid_encode_mlp_fwd(const hashgrid_t* hg, uint32_t B, const float* x, const void* params,
                                   const void* W1, const void* W2, const void* W3, uint32_t n_out, float* out,
                                   void* stream);
-
-/* Machine probes (not part of the method; for callers that have no paper to cite: the
- * benchmark, which states its rates as fractions of what this GPU delivers).  Each call
- * enqueues one kernel on `stream`; the caller times it.  All pointers are device pointers.
- *   copy        dst[0..bytes) = src[0..bytes) with 16-byte accesses; bytes a multiple of 16,
- *               both pointers 16-byte aligned.  Moves 2 * bytes.
- *   gather      n_gathers independent 4-byte loads at pseudo-random words of table
- *               [table_words] (a power of two, at most 2^32), 16 per thread; the per-thread sums
- *               go to sink [n_gathers / 16].  n_gathers must be a multiple of 4096.
- *   atomic_add  n_adds device-scope fp32 atomic adds of 1.0 at pseudo-random words of table
- *               [table_words] (same constraints); the table is modified.
- * HG_ERR_INVALID_ARG when a constraint above is not met; a size of 0 is HG_OK. */
-hg_status hashgrid_probe_copy(const void* src, void* dst, uint64_t bytes, void* stream);
-hg_status hashgrid_probe_gather(const uint32_t* table, uint64_t table_words, uint64_t n_gathers, uint32_t seed,
-                                uint32_t* sink, void* stream);
-hg_status hashgrid_probe_atomic_add(float* table, uint64_t table_words, uint64_t n_adds, uint32_t seed,
-                                    void* stream);
 
 /* Static, NUL-terminated description of a status code. */
 const char* hashgrid_strerror(hg_status s);

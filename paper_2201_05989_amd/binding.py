@@ -13,7 +13,7 @@ from dataclasses import dataclass
 
 import torch  # imported before the library so that both share one HIP runtime
 
-from .build import LIB_PATH
+from .build import LIB_PATH, PROBES_LIB_PATH
 
 HG_OK = 0
 HG_F32, HG_F16 = 0, 1
@@ -31,8 +31,9 @@ EXPORTS = ("hashgrid_create", "hashgrid_destroy", "hashgrid_n_entries", "hashgri
            "hashgrid_encode_fwd", "hashgrid_encode_bwd", "hashgrid_encode_bwd_input",
            "hashgrid_debug_indices", "hashgrid_debug_count_outside", "hashgrid_strerror", "hashgrid_bwd_workspace_bytes",
            "hashgrid_encode_bwd_ws", "hashgrid_encode_fwd_ws", "hashgrid_bwd_ws_pays", "hashgrid_adam_step",
-           "hashgrid_encode_mlp_fwd", "hashgrid_encode_bwd_static", "hashgrid_probe_copy", "hashgrid_probe_gather",
-           "hashgrid_probe_atomic_add")
+           "hashgrid_encode_mlp_fwd", "hashgrid_encode_bwd_static")
+PROBE_EXPORTS = ("hashgrid_probe_copy", "hashgrid_probe_gather", "hashgrid_probe_atomic_add",
+                 "hashgrid_probe_gather_lines")
 
 
 class HashGridError(RuntimeError):
@@ -95,15 +96,34 @@ def load_library() -> ctypes.CDLL:
     lib.hashgrid_adam_step.argtypes = [u64, vp, vp, vp, vp, vp, ctypes.POINTER(hashgrid_adam_config), u32, ctypes.c_int,
                                        vp]
     lib.hashgrid_adam_step.restype = ctypes.c_int
+    lib.hashgrid_strerror.argtypes = [ctypes.c_int]
+    lib.hashgrid_strerror.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+_probes = None
+
+
+def load_probes() -> ctypes.CDLL:
+    """Loads the in-tree library of machine probes (the benchmark's); raises if it has not been built."""
+    global _probes
+    if _probes is not None:
+        return _probes
+    if not os.path.exists(PROBES_LIB_PATH):
+        raise HashGridError(
+            f"{PROBES_LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+    lib = ctypes.CDLL(PROBES_LIB_PATH)
+    vp, u32, u64 = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64
     lib.hashgrid_probe_copy.argtypes = [vp, vp, u64, vp]
     lib.hashgrid_probe_copy.restype = ctypes.c_int
     lib.hashgrid_probe_gather.argtypes = [vp, u64, u64, u32, vp, vp]
     lib.hashgrid_probe_gather.restype = ctypes.c_int
     lib.hashgrid_probe_atomic_add.argtypes = [vp, u64, u64, u32, vp]
     lib.hashgrid_probe_atomic_add.restype = ctypes.c_int
-    lib.hashgrid_strerror.argtypes = [ctypes.c_int]
-    lib.hashgrid_strerror.restype = ctypes.c_char_p
-    _lib = lib
+    lib.hashgrid_probe_gather_lines.argtypes = [vp, u64, u32, u64, u32, u32, vp, vp]
+    lib.hashgrid_probe_gather_lines.restype = ctypes.c_int
+    _probes = lib
     return lib
 
 
@@ -151,8 +171,8 @@ class HashGrid:
         self.param_dtype = _TORCH[self.cfg.param_dtype]
         self.io_dtype = _TORCH[self.cfg.io_dtype]
         self.n_entries = int(self._lib.hashgrid_n_entries(self._h))
-        self._ws = None
-        self._counted = None  # (x pointer, B, workspace pointer) the workspace holds counts for
+        self._ws = {}  # (device, stream) -> scratch buffer kept for calls that pass none
+        self._counted = None  # (x pointer, B, workspace pointer, x version, stream) the workspace holds counts for
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None
@@ -168,10 +188,17 @@ class HashGrid:
     def levels(self):
         return [self.level_info(l) for l in range(self.L)]
 
-    def _workspace(self, need: int, device) -> torch.Tensor:
-        if self._ws is None or self._ws.numel() < need or self._ws.device != device:
-            self._ws = torch.empty(need, dtype=torch.uint8, device=device)
-        return self._ws
+    def _workspace(self, need: int, device, stream) -> torch.Tensor:
+        """The scratch buffer this object keeps for calls that pass none: one per (device, stream), because
+        calls that overlap in time need separate buffers and calls on one stream never overlap."""
+        key = (device, _stream_ptr(stream))
+        ws = self._ws.get(key)
+        if ws is None or ws.numel() < need:
+            ws = torch.empty(need, dtype=torch.uint8, device=device)
+            self._ws[key] = ws
+        if stream is not None:
+            ws.record_stream(stream)  # allocated on torch's current stream, used on this one
+        return ws
 
     def bwd_ws_pays(self, B: int) -> bool:
         return bool(self._lib.hashgrid_bwd_ws_pays(self._h, B))
@@ -189,7 +216,7 @@ class HashGrid:
         want = bool(count_for_bwd) and B and (count_for_bwd == "always" or self.bwd_ws_pays(B))
         need = self.bwd_workspace_bytes(B) if want else 0
         if need:
-            ws = workspace if workspace is not None else self._workspace(need, x.device)
+            ws = workspace if workspace is not None else self._workspace(need, x.device, stream)
             st = self._lib.hashgrid_encode_fwd_ws(
                 self._h, B, _dev(x, torch.float32, (B, self.d), "x"),
                 _dev(params, self.param_dtype, (self.n_entries, self.F), "params"),
@@ -197,7 +224,7 @@ class HashGrid:
                 _stream_ptr(stream))
             if st != HG_ERR_UNSUPPORTED:
                 _check(st, "hashgrid_encode_fwd_ws")
-                self._counted = (x.data_ptr(), B, ws.data_ptr(), x._version)  # x unchanged since, as far as torch knows
+                self._counted = (x.data_ptr(), B, ws.data_ptr(), x._version, _stream_ptr(stream))  # x unchanged since, as far as torch knows
                 return y
         _check(self._lib.hashgrid_encode_fwd(
             self._h, B, _dev(x, torch.float32, (B, self.d), "x"),
@@ -226,8 +253,9 @@ class HashGrid:
         counted, self._counted = self._counted, None  # the pass consumes the counts
         if need:
             if workspace is None:
-                workspace = self._workspace(need, x.device)
-            flags = HG_BWD_COUNTED if counted == (x.data_ptr(), B, workspace.data_ptr(), x._version) else 0
+                workspace = self._workspace(need, x.device, stream)
+            # the counts are only there for a call ordered after the forward: same stream
+            flags = HG_BWD_COUNTED if counted == (x.data_ptr(), B, workspace.data_ptr(), x._version, _stream_ptr(stream)) else 0
             if overwrite and not fresh:
                 flags |= HG_BWD_OVERWRITE
             _check(self._lib.hashgrid_encode_bwd_ws(
@@ -332,7 +360,7 @@ def probe_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:
     if not (src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()
             and dst.numel() * dst.element_size() == nbytes):
         raise HashGridError("src and dst must be contiguous device tensors of equal size")
-    _check(load_library().hashgrid_probe_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream_ptr(stream)),
+    _check(load_probes().hashgrid_probe_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream_ptr(stream)),
            "hashgrid_probe_copy")
 
 
@@ -341,7 +369,7 @@ def probe_gather(table: torch.Tensor, n_gathers: int, sink: torch.Tensor, seed: 
     if not (table.is_cuda and table.is_contiguous() and table.element_size() == 4 and sink.is_cuda
             and sink.is_contiguous() and sink.element_size() == 4 and sink.numel() >= n_gathers // 16):
         raise HashGridError("table and sink must be contiguous 4-byte device tensors, sink of n_gathers/16 words")
-    _check(load_library().hashgrid_probe_gather(table.data_ptr(), table.numel(), n_gathers, seed, sink.data_ptr(),
+    _check(load_probes().hashgrid_probe_gather(table.data_ptr(), table.numel(), n_gathers, seed, sink.data_ptr(),
                                                 _stream_ptr(stream)), "hashgrid_probe_gather")
 
 
@@ -349,5 +377,18 @@ def probe_atomic_add(table: torch.Tensor, n_adds: int, seed: int = 1, stream=Non
     """hashgrid_probe_atomic_add over an fp32 device tensor with a power-of-two number of words."""
     if not (table.is_cuda and table.is_contiguous() and table.dtype == torch.float32):
         raise HashGridError("table must be a contiguous fp32 device tensor")
-    _check(load_library().hashgrid_probe_atomic_add(table.data_ptr(), table.numel(), n_adds, seed,
+    _check(load_probes().hashgrid_probe_atomic_add(table.data_ptr(), table.numel(), n_adds, seed,
                                                     _stream_ptr(stream)), "hashgrid_probe_atomic_add")
+
+
+def probe_gather_lines(table: torch.Tensor, slice_words: int, n_slices: int, n_points: int, n_levels: int,
+                       sink: torch.Tensor, seed: int = 1, stream=None) -> None:
+    """hashgrid_probe_gather_lines: the forward pass's access shape (4 lines x 2 adjacent words per point
+    and level, a barrier per level, slice l mod n_slices of the table for level l)."""
+    if not (table.is_cuda and table.is_contiguous() and table.element_size() == 4
+            and table.numel() >= slice_words * n_slices and sink.is_cuda and sink.is_contiguous()
+            and sink.element_size() == 4 and sink.numel() >= n_points):
+        raise HashGridError("table must hold n_slices * slice_words 4-byte words, sink n_points words")
+    _check(load_probes().hashgrid_probe_gather_lines(table.data_ptr(), slice_words, n_slices, n_points, n_levels,
+                                                     seed, sink.data_ptr(), _stream_ptr(stream)),
+           "hashgrid_probe_gather_lines")

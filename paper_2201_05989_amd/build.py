@@ -9,8 +9,10 @@ _ROOT = os.path.dirname(_PKG)
 CSRC = os.path.join(_PKG, "csrc")
 INCLUDE = os.path.join(_ROOT, "include")
 LIB_PATH = os.environ.get("HASHGRID_LIB") or os.path.join(_PKG, "libhashgrid.so")
+PROBES_LIB_PATH = os.path.join(_PKG, "libhashgrid_probes.so")  # the benchmark's machine probes, a library of their own
 
-SOURCES = ["hashgrid.hip", "bwd_binned.hip", "adam.hip", "probes.hip", "mlp_fused.hip"]
+SOURCES = ["hashgrid.hip", "bwd_binned.hip", "adam.hip", "mlp_fused.hip"]
+PROBE_SOURCES = ["probes.hip"]
 
 # fp contraction is off so that the scale step of the encoding stays one rounded
 # fp32 multiply (it decides voxel corners); FMAs are written out where wanted.
@@ -30,12 +32,10 @@ def hipcc() -> str:
     return "hipcc"
 
 
-def build_library(verbose: bool = False, extra_flags=(), out: str | None = None) -> str:
-    """Compiles every source (one hipcc process each, side by side) and links the shared library."""
+def _compile_and_link(sources, out: str, verbose: bool, extra_flags) -> str:
     import tempfile
     from concurrent.futures import ThreadPoolExecutor
 
-    out = out or LIB_PATH
     tmp = out + f".tmp{os.getpid()}"
     flags = [f for f in HIPCC_FLAGS if f != "-shared"]
     with tempfile.TemporaryDirectory(prefix="hashgrid_obj_") as objdir:
@@ -47,8 +47,8 @@ def build_library(verbose: bool = False, extra_flags=(), out: str | None = None)
             subprocess.run(cmd, check=True)
             return obj
 
-        with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 1)) as pool:
-            objs = list(pool.map(compile_one, SOURCES))
+        with ThreadPoolExecutor(max_workers=min(len(sources), os.cpu_count() or 1)) as pool:
+            objs = list(pool.map(compile_one, sources))
         link = [hipcc(), "--offload-arch=gfx950", "-fPIC", "-shared", "-o", tmp, *objs]
         if verbose:
             print(" ".join(link), flush=True)
@@ -57,5 +57,16 @@ def build_library(verbose: bool = False, extra_flags=(), out: str | None = None)
     return out
 
 
+def build_library(verbose: bool = False, extra_flags=(), out: str | None = None) -> str:
+    """Compiles every source of libhashgrid (one hipcc process each, side by side) and links it."""
+    return _compile_and_link(SOURCES, out or LIB_PATH, verbose, extra_flags)
+
+
+def build_probes(verbose: bool = False, extra_flags=(), out: str | None = None) -> str:
+    """libhashgrid_probes: the machine probes the benchmark uses for its measured denominators."""
+    return _compile_and_link(PROBE_SOURCES, out or PROBES_LIB_PATH, verbose, extra_flags)
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_probes(verbose=True))

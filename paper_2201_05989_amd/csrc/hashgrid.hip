@@ -193,20 +193,56 @@ __global__ __launch_bounds__(kPmBlock) void fwd_point_major(const LevelTable lv,
   // 16-byte pieces are stored two at a time so that a 32-byte sector of the row is written
   // once, not twice
   Vec<IT, F * G> held[SB];
+  // One point per thread: the gathers of level l+1 are issued before level l is blended, so the
+  // texture path has work while the waves compute indices and wait at the barrier (two register
+  // sets that alternate; the parity of a level inside a piece must be known at compile time).
+  constexpr bool PIPE = SB == 1 && G % 2 == 0;
+  constexpr int kSets = PIPE ? 2 : 1;
+  Vec<PT, F> e[kSets][SB][1 << D];
+  float wr[kSets][SB][1 << (D - 1)], w0[kSets][SB], u0[kSets][SB];
+  auto gather_level = [&](const uint32_t l, const int set) {
+    const Vec<PT, F>* tab = reinterpret_cast<const Vec<PT, F>*>(theta) + lv.offset[l];
+#pragma unroll
+    for (int q = 0; q < SB; ++q) {
+      uint32_t idx[1 << D], c0[D];
+      level_corners<D, POW2>(lv, l, smooth, xp[q], idx, wr[set][q], w0[set][q], u0[set][q], c0);
+#pragma unroll
+      for (uint32_t m = 0; m < (1u << D); ++m) e[set][q][m] = tab[idx[m]];
+      if constexpr (COUNT) {
+        // The bin of each pair of corners along dimension 0, as rows_of (bwd_bins.hpp) defines it, from
+        // what the gathers have just computed: a hashed level's bin is the chunk of the lower corner's
+        // entry, a 1:1 level's the group of grid rows of the pair.  (COUNT implies a power-of-two T.)
+        if (valid[q]) {
+          const uint32_t cl = ca.bp.chunk_log2, gb0 = ca.bp.bin_base[l];
+          uint32_t* h = hist + (q * (kPmBlock / kBinThreads) + threadIdx.x / kBinThreads) * ca.n_bins;
+          if ((lv.dense_mask >> l) & 1u) {  // uniform
+            const uint32_t sh = ca.bp.row_shift[l], verts = lv.verts[l];
+#pragma unroll
+            for (uint32_t r = 0; r < (1u << (D - 1)); ++r) {
+              uint32_t row = c0[1] + (r & 1u);
+              if (D == 3) row += (c0[D - 1] + (r >> 1)) * verts;
+              __hip_atomic_fetch_add(&h[gb0 + (row >> sh)], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+          } else if ((c0[0] & ((1u << cl) - 1u)) != (1u << cl) - 1u) {  // else the pairs straddle two chunks: no record
+#pragma unroll
+            for (uint32_t r = 0; r < (1u << (D - 1)); ++r)
+              __hip_atomic_fetch_add(&h[gb0 + (idx[2 * r] >> cl)], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+          }
+        }
+      }
+    }
+  };
+  if constexpr (PIPE) gather_level(0, 0);
   for (uint32_t l0 = 0; l0 < lv.L; l0 += G) {
     Vec<IT, F * G> out[SB];
 #pragma unroll
     for (int j = 0; j < G; ++j) {
       const uint32_t l = l0 + j;
-      const Vec<PT, F>* tab = reinterpret_cast<const Vec<PT, F>*>(theta) + lv.offset[l];
-      Vec<PT, F> e[SB][1 << D];
-      float wr[SB][1 << (D - 1)], w0[SB], u0[SB];
-#pragma unroll
-      for (int q = 0; q < SB; ++q) {
-        uint32_t idx[1 << D];
-        level_corners<D, POW2>(lv, l, smooth, xp[q], idx, wr[q], w0[q], u0[q]);
-#pragma unroll
-        for (uint32_t m = 0; m < (1u << D); ++m) e[q][m] = tab[idx[m]];
+      const int set = PIPE ? (j & 1) : 0;  // lv.L is a multiple of G (checked at launch), G even: l and j have the same parity
+      if constexpr (PIPE) {
+        if (l + 1 < lv.L) gather_level(l + 1, set ^ 1);
+      } else {
+        gather_level(l, 0);
       }
 #pragma unroll
       for (int q = 0; q < SB; ++q) {
@@ -215,29 +251,21 @@ __global__ __launch_bounds__(kPmBlock) void fwd_point_major(const LevelTable lv,
         for (int f = 0; f < F; ++f) acc[f] = 0.0f;
 #pragma unroll
         for (uint32_t m = 0; m < (1u << D); ++m) {
-          const float wt = wr[q][m >> 1] * ((m & 1u) ? w0[q] : u0[q]);
+          const float wt = wr[set][q][m >> 1] * ((m & 1u) ? w0[set][q] : u0[set][q]);
 #pragma unroll
-          for (int f = 0; f < F; ++f) acc[f] = fmaf(wt, (float)e[q][m].v[f], acc[f]);
+          for (int f = 0; f < F; ++f) acc[f] = fmaf(wt, (float)e[set][q][m].v[f], acc[f]);
         }
 #pragma unroll
         // (the compiler folds this conversion into the last multiply-add in some instantiations and
         // not in others - one rounding instead of two - so two variants of the kernel may differ in
         // the last bit of an fp16 output that is an exact tie)
         for (int f = 0; f < F; ++f) out[q].v[F * j + f] = (IT)acc[f];
-        if constexpr (COUNT) {
-          if (valid[q]) {
-            Rows<D> rw;
-            rows_of<D, true>(lv, ca.bp, l, smooth, xp[q], rw);
-            uint32_t* h = hist + (q * (kPmBlock / kBinThreads) + threadIdx.x / kBinThreads) * ca.n_bins;
-#pragma unroll
-            for (uint32_t r = 0; r < (1u << (D - 1)); ++r)
-              if (!rw.cross)
-                __hip_atomic_fetch_add(&h[rw.bin[r]], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-          }
-        }
       }
       asm volatile("" ::: "memory");  // keep the gathers of one level together
-      __syncthreads();
+      // Pacing only: the barrier keeps the waves of the workgroup on the same level's slice; no data
+      // passes between them here, so it carries no fence and the gathers already issued for the
+      // next level stay in flight across it.
+      __builtin_amdgcn_s_barrier();
     }
     const uint32_t piece = l0 / G;
 #pragma unroll
@@ -250,7 +278,8 @@ __global__ __launch_bounds__(kPmBlock) void fwd_point_major(const LevelTable lv,
       }
     }
   }
-  if constexpr (COUNT) {  // the last level's barrier has passed: the histograms are complete
+  if constexpr (COUNT) {
+    __syncthreads();  // every wave's LDS atomics have landed: the histograms are complete
 #pragma unroll
     for (uint32_t t = 0; t < kTiles; ++t) {
       const uint32_t tile = blockIdx.x * kTiles + t;
@@ -510,6 +539,8 @@ static hg_status build_levels(const hashgrid_config& c, LevelTable& lv, uint64_t
 
 static inline bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
 static inline size_t dtype_size(uint32_t t) { return t == HG_F16 ? 2 : 4; }
+// alignment the entry points ask of an array of F-scalar entries: one entry, 16 bytes at most
+static inline size_t entry_align(uint32_t F, uint32_t t) { return F * dtype_size(t) > 16 ? 16 : F * dtype_size(t); }
 
 static hg_status launched() { return hipGetLastError() == hipSuccess ? HG_OK : HG_ERR_DEVICE; }
 
@@ -708,8 +739,8 @@ hg_status hashgrid_encode_fwd(const hashgrid_t* hg, uint32_t B, const float* x, 
   if (B > HG_MAX_BATCH) return HG_ERR_UNSUPPORTED;
   if (!x || !params || !y) return HG_ERR_INVALID_ARG;
   const hashgrid_config& c = hg->cfg;
-  if (hg::misaligned(x, 4) || hg::misaligned(params, c.F * hg::dtype_size(c.param_dtype)) ||
-      hg::misaligned(y, c.F * hg::dtype_size(c.io_dtype)))
+  if (hg::misaligned(x, 4) || hg::misaligned(params, hg::entry_align(c.F, c.param_dtype)) ||
+      hg::misaligned(y, hg::entry_align(c.F, c.io_dtype)))
     return HG_ERR_INVALID_ARG;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool p16 = c.param_dtype == HG_F16, i16 = c.io_dtype == HG_F16;
@@ -729,7 +760,7 @@ hg_status hashgrid_encode_bwd(const hashgrid_t* hg, uint32_t B, const float* x, 
   if (B > HG_MAX_BATCH) return HG_ERR_UNSUPPORTED;
   if (!x || !dLdy || !grad_params) return HG_ERR_INVALID_ARG;
   const hashgrid_config& c = hg->cfg;
-  if (hg::misaligned(x, 4) || hg::misaligned(dLdy, c.F * hg::dtype_size(c.io_dtype)) ||
+  if (hg::misaligned(x, 4) || hg::misaligned(dLdy, hg::entry_align(c.F, c.io_dtype)) ||
       hg::misaligned(grad_params, 4))
     return HG_ERR_INVALID_ARG;
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -749,8 +780,8 @@ hg_status hashgrid_encode_bwd_input(const hashgrid_t* hg, uint32_t B, const floa
   if (!x || !params || !dLdy || !dLdx) return HG_ERR_INVALID_ARG;
   const hashgrid_config& c = hg->cfg;
   if (hg::misaligned(x, 4) || hg::misaligned(dLdx, 4) ||
-      hg::misaligned(params, c.F * hg::dtype_size(c.param_dtype)) ||
-      hg::misaligned(dLdy, c.F * hg::dtype_size(c.io_dtype)))
+      hg::misaligned(params, hg::entry_align(c.F, c.param_dtype)) ||
+      hg::misaligned(dLdy, hg::entry_align(c.F, c.io_dtype)))
     return HG_ERR_INVALID_ARG;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool p16 = c.param_dtype == HG_F16, i16 = c.io_dtype == HG_F16;

@@ -83,9 +83,10 @@ __host__ __device__ __forceinline__ float smoothstep(float w) { return w * w * (
 __device__ __forceinline__ float dsmoothstep(float w) { return 6.0f * w * (1.0f - w); }
 
 // F scalars of one table entry / one output fragment, loaded and stored as one
-// vector access.
+// vector access (two for the 32-byte ones: the entry points ask for 16-byte
+// alignment at most, so the type must not promise more).
 template <typename T, int F>
-struct alignas(sizeof(T) * F) Vec {
+struct alignas(sizeof(T) * F > 16 ? 16 : sizeof(T) * F) Vec {
   T v[F];
 };
 
@@ -115,14 +116,14 @@ __device__ __forceinline__ void corner_indices_uniform(const uint32_t (&c0)[D], 
 
 // Per level and point: the 2^D entry indices and the weights of the corners, split into the
 // product over dimensions 1.. (wr) and the two weights of dimension 0 (w0 upper, u0 lower).
+// c0: the voxel's lower corner (integer coordinates).
 template <int D, bool POW2>
 __device__ __forceinline__ void level_corners(const LevelTable& lv, uint32_t l, bool smooth, const float (&xp)[D],
                                               uint32_t (&idx)[1 << D], float (&wr)[1 << (D - 1)], float& w0,
-                                              float& u0) {
+                                              float& u0, uint32_t (&c0)[D]) {
   const float Nf = (float)lv.N[l];
   const float shift = smooth ? 0.5f : 0.0f;
   const float cmaxf = smooth ? Nf : Nf - 1.0f;
-  uint32_t c0[D];
   float w[D], u[D];
 #pragma unroll
   for (int i = 0; i < D; ++i) {
@@ -149,6 +150,14 @@ __device__ __forceinline__ void level_corners(const LevelTable& lv, uint32_t l, 
   }
   w0 = w[0];
   u0 = u[0];
+}
+
+template <int D, bool POW2>
+__device__ __forceinline__ void level_corners(const LevelTable& lv, uint32_t l, bool smooth, const float (&xp)[D],
+                                              uint32_t (&idx)[1 << D], float (&wr)[1 << (D - 1)], float& w0,
+                                              float& u0) {
+  uint32_t c0[D];
+  level_corners<D, POW2>(lv, l, smooth, xp, idx, wr, w0, u0, c0);
 }
 
 }  // namespace hg

@@ -1,12 +1,12 @@
-// Machine probes: three small kernels that measure, on the GPU at hand, the rates
-// the encoding's passes are compared with - streaming copy (HBM), random 4-byte
-// gathers from a table of a given size (L2 or memory-side request rate) and random
-// fp32 atomic adds (device-scope atomic rate).  They are not part of the method;
-// the caller times them.
+// Machine probes (libhashgrid_probes, declared in include/hashgrid_probes.h): small kernels
+// that measure, on the GPU at hand, the rates the encoding's passes are compared with -
+// streaming copy (HBM), random 4-byte gathers from a table of a given size (L2 or memory-side
+// request rate), random fp32 atomic adds (device-scope atomic rate) and line fetches in the
+// access shape of the forward pass.  They are not part of the method; the caller times them.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "hashgrid.h"
+#include "hashgrid_probes.h"
 
 namespace hg {
 
@@ -54,6 +54,33 @@ __global__ __launch_bounds__(kProbeThreads) void probe_atomic_add(float* __restr
   }
 }
 
+// The forward pass's access shape on hashed levels: per point and level four lines, two adjacent
+// words in each, a barrier per level, a new slice every level.
+constexpr int kLineProbeThreads = 1024;
+__global__ __launch_bounds__(kLineProbeThreads) void probe_gather_lines(const uint32_t* __restrict__ table,
+                                                                        const uint32_t slice_words,
+                                                                        const uint32_t n_slices, const uint32_t n_levels,
+                                                                        const uint32_t seed, uint32_t* __restrict__ sink) {
+  const uint32_t tid = blockIdx.x * kLineProbeThreads + threadIdx.x;
+  const uint32_t mask = slice_words - 1u;
+  uint32_t h = mix32(tid * 2654435761u + seed), sum = 0;
+  for (uint32_t l = 0; l < n_levels; ++l) {
+    const uint32_t* t = table + (uint64_t)(l % n_slices) * slice_words;
+    uint32_t v[8];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      h = mix32(h + (uint32_t)r * 0x9e3779b9u + l);
+      const uint32_t i = h & mask;
+      v[2 * r] = t[i];
+      v[2 * r + 1] = t[i ^ 1u];
+    }
+#pragma unroll
+    for (int r = 0; r < 8; ++r) sum += v[r];
+    __syncthreads();
+  }
+  sink[tid] = sum;
+}
+
 static bool pow2(uint64_t v) { return v && !(v & (v - 1)); }
 
 }  // namespace hg
@@ -93,6 +120,19 @@ hg_status hashgrid_probe_atomic_add(float* table, uint64_t table_words, uint64_t
     return HG_ERR_INVALID_ARG;
   hipLaunchKernelGGL(hg::probe_atomic_add, dim3((uint32_t)(n_adds / per_wg)), dim3(hg::kProbeThreads), 0,
                      static_cast<hipStream_t>(stream), table, (uint32_t)(table_words - 1), seed);
+  return hipGetLastError() == hipSuccess ? HG_OK : HG_ERR_DEVICE;
+}
+
+hg_status hashgrid_probe_gather_lines(const uint32_t* table, uint64_t slice_words, uint32_t n_slices,
+                                      uint64_t n_points, uint32_t n_levels, uint32_t seed, uint32_t* sink,
+                                      void* stream) {
+  if (n_points == 0 || n_levels == 0) return HG_OK;
+  if (!table || !sink || !hg::pow2(slice_words) || slice_words < 32 || slice_words > (1ull << 31) || n_slices == 0 ||
+      n_points % hg::kLineProbeThreads || n_points / hg::kLineProbeThreads > 0x7fffffffull)
+    return HG_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(hg::probe_gather_lines, dim3((uint32_t)(n_points / hg::kLineProbeThreads)),
+                     dim3(hg::kLineProbeThreads), 0, static_cast<hipStream_t>(stream), table, (uint32_t)slice_words,
+                     n_slices, n_levels, seed, sink);
   return hipGetLastError() == hipSuccess ? HG_OK : HG_ERR_DEVICE;
 }
 

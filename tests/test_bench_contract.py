@@ -17,7 +17,7 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 @pytest.mark.gpu
 def test_one_json_line_with_the_fields_of_the_contract():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--steps", "20", "--warmup", "3", "--workload",
-                        "tiny2d", "--no-probes"], capture_output=True, text=True, timeout=600)
+                        "tiny2d", "--no-probes", "--other-workloads", "image2d"], capture_output=True, text=True, timeout=600)
     assert r.returncode == 0, r.stderr[-2000:]
     lines = [ln for ln in r.stdout.splitlines() if ln.strip()]
     assert len(lines) == 1
@@ -33,5 +33,11 @@ def test_one_json_line_with_the_fields_of_the_contract():
     for key in ("bound", "achieved", "peak", "unit", "frac", "traffic"):
         assert key in roof, key
     assert roof["bound"] == "hbm" and roof["peak"] == 8000.0 and abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-12
+    assert roof["pass"] in ("fwd", "bwd") and set(roof["passes"]) == {"fwd", "bwd", "step"}
+    (other,) = j["workloads"]  # the other workloads asked for: the same step, GPU side only
+    assert other["name"] == "image2d" and other["B"] == 1 << 18 and other["sorted_backward"] is True
+    for key in ("ms_step", "mpoints_s", "ms_fwd", "ms_bwd", "frac"):
+        assert other[key] > 0, key
+    assert abs(other["mpoints_s"] - other["B"] / (other["ms_step"] * 1e-3) / 1e6) < 1e-6 * other["mpoints_s"]
     cpu = j["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["cores"] >= 1 and cpu["value"] > 0 and cpu["sample"]

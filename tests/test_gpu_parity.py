@@ -370,10 +370,13 @@ def test_workspace_backward_with_very_many_chunks(d, F, iot, interp, B):
     assert grid.bwd_workspace_bytes(B) > 0
 
 
-@pytest.mark.parametrize("F,pdt,iot", [(2, "f16", "f16"), (1, "f32", "f16"), (4, "f16", "f32")])
-def test_buffers_aligned_to_one_entry_only(F, pdt, iot):
+@pytest.mark.parametrize("F,pdt,iot,shift", [(2, "f16", "f16", None), (1, "f32", "f16", None), (4, "f16", "f32", None),
+                                             (8, "f32", "f32", 4)])
+def test_buffers_aligned_to_one_entry_only(F, pdt, iot, shift):
     # every array starts one table entry (one level's outputs) past a 256-byte boundary: allowed by
-    # the interface, but not the 16-byte alignment the vector paths of the kernels want
+    # the interface, but not the 16-byte alignment the vector paths of the kernels want.  Last row:
+    # 32-byte entries and output rows that start 16 bytes past a 32-byte boundary (the widest
+    # alignment the entry points may assume is 16 bytes)
     d, L, T, N_min, N_max, B = 3, 8, 1 << 12, 4, 128, 3000
     cfg = orc.OracleConfig(d, L, F, T, N_min, N_max)
     lv = orc.levels(cfg)
@@ -384,9 +387,11 @@ def test_buffers_aligned_to_one_entry_only(F, pdt, iot):
     grid = HashGrid(d, L, F, T, N_min, N_max, pdt, iot)
 
     def shifted(a, fill=None):
-        t = torch.empty(a.size + F, dtype=torch.from_numpy(a[:0]).dtype, device="cuda")
-        v = t[F:].view(a.shape)
+        k = F if shift is None else shift
+        t = torch.empty(a.size + k, dtype=torch.from_numpy(a[:0]).dtype, device="cuda")
+        v = t[k:].view(a.shape)
         assert v.data_ptr() % 16 != 0 or F * a.itemsize >= 16
+        assert shift is None or v.data_ptr() % 32 == 16
         v.copy_(dev(a)) if fill is None else v.fill_(fill)
         return v
 
@@ -584,7 +589,7 @@ def test_binding_picks_the_backward_pass_by_batch_size():
         ga = grid.encode_bwd(x, dy)                        # the binding's choice
         gb = grid.encode_bwd(x, dy, use_workspace=False)   # atomics
         torch.testing.assert_close(ga, gb, rtol=1e-4, atol=1e-4 * float(gb.abs().max()))
-        assert (grid._ws is not None) == (B == 1 << 16)    # the scratch buffer appears only when the sort is used
+        assert bool(grid._ws) == (B == 1 << 16)            # the scratch buffer appears only when the sort is used
 
 
 def test_workspace_backward_argument_checks():

@@ -3,7 +3,7 @@ so the checks are about bounds and bookkeeping, not about the paper's method).""
 import pytest
 import torch
 
-from paper_2201_05989_amd import probe_atomic_add, probe_copy, probe_gather
+from paper_2201_05989_amd import probe_atomic_add, probe_copy, probe_gather, probe_gather_lines
 
 pytestmark = pytest.mark.gpu
 
@@ -32,3 +32,13 @@ def test_atomic_add_adds_exactly_n_ones_spread_over_the_table():
     assert float(table.sum()) == float(n)
     assert int((table > 0).sum()) > 900  # pseudo-random addresses reach nearly every word
     assert float(guard.sum()) == 0.0
+
+
+def test_gather_lines_reads_only_inside_its_slices_and_sums_what_it_read():
+    # 3 slices of 2^10 words holding 1, 2, 3; a guard slice after them must never be read (its value would show)
+    words, levels, n = 1 << 10, 7, 1024 * 3
+    table = torch.cat([torch.full((words,), v, dtype=torch.int32, device="cuda") for v in (1, 2, 3, 1000000)])
+    sink = torch.zeros(n, dtype=torch.int32, device="cuda")
+    probe_gather_lines(table, words, 3, n, levels, sink)
+    expect = 8 * sum((1, 2, 3)[l % 3] for l in range(levels))  # 8 words per point and level
+    assert bool((sink == expect).all())

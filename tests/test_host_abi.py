@@ -9,13 +9,13 @@ import pytest
 
 from oracle import hashgrid_oracle as orc
 from paper_2201_05989_amd import binding
-from paper_2201_05989_amd.build import LIB_PATH
+from paper_2201_05989_amd.build import LIB_PATH, PROBES_LIB_PATH
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared_symbols():
-    text = open(os.path.join(ROOT, "include", "hashgrid.h")).read()
+def _declared_symbols(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(hashgrid_[a-z_]+)\s*\(", text)))
 
@@ -23,8 +23,18 @@ def _declared_symbols():
 def test_library_is_built_and_exports_every_declared_symbol():
     assert os.path.exists(LIB_PATH), "build the library first: __graft_entry__.build()"
     lib = ctypes.CDLL(LIB_PATH)
-    names = _declared_symbols()
+    names = _declared_symbols("hashgrid.h")
     assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert not any("probe" in n for n in names)  # measurement tooling is not behind the method's ABI
+
+
+def test_probe_library_is_built_and_exports_every_declared_symbol():
+    assert os.path.exists(PROBES_LIB_PATH), "build the probes first: __graft_entry__.build()"
+    lib = ctypes.CDLL(PROBES_LIB_PATH)
+    names = _declared_symbols("hashgrid_probes.h")
+    assert set(names) == set(binding.PROBE_EXPORTS)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -118,7 +128,7 @@ def test_adam_step_status_codes_need_no_device():
 
 
 def test_probe_status_codes_need_no_device():
-    lib = binding.load_library()
+    lib = binding.load_probes()
     assert lib.hashgrid_probe_copy(None, None, 0, None) == 0
     assert lib.hashgrid_probe_copy(None, 4096, 64, None) == 1
     assert lib.hashgrid_probe_copy(4096, 8192, 24, None) == 1      # not a multiple of 16
@@ -128,6 +138,10 @@ def test_probe_status_codes_need_no_device():
     assert lib.hashgrid_probe_gather(4096, 1024, 100, 1, 8192, None) == 1    # not a multiple of 4096
     assert lib.hashgrid_probe_atomic_add(None, 1024, 4096, 1, None) == 1
     assert lib.hashgrid_probe_atomic_add(4096, 1 << 33, 4096, 1, None) == 1
+    assert lib.hashgrid_probe_gather_lines(None, 1024, 1, 0, 16, 1, None, None) == 0
+    assert lib.hashgrid_probe_gather_lines(4096, 1000, 1, 1024, 16, 1, 8192, None) == 1   # slice not a power of two
+    assert lib.hashgrid_probe_gather_lines(4096, 1024, 1, 1000, 16, 1, 8192, None) == 1   # not a multiple of 1024
+    assert lib.hashgrid_probe_gather_lines(4096, 1024, 0, 1024, 16, 1, 8192, None) == 1   # no slice
 
 
 def test_encode_mlp_status_codes_need_no_device():
