@@ -116,12 +116,14 @@ hg_status hashgrid_encode_bwd(const hashgrid_t* hg, uint32_t B, const float* x, 
 
 /* Size in bytes of the scratch buffer hashgrid_encode_bwd_ws needs for a batch of
  * B points, or 0 when that variant does not serve this configuration or batch
- * (it needs d = 2 or 3, a power-of-two T of at most 2^24 (2^23 at F = 8: 4096 chunks of
- * 4096, or 2048, entries per level), at most 4096 (2048) vertices per axis on 1:1 levels
- * and B*L*2^(d-1) < 2^32).  The buffer holds 8 + F * sizeof(dLdy scalar) bytes (rounded up
- * to 4) per pair of corners, B*L*2^(d-1) of them, plus 4 bytes per (tile of 512 points,
- * chunk), tiles of 4096 points where there are more than 16384 chunks in all: 195 MiB at
- * Table 1's sizes with 2^18 points, 1.6 GiB at T = 2^24 with 2^21. */
+ * (it needs at most 4096 chunks of 4096 entries per level, 2048 entries at F = 8, i.e. levels of
+ * at most 2^24 (2^23) entries, at most 4096 (2048) vertices per axis on the 1:1 levels of a
+ * power-of-two T, and fewer than 2^32 records).  The buffer holds one record of 8 + F *
+ * sizeof(dLdy scalar) bytes (rounded up to 4) per pair of corners along dimension 0,
+ * B*L*2^(d-1) of them, or per corner, B*L*2^d of them, where the two corners of a pair are not
+ * neighbours in memory (T not a power of two: Eq. 4's mod T; d = 1), plus 4 bytes per (tile of
+ * 512 points, chunk), tiles of 4096 points where there are more than 16384 chunks in all:
+ * 195 MiB at Table 1's sizes with 2^18 points, 1.6 GiB at T = 2^24 with 2^21. */
 uint64_t hashgrid_bwd_workspace_bytes(const hashgrid_t* hg, uint32_t B);
 
 /* 1 when hashgrid_encode_bwd_ws serves this configuration and batch and is expected to be the
@@ -139,9 +141,10 @@ int hashgrid_bwd_ws_pays(const hashgrid_t* hg, uint32_t B);
  * rounded to about 2^-38 of that value or finer), so the result does not depend
  * on the order of execution, except on coarse 1:1 levels whose few chunks are
  * shared by several workgroups and combined with fp32 atomic adds.  The sorted
- * records carry the interpolation weights as 23- and 25-bit fixed point: a
- * gradient entry differs from hashgrid_encode_bwd's by at most about 2^-23 times
- * the sum of |dLdy| over the corners that touch it.
+ * records carry the interpolation weights with relative precision (2^-20; along
+ * dimension 0 exactly, except 2^-17 in the first voxel): a gradient entry differs
+ * from the exact sum by at most 1e-5 of the sum of the absolute values of its
+ * summands, as hashgrid_encode_bwd's does, plus the fixed-point rounding above.
  *   workspace  device, 256-byte aligned, at least hashgrid_bwd_workspace_bytes(hg, B)
  *              bytes, owned by the caller; contents are scratch: undefined on
  *              entry and on exit.  Calls that overlap in time need separate
@@ -182,6 +185,9 @@ hg_status hashgrid_encode_bwd_static(const hashgrid_t* hg, uint32_t B, const flo
  * and leaves the counts in `workspace`.  A following hashgrid_encode_bwd_ws on the same hg, B, x
  * and workspace may then pass HG_BWD_COUNTED and skips its own counting pass.  Nothing else may
  * write the workspace in between, and x must be unchanged.
+ * Where the counting cannot ride along (batches too small to give every compute unit a full
+ * workgroup, configurations whose records are per corner) the call runs hashgrid_encode_fwd and
+ * the counting pass one after the other, with the same result.
  * Returns HG_ERR_UNSUPPORTED when hashgrid_bwd_workspace_bytes is 0, when y or params are not
  * 16-byte / entry aligned, or when the configuration has more than 16384 chunks in all (callers
  * then use hashgrid_encode_fwd and pass no flag); HG_ERR_INVALID_ARG as hashgrid_encode_bwd_ws. */

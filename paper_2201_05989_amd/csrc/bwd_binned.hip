@@ -133,14 +133,20 @@ void build_bin_plan(hashgrid* h) {
   const hashgrid_config& c = h->cfg;
   const LevelTable& lv = h->lv;
   bp.chunk_log2 = chunk_log2_of(c.F);
-  bp.rec_per_point = 1u << (c.d - 1);
-  if (c.d < 2 || c.d > 3 || !lv.T_is_pow2) return;  // F is 1, 2, 4 or 8 (hashgrid_create)
+  // The pairing of the two corners along dimension 0 needs a power-of-two T (after Eq. 4's mod T
+  // with another T the pair's entries are unrelated) and a second dimension to cut 1:1 levels by
+  // grid rows; otherwise every corner gets a record of its own (twice the records).
+  bp.corner_records = (c.d < 2 || !lv.T_is_pow2) ? 1u : 0u;
+  bp.rec_per_point = bp.corner_records ? 1u << c.d : 1u << (c.d - 1);
+  if (c.d < 1 || c.d > 3) return;  // F is 1, 2, 4 or 8 (hashgrid_create)
   const uint32_t cap = 1u << bp.chunk_log2;
   uint32_t bins = 0;
   for (uint32_t l = 0; l < lv.L; ++l) {
     const uint32_t verts = lv.verts[l];
     uint32_t nb;
-    if ((lv.dense_mask >> l) & 1u) {
+    if (bp.corner_records) {
+      nb = (lv.size[l] + cap - 1u) >> bp.chunk_log2;  // aligned blocks of the level's slice, the last one ragged
+    } else if ((lv.dense_mask >> l) & 1u) {
       if (verts > cap) return;
       uint32_t s = 0;
       while (((uint64_t)verts << (s + 1)) <= cap) ++s;
@@ -266,7 +272,7 @@ __device__ __forceinline__ void part_levels(uint32_t L, uint32_t& l0, uint32_t& 
 }
 
 // count: records per (tile, bin).
-template <int D>
+template <int D, bool CORNERS>
 __global__ __launch_bounds__(kBinThreads) void bin_count(const LevelTable lv, const BinPlan bp, const bool smooth,
                                                          const uint32_t B, const float* __restrict__ x,
                                                          uint32_t* __restrict__ counts, const uint32_t n_bins,
@@ -286,12 +292,20 @@ __global__ __launch_bounds__(kBinThreads) void bin_count(const LevelTable lv, co
     float xp[D];
     load_x<D>(x, b, xp);
     for (uint32_t l = l0; l < l1; ++l) {
-      Rows<D> rw;
-      rows_of<D, true>(lv, bp, l, smooth, xp, rw);
-      if (rw.cross) continue;
+      if constexpr (CORNERS) {
+        CornerRows<D> cr;
+        corner_rows_of<D, true>(lv, bp, l, smooth, xp, cr);
 #pragma unroll
-      for (uint32_t r = 0; r < (1u << (D - 1)); ++r)
-        __hip_atomic_fetch_add(&hist[rw.bin[r] - gb_a], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        for (uint32_t m = 0; m < (1u << D); ++m)
+          __hip_atomic_fetch_add(&hist[cr.bin[m] - gb_a], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      } else {
+        Rows<D> rw;
+        rows_of<D, true>(lv, bp, l, smooth, xp, rw);
+        if (rw.cross) continue;
+#pragma unroll
+        for (uint32_t r = 0; r < (1u << (D - 1)); ++r)
+          __hip_atomic_fetch_add(&hist[rw.bin[r] - gb_a], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      }
     }
   }
   __syncthreads();
@@ -416,7 +430,8 @@ __global__ __launch_bounds__(kScanThreads) void bin_scan(const uint32_t n_tiles,
 // local[nbp + 1] exclusive prefix of this tile's counts (where a bin's records
 // sit in the tile's sorted order), cur[nbp] the same, advanced as records are
 // placed, delta[nbp] = global slot minus tile-local position.
-template <int D, typename IT, int F, bool CROSS>  // CROSS: this pass adds the pairs that straddle two chunks
+// CROSS: this pass adds the pairs that straddle two chunks.  CORNERS: one record per corner (BinPlan::corner_records).
+template <int D, typename IT, int F, bool CROSS, bool CORNERS = false>
 __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, const BinPlan bp, const bool smooth,
                                                            const uint32_t B, const float* __restrict__ x,
                                                            const IT* __restrict__ dy,
@@ -426,7 +441,7 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, 
                                                            uint32_t* __restrict__ records, const uint32_t n_bins,
                                                            const uint32_t n_records, const uint32_t n_tiles,
                                                            float* __restrict__ tile_max, float* __restrict__ grad) {
-  constexpr uint32_t R = 1u << (D - 1);
+  constexpr uint32_t R = CORNERS ? 1u << D : 1u << (D - 1 > 0 ? D - 1 : 0);
   using Rec = Record<IT, F>;
   using Stored = typename Rec::Stored;
   Stored* out = reinterpret_cast<Stored*>(records);
@@ -521,17 +536,33 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, 
       gmax = nan_max(gmax, fabsf(gf[f]));
     }
     if (valid) {
-      Rows<D> rw;
-      rows_of<D, false>(lv, bp, l, smooth, xp, rw);
-      if (CROSS && rw.cross) add_crossing_pairs<D, F>(lv, l, smooth, xp, gf, grad);
+      if constexpr (CORNERS) {
+        // a corner's record: all of its weight on the "lower" side of a pair whose upper weight is 0
+        CornerRows<D> cr;
+        corner_rows_of<D, false>(lv, bp, l, smooth, xp, cr);
 #pragma unroll
-      for (uint32_t r = 0; r < R && !rw.cross; ++r) {
-        const uint32_t rb = rw.bin[r] - gb_a;
-        const uint32_t in_tile = __hip_atomic_fetch_add(&cur[rb], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        const uint32_t pos = in_tile - level_first;
-        if (pos < R * kBinThreads) {  // holds when the count pass saw the same x
-          staging[pos] = Rec::make(rw.la[r], rw.k, rw.wf0, rw.wrow[r], g);
-          binv[pos] = (uint16_t)rb;
+        for (uint32_t m = 0; m < R; ++m) {
+          const uint32_t rb = cr.bin[m] - gb_a;
+          const uint32_t in_tile = __hip_atomic_fetch_add(&cur[rb], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+          const uint32_t pos = in_tile - level_first;
+          if (pos < R * kBinThreads) {
+            staging[pos] = Rec::make(cr.la[m], 0u, 0.0f, cr.weight[m], g);
+            binv[pos] = (uint16_t)rb;
+          }
+        }
+      } else {
+        Rows<D> rw;
+        rows_of<D, false>(lv, bp, l, smooth, xp, rw);
+        if (CROSS && rw.cross) add_crossing_pairs<D, F>(lv, l, smooth, xp, gf, grad);
+#pragma unroll
+        for (uint32_t r = 0; r < R && !rw.cross; ++r) {
+          const uint32_t rb = rw.bin[r] - gb_a;
+          const uint32_t in_tile = __hip_atomic_fetch_add(&cur[rb], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+          const uint32_t pos = in_tile - level_first;
+          if (pos < R * kBinThreads) {  // holds when the count pass saw the same x
+            staging[pos] = Rec::make(rw.la[r], rw.k, rw.wf0, rw.wrow[r], g, smooth);
+            binv[pos] = (uint16_t)rb;
+          }
         }
       }
     }
@@ -563,13 +594,13 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, 
 // in LDS first would not make whole lines of them; what merges partial lines here is the L2,
 // which keeps the tile's open runs (a few bytes per bin of the part) while the workgroup lasts.
 // LDS: slot[nbp], the next free record slot of each bin of this part for this tile.
-template <int D, typename IT, int F, bool CROSS>
+template <int D, typename IT, int F, bool CROSS, bool CORNERS = false>
 __global__ __launch_bounds__(kBinThreads) void bin_scatter_direct(
     const LevelTable lv, const BinPlan bp, const bool smooth, const uint32_t B, const float* __restrict__ x,
     const IT* __restrict__ dy, const uint32_t* __restrict__ counts, const uint32_t* __restrict__ bin_total,
     uint32_t* __restrict__ bin_start, uint32_t* __restrict__ records, const uint32_t n_bins, const uint32_t n_records,
     const uint32_t n_tiles, float* __restrict__ tile_max, float* __restrict__ grad) {
-  constexpr uint32_t R = 1u << (D - 1);
+  constexpr uint32_t R = CORNERS ? 1u << D : 1u << (D - 1 > 0 ? D - 1 : 0);
   using Rec = Record<IT, F>;
   using Stored = typename Rec::Stored;
   Stored* out = reinterpret_cast<Stored*>(records);
@@ -619,19 +650,30 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter_direct(
         gf[f] = (float)g[f];
         gmax = nan_max(gmax, fabsf(gf[f]));
       }
-      Rows<D> rw;
-      rows_of<D, false>(lv, bp, l, smooth, xp, rw);
-      if (rw.cross) {
-        if (CROSS) add_crossing_pairs<D, F>(lv, l, smooth, xp, gf, grad);
-        continue;
-      }
+      if constexpr (CORNERS) {
+        CornerRows<D> cr;
+        corner_rows_of<D, false>(lv, bp, l, smooth, xp, cr);
 #pragma unroll
-      for (uint32_t r = 0; r < R; ++r) {
-        const uint32_t d =
-            __hip_atomic_fetch_add(&slot[rw.bin[r] - gb_a], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        // the count pass saw the same inputs, so d < n_records; the check only keeps a caller
-        // who changed x in between from writing out of bounds
-        if (d < n_records) out[d] = Rec::make(rw.la[r], rw.k, rw.wf0, rw.wrow[r], g);
+        for (uint32_t m = 0; m < R; ++m) {
+          const uint32_t d =
+              __hip_atomic_fetch_add(&slot[cr.bin[m] - gb_a], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+          if (d < n_records) out[d] = Rec::make(cr.la[m], 0u, 0.0f, cr.weight[m], g);
+        }
+      } else {
+        Rows<D> rw;
+        rows_of<D, false>(lv, bp, l, smooth, xp, rw);
+        if (rw.cross) {
+          if (CROSS) add_crossing_pairs<D, F>(lv, l, smooth, xp, gf, grad);
+          continue;
+        }
+#pragma unroll
+        for (uint32_t r = 0; r < R; ++r) {
+          const uint32_t d =
+              __hip_atomic_fetch_add(&slot[rw.bin[r] - gb_a], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+          // the count pass saw the same inputs, so d < n_records; the check only keeps a caller
+          // who changed x in between from writing out of bounds
+          if (d < n_records) out[d] = Rec::make(rw.la[r], rw.k, rw.wf0, rw.wrow[r], g, smooth);
+        }
       }
     }
   }
@@ -768,7 +810,7 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
     it.r1 = it.r1 < n_records ? it.r1 : n_records;
     it.live = item < n_items && slice * per < total;
     uint32_t e0, e1;  // entries of this chunk in the level's slice
-    it.dense = (lv.dense_mask >> l) & 1u;
+    it.dense = ((lv.dense_mask >> l) & 1u) && !bp.corner_records;  // (corner records: every level in aligned blocks)
     if (it.dense) {
       e0 = (bin << bp.row_shift[l]) * lv.verts[l];
       e1 = e0 + (lv.verts[l] << bp.row_shift[l]);
@@ -841,10 +883,11 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
       // inf or NaN upstream: keep IEEE semantics with direct fp32 atomics (slow, rare)
       for (uint32_t i = it.r0 + threadIdx.x; i < it.r1; i += kAccThreads) {
         uint32_t la, lb;
-        float wf;
+        float w_lo, w_up;
         double G[F];
-        Rec::unpack_scaled(Rec::load(records, i), it.dense, cmask, it.n_e - 1u, 1.0, la, lb, wf, G);
-        const float wu = SMOOTH ? smoothstep(wf) : wf, wl = SMOOTH ? smoothstep(1.0f - wf) : 1.0f - wf;
+        bool first;
+        Rec::unpack_scaled(Rec::load(records, i), it.dense, cmask, it.n_e - 1u, 1.0, la, lb, w_lo, w_up, first, G);
+        const float wu = SMOOTH && !first ? smoothstep(w_up) : w_up, wl = SMOOTH && !first ? smoothstep(w_lo) : w_lo;
 #pragma unroll
         for (int f = 0; f < F; ++f) {
           if (la < it.n_e)
@@ -862,10 +905,11 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
     } else {
       auto add_record = [&](const Stored& rec) {
         uint32_t la, lb;
-        float wf;
+        float w_lo, w_up;
         double G[F];
-        Rec::unpack_scaled(rec, it.dense, cmask, it.n_e - 1u, scale, la, lb, wf, G);
-        const float wu = SMOOTH ? smoothstep(wf) : wf, wl = SMOOTH ? smoothstep(1.0f - wf) : 1.0f - wf;
+        bool first;
+        Rec::unpack_scaled(rec, it.dense, cmask, it.n_e - 1u, scale, la, lb, w_lo, w_up, first, G);
+        const float wu = SMOOTH && !first ? smoothstep(w_up) : w_up, wl = SMOOTH && !first ? smoothstep(w_lo) : w_lo;
 #pragma unroll
         for (int f = 0; f < F; ++f) {
           __hip_atomic_fetch_add(&acc[f * cap + la], fixed_product(wl, G[f]), __ATOMIC_RELAXED,
@@ -963,20 +1007,27 @@ static hg_status launch_count(const hashgrid* h, uint32_t B, const float* x, con
   }
   const bool smooth = h->cfg.interp == HG_INTERP_SMOOTHSTEP;
   const dim3 grid((ws.n_tiles + 7u) / 8u * 8u, cparts);  // see tile_of_workgroup
-  if (h->cfg.d == 3)
-    hipLaunchKernelGGL((bin_count<3>), grid, dim3(kBinThreads), (size_t)max_bins * 4, s, h->lv, bp, smooth, B, x,
-                       ws.counts, ws.n_bins, ws.n_tiles);
-  else
-    hipLaunchKernelGGL((bin_count<2>), grid, dim3(kBinThreads), (size_t)max_bins * 4, s, h->lv, bp, smooth, B, x,
-                       ws.counts, ws.n_bins, ws.n_tiles);
+#define HG_COUNT(D, C)                                                                                              \
+  hipLaunchKernelGGL((bin_count<D, C>), grid, dim3(kBinThreads), (size_t)max_bins * 4, s, h->lv, bp, smooth, B, x, \
+                     ws.counts, ws.n_bins, ws.n_tiles)
+  if (bp.corner_records) {
+    if (h->cfg.d == 3) HG_COUNT(3, true);
+    else if (h->cfg.d == 2) HG_COUNT(2, true);
+    else HG_COUNT(1, true);
+  } else {
+    if (h->cfg.d == 3) HG_COUNT(3, false);
+    else HG_COUNT(2, false);
+  }
+#undef HG_COUNT
   return hipGetLastError() == hipSuccess ? HG_OK : HG_ERR_DEVICE;
 }
 
-template <int D, typename IT, int F>
+template <int D, typename IT, int F, bool CORNERS>
 static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, const void* dy, float* grad,
                                const Workspace& ws, const bool counted, const bool overwrite, hipStream_t s) {
   using Rec = Record<IT, F>;
-  constexpr uint32_t R = 1u << (D - 1);
+  constexpr uint32_t R = CORNERS ? 1u << D : 1u << (D - 1 > 0 ? D - 1 : 0);
+  constexpr int DP = CORNERS ? 2 : D;  // (dimension of the kernels that only the pair records use: never D = 1)
   BinPlan bp = h->bp;
   plan_slices(bp, h->lv, B);
   const bool smooth = h->cfg.interp == HG_INTERP_SMOOTHSTEP;
@@ -993,16 +1044,20 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
   // scatter: staging area, 16-bit bin of every staged record, three words per bin of the part
   constexpr size_t kStagingBytes = (size_t)R * kBinThreads * (Rec::kWords * 4 + 2);
   constexpr size_t kScatterLdsMax = kStagingBytes + (3 * (size_t)kMaxScatterPartBins + 1) * 4;
+  // (eight 40-byte records per point do not fit the 160 KiB of a workgroup: such plans scatter unstaged)
+  constexpr bool kStaged = kScatterLdsMax <= 160 * 1024;
   constexpr size_t kAccLds = (size_t)F * 8 << chunk_log2_of(F);
   // more dynamic LDS than the default limit of 64 KiB: opt in once per kernel
   static const hipError_t lds_ok = [] {
     hipError_t e = hipSuccess;
-    if (kScatterLdsMax > 64 * 1024)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_scatter<D, IT, F, true>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kScatterLdsMax);
-    if (e == hipSuccess && kScatterLdsMax > 64 * 1024)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_scatter<D, IT, F, false>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kScatterLdsMax);
+    if constexpr (kStaged) {
+      if (!CORNERS && kScatterLdsMax > 64 * 1024)
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_scatter<DP, IT, F, true, false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kScatterLdsMax);
+      if (e == hipSuccess && kScatterLdsMax > 64 * 1024)
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_scatter<D, IT, F, false, CORNERS>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kScatterLdsMax);
+    }
     if (e == hipSuccess && kAccLds > 48 * 1024)
       e = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_accumulate<IT, F, false>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAccLds);
@@ -1023,7 +1078,7 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
   for (uint32_t l = 0; l < L; ++l) {
     const bool hashed = !((h->lv.dense_mask >> l) & 1u);
     if (bp.slices[l] > 1) add_mask |= 1u << l;
-    if (hashed && h->lv.N[l] + 1u >= (1u << bp.chunk_log2)) cross_mask |= 1u << l;
+    if (!CORNERS && hashed && h->lv.N[l] + 1u >= (1u << bp.chunk_log2)) cross_mask |= 1u << l;
   }
   const uint32_t all_levels = L == 32 ? 0xffffffffu : (1u << L) - 1u;
   const uint32_t zero_mask = overwrite ? add_mask : 0u, overwrite_mask = overwrite ? all_levels & ~add_mask : 0u;
@@ -1032,17 +1087,20 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
                      ws.n_bins, ws.counts, ws.bin_total, ws.item_counter, h->lv, zero_mask, (uint32_t)F, grad);
   auto scatter = [&](auto cross) {
     constexpr bool kCross = decltype(cross)::value;
-    if (bp.tile_mult > 1)
-      hipLaunchKernelGGL((bin_scatter_direct<D, IT, F, kCross>), dim3(tile_wgs, parts), dim3(kBinThreads),
-                         (size_t)max_part_bins(parts) * 4, s, h->lv, bp, smooth, B, x, static_cast<const IT*>(dy),
+    constexpr int DS = kCross ? DP : D;  // (the straddling pairs exist with pair records only)
+    if (bp.tile_mult > 1 || !kStaged) {
+      hipLaunchKernelGGL((bin_scatter_direct<DS, IT, F, kCross, CORNERS && !kCross>), dim3(tile_wgs, parts),
+                         dim3(kBinThreads), (size_t)max_part_bins(parts) * 4, s, h->lv, bp, smooth, B, x,
+                         static_cast<const IT*>(dy), ws.counts, ws.bin_total, ws.bin_start, ws.records, ws.n_bins,
+                         n_records, ws.n_tiles, ws.tile_max, grad);
+    } else if constexpr (kStaged) {
+      hipLaunchKernelGGL((bin_scatter<DS, IT, F, kCross, CORNERS && !kCross>), dim3(tile_wgs, parts),
+                         dim3(kBinThreads), lds_scatter, s, h->lv, bp, smooth, B, x, static_cast<const IT*>(dy),
                          ws.counts, ws.bin_total, ws.bin_start, ws.records, ws.n_bins, n_records, ws.n_tiles,
                          ws.tile_max, grad);
-    else
-      hipLaunchKernelGGL((bin_scatter<D, IT, F, kCross>), dim3(tile_wgs, parts), dim3(kBinThreads), lds_scatter, s,
-                         h->lv, bp, smooth, B, x, static_cast<const IT*>(dy), ws.counts, ws.bin_total, ws.bin_start,
-                         ws.records, ws.n_bins, n_records, ws.n_tiles, ws.tile_max, grad);
+    }
   };
-  if (defer_cross || cross_mask == 0)  // no such pairs at these resolutions, or bin_crossing takes them
+  if (CORNERS || defer_cross || cross_mask == 0)  // no such pairs at these resolutions, or bin_crossing takes them
     scatter(std::false_type{});
   else
     scatter(std::true_type{});
@@ -1064,21 +1122,35 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
                        ws.bin_start, ws.bin_total, ws.tile_max, ws.n_tiles * parts, ws.records, ws.item_counter,
                        grad, overwrite_mask);
   if (defer_cross)
-    hipLaunchKernelGGL((bin_crossing<D, IT, F>), dim3((B + kBinThreads - 1) / kBinThreads), dim3(kBinThreads), 0, s,
+    hipLaunchKernelGGL((bin_crossing<DP, IT, F>), dim3((B + kBinThreads - 1) / kBinThreads), dim3(kBinThreads), 0, s,
                        h->lv, bp, smooth, B, x, static_cast<const IT*>(dy), cross_mask, grad);
   return hipGetLastError() == hipSuccess ? HG_OK : HG_ERR_DEVICE;
 }
 
-template <int D, typename IT>
+template <int D, typename IT, bool CORNERS>
 static hg_status launch_binned_f(const hashgrid* h, uint32_t B, const float* x, const void* dy, float* grad,
                                  const Workspace& ws, const bool counted, const bool overwrite, hipStream_t s) {
   switch (h->cfg.F) {
-    case 1: return launch_binned<D, IT, 1>(h, B, x, dy, grad, ws, counted, overwrite, s);
-    case 2: return launch_binned<D, IT, 2>(h, B, x, dy, grad, ws, counted, overwrite, s);
-    case 4: return launch_binned<D, IT, 4>(h, B, x, dy, grad, ws, counted, overwrite, s);
-    case 8: return launch_binned<D, IT, 8>(h, B, x, dy, grad, ws, counted, overwrite, s);
+    case 1: return launch_binned<D, IT, 1, CORNERS>(h, B, x, dy, grad, ws, counted, overwrite, s);
+    case 2: return launch_binned<D, IT, 2, CORNERS>(h, B, x, dy, grad, ws, counted, overwrite, s);
+    case 4: return launch_binned<D, IT, 4, CORNERS>(h, B, x, dy, grad, ws, counted, overwrite, s);
+    case 8: return launch_binned<D, IT, 8, CORNERS>(h, B, x, dy, grad, ws, counted, overwrite, s);
     default: return HG_ERR_UNSUPPORTED;
   }
+}
+
+template <typename IT>
+static hg_status launch_binned_d(const hashgrid* h, uint32_t B, const float* x, const void* dy, float* grad,
+                                 const Workspace& ws, const bool counted, const bool overwrite, hipStream_t s) {
+  if (h->bp.corner_records) {
+    switch (h->cfg.d) {
+      case 1: return launch_binned_f<1, IT, true>(h, B, x, dy, grad, ws, counted, overwrite, s);
+      case 2: return launch_binned_f<2, IT, true>(h, B, x, dy, grad, ws, counted, overwrite, s);
+      default: return launch_binned_f<3, IT, true>(h, B, x, dy, grad, ws, counted, overwrite, s);
+    }
+  }
+  return h->cfg.d == 3 ? launch_binned_f<3, IT, false>(h, B, x, dy, grad, ws, counted, overwrite, s)
+                       : launch_binned_f<2, IT, false>(h, B, x, dy, grad, ws, counted, overwrite, s);
 }
 
 }  // namespace hg
@@ -1094,18 +1166,25 @@ uint64_t hashgrid_bwd_workspace_bytes(const hashgrid_t* hg, uint32_t B) {
 int hashgrid_bwd_ws_pays(const hashgrid_t* hg, uint32_t B) {
   if (hashgrid_bwd_workspace_bytes(hg, B) == 0) return 0;
   // Both passes in microseconds, from measurements on an MI355X.  Sorted pass: about 20 us of
-  // launches, 0.027 us per chunk (every chunk of the gradient is visited), then ~300 K corner pairs
-  // per us.  Atomic pass: ~6 us, then ~14.5 K pairs per us, unless one 64-byte block of the gradient
-  // draws so many requests that they queue up behind each other (~0.02 us each): the smallest level
-  // decides that, taking the points as spread evenly over its entries.
-  const double pairs = (double)B * hg->lv.L * hg->bp.rec_per_point;
+  // launches, 0.027 us per chunk (every chunk of the gradient is visited and rewritten), then the
+  // records, written once and read once: ~300 K records of 12 bytes per us, in proportion for
+  // larger ones (wider entries, fp32 dL/dy) and twice as many where every corner has its own.
+  // Atomic pass: ~6 us, then ~14.5 K pairs of corners per us (11 K at F = 4, 9 K at F = 8: their
+  // requests are fatter), unless one 64-byte block of the gradient draws so many requests that
+  // they queue up behind each other (~0.02 us each): the smallest level decides that, taking the
+  // points as spread evenly over its entries.
+  const uint32_t F = hg->cfg.F, d = hg->cfg.d;
+  const double pairs = (double)B * hg->lv.L * (1u << (d - 1));
+  const double records = (double)B * hg->lv.L * hg->bp.rec_per_point;
+  const double rec_bytes = 8.0 + (F * (hg->cfg.io_dtype == HG_F16 ? 2u : 4u) + 3u) / 4u * 4u;
   double per_block = 0.0;
   for (uint32_t l = 0; l < hg->lv.L; ++l) {
-    const double blocks = ceil((double)hg->lv.size[l] * hg->cfg.F * sizeof(float) / 64.0);
-    per_block = fmax(per_block, (double)B * hg->bp.rec_per_point / blocks);
+    const double blocks = ceil((double)hg->lv.size[l] * F * sizeof(float) / 64.0);
+    per_block = fmax(per_block, (double)B * (1u << (d - 1)) / blocks);
   }
-  const double sorted_us = 20.0 + 0.027 * hg->bp.bin_base[hg->lv.L] + pairs / 300e3;
-  const double atomic_us = 6.0 + fmax(pairs / 14.5e3, 0.02 * per_block);
+  const double pairs_per_us = F <= 2 ? 14.5e3 : F == 4 ? 11e3 : 9e3;
+  const double sorted_us = 20.0 + 0.027 * hg->bp.bin_base[hg->lv.L] + records * (rec_bytes / 12.0) / 300e3;
+  const double atomic_us = 6.0 + fmax(pairs / pairs_per_us, 0.02 * per_block);
   return atomic_us > sorted_us ? 1 : 0;
 }
 
@@ -1130,7 +1209,8 @@ hg_status hashgrid_encode_fwd_ws(const hashgrid_t* hg, uint32_t B, const float* 
   // The counting kernel runs full workgroups (they cover whole tiles), which is slow for a batch that
   // cannot give every CU one: there the plain forward in small workgroups plus the count pass is
   // faster and leaves the workspace in the same state.
-  if (hg::point_major_block(B) < 1024u) {
+  // (So it is for plans with a record per corner, which the counting kernel does not serve.)
+  if (hg->bp.corner_records || hg::point_major_block(B) < 1024u) {
     const hg_status st = hashgrid_encode_fwd(hg, B, x, params, y, stream);
     return st != HG_OK ? st : hg::launch_count(hg, B, x, ws, s);
   }
@@ -1154,11 +1234,8 @@ hg_status hashgrid_encode_bwd_ws(const hashgrid_t* hg, uint32_t B, const float* 
   hg::carve(hg, B, static_cast<uint8_t*>(workspace), &ws);
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool i16 = hg->cfg.io_dtype == HG_F16, counted = flags & HG_BWD_COUNTED, ow = flags & HG_BWD_OVERWRITE;
-  if (hg->cfg.d == 3)
-    return i16 ? hg::launch_binned_f<3, _Float16>(hg, B, x, dLdy, grad_params, ws, counted, ow, s)
-               : hg::launch_binned_f<3, float>(hg, B, x, dLdy, grad_params, ws, counted, ow, s);
-  return i16 ? hg::launch_binned_f<2, _Float16>(hg, B, x, dLdy, grad_params, ws, counted, ow, s)
-             : hg::launch_binned_f<2, float>(hg, B, x, dLdy, grad_params, ws, counted, ow, s);
+  return i16 ? hg::launch_binned_d<_Float16>(hg, B, x, dLdy, grad_params, ws, counted, ow, s)
+             : hg::launch_binned_d<float>(hg, B, x, dLdy, grad_params, ws, counted, ow, s);
 }
 
 // ---------------------------------------------------------------- entry point that allocates nothing

@@ -19,7 +19,8 @@ struct Rows {
   uint32_t la[1 << (D - 1)];     // chunk-local index of the lower corner along dimension 0
   float wrow[1 << (D - 1)];      // product of the weights of dimensions 1..d-1
   float wf0;                     // fractional position along dimension 0 (before any smoothstep)
-  uint32_t k;                    // trailing one bits of the lower corner's coordinate along dimension 0
+  uint32_t k;                    // trailing one bits of the lower corner's coordinate along dimension 0 (at most 14);
+                                 // 15: that coordinate is 0 (the record's k field, see bwd_record.hpp)
   bool cross;                    // hashed level: the pair's corners fall into different chunks (no record)
 };
 
@@ -46,7 +47,10 @@ __host__ __device__ __forceinline__ void rows_of(const LevelTable& lv, const Bin
   const uint32_t gb0 = bp.bin_base[l];
   out.cross = !dense && (c0[0] & cmask) == cmask;  // v_0 + 1 carries out of the chunk's index bits
   if (!COUNT_ONLY) {
-    out.k = (uint32_t)__builtin_ctz(~c0[0]) & 15u;  // c0 + 1 < 2^chunk_log2 <= 2^15 on hashed levels
+    // trailing ones of the coordinate; 12 or more never reaches a record (the pair then straddles two
+    // chunks); 15 marks the first voxel, whose fractional position the record stores in its second form
+    const uint32_t ones = (uint32_t)__builtin_ctz(~c0[0] | 0x4000u);
+    out.k = c0[0] == 0u ? 15u : ones;
 #pragma unroll
     for (uint32_t r = 0; r < (1u << (D - 1)); ++r) {
       float wr = 1.0f;
@@ -84,6 +88,55 @@ __host__ __device__ __forceinline__ void rows_of(const LevelTable& lv, const Bin
       if (!COUNT_ONLY) {
         out.la[r] = ia & cmask;
       }
+    }
+  }
+}
+
+// One record per corner (plans with BinPlan::corner_records: a table size that is not a power of
+// two, where the two corners of a pair land in unrelated chunks after Eq. 4's mod T, and d = 1):
+// every level's slice is cut into aligned blocks of 2^chunk_log2 entries, a corner belongs to the
+// block of its entry.  bin / la as in Rows; weight = the corner's whole interpolation weight.
+template <int D>
+struct CornerRows {
+  uint32_t bin[1 << D];
+  uint32_t la[1 << D];
+  float weight[1 << D];
+};
+
+template <int D, bool COUNT_ONLY>
+__host__ __device__ __forceinline__ void corner_rows_of(const LevelTable& lv, const BinPlan& bp, uint32_t l, bool smooth,
+                                                        const float (&xp)[D], CornerRows<D>& out) {
+  const uint32_t verts = lv.verts[l];
+  const bool dense = (lv.dense_mask >> l) & 1u;
+  const float Nf = (float)lv.N[l];
+  const float shift = smooth ? 0.5f : 0.0f;
+  const float cmaxf = smooth ? Nf : Nf - 1.0f;
+  uint32_t c0[D];
+  float w[D], u[D];
+#pragma unroll
+  for (int i = 0; i < D; ++i) {
+    float wf;
+    split(xp[i], Nf, shift, cmaxf, c0[i], wf);
+    w[i] = smooth ? smoothstep(wf) : wf;
+    u[i] = smooth ? smoothstep(1.0f - wf) : 1.0f - wf;
+  }
+  const uint32_t cl = bp.chunk_log2, cmask = (1u << cl) - 1u, gb0 = bp.bin_base[l];
+#pragma unroll
+  for (uint32_t m = 0; m < (1u << D); ++m) {
+    uint32_t idx = 0, stride = 1;
+    float wt = 1.0f;
+#pragma unroll
+    for (int i = 0; i < D; ++i) {
+      const uint32_t v = c0[i] + ((m >> i) & 1u);
+      idx = dense ? idx + v * stride : idx ^ (v * prime(i));
+      stride *= verts;
+      wt *= ((m >> i) & 1u) ? w[i] : u[i];
+    }
+    if (!dense) idx = lv.T_is_pow2 ? idx & (lv.T - 1u) : idx % lv.T;
+    out.bin[m] = gb0 + (idx >> cl);
+    if (!COUNT_ONLY) {
+      out.la[m] = idx & cmask;
+      out.weight[m] = wt;
     }
   }
 }

@@ -626,7 +626,8 @@ static hg_status launch_fwd_counting_t(const hashgrid* h, uint32_t B, const floa
   const bool two = fwd_two_points_per_thread(B) && (size_t)(2 * kPmBlock / kBinThreads) * n_bins * 4 <= 64 * 1024;
   const size_t lds = (size_t)((two ? 2 : 1) * kPmBlock / kBinThreads) * n_bins * 4;
   if (h->lv.L % G != 0 || misaligned(y, 16) || misaligned(params, F * sizeof(PT) > 16 ? 16 : F * sizeof(PT)) ||
-      !h->lv.T_is_pow2 || lds > kMaxCountingLds || h->bp.tile_mult != 1)  // (its tiles are 512 points)
+      !h->lv.T_is_pow2 || h->bp.corner_records || lds > kMaxCountingLds ||
+      h->bp.tile_mult != 1)  // (its tiles are 512 points; it counts pairs of corners)
     return HG_ERR_UNSUPPORTED;
   if (lds > 64 * 1024) {  // more dynamic LDS than the default limit: opt in once per kernel
     static const hipError_t lds_ok =

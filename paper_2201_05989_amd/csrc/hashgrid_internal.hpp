@@ -14,7 +14,9 @@ struct BinPlan {
   uint32_t slices[HG_MAX_LEVELS];        // workgroups that share one bin of the level
   uint8_t row_shift[HG_MAX_LEVELS];      // 1:1 levels: log2 of grid rows per chunk
   uint32_t chunk_log2;                   // log2 of the entries a chunk can hold
-  uint32_t rec_per_point;                // records per (point, level): 2^(d-1)
+  uint32_t rec_per_point;                // records per (point, level): 2^(d-1) pairs of corners, or 2^d corners
+  uint32_t corner_records;               // 1: one record per corner and every level cut into aligned blocks of
+                                         // 2^chunk_log2 entries (T not a power of two, or d = 1); 0: one per pair
   uint32_t count_parts, scatter_parts;   // level parts (gridDim.y) of the count and scatter grids
   uint32_t tile_mult;                    // a tile of the sort = tile_mult * 512 points; above 1: no staging (bin_scatter_direct)
   uint32_t supported;                    // 0: configuration not served by the binned path

@@ -165,8 +165,13 @@ def test_choice_between_the_backward_passes_needs_no_device():
     assert table1.bwd_ws_pays(1 << 14) and table1.bwd_ws_pays(1 << 18)
     small_levels = binding.HashGrid(2, 4, 2, 1 << 10, 4, 32, "f32", "f32")  # level 0 has 25 entries
     assert not small_levels.bwd_ws_pays(512) and small_levels.bwd_ws_pays(4096)
-    assert not binding.HashGrid(3, 16, 2, 1000003, 16, 2048).bwd_ws_pays(1 << 20)  # not served: T not 2^k
-    for grid in (table1, small_levels):  # once it pays it keeps paying
+    odd = binding.HashGrid(3, 16, 2, 1000003, 16, 2048)  # T not 2^k: a record per corner, twice as many
+    assert odd.bwd_ws_pays(1 << 20) and not odd.bwd_ws_pays(4096)
+    assert not binding.HashGrid(3, 2, 2, 1 << 25, 16, 2048).bwd_ws_pays(1 << 20)  # not served: too many chunks
+    wide = binding.HashGrid(3, 16, 8, 1 << 19, 16, 2048, "f16", "f32")  # 40-byte records: pays later
+    first = [min(k for k in range(6, 22) if g.bwd_ws_pays(1 << k)) for g in (table1, wide)]
+    assert first[0] <= first[1]
+    for grid in (table1, small_levels, odd, wide):  # once it pays it keeps paying
         flags = [grid.bwd_ws_pays(1 << k) for k in range(6, 22)]
         assert flags == sorted(flags)
 
@@ -188,8 +193,10 @@ def test_workspace_size_of_the_sorted_backward_needs_no_device():
     need = large.bwd_workspace_bytes(1 << 21)
     assert (1 << 21) * 16 * 4 * 12 < need < (1 << 21) * 16 * 4 * 12 + 600 * 50000 * 4
     # not served: one dimension, T not a power of two, T beyond 2^24, too many pairs for 32-bit slots
-    assert binding.HashGrid(1, 4, 2, 1 << 10, 4, 64).bwd_workspace_bytes(1000) == 0
-    assert binding.HashGrid(3, 16, 2, 1000003, 16, 2048).bwd_workspace_bytes(1000) == 0
+    # one record per corner where the pairing along dimension 0 does not hold: d = 1, T not a power of two
+    assert binding.HashGrid(1, 4, 2, 1 << 10, 4, 64).bwd_workspace_bytes(1000) > 1000 * 4 * 2 * 12
+    odd = binding.HashGrid(3, 16, 2, 1000003, 16, 2048).bwd_workspace_bytes(1000)
+    assert 1000 * 16 * 8 * 12 < odd < 1000 * 16 * 8 * 12 + (1 << 20)
     assert binding.HashGrid(3, 2, 2, 1 << 25, 16, 2048).bwd_workspace_bytes(1000) == 0
     assert table1.bwd_workspace_bytes(1 << 27) == 0
     assert table1.bwd_workspace_bytes(0) == 0

@@ -69,6 +69,25 @@ def test_plan_of_random_configurations(plan_check, seed):
     assert bad == (0 if served else 2 ** 64 - 1)
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_plan_with_a_record_per_corner(plan_check, seed):
+    # table sizes that are not powers of two (Eq. 4's mod T) and one-dimensional inputs: no pairing
+    rng = np.random.default_rng(700 + seed)
+    d = int(rng.integers(1, 4))
+    F = int(rng.choice([1, 2, 4, 8]))
+    L = int(rng.integers(1, 12))
+    T = int(rng.choice([1, 2, 3, 1000, 4097, 12345, 1000003, 5 * 2 ** 20 + 1])) if d > 1 or seed % 2 else 1 << int(rng.integers(0, 22))
+    N_min = int(rng.integers(1, 40))
+    N_max = int(N_min * rng.choice([1, 2, 7, 100, 3000]) + rng.integers(0, 5))
+    interp = int(rng.integers(0, 2))
+    x = synth.points_uniform(rng, 3000, d)
+    x[:50] = 0.0
+    x[50:100] = 1 - 2.0 ** -24
+    bad, _ = plan_check(d, L, F, T, N_min, N_max, interp, x)
+    served = binding.HashGrid(d, L, F, T, N_min, N_max, "f16", "f16", interp).bwd_workspace_bytes(3000) > 0
+    assert served and bad == 0
+
+
 def test_plan_where_half_of_the_pairs_straddle_two_chunks(plan_check):
     rng = np.random.default_rng(5)
     for d in (2, 3):

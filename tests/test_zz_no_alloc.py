@@ -5,7 +5,7 @@ with a smaller batch, so that the second call runs over what the first one left 
 Bar: the two entry points run the same kernels; where one workgroup owns a chunk of the gradient the
 sums are exact fixed point and the results are bit-equal, on the few coarse 1:1 levels whose chunks are
 shared the fp32 atomic order varies: both are held to the backward bar of the parity suite against the
-oracle, |g - g*| <= 1e-5 A + M 2^(H-54) + 2^-23 G (see test_gpu_parity.py).
+oracle, |g - g*| <= 1e-5 A + M 2^(H-54) (see test_gpu_parity.py).
 """
 import ctypes
 
@@ -22,18 +22,6 @@ pytestmark = pytest.mark.gpu
 def _floor(dy, B):
     H = max(3 + int(np.ceil(np.log2(max(B, 2)))), 11)
     return float(np.abs(dy.astype(np.float64)).max()) * 2.0 ** (H - 54)
-
-
-def _corner_abs_sum(cfg, lv, x, dy):
-    a = np.abs(dy.astype(np.float64)).reshape(len(x), cfg.L, cfg.F)
-    G = np.zeros((lv.total, cfg.F))
-    for l in range(cfg.L):
-        idx, _ = orc.indices(cfg, x, l)
-        flat = idx.astype(np.int64).ravel()
-        for f in range(cfg.F):
-            G[int(lv.offset[l]):int(lv.offset[l]) + int(lv.size[l]), f] = np.bincount(
-                flat, weights=np.repeat(a[:, l, f], idx.shape[1]), minlength=int(lv.size[l]))
-    return G
 
 
 def test_static_scratch_backward_matches_workspace_backward_twice_in_a_row():
@@ -61,7 +49,7 @@ def test_static_scratch_backward_matches_workspace_backward_twice_in_a_row():
         a, b = g_ws.cpu().numpy(), g_st.cpu().numpy()
         g_ref = orc.encode_bwd(cfg, x, dy)
         g_abs = orc.encode_bwd(cfg, x, np.abs(dy.astype(np.float64)))
-        bound = 1e-5 * g_abs + 1e-30 + _floor(dy, B) + 2.0 ** -23 * _corner_abs_sum(cfg, lv, x, dy)
+        bound = 1e-5 * g_abs + 1e-30 + _floor(dy, B)
         for g in (a, b):
             assert (np.abs(g.astype(np.float64) - g_ref) <= bound).all()
             assert (g[g_abs == 0] == 0).all()
@@ -89,6 +77,6 @@ def test_static_scratch_backward_rejects_what_it_cannot_serve():
     assert lib.hashgrid_encode_bwd_static(grid._h, 4096, x.data_ptr(), dy.data_ptr(), g.data_ptr(), 1, None) == 1  # COUNTED
     assert lib.hashgrid_encode_bwd_static(grid._h, 0, None, None, None, 0, None) == 0
     assert lib.hashgrid_encode_bwd_static(grid._h, 4096, None, dy.data_ptr(), g.data_ptr(), 0, None) == 1
-    odd = HashGrid(3, 4, 2, 1000, 4, 64, "f32", "f32")  # not a power of two: no sorted pass
-    if odd.bwd_workspace_bytes(4096) == 0:
-        assert lib.hashgrid_encode_bwd_static(odd._h, 4096, x.data_ptr(), x.data_ptr(), g.data_ptr(), 0, None) == 2
+    huge = HashGrid(3, 2, 2, 1 << 25, 16, 2048)  # more than 4096 chunks per level: no sorted pass
+    assert huge.bwd_workspace_bytes(4096) == 0
+    assert lib.hashgrid_encode_bwd_static(huge._h, 4096, x.data_ptr(), dy.data_ptr(), g.data_ptr(), 0, None) == 2
