@@ -270,6 +270,21 @@ def headline_extras(c, ms_fwd, ms_bwd, n, steps, torch):
                  "cache_resident": footprint < 256e6,  # then the rate is the memory-side cache's, not HBM's
                  "train_step_ms": ms_train, "train_step_mpoints_s": w.B / (ms_train * 1e-3) / 1e6},
     }
+    # half-precision gradients as the paper keeps them: the sorted pass (sums exact, rounded once per call)
+    # and the pass of packed two-half atomics
+    from paper_2201_05989_amd import HashGrid
+    g16 = HashGrid(w.d, w.L, w.F, w.T, w.N_min, w.N_max, w.param_dtype, w.io_dtype, grad_dtype="f16")
+    grad16 = torch.zeros((g16.n_entries, w.F), dtype=torch.float16, device="cuda")
+    half = {}
+    if g16.bwd_workspace_bytes(w.B):
+        half["ms_bwd_sorted"] = time_launches(lambda: g16.encode_bwd(xd, gd, grad16, use_workspace=True), n, torch)
+        half["ms_bwd_sorted_overwrite"] = time_launches(
+            lambda: g16.encode_bwd(xd, gd, grad16, use_workspace=True, overwrite=True), n, torch)
+    grad16.zero_()
+    half["ms_bwd_atomic"] = time_launches(lambda: g16.encode_bwd(xd, gd, grad16, use_workspace=False), 10, torch)
+    extras["grad_f16"] = half
+    del g16, grad16
+
     # last row of the path's table: the encoding fused with the paper's 64-64 ReLU network (one output,
     # as for a signed distance function); served for fp16 tables with at most 64 encoded features
     n_in = w.L * w.F

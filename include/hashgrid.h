@@ -25,7 +25,12 @@
  *     entries, with no padding between levels.
  *   - y and dL/dy are row-major [B, L*F] of `io_dtype`, level-major inside a row
  *     (the concatenation of Fig. 3, step 4).
- *   - Table gradients are always fp32, same shape as theta.
+ *   - Table gradients have the shape of theta and are of `grad_dtype`: fp32, or fp16 as the paper
+ *     accumulates them (Section 4, "Performance considerations"; Fig. 5).  An fp16 gradient buffer
+ *     must start on a 4-byte boundary and its allocation must extend to one (packed two-half
+ *     atomics).  fp16 sums lose precision with every rounded addition; the sorted pass
+ *     (hashgrid_encode_bwd_ws) sums exactly and rounds once per call where one workgroup owns the
+ *     chunk.  hashgrid_adam_step takes fp32 gradients only.
  *   - Alignment: x 4 bytes; tables, y, dL/dy and gradients one entry (F scalars of their type) or
  *     16 bytes, whichever is smaller; anything less is HG_ERR_INVALID_ARG.  The fastest kernels
  *     want 16 bytes and rows of y that are a multiple of 16 bytes; other cases take a slower path.
@@ -76,6 +81,7 @@ typedef struct {
   uint32_t param_dtype; /* hg_dtype of the tables                                               */
   uint32_t io_dtype;    /* hg_dtype of y and dL/dy                                              */
   uint32_t interp;      /* hg_interp                                                            */
+  uint32_t grad_dtype;  /* hg_dtype of the table gradients: HG_F32, or HG_F16 as in the paper   */
 } hashgrid_config;
 
 /* Builds the level table of Eq. 2-3 on the host: N_l, the 1:1-or-hashed decision
@@ -108,11 +114,11 @@ hg_status hashgrid_encode_fwd(const hashgrid_t* hg, uint32_t B, const float* x, 
 /* Backward pass to the tables (Fig. 3 caption; collisions are summed):
  * grad_params[offset_l + index(corner), f] += weight * dLdy[b, l*F+f].
  *   dLdy        [B, L*F]        io_dtype, device, read
- *   grad_params [n_entries, F]  fp32, device, ACCUMULATED INTO with atomic adds
+ *   grad_params [n_entries, F]  grad_dtype, device, ACCUMULATED INTO with atomic adds
  *                               (zeroing it is the caller's job; the summation
  *                               order, hence the last bits, varies run to run) */
 hg_status hashgrid_encode_bwd(const hashgrid_t* hg, uint32_t B, const float* x, const void* dLdy,
-                              float* grad_params, void* stream);
+                              void* grad_params, void* stream);
 
 /* Size in bytes of the scratch buffer hashgrid_encode_bwd_ws needs for a batch of
  * B points, or 0 when that variant does not serve this configuration or batch
@@ -158,7 +164,7 @@ int hashgrid_bwd_ws_pays(const hashgrid_t* hg, uint32_t B);
  * HG_ERR_INVALID_ARG when the buffer is missing, misaligned or too small or a flag is
  * unknown.  x and dLdy must not be written while the call is in flight. */
 hg_status hashgrid_encode_bwd_ws(const hashgrid_t* hg, uint32_t B, const float* x, const void* dLdy,
-                                 float* grad_params, void* workspace, uint64_t workspace_bytes, uint32_t flags,
+                                 void* grad_params, void* workspace, uint64_t workspace_bytes, uint32_t flags,
                                  void* stream);
 
 /* hashgrid_encode_bwd_ws for callers that cannot allocate and have no scratch buffer to pass: code
@@ -176,7 +182,7 @@ hg_status hashgrid_encode_bwd_ws(const hashgrid_t* hg, uint32_t B, const float* 
  * array keeps what the last call left; nothing in it needs clearing between calls. */
 #define HG_STATIC_SCRATCH_BYTES (64u << 20)
 hg_status hashgrid_encode_bwd_static(const hashgrid_t* hg, uint32_t B, const float* x, const void* dLdy,
-                                     float* grad_params, uint32_t flags, void* stream);
+                                     void* grad_params, uint32_t flags, void* stream);
 
 /* Forward pass, the arithmetic of hashgrid_encode_fwd (Section 3; Fig. 3 steps 1-4; an fp16 output
  * that is an exact tie may differ from that call's in its last bit), that also does

@@ -42,7 +42,7 @@ class HashGridError(RuntimeError):
 
 class hashgrid_config(ctypes.Structure):
     _fields_ = [(n, ctypes.c_uint32) for n in
-                ("d", "L", "F", "T", "N_min", "N_max", "param_dtype", "io_dtype", "interp")]
+                ("d", "L", "F", "T", "N_min", "N_max", "param_dtype", "io_dtype", "interp", "grad_dtype")]
 
 
 class hashgrid_adam_config(ctypes.Structure):
@@ -161,15 +161,17 @@ class HashGrid:
     """Handle on one encoding configuration (hashgrid_create / hashgrid_destroy)."""
 
     def __init__(self, d: int, L: int, F: int, T: int, N_min: int, N_max: int, param_dtype="f16",
-                 io_dtype="f16", interp: int = HG_INTERP_LINEAR):
+                 io_dtype="f16", interp: int = HG_INTERP_LINEAR, grad_dtype="f32"):
         self._lib = load_library()
-        self.cfg = hashgrid_config(d, L, F, T, N_min, N_max, _DTYPES[param_dtype], _DTYPES[io_dtype], interp)
+        self.cfg = hashgrid_config(d, L, F, T, N_min, N_max, _DTYPES[param_dtype], _DTYPES[io_dtype], interp,
+                                   _DTYPES[grad_dtype])
         h = ctypes.c_void_p()
         _check(self._lib.hashgrid_create(ctypes.byref(self.cfg), ctypes.byref(h)), "hashgrid_create")
         self._h = h
         self.d, self.L, self.F, self.T = d, L, F, T
         self.param_dtype = _TORCH[self.cfg.param_dtype]
         self.io_dtype = _TORCH[self.cfg.io_dtype]
+        self.grad_dtype = _TORCH[self.cfg.grad_dtype]
         self.n_entries = int(self._lib.hashgrid_n_entries(self._h))
         self._ws = {}  # (device, stream) -> scratch buffer kept for calls that pass none
         self._counted = None  # (x pointer, B, workspace pointer, x version, stream) the workspace holds counts for
@@ -246,7 +248,7 @@ class HashGrid:
         B = x.shape[0]
         fresh = grad_params is None
         if fresh:
-            grad_params = torch.zeros((self.n_entries, self.F), dtype=torch.float32, device=x.device)
+            grad_params = torch.zeros((self.n_entries, self.F), dtype=self.grad_dtype, device=x.device)
         if use_workspace is None:
             use_workspace = self._counted is not None or self.bwd_ws_pays(B)
         need = self.bwd_workspace_bytes(B) if use_workspace else 0
@@ -261,18 +263,18 @@ class HashGrid:
             _check(self._lib.hashgrid_encode_bwd_ws(
                 self._h, B, _dev(x, torch.float32, (B, self.d), "x"),
                 _dev(dLdy, self.io_dtype, (B, self.L * self.F), "dLdy"),
-                _dev(grad_params, torch.float32, (self.n_entries, self.F), "grad_params"),
+                _dev(grad_params, self.grad_dtype, (self.n_entries, self.F), "grad_params"),
                 workspace.data_ptr(), workspace.numel() * workspace.element_size(), flags, _stream_ptr(stream)),
                 "hashgrid_encode_bwd_ws")
             return grad_params
         if overwrite and not fresh:  # the atomic pass only adds: clear first, on the same stream
-            _dev(grad_params, torch.float32, (self.n_entries, self.F), "grad_params")
+            _dev(grad_params, self.grad_dtype, (self.n_entries, self.F), "grad_params")
             with torch.cuda.stream(torch.cuda.current_stream() if stream is None else stream):
                 grad_params.zero_()
         _check(self._lib.hashgrid_encode_bwd(
             self._h, B, _dev(x, torch.float32, (B, self.d), "x"),
             _dev(dLdy, self.io_dtype, (B, self.L * self.F), "dLdy"),
-            _dev(grad_params, torch.float32, (self.n_entries, self.F), "grad_params"), _stream_ptr(stream)),
+            _dev(grad_params, self.grad_dtype, (self.n_entries, self.F), "grad_params"), _stream_ptr(stream)),
             "hashgrid_encode_bwd")
         return grad_params
 
@@ -284,7 +286,7 @@ class HashGrid:
         _check(self._lib.hashgrid_encode_bwd_static(
             self._h, B, _dev(x, torch.float32, (B, self.d), "x"),
             _dev(dLdy, self.io_dtype, (B, self.L * self.F), "dLdy"),
-            _dev(grad_params, torch.float32, (self.n_entries, self.F), "grad_params"),
+            _dev(grad_params, self.grad_dtype, (self.n_entries, self.F), "grad_params"),
             HG_BWD_OVERWRITE if overwrite else 0, _stream_ptr(stream)), "hashgrid_encode_bwd_static")
         return grad_params
 

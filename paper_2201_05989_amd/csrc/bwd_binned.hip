@@ -212,7 +212,7 @@ static void plan_slices(BinPlan& bp, const LevelTable& lv, uint32_t B) {
 // record: their 2^d products go to the gradient with device-scope atomics.  T is a power of two.
 template <int D, int F>
 __device__ __forceinline__ void add_crossing_pairs(const LevelTable& lv, uint32_t l, bool smooth, const float (&xp)[D],
-                                                   const float (&g)[F], float* __restrict__ grad) {
+                                                   const float (&g)[F], void* __restrict__ grad, const bool g16) {
   const float Nf = (float)lv.N[l];
   const float shift = smooth ? 0.5f : 0.0f;
   const float cmaxf = smooth ? Nf : Nf - 1.0f;
@@ -226,7 +226,8 @@ __device__ __forceinline__ void add_crossing_pairs(const LevelTable& lv, uint32_
     u[i] = smooth ? smoothstep(1.0f - wf) : 1.0f - wf;
   }
   const uint32_t tmask = lv.T - 1u;
-  float* gl = grad + lv.offset[l] * F;
+  float* gl = static_cast<float*>(grad) + lv.offset[l] * F;          // (g16: the same entries, as halves)
+  _Float16* gl16 = static_cast<_Float16*>(grad) + lv.offset[l] * F;
 #pragma unroll
   for (uint32_t r = 0; r < (1u << (D - 1)); ++r) {
     float wr = 1.0f;
@@ -240,8 +241,13 @@ __device__ __forceinline__ void add_crossing_pairs(const LevelTable& lv, uint32_
     const uint32_t ia = (c0[0] ^ rt) & tmask, ib = ((c0[0] + 1u) ^ rt) & tmask;
 #pragma unroll
     for (int f = 0; f < F; ++f) {
-      __hip_atomic_fetch_add(gl + F * (uint64_t)ia + f, u[0] * (wr * g[f]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_fetch_add(gl + F * (uint64_t)ib + f, w[0] * (wr * g[f]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (g16) {  // uniform
+        grad_atomic_add(gl16, F * (uint64_t)ia + f, u[0] * (wr * g[f]));
+        grad_atomic_add(gl16, F * (uint64_t)ib + f, w[0] * (wr * g[f]));
+      } else {
+        grad_atomic_add(gl, F * (uint64_t)ia + f, u[0] * (wr * g[f]));
+        grad_atomic_add(gl, F * (uint64_t)ib + f, w[0] * (wr * g[f]));
+      }
     }
   }
 }
@@ -354,15 +360,16 @@ __global__ __launch_bounds__(kScanThreads) void bin_scan(const uint32_t n_tiles,
                                                          uint32_t* __restrict__ bin_total,
                                                          uint32_t* __restrict__ item_counter, const LevelTable lv,
                                                          const uint32_t zero_mask, const uint32_t F,
-                                                         float* __restrict__ grad) {
+                                                         void* __restrict__ grad, const bool g16) {
   __shared__ uint32_t seg_sum[kScanThreads];
   if (blockIdx.x == 0 && threadIdx.x == 0) item_counter[0] = 0;  // the accumulate pass draws its work items from here
   for (uint32_t l = 0; zero_mask >> l; ++l) {  // uniform
     if (!((zero_mask >> l) & 1u)) continue;
-    float* g = grad + lv.offset[l] * F;
-    const uint64_t n = (uint64_t)lv.size[l] * F;
-    for (uint64_t i = (uint64_t)blockIdx.x * kScanThreads + threadIdx.x; i < n; i += (uint64_t)gridDim.x * kScanThreads)
-      g[i] = 0.0f;
+    const uint64_t first = lv.offset[l] * F, n = (uint64_t)lv.size[l] * F;
+    for (uint64_t i = (uint64_t)blockIdx.x * kScanThreads + threadIdx.x; i < n; i += (uint64_t)gridDim.x * kScanThreads) {
+      if (g16) static_cast<_Float16*>(grad)[first + i] = (_Float16)0.0f;
+      else static_cast<float*>(grad)[first + i] = 0.0f;
+    }
   }
   constexpr uint32_t segs = kScanThreads / kScanBins;
   const uint32_t bin_in = threadIdx.x % kScanBins, seg = threadIdx.x / kScanBins;
@@ -440,7 +447,7 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, 
                                                            uint32_t* __restrict__ bin_start,
                                                            uint32_t* __restrict__ records, const uint32_t n_bins,
                                                            const uint32_t n_records, const uint32_t n_tiles,
-                                                           float* __restrict__ tile_max, float* __restrict__ grad) {
+                                                           float* __restrict__ tile_max, void* __restrict__ grad, const bool g16) {
   constexpr uint32_t R = CORNERS ? 1u << D : 1u << (D - 1 > 0 ? D - 1 : 0);
   using Rec = Record<IT, F>;
   using Stored = typename Rec::Stored;
@@ -553,7 +560,7 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, 
       } else {
         Rows<D> rw;
         rows_of<D, false>(lv, bp, l, smooth, xp, rw);
-        if (CROSS && rw.cross) add_crossing_pairs<D, F>(lv, l, smooth, xp, gf, grad);
+        if (CROSS && rw.cross) add_crossing_pairs<D, F>(lv, l, smooth, xp, gf, grad, g16);
 #pragma unroll
         for (uint32_t r = 0; r < R && !rw.cross; ++r) {
           const uint32_t rb = rw.bin[r] - gb_a;
@@ -599,7 +606,7 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter_direct(
     const LevelTable lv, const BinPlan bp, const bool smooth, const uint32_t B, const float* __restrict__ x,
     const IT* __restrict__ dy, const uint32_t* __restrict__ counts, const uint32_t* __restrict__ bin_total,
     uint32_t* __restrict__ bin_start, uint32_t* __restrict__ records, const uint32_t n_bins, const uint32_t n_records,
-    const uint32_t n_tiles, float* __restrict__ tile_max, float* __restrict__ grad) {
+    const uint32_t n_tiles, float* __restrict__ tile_max, void* __restrict__ grad, const bool g16) {
   constexpr uint32_t R = CORNERS ? 1u << D : 1u << (D - 1 > 0 ? D - 1 : 0);
   using Rec = Record<IT, F>;
   using Stored = typename Rec::Stored;
@@ -663,7 +670,7 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter_direct(
         Rows<D> rw;
         rows_of<D, false>(lv, bp, l, smooth, xp, rw);
         if (rw.cross) {
-          if (CROSS) add_crossing_pairs<D, F>(lv, l, smooth, xp, gf, grad);
+          if (CROSS) add_crossing_pairs<D, F>(lv, l, smooth, xp, gf, grad, g16);
           continue;
         }
 #pragma unroll
@@ -697,7 +704,7 @@ template <int D, typename IT, int F>
 __global__ __launch_bounds__(kBinThreads) void bin_crossing(const LevelTable lv, const BinPlan bp, const bool smooth,
                                                             const uint32_t B, const float* __restrict__ x,
                                                             const IT* __restrict__ dy, const uint32_t level_mask,
-                                                            float* __restrict__ grad) {
+                                                            void* __restrict__ grad, const bool g16) {
   const uint64_t b64 = (uint64_t)blockIdx.x * kBinThreads + threadIdx.x;
   if (b64 >= B) return;
   const uint32_t b = (uint32_t)b64;
@@ -711,7 +718,7 @@ __global__ __launch_bounds__(kBinThreads) void bin_crossing(const LevelTable lv,
     float gf[F];
 #pragma unroll
     for (int f = 0; f < F; ++f) gf[f] = (float)dy[((uint64_t)b * lv.L + l) * F + f];
-    add_crossing_pairs<D, F>(lv, l, smooth, xp, gf, grad);
+    add_crossing_pairs<D, F>(lv, l, smooth, xp, gf, grad, g16);
   }
 }
 
@@ -723,7 +730,9 @@ __global__ __launch_bounds__(kBinThreads) void bin_crossing(const LevelTable lv,
 // draw more of them: items differ in size by a factor of ten on 1:1 levels when
 // the points crowd around a surface.  The LDS accumulators are re-zeroed by the
 // lanes that have just read them.
-template <typename IT, int F, bool SMOOTH>
+// GT: type of the gradient scalars (float, or _Float16: the sums are still exact fixed point and are
+// rounded to half precision once, where they are added to the gradient).
+template <typename IT, int F, bool SMOOTH, typename GT = float>
 __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable lv, const BinPlan bp,
                                                               const uint32_t B, const uint32_t n_items,
                                                               const uint32_t* __restrict__ bin_start,
@@ -732,7 +741,7 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
                                                               const uint32_t n_max,
                                                               const uint32_t* __restrict__ records,
                                                               uint32_t* __restrict__ item_counter,
-                                                              float* __restrict__ grad, const uint32_t overwrite_mask) {
+                                                              GT* __restrict__ grad, const uint32_t overwrite_mask) {
   // bit l of overwrite_mask: the owner of a chunk of level l stores its sums (HG_BWD_OVERWRITE, one
   // slice per chunk, no pairs that straddle chunks) instead of adding them to what is there
   __shared__ uint32_t s_ticket;
@@ -760,8 +769,8 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
   const double scale = ldexp(1.0, S), inv_scale = ldexp(1.0, -S);
   const uint32_t n_records = B * lv.L * bp.rec_per_point;  // < 2^32 (hashgrid_bwd_workspace_bytes)
   constexpr int kPer = (int)cap / kAccThreads;  // entries per lane
-  struct alignas(F * 4 > 16 ? 16 : F * 4) Entry {
-    float v[F];
+  struct alignas(F * sizeof(GT) > 16 ? 16 : F * sizeof(GT)) Entry {
+    GT v[F];
   };
 
   // item_counter starts at 0 (bin_scan clears it); a ticket is the item it stands for
@@ -787,7 +796,7 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
   // gradient chunk, both requested while the previous item is still being flushed.
   struct Item {
     uint32_t l, n_sl, r0, r1, n_e;
-    float* gl;
+    GT* gl;
     bool live, dense;
   };
   using Rec = Record<IT, F>;
@@ -872,7 +881,7 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
     Entry cur_n[kPer];
     // HG_BWD_OVERWRITE: a chunk that gets no sums stored below is cleared by its owner
     auto clear_chunk = [&](const Item& c) {
-      for (uint32_t q = threadIdx.x; q < c.n_e * F; q += kAccThreads) c.gl[q] = 0.0f;
+      for (uint32_t q = threadIdx.x; q < c.n_e * F; q += kAccThreads) c.gl[q] = (GT)0.0f;
     };
     if (it.live && !finite) {
       if (overwrites(it)) {  // uniform
@@ -890,10 +899,8 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
         const float wu = SMOOTH && !first ? smoothstep(w_up) : w_up, wl = SMOOTH && !first ? smoothstep(w_lo) : w_lo;
 #pragma unroll
         for (int f = 0; f < F; ++f) {
-          if (la < it.n_e)
-            __hip_atomic_fetch_add(it.gl + F * la + f, wl * (float)G[f], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          if (lb < it.n_e)
-            __hip_atomic_fetch_add(it.gl + F * lb + f, wu * (float)G[f], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          if (la < it.n_e) grad_atomic_add(it.gl, F * la + f, wl * (float)G[f]);
+          if (lb < it.n_e) grad_atomic_add(it.gl, F * lb + f, wu * (float)G[f]);
         }
       }
       it_n = describe(next, start_n, total_n, l_n, bin_n, slice_n);
@@ -961,15 +968,38 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
           if (overwrites(it)) {
             // what adding to a cleared entry would leave
 #pragma unroll
-            for (int f = 0; f < F; ++f) cur[j].v[f] = 0.0f + (a[f] ? (float)((double)a[f] * inv_scale) : 0.0f);
+            for (int f = 0; f < F; ++f) cur[j].v[f] = (GT)(0.0f + (a[f] ? (float)((double)a[f] * inv_scale) : 0.0f));
           } else {
             if (!kChunkAhead) cur[j] = reinterpret_cast<const Entry*>(it.gl)[e];
             // an entry no record reached gets -0.0f added, which leaves every float (either zero,
             // NaNs included) exactly as it was; storing it anyway keeps the stores of a wave contiguous
 #pragma unroll
-            for (int f = 0; f < F; ++f) cur[j].v[f] += a[f] ? (float)((double)a[f] * inv_scale) : -0.0f;
+            for (int f = 0; f < F; ++f)
+              cur[j].v[f] = (GT)((float)cur[j].v[f] + (a[f] ? (float)((double)a[f] * inv_scale) : -0.0f));
           }
           reinterpret_cast<Entry*>(it.gl)[e] = cur[j];
+        }
+      } else if constexpr (sizeof(GT) == 2) {
+        // several workgroups share this chunk, half-precision gradient: packed two-half atomics, one
+        // lane per aligned pair of halves (two lanes that add to the halves of one word would be
+        // served one after the other); the chunk may start on the odd half of a word
+        const uint32_t par = (uint32_t)(reinterpret_cast<uintptr_t>(it.gl) >> 1) & 1u;
+        const int n_h = (int)(it.n_e * F);
+#pragma unroll
+        for (int j = 0; j < (F * kPer) / 2 + 1; ++j) {
+          const int p = (int)threadIdx.x + j * kAccThreads;
+          const int q0 = 2 * p - (int)par;
+          float v[2] = {0.0f, 0.0f};
+#pragma unroll
+          for (int t = 0; t < 2; ++t) {
+            const int q = q0 + t;
+            if (q < 0 || q >= F * (int)cap) continue;
+            unsigned long long* slot = &acc[(q % F) * cap + q / F];
+            const long long a = (long long)*slot;
+            *slot = 0ull;
+            if (q < n_h && a != 0) v[t] = (float)((double)a * inv_scale);
+          }
+          if (v[0] != 0.0f || v[1] != 0.0f) grad_atomic_add2(it.gl + q0, 0, v[0], v[1]);
         }
       } else {
         // several workgroups share this chunk: fp32 atomics, one lane per float so that the
@@ -981,9 +1011,7 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
           unsigned long long* slot = &acc[(q % F) * cap + e];
           const long long a = (long long)*slot;
           *slot = 0ull;
-          if (e < it.n_e && a != 0)
-            __hip_atomic_fetch_add(it.gl + q, (float)((double)a * inv_scale), __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
+          if (e < it.n_e && a != 0) grad_atomic_add(it.gl, q, (float)((double)a * inv_scale));
         }
       }
     }
@@ -1023,8 +1051,9 @@ static hg_status launch_count(const hashgrid* h, uint32_t B, const float* x, con
 }
 
 template <int D, typename IT, int F, bool CORNERS>
-static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, const void* dy, float* grad,
+static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, const void* dy, void* grad,
                                const Workspace& ws, const bool counted, const bool overwrite, hipStream_t s) {
+  const bool g16 = h->cfg.grad_dtype == HG_F16;
   using Rec = Record<IT, F>;
   constexpr uint32_t R = CORNERS ? 1u << D : 1u << (D - 1 > 0 ? D - 1 : 0);
   constexpr int DP = CORNERS ? 2 : D;  // (dimension of the kernels that only the pair records use: never D = 1)
@@ -1059,10 +1088,16 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kScatterLdsMax);
     }
     if (e == hipSuccess && kAccLds > 48 * 1024)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_accumulate<IT, F, false>),
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_accumulate<IT, F, false, float>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAccLds);
     if (e == hipSuccess && kAccLds > 48 * 1024)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_accumulate<IT, F, true>),
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_accumulate<IT, F, true, float>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAccLds);
+    if (e == hipSuccess && kAccLds > 48 * 1024)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_accumulate<IT, F, false, _Float16>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAccLds);
+    if (e == hipSuccess && kAccLds > 48 * 1024)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(bin_accumulate<IT, F, true, _Float16>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAccLds);
     return e;
   }();
@@ -1084,7 +1119,7 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
   const uint32_t zero_mask = overwrite ? add_mask : 0u, overwrite_mask = overwrite ? all_levels & ~add_mask : 0u;
   const bool defer_cross = overwrite && cross_mask != 0;  // those atomic adds then follow the accumulate pass
   hipLaunchKernelGGL(bin_scan, dim3((ws.n_bins + kScanBins - 1) / kScanBins), dim3(kScanThreads), 0, s, ws.n_tiles,
-                     ws.n_bins, ws.counts, ws.bin_total, ws.item_counter, h->lv, zero_mask, (uint32_t)F, grad);
+                     ws.n_bins, ws.counts, ws.bin_total, ws.item_counter, h->lv, zero_mask, (uint32_t)F, grad, g16);
   auto scatter = [&](auto cross) {
     constexpr bool kCross = decltype(cross)::value;
     constexpr int DS = kCross ? DP : D;  // (the straddling pairs exist with pair records only)
@@ -1092,12 +1127,12 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
       hipLaunchKernelGGL((bin_scatter_direct<DS, IT, F, kCross, CORNERS && !kCross>), dim3(tile_wgs, parts),
                          dim3(kBinThreads), (size_t)max_part_bins(parts) * 4, s, h->lv, bp, smooth, B, x,
                          static_cast<const IT*>(dy), ws.counts, ws.bin_total, ws.bin_start, ws.records, ws.n_bins,
-                         n_records, ws.n_tiles, ws.tile_max, grad);
+                         n_records, ws.n_tiles, ws.tile_max, grad, g16);
     } else if constexpr (kStaged) {
       hipLaunchKernelGGL((bin_scatter<DS, IT, F, kCross, CORNERS && !kCross>), dim3(tile_wgs, parts),
                          dim3(kBinThreads), lds_scatter, s, h->lv, bp, smooth, B, x, static_cast<const IT*>(dy),
                          ws.counts, ws.bin_total, ws.bin_start, ws.records, ws.n_bins, n_records, ws.n_tiles,
-                         ws.tile_max, grad);
+                         ws.tile_max, grad, g16);
     }
   };
   if (CORNERS || defer_cross || cross_mask == 0)  // no such pairs at these resolutions, or bin_crossing takes them
@@ -1113,22 +1148,27 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
     return (uint32_t)cus * kAccWgsPerCu;
   }();
   const dim3 acc_grid(n_items < acc_slots ? n_items : acc_slots);
-  if (smooth)
-    hipLaunchKernelGGL((bin_accumulate<IT, F, true>), acc_grid, dim3(kAccThreads), kAccLds, s, h->lv, bp, B, n_items,
-                       ws.bin_start, ws.bin_total, ws.tile_max, ws.n_tiles * parts, ws.records, ws.item_counter,
-                       grad, overwrite_mask);
-  else
-    hipLaunchKernelGGL((bin_accumulate<IT, F, false>), acc_grid, dim3(kAccThreads), kAccLds, s, h->lv, bp, B, n_items,
-                       ws.bin_start, ws.bin_total, ws.tile_max, ws.n_tiles * parts, ws.records, ws.item_counter,
-                       grad, overwrite_mask);
+  auto accumulate = [&](auto smooth_t, auto* g) {
+    using GT = typename std::remove_pointer<decltype(g)>::type;
+    hipLaunchKernelGGL((bin_accumulate<IT, F, decltype(smooth_t)::value, GT>), acc_grid, dim3(kAccThreads), kAccLds, s,
+                       h->lv, bp, B, n_items, ws.bin_start, ws.bin_total, ws.tile_max, ws.n_tiles * parts, ws.records,
+                       ws.item_counter, g, overwrite_mask);
+  };
+  if (g16) {
+    if (smooth) accumulate(std::true_type{}, static_cast<_Float16*>(grad));
+    else accumulate(std::false_type{}, static_cast<_Float16*>(grad));
+  } else {
+    if (smooth) accumulate(std::true_type{}, static_cast<float*>(grad));
+    else accumulate(std::false_type{}, static_cast<float*>(grad));
+  }
   if (defer_cross)
     hipLaunchKernelGGL((bin_crossing<DP, IT, F>), dim3((B + kBinThreads - 1) / kBinThreads), dim3(kBinThreads), 0, s,
-                       h->lv, bp, smooth, B, x, static_cast<const IT*>(dy), cross_mask, grad);
+                       h->lv, bp, smooth, B, x, static_cast<const IT*>(dy), cross_mask, grad, g16);
   return hipGetLastError() == hipSuccess ? HG_OK : HG_ERR_DEVICE;
 }
 
 template <int D, typename IT, bool CORNERS>
-static hg_status launch_binned_f(const hashgrid* h, uint32_t B, const float* x, const void* dy, float* grad,
+static hg_status launch_binned_f(const hashgrid* h, uint32_t B, const float* x, const void* dy, void* grad,
                                  const Workspace& ws, const bool counted, const bool overwrite, hipStream_t s) {
   switch (h->cfg.F) {
     case 1: return launch_binned<D, IT, 1, CORNERS>(h, B, x, dy, grad, ws, counted, overwrite, s);
@@ -1140,7 +1180,7 @@ static hg_status launch_binned_f(const hashgrid* h, uint32_t B, const float* x, 
 }
 
 template <typename IT>
-static hg_status launch_binned_d(const hashgrid* h, uint32_t B, const float* x, const void* dy, float* grad,
+static hg_status launch_binned_d(const hashgrid* h, uint32_t B, const float* x, const void* dy, void* grad,
                                  const Workspace& ws, const bool counted, const bool overwrite, hipStream_t s) {
   if (h->bp.corner_records) {
     switch (h->cfg.d) {
@@ -1218,7 +1258,7 @@ hg_status hashgrid_encode_fwd_ws(const hashgrid_t* hg, uint32_t B, const float* 
 }
 
 hg_status hashgrid_encode_bwd_ws(const hashgrid_t* hg, uint32_t B, const float* x, const void* dLdy,
-                                 float* grad_params, void* workspace, uint64_t workspace_bytes, uint32_t flags,
+                                 void* grad_params, void* workspace, uint64_t workspace_bytes, uint32_t flags,
                                  void* stream) {
   if (!hg || (flags & ~(uint32_t)(HG_BWD_COUNTED | HG_BWD_OVERWRITE))) return HG_ERR_INVALID_ARG;
   if (B == 0) return HG_OK;
@@ -1226,7 +1266,9 @@ hg_status hashgrid_encode_bwd_ws(const hashgrid_t* hg, uint32_t B, const float* 
   if (ok != HG_OK) return ok;
   if (!x || !dLdy || !grad_params) return HG_ERR_INVALID_ARG;
   const size_t io = hg->cfg.io_dtype == HG_F16 ? 2 : 4, F = hg->cfg.F;
-  const size_t grad_align = F * 4 > 16 ? 16 : F * 4;  // one entry's gradient, up to 16 bytes
+  const size_t gs = hg->cfg.grad_dtype == HG_F16 ? 2 : 4;
+  // one entry's gradient, up to 16 bytes (and the 4 bytes of a packed atomic at least)
+  const size_t grad_align = F * gs > 16 ? 16 : (F * gs < 4 ? 4 : F * gs);
   if ((reinterpret_cast<uintptr_t>(x) & 3) || (reinterpret_cast<uintptr_t>(dLdy) & (F * io - 1) & 15) ||
       (reinterpret_cast<uintptr_t>(grad_params) & (grad_align - 1)))
     return HG_ERR_INVALID_ARG;
@@ -1269,7 +1311,7 @@ static void* static_scratch_of_current_device() {
 }  // namespace hg
 
 hg_status hashgrid_encode_bwd_static(const hashgrid_t* hg, uint32_t B, const float* x, const void* dLdy,
-                                     float* grad_params, uint32_t flags, void* stream) {
+                                     void* grad_params, uint32_t flags, void* stream) {
   if (!hg || (flags & ~(uint32_t)HG_BWD_OVERWRITE)) return HG_ERR_INVALID_ARG;
   if (B == 0) return HG_OK;
   const uint64_t need = hashgrid_bwd_workspace_bytes(hg, B);

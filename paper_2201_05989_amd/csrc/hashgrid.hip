@@ -428,6 +428,39 @@ __global__ __launch_bounds__(kBlock) void bwd_general(const LevelTable lv, const
   }
 }
 
+// The same with half-precision gradients, accumulated with the packed two-half atomic as the paper
+// does (Section 4; Fig. 5: efficient for pairs of features, not for single ones): a lane owns two
+// neighbouring features of one corner, so F lanes share a (point, level) (2 lanes at F = 1, where
+// each atomic carries one feature and a zero for the neighbouring entry).
+template <int D, int F, typename IT>
+__global__ __launch_bounds__(kBlock) void bwd_general_half(const LevelTable lv, const bool smooth, const uint32_t B,
+                                                           const float* __restrict__ x, const IT* __restrict__ dy,
+                                                           _Float16* __restrict__ grad) {
+  constexpr uint32_t P = F >= 2 ? F / 2 : 1;  // feature pairs per entry
+  constexpr uint32_t G = 2 * P;               // lanes per (point, level)
+  const uint32_t l = blockIdx.y;
+  const uint32_t sub = threadIdx.x % G;
+  const uint32_t xbit = sub / P, fp = sub % P;
+  const uint64_t b64 = (uint64_t)blockIdx.x * (kBlock / G) + threadIdx.x / G;
+  if (b64 >= B) return;
+  const uint32_t b = (uint32_t)b64;
+  float xp[D];
+  load_point<D>(x, b, xp);
+  Corners<D> cn;
+  corners_of<D, false>(lv, l, smooth, xp, cn, nullptr);
+  const IT* gp = dy + ((uint64_t)b * lv.L + l) * F + 2 * fp;
+  const float g0 = (float)gp[0], g1 = F >= 2 ? (float)gp[F >= 2 ? 1 : 0] : 0.0f;
+  _Float16* gl = grad + lv.offset[l] * F;
+#pragma unroll
+  for (uint32_t r = 0; r < (1u << (D - 1)); ++r) {
+    const uint32_t m0 = r << 1;
+    const uint32_t idx = xbit ? cn.idx[m0 | 1u] : cn.idx[m0];
+    const float wt = xbit ? cn.wt[m0 | 1u] : cn.wt[m0];
+    if (F >= 2) grad_atomic_add2(gl, (uint64_t)idx * F + 2 * fp, wt * g0, wt * g1);  // (offset + idx) * F is even
+    else grad_atomic_add(gl, (uint64_t)idx, wt * g0);
+  }
+}
+
 // Gradient with respect to the position: one thread per point, all levels.
 template <int D, int F, typename PT, typename IT>
 __global__ __launch_bounds__(kBlock) void bwd_input_general(const LevelTable lv, const bool smooth, const uint32_t B,
@@ -606,12 +639,20 @@ static hg_status launch_bwd_input(const hashgrid* h, uint32_t B, const float* x,
 }
 
 template <int D, int F, typename IT>
-static hg_status launch_bwd(const hashgrid* h, uint32_t B, const float* x, const void* dy, float* grad,
+static hg_status launch_bwd(const hashgrid* h, uint32_t B, const float* x, const void* dy, void* grad,
                             hipStream_t s) {
+  const bool smooth = h->cfg.interp == HG_INTERP_SMOOTHSTEP;
+  if (h->cfg.grad_dtype == HG_F16) {
+    constexpr uint32_t per_block = kBlock / (F >= 2 ? F : 2);
+    dim3 grid((uint32_t)(((uint64_t)B + per_block - 1) / per_block), h->lv.L);
+    hipLaunchKernelGGL((bwd_general_half<D, F, IT>), grid, dim3(kBlock), 0, s, h->lv, smooth, B, x,
+                       static_cast<const IT*>(dy), static_cast<_Float16*>(grad));
+    return launched();
+  }
   constexpr uint32_t per_block = kBlock / (2 * F);
   dim3 grid((uint32_t)(((uint64_t)B + per_block - 1) / per_block), h->lv.L);
-  hipLaunchKernelGGL((bwd_general<D, F, IT>), grid, dim3(kBlock), 0, s, h->lv,
-                     h->cfg.interp == HG_INTERP_SMOOTHSTEP, B, x, static_cast<const IT*>(dy), grad);
+  hipLaunchKernelGGL((bwd_general<D, F, IT>), grid, dim3(kBlock), 0, s, h->lv, smooth, B, x,
+                     static_cast<const IT*>(dy), static_cast<float*>(grad));
   return launched();
 }
 
@@ -703,7 +744,8 @@ hg_status hashgrid_create(const hashgrid_config* cfg, hashgrid_t** out) {
   const hashgrid_config& c = *cfg;
   if (c.d == 0 || c.L == 0 || c.F == 0 || c.T == 0 || c.N_min == 0 || c.N_max < c.N_min)
     return HG_ERR_INVALID_ARG;
-  if (c.param_dtype > HG_F16 || c.io_dtype > HG_F16 || c.interp > HG_INTERP_SMOOTHSTEP) return HG_ERR_INVALID_ARG;
+  if (c.param_dtype > HG_F16 || c.io_dtype > HG_F16 || c.grad_dtype > HG_F16 || c.interp > HG_INTERP_SMOOTHSTEP)
+    return HG_ERR_INVALID_ARG;
   if (c.d > 3 || c.L > HG_MAX_LEVELS) return HG_ERR_UNSUPPORTED;
   if (!(c.F == 1 || c.F == 2 || c.F == 4 || c.F == 8)) return HG_ERR_UNSUPPORTED;
   hashgrid* h = new (std::nothrow) hashgrid;
@@ -755,7 +797,7 @@ hg_status hashgrid_encode_fwd(const hashgrid_t* hg, uint32_t B, const float* x, 
 }
 
 hg_status hashgrid_encode_bwd(const hashgrid_t* hg, uint32_t B, const float* x, const void* dLdy,
-                              float* grad_params, void* stream) {
+                              void* grad_params, void* stream) {
   if (!hg) return HG_ERR_INVALID_ARG;
   if (B == 0) return HG_OK;
   if (B > HG_MAX_BATCH) return HG_ERR_UNSUPPORTED;

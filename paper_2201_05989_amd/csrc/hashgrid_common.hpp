@@ -78,6 +78,30 @@ __device__ __forceinline__ uint32_t corner_index(const CornerTerms<D>& ct, uint3
   return pow2 ? (h & (T - 1u)) : (h % T);
 }
 
+// Device-scope atomic add of one scalar of the table gradient.  Half-precision gradients (the
+// paper accumulates them in half precision, Section 4 / Fig. 5) use the packed two-half atomic, the
+// partner half receiving +0: the buffer must therefore start on a 4-byte boundary and its allocation
+// must extend to one.
+using half2_t = _Float16 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void grad_atomic_add(float* base, uint64_t i, float v) {
+  __hip_atomic_fetch_add(base + i, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void grad_atomic_add(_Float16* base, uint64_t i, float v) {
+  const uintptr_t a = reinterpret_cast<uintptr_t>(base + i);
+  half2_t pk;
+  pk.x = (a & 2u) ? (_Float16)0.0f : (_Float16)v;
+  pk.y = (a & 2u) ? (_Float16)v : (_Float16)0.0f;
+  __builtin_amdgcn_global_atomic_fadd_v2f16(reinterpret_cast<half2_t*>(a & ~(uintptr_t)3), pk);
+}
+// ... of two neighbouring scalars that start on a 4-byte boundary (one request instead of two)
+__device__ __forceinline__ void grad_atomic_add2(float*, uint64_t, float, float) {}  // (never called: fp32 gradients add scalars)
+__device__ __forceinline__ void grad_atomic_add2(_Float16* base, uint64_t i, float v0, float v1) {
+  half2_t pk;
+  pk.x = (_Float16)v0;
+  pk.y = (_Float16)v1;
+  __builtin_amdgcn_global_atomic_fadd_v2f16(reinterpret_cast<half2_t*>(base + i), pk);
+}
+
 // Appendix A: S(w) = w^2 (3 - 2w), S'(w) = 6 w (1 - w).
 __host__ __device__ __forceinline__ float smoothstep(float w) { return w * w * (3.0f - 2.0f * w); }
 __device__ __forceinline__ float dsmoothstep(float w) { return 6.0f * w * (1.0f - w); }

@@ -67,7 +67,7 @@ def test_level_table_sweep_of_resolutions_matches_oracle():
 
 
 def _create(**kw):
-    base = dict(d=3, L=16, F=2, T=1 << 19, N_min=16, N_max=2048, param_dtype=1, io_dtype=1, interp=0)
+    base = dict(d=3, L=16, F=2, T=1 << 19, N_min=16, N_max=2048, param_dtype=1, io_dtype=1, interp=0, grad_dtype=0)
     base.update(kw)
     lib = binding.load_library()
     cfg = binding.hashgrid_config(*[base[k] for k, _ in binding.hashgrid_config._fields_])
@@ -79,9 +79,9 @@ def _create(**kw):
 
 
 def test_create_status_codes():
-    assert _create() == 0
+    assert _create() == 0 and _create(grad_dtype=1) == 0
     for bad in (dict(d=0), dict(L=0), dict(F=0), dict(T=0), dict(N_min=0), dict(N_max=8), dict(param_dtype=2),
-                dict(io_dtype=7), dict(interp=2)):
+                dict(io_dtype=7), dict(interp=2), dict(grad_dtype=2)):
         assert _create(**bad) == 1, bad  # HG_ERR_INVALID_ARG
     for unsup in (dict(d=4), dict(L=33), dict(F=3), dict(F=16)):
         assert _create(**unsup) == 2, unsup  # HG_ERR_UNSUPPORTED

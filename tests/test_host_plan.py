@@ -30,7 +30,7 @@ def plan_check(tmp_path_factory):
                                ctypes.POINTER(ctypes.c_uint64)]
 
     def run(d, L, F, T, N_min, N_max, interp, x):
-        cfg = binding.hashgrid_config(d, L, F, T, N_min, N_max, binding.HG_F16, binding.HG_F16, interp)
+        cfg = binding.hashgrid_config(d, L, F, T, N_min, N_max, binding.HG_F16, binding.HG_F16, interp, binding.HG_F32)
         x = np.ascontiguousarray(x, dtype=np.float32)
         crossing = ctypes.c_uint64(0)
         bad = lib.plan_check(ctypes.byref(cfg), len(x), x.ctypes.data, ctypes.byref(crossing))
