@@ -317,6 +317,8 @@ def main():
     ap.add_argument("--step-only", action="store_true",
                     help="only the step and its two passes (what the profiles are taken of): no stand-alone "
                          "calls, other entry points, other workloads, probes or CPU baseline")
+    ap.add_argument("--probes-only", action="store_true",
+                    help="run only the machine probes (for counter runs that check what a probe moves)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a 1 GiB device-to-device copy (20 times): the known-size kernel that "
                          "FETCH_SIZE / WRITE_SIZE counter readings are scaled by")
@@ -335,6 +337,10 @@ def main():
             b.copy_(a)
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes_read": a.numel() * 4, "bytes_written": a.numel() * 4, "launches": 20}))
+        return
+
+    if args.probes_only:
+        print(json.dumps({"measured_peaks": machine_probes(torch)}))
         return
 
     w = synth.WORKLOADS[args.workload]

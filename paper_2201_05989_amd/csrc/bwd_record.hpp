@@ -21,9 +21,9 @@ __host__ __device__ __forceinline__ uint32_t pack_weight(float w) {
 }
 template <int MBITS, int LOW>
 __host__ __device__ __forceinline__ float unpack_weight(uint32_t c) {
-  const uint32_t e5 = c >> MBITS;
-  const uint32_t bits = ((e5 + (LOW - 1)) << 23) | ((c & ((1u << MBITS) - 1u)) << (23 - MBITS));
-  return e5 ? __builtin_bit_cast(float, bits) : 0.0f;
+  // exponent code and mantissa sit in the float's own order: one shift and one add rebuild it
+  const uint32_t bits = (c << (23 - MBITS)) + ((uint32_t)(LOW - 1) << 23);
+  return c >> MBITS ? __builtin_bit_cast(float, bits) : 0.0f;
 }
 constexpr uint32_t kFirstVoxel = 15u;  // value of the record's k field for a pair in the first voxel along dimension 0
 
@@ -105,7 +105,7 @@ struct Record {
     uint32_t k = (r.w[0] >> 12) & 0xfu;
     const uint32_t q0 = (uint32_t)(p >> 16) & 0x7fffffu;
     first = k == kFirstVoxel;
-    if (first) {  // rare: one voxel in N_l along dimension 0
+    if (__builtin_expect(first, 0)) {  // rare: one voxel in N_l along dimension 0
       k = 0;
       const float small = unpack_weight<16, 64>(q0 & 0x3fffffu), big = 1.0f - small;
       const bool upper_small = (q0 >> 22) == 0u;

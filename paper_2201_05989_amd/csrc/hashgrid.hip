@@ -193,10 +193,11 @@ __global__ __launch_bounds__(kPmBlock) void fwd_point_major(const LevelTable lv,
   // 16-byte pieces are stored two at a time so that a 32-byte sector of the row is written
   // once, not twice
   Vec<IT, F * G> held[SB];
-  // One point per thread: the gathers of level l+1 are issued before level l is blended, so the
-  // texture path has work while the waves compute indices and wait at the barrier (two register
-  // sets that alternate; the parity of a level inside a piece must be known at compile time).
-  constexpr bool PIPE = SB == 1 && G % 2 == 0;
+  // One point per thread, no counting: the gathers of level l+1 are issued before level l is blended, so
+  // the texture path has work while the waves compute indices and wait at the barrier (two register
+  // sets that alternate; the parity of a level inside a piece must be known at compile time).  With
+  // the counting on the side the plain order is the faster one: there the counting fills those gaps.
+  constexpr bool PIPE = SB == 1 && G % 2 == 0 && !COUNT;
   constexpr int kSets = PIPE ? 2 : 1;
   Vec<PT, F> e[kSets][SB][1 << D];
   float wr[kSets][SB][1 << (D - 1)], w0[kSets][SB], u0[kSets][SB];
@@ -263,9 +264,10 @@ __global__ __launch_bounds__(kPmBlock) void fwd_point_major(const LevelTable lv,
       }
       asm volatile("" ::: "memory");  // keep the gathers of one level together
       // Pacing only: the barrier keeps the waves of the workgroup on the same level's slice; no data
-      // passes between them here, so it carries no fence and the gathers already issued for the
-      // next level stay in flight across it.
-      __builtin_amdgcn_s_barrier();
+      // passes between them here.  Measured: the counting variant is faster with the bare barrier
+      // (no fence: its LDS atomics need not have landed), the plain one with the fenced one.
+      if constexpr (COUNT) __builtin_amdgcn_s_barrier();
+      else __syncthreads();
     }
     const uint32_t piece = l0 / G;
 #pragma unroll
