@@ -275,14 +275,14 @@ def headline_extras(c, ms_fwd, ms_bwd, n, steps, torch):
     from paper_2201_05989_amd import HashGrid
     g16 = HashGrid(w.d, w.L, w.F, w.T, w.N_min, w.N_max, w.param_dtype, w.io_dtype, grad_dtype="f16")
     grad16 = torch.zeros((g16.n_entries, w.F), dtype=torch.float16, device="cuda")
-    half = {}
+    half_grads = {}
     if g16.bwd_workspace_bytes(w.B):
-        half["ms_bwd_sorted"] = time_launches(lambda: g16.encode_bwd(xd, gd, grad16, use_workspace=True), n, torch)
-        half["ms_bwd_sorted_overwrite"] = time_launches(
+        half_grads["ms_bwd_sorted"] = time_launches(lambda: g16.encode_bwd(xd, gd, grad16, use_workspace=True), n, torch)
+        half_grads["ms_bwd_sorted_overwrite"] = time_launches(
             lambda: g16.encode_bwd(xd, gd, grad16, use_workspace=True, overwrite=True), n, torch)
     grad16.zero_()
-    half["ms_bwd_atomic"] = time_launches(lambda: g16.encode_bwd(xd, gd, grad16, use_workspace=False), 10, torch)
-    extras["grad_f16"] = half
+    half_grads["ms_bwd_atomic"] = time_launches(lambda: g16.encode_bwd(xd, gd, grad16, use_workspace=False), 10, torch)
+    extras["grad_f16"] = half_grads
     del g16, grad16
 
     # last row of the path's table: the encoding fused with the paper's 64-64 ReLU network (one output,
@@ -301,6 +301,26 @@ def headline_extras(c, ms_fwd, ms_bwd, n, steps, torch):
         extras["encode_mlp_fwd"] = {"ms": ms_mlp, "mpoints_s": w.B / (ms_mlp * 1e-3) / 1e6, "n_out": 1,
                                     "network_tflop_s": flops / (ms_mlp * 1e-3) / 1e12,
                                     "ms_over_forward_alone": ms_mlp - ms_fwd_alone}
+        # training the whole model: fused forward that keeps y, backward of the network (dL/dout = out, as for
+        # a squared loss against zero), sorted backward of the encoding into the tables, optimiser on the tables
+        from paper_2201_05989_amd import mlp_bwd
+        yk = torch.empty((w.B, n_in), dtype=torch.float16, device="cuda")
+        dyk = torch.empty_like(yk)
+        dWs = [torch.zeros((64, n_in), device="cuda"), torch.zeros((64, 64), device="cuda"), torch.zeros((1, 64), device="cuda")]
+        grid.encode_mlp_fwd(xd, td, W1, W2, W3, o, y=yk)
+        ms_net_bwd = time_launches(lambda: mlp_bwd(yk, W1, W2, W3, o, dyk, *dWs), max(n // 2, 10), torch)
+
+        def model_step():
+            grid.encode_mlp_fwd(xd, td, W1, W2, W3, o, y=yk)
+            mlp_bwd(yk, W1, W2, W3, o, dyk, *dWs)
+            grid.encode_bwd(xd, dyk, grad, overwrite=True)
+            adam(zero_grad=False)
+
+        ms_model = time_launches(model_step, max(n // 2, 10), torch)
+        extras["network_training"] = {
+            "ms_mlp_bwd": ms_net_bwd, "mlp_bwd_tflop_s": 4.0 * flops / (ms_net_bwd * 1e-3) / 1e12,
+            "ms_step": ms_model, "mpoints_s": w.B / (ms_model * 1e-3) / 1e6,
+            "step": "encode_mlp_fwd_train + mlp_bwd + encode_bwd_ws (overwrite) + adam_step on the tables"}
     return extras
 
 

@@ -259,6 +259,31 @@ hg_status hashgrid_encode_mlp_fwd(const hashgrid_t* hg, uint32_t B, const float*
                                   const void* W1, const void* W2, const void* W3, uint32_t n_out, float* out,
                                   void* stream);
 
+/* hashgrid_encode_mlp_fwd for training: the same call, which also writes the encoded features as the
+ * network saw them (rounded to fp16) for the backward pass of the network below.
+ *   y  [B, L*F]  fp16, device, 16-byte aligned, written in full */
+hg_status hashgrid_encode_mlp_fwd_train(const hashgrid_t* hg, uint32_t B, const float* x, const void* params,
+                                        const void* W1, const void* W2, const void* W3, uint32_t n_out, float* out,
+                                        void* y, void* stream);
+
+/* Backward pass of that network (Section 4, "Architecture"; chain rule through the three layers,
+ * ReLU passing the gradient where its output is positive), in one kernel on the matrix cores.  The
+ * hidden activations are recomputed from y.  Half-precision operands with fp32 accumulation: dL/dout
+ * and the two hidden-layer gradients are rounded to fp16 where they enter the next product (callers
+ * that train in half precision scale their loss accordingly).
+ *   y       [B, n_in]   fp16, device, 16-byte aligned, read: the encoded features (n_in = L*F)
+ *   W1, W2, W3          as in hashgrid_encode_mlp_fwd, read
+ *   dLdout  [B, n_out]  fp32, device, read
+ *   dLdy    [B, n_in]   fp16, device, 8-byte aligned, written in full: what hashgrid_encode_bwd[_ws]
+ *                       takes as dL/dy (io_dtype fp16)
+ *   dW1 [64, n_in], dW2 [64, 64], dW3 [n_out, 64]   fp32, device, ACCUMULATED INTO (sums over the
+ *                       batch; fp32 atomic adds, so the last bits vary from run to run)
+ * HG_ERR_UNSUPPORTED unless n_in is a multiple of 8 and at most 64 and n_out at most 32;
+ * HG_ERR_INVALID_ARG for NULL or misaligned pointers, n_in == 0 or n_out == 0.  B == 0 is HG_OK. */
+hg_status hashgrid_mlp_bwd(uint32_t B, uint32_t n_in, uint32_t n_out, const void* y, const void* W1, const void* W2,
+                           const void* W3, const float* dLdout, void* dLdy, float* dW1, float* dW2, float* dW3,
+                           void* stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char* hashgrid_strerror(hg_status s);
 

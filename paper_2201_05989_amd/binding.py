@@ -31,7 +31,7 @@ EXPORTS = ("hashgrid_create", "hashgrid_destroy", "hashgrid_n_entries", "hashgri
            "hashgrid_encode_fwd", "hashgrid_encode_bwd", "hashgrid_encode_bwd_input",
            "hashgrid_debug_indices", "hashgrid_debug_count_outside", "hashgrid_strerror", "hashgrid_bwd_workspace_bytes",
            "hashgrid_encode_bwd_ws", "hashgrid_encode_fwd_ws", "hashgrid_bwd_ws_pays", "hashgrid_adam_step",
-           "hashgrid_encode_mlp_fwd", "hashgrid_encode_bwd_static")
+           "hashgrid_encode_mlp_fwd", "hashgrid_encode_bwd_static", "hashgrid_encode_mlp_fwd_train", "hashgrid_mlp_bwd")
 PROBE_EXPORTS = ("hashgrid_probe_copy", "hashgrid_probe_gather", "hashgrid_probe_atomic_add",
                  "hashgrid_probe_gather_lines")
 
@@ -90,6 +90,10 @@ def load_library() -> ctypes.CDLL:
     lib.hashgrid_encode_fwd_ws.restype = ctypes.c_int
     lib.hashgrid_encode_mlp_fwd.argtypes = [vp, u32, vp, vp, vp, vp, vp, u32, vp, vp]
     lib.hashgrid_encode_mlp_fwd.restype = ctypes.c_int
+    lib.hashgrid_encode_mlp_fwd_train.argtypes = [vp, u32, vp, vp, vp, vp, vp, u32, vp, vp, vp]
+    lib.hashgrid_encode_mlp_fwd_train.restype = ctypes.c_int
+    lib.hashgrid_mlp_bwd.argtypes = [u32, u32, u32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.hashgrid_mlp_bwd.restype = ctypes.c_int
     lib.hashgrid_bwd_ws_pays.argtypes = [vp, u32]
     lib.hashgrid_bwd_ws_pays.restype = ctypes.c_int
     lib.hashgrid_encode_bwd_ws.restype = ctypes.c_int
@@ -303,18 +307,23 @@ class HashGrid:
         return dLdx
 
     def encode_mlp_fwd(self, x: torch.Tensor, params: torch.Tensor, W1: torch.Tensor, W2: torch.Tensor,
-                       W3: torch.Tensor, out: torch.Tensor | None = None, stream=None):
+                       W3: torch.Tensor, out: torch.Tensor | None = None, stream=None, y: torch.Tensor | None = None):
         """hashgrid_encode_mlp_fwd: the encoding followed by the 64-64 ReLU network, fp16 weights
-        W1 [64, L*F], W2 [64, 64], W3 [n_out, 64]; returns out [B, n_out] fp32."""
+        W1 [64, L*F], W2 [64, 64], W3 [n_out, 64]; returns out [B, n_out] fp32.  With y [B, L*F] fp16:
+        hashgrid_encode_mlp_fwd_train, which also keeps the encoded features for mlp_bwd."""
         B, n_out = x.shape[0], W3.shape[0]
         if out is None:
             out = torch.empty((B, n_out), dtype=torch.float32, device=x.device)
-        _check(self._lib.hashgrid_encode_mlp_fwd(
-            self._h, B, _dev(x, torch.float32, (B, self.d), "x"),
-            _dev(params, self.param_dtype, (self.n_entries, self.F), "params"),
-            _dev(W1, torch.float16, (64, self.L * self.F), "W1"), _dev(W2, torch.float16, (64, 64), "W2"),
-            _dev(W3, torch.float16, (n_out, 64), "W3"), n_out, _dev(out, torch.float32, (B, n_out), "out"),
-            _stream_ptr(stream)), "hashgrid_encode_mlp_fwd")
+        args = (self._h, B, _dev(x, torch.float32, (B, self.d), "x"),
+                _dev(params, self.param_dtype, (self.n_entries, self.F), "params"),
+                _dev(W1, torch.float16, (64, self.L * self.F), "W1"), _dev(W2, torch.float16, (64, 64), "W2"),
+                _dev(W3, torch.float16, (n_out, 64), "W3"), n_out, _dev(out, torch.float32, (B, n_out), "out"))
+        if y is None:
+            _check(self._lib.hashgrid_encode_mlp_fwd(*args, _stream_ptr(stream)), "hashgrid_encode_mlp_fwd")
+        else:
+            _check(self._lib.hashgrid_encode_mlp_fwd_train(
+                *args, _dev(y, torch.float16, (B, self.L * self.F), "y"), _stream_ptr(stream)),
+                "hashgrid_encode_mlp_fwd_train")
         return out
 
     def debug_count_outside(self, x: torch.Tensor, stream=None) -> int:
@@ -394,3 +403,17 @@ def probe_gather_lines(table: torch.Tensor, slice_words: int, n_slices: int, n_p
     _check(load_probes().hashgrid_probe_gather_lines(table.data_ptr(), slice_words, n_slices, n_points, n_levels,
                                                      seed, sink.data_ptr(), _stream_ptr(stream)),
            "hashgrid_probe_gather_lines")
+
+
+def mlp_bwd(y: torch.Tensor, W1: torch.Tensor, W2: torch.Tensor, W3: torch.Tensor, dLdout: torch.Tensor,
+            dLdy: torch.Tensor, dW1: torch.Tensor, dW2: torch.Tensor, dW3: torch.Tensor, stream=None) -> None:
+    """hashgrid_mlp_bwd: y [B, n_in] fp16, fp16 weights, dLdout [B, n_out] fp32 -> dLdy [B, n_in] fp16 (written),
+    dW1, dW2, dW3 fp32 (accumulated into)."""
+    B, n_in = y.shape
+    n_out = W3.shape[0]
+    _check(load_library().hashgrid_mlp_bwd(
+        B, n_in, n_out, _dev(y, torch.float16, (B, n_in), "y"), _dev(W1, torch.float16, (64, n_in), "W1"),
+        _dev(W2, torch.float16, (64, 64), "W2"), _dev(W3, torch.float16, (n_out, 64), "W3"),
+        _dev(dLdout, torch.float32, (B, n_out), "dLdout"), _dev(dLdy, torch.float16, (B, n_in), "dLdy"),
+        _dev(dW1, torch.float32, (64, n_in), "dW1"), _dev(dW2, torch.float32, (64, 64), "dW2"),
+        _dev(dW3, torch.float32, (n_out, 64), "dW3"), _stream_ptr(stream)), "hashgrid_mlp_bwd")

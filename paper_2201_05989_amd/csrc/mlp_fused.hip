@@ -74,7 +74,7 @@ __global__ __launch_bounds__(kMlpBlock) void encode_mlp_fwd(const LevelTable lv,
                                                             const _Float16* __restrict__ W1,
                                                             const _Float16* __restrict__ W2,
                                                             const _Float16* __restrict__ W3, const uint32_t n_out,
-                                                            float* __restrict__ out) {
+                                                            float* __restrict__ out, _Float16* __restrict__ y_out) {
   extern __shared__ _Float16 lds[];
   const int n_in = (int)lv.L * F;  // a multiple of 8, at most 64 (checked on the host)
   const int w1_stride = n_in + kRowPad;
@@ -106,27 +106,47 @@ __global__ __launch_bounds__(kMlpBlock) void encode_mlp_fwd(const LevelTable lv,
 #pragma unroll
   for (int i = 0; i < D; ++i) xp[i] = x[(uint64_t)b * D + i];
   _Float16* my_row = act + threadIdx.x * kActStride;
-  for (uint32_t l = 0; l < lv.L; ++l) {
+  // two levels in flight, as in the forward kernel: the gathers of level l + 1 are issued before level l
+  // is blended (two register sets that alternate)
+  Vec<_Float16, F> e[2][1 << D];
+  float wr[2][1 << (D - 1)], w0[2], u0[2];
+  auto gather_level = [&](const uint32_t l, const int set) {
     uint32_t idx[1 << D];
-    float wr[1 << (D - 1)], w0, u0;
-    level_corners<D, true>(lv, l, smooth, xp, idx, wr, w0, u0);
+    level_corners<D, true>(lv, l, smooth, xp, idx, wr[set], w0[set], u0[set]);
     const Vec<_Float16, F>* tab = reinterpret_cast<const Vec<_Float16, F>*>(theta) + lv.offset[l];
-    Vec<_Float16, F> e[1 << D];
 #pragma unroll
-    for (uint32_t m = 0; m < (1u << D); ++m) e[m] = tab[idx[m]];
+    for (uint32_t m = 0; m < (1u << D); ++m) e[set][m] = tab[idx[m]];
+  };
+  auto blend_level = [&](const uint32_t l, const int set) {
     float acc[F];
 #pragma unroll
     for (int f = 0; f < F; ++f) acc[f] = 0.0f;
 #pragma unroll
     for (uint32_t m = 0; m < (1u << D); ++m) {
-      const float wt = wr[m >> 1] * ((m & 1u) ? w0 : u0);
+      const float wt = wr[set][m >> 1] * ((m & 1u) ? w0[set] : u0[set]);
 #pragma unroll
-      for (int f = 0; f < F; ++f) acc[f] = fmaf(wt, (float)e[m].v[f], acc[f]);
+      for (int f = 0; f < F; ++f) acc[f] = fmaf(wt, (float)e[set][m].v[f], acc[f]);
     }
 #pragma unroll
     for (int f = 0; f < F; ++f) my_row[l * F + f] = (_Float16)acc[f];  // rows are 8-byte, not 16-byte, aligned
     asm volatile("" ::: "memory");  // keep the gathers of one level together
     __syncthreads();                // (also: the weights are in place before the first product)
+  };
+  gather_level(0, 0);
+  for (uint32_t l = 0; l < lv.L; l += 2) {
+    if (l + 1 < lv.L) gather_level(l + 1, 1);
+    blend_level(l, 0);
+    if (l + 1 < lv.L) {  // uniform
+      if (l + 2 < lv.L) gather_level(l + 2, 0);
+      blend_level(l + 1, 1);
+    }
+  }
+
+  // training: the encoded features, as the network sees them (rounded to half), are kept for the
+  // backward pass of the network; each thread copies its own row
+  if (y_out != nullptr && b0 < B) {
+    for (int k = 0; k < n_in; k += 4)
+      *reinterpret_cast<half4*>(y_out + (uint64_t)b0 * n_in + k) = *reinterpret_cast<const half4*>(my_row + k);
   }
 
   // the network, per wave on its own 64 points; a layer's four blocks are computed before its
@@ -169,7 +189,7 @@ __global__ __launch_bounds__(kMlpBlock) void encode_mlp_fwd(const LevelTable lv,
 
 template <int D, int F>
 static hg_status launch_mlp(const hashgrid* h, uint32_t B, const float* x, const void* params, const void* W1,
-                            const void* W2, const void* W3, uint32_t n_out, float* out, hipStream_t s) {
+                            const void* W2, const void* W3, uint32_t n_out, float* out, void* y_out, hipStream_t s) {
   const int n_in = (int)h->lv.L * F;
   const uint32_t block = point_major_block(B);
   const size_t lds = ((size_t)block * kActStride + (size_t)kHidden * (n_in + kRowPad) +
@@ -180,15 +200,15 @@ static hg_status launch_mlp(const hashgrid* h, uint32_t B, const float* x, const
   hipLaunchKernelGGL((encode_mlp_fwd<D, F>), dim3((B + block - 1) / block), dim3(block), lds, s, h->lv,
                      h->cfg.interp == HG_INTERP_SMOOTHSTEP, B, x, static_cast<const _Float16*>(params),
                      static_cast<const _Float16*>(W1), static_cast<const _Float16*>(W2),
-                     static_cast<const _Float16*>(W3), n_out, out);
+                     static_cast<const _Float16*>(W3), n_out, out, static_cast<_Float16*>(y_out));
   return hipGetLastError() == hipSuccess ? HG_OK : HG_ERR_DEVICE;
 }
 
 }  // namespace hg
 
-extern "C" hg_status hashgrid_encode_mlp_fwd(const hashgrid_t* hg, uint32_t B, const float* x, const void* params,
-                                             const void* W1, const void* W2, const void* W3, uint32_t n_out,
-                                             float* out, void* stream) {
+static hg_status encode_mlp_fwd_any(const hashgrid_t* hg, uint32_t B, const float* x, const void* params, const void* W1,
+                                    const void* W2, const void* W3, uint32_t n_out, float* out, void* y_out,
+                                    void* stream) {
   if (!hg) return HG_ERR_INVALID_ARG;
   if (B == 0) return HG_OK;
   if (B > HG_MAX_BATCH) return HG_ERR_UNSUPPORTED;
@@ -199,10 +219,10 @@ extern "C" hg_status hashgrid_encode_mlp_fwd(const hashgrid_t* hg, uint32_t B, c
       n_out > (uint32_t)hg::kMaxOut)
     return HG_ERR_UNSUPPORTED;
   auto bad = [](const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; };
-  if (bad(x, 4) || bad(params, c.F * 2) || bad(W1, 8) || bad(W2, 8) || bad(W3, 8) || bad(out, 4))
+  if (bad(x, 4) || bad(params, c.F * 2) || bad(W1, 8) || bad(W2, 8) || bad(W3, 8) || bad(out, 4) || bad(y_out, 16))
     return HG_ERR_INVALID_ARG;
   hipStream_t s = static_cast<hipStream_t>(stream);
-#define HG_MLP(D, F) hg::launch_mlp<D, F>(hg, B, x, params, W1, W2, W3, n_out, out, s)
+#define HG_MLP(D, F) hg::launch_mlp<D, F>(hg, B, x, params, W1, W2, W3, n_out, out, y_out, s)
   switch (c.d * 16 + c.F) {
     case 2 * 16 + 1: return HG_MLP(2, 1);
     case 2 * 16 + 2: return HG_MLP(2, 2);
@@ -215,4 +235,17 @@ extern "C" hg_status hashgrid_encode_mlp_fwd(const hashgrid_t* hg, uint32_t B, c
     default: return HG_ERR_UNSUPPORTED;
   }
 #undef HG_MLP
+}
+
+extern "C" hg_status hashgrid_encode_mlp_fwd(const hashgrid_t* hg, uint32_t B, const float* x, const void* params,
+                                             const void* W1, const void* W2, const void* W3, uint32_t n_out,
+                                             float* out, void* stream) {
+  return encode_mlp_fwd_any(hg, B, x, params, W1, W2, W3, n_out, out, nullptr, stream);
+}
+
+extern "C" hg_status hashgrid_encode_mlp_fwd_train(const hashgrid_t* hg, uint32_t B, const float* x, const void* params,
+                                                   const void* W1, const void* W2, const void* W3, uint32_t n_out,
+                                                   float* out, void* y, void* stream) {
+  if (B != 0 && !y) return HG_ERR_INVALID_ARG;
+  return encode_mlp_fwd_any(hg, B, x, params, W1, W2, W3, n_out, out, y, stream);
 }
