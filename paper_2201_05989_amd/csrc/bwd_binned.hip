@@ -61,6 +61,7 @@ namespace hg {
 // Launch shapes, each the best of a sweep on the headline configuration.
 constexpr int kScanThreads = 1024;
 constexpr int kAccThreads = 1024;                // accumulate workgroup (512 x 2 per CU is slower)
+constexpr uint32_t kFewBins = 32;                 // bins of a level up to which the scatter pass spreads a tile's records (bin_scatter)
 constexpr int kAccUnroll = 4;                    // record loads in flight per lane in the tail of a long item
 constexpr int kAccPreWords = 24;                 // registers per lane for records requested one item ahead
 constexpr uint32_t kAccWgsPerCu = 1;             // its registers let one accumulate workgroup run per CU
@@ -542,6 +543,16 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, 
       gf[f] = (float)g[f];
       gmax = nan_max(gmax, fabsf(gf[f]));
     }
+    // Position of a new record of bin rb in the tile's sorted order.  On a level of few bins a wave's
+    // lanes crowd into the same counters and a tile's run for a bin is long: there the wave draws
+    // its slots with one add per bin (wave_add_one) and the run is filled with a stride
+    // (spread_in_run), for the accumulate pass.  Levels of many bins take the plain atomic.
+    const bool few_bins = rb1 - rb0 <= kFewBins;  // uniform
+    auto take_slot = [&](const uint32_t rb) {
+      if (!few_bins) return __hip_atomic_fetch_add(&cur[rb], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      const uint32_t first = local[rb];
+      return first + spread_in_run(wave_add_one<true>(cur, rb) - first, local[rb + 1] - first);
+    };
     if (valid) {
       if constexpr (CORNERS) {
         // a corner's record: all of its weight on the "lower" side of a pair whose upper weight is 0
@@ -550,8 +561,7 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, 
 #pragma unroll
         for (uint32_t m = 0; m < R; ++m) {
           const uint32_t rb = cr.bin[m] - gb_a;
-          const uint32_t in_tile = __hip_atomic_fetch_add(&cur[rb], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-          const uint32_t pos = in_tile - level_first;
+          const uint32_t pos = take_slot(rb) - level_first;
           if (pos < R * kBinThreads) {
             staging[pos] = Rec::make(cr.la[m], 0u, 0.0f, cr.weight[m], g);
             binv[pos] = (uint16_t)rb;
@@ -564,8 +574,7 @@ __global__ __launch_bounds__(kBinThreads) void bin_scatter(const LevelTable lv, 
 #pragma unroll
         for (uint32_t r = 0; r < R && !rw.cross; ++r) {
           const uint32_t rb = rw.bin[r] - gb_a;
-          const uint32_t in_tile = __hip_atomic_fetch_add(&cur[rb], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-          const uint32_t pos = in_tile - level_first;
+          const uint32_t pos = take_slot(rb) - level_first;
           if (pos < R * kBinThreads) {  // holds when the count pass saw the same x
             staging[pos] = Rec::make(rw.la[r], rw.k, rw.wf0, rw.wrow[r], g, smooth);
             binv[pos] = (uint16_t)rb;

@@ -141,4 +141,63 @@ __host__ __device__ __forceinline__ void corner_rows_of(const LevelTable& lv, co
   }
 }
 
+// Where the k-th record that a tile places into a bin goes inside the tile's run of n records for
+// that bin: k * s mod n for a prime s that does not divide n, a bijection of [0, n).  Points that
+// follow each other in the batch often share a voxel (samples along a ray), their records would
+// sit next to each other, and the accumulate pass, whose 64 lanes take 64 consecutive records,
+// would add them to one LDS address in one instruction, served one lane after the other.  With
+// the stride such records are at least 67 slots apart.  Short runs (fine levels, where neighbours
+// in the batch do not share voxels) stay in order.  n <= 2^12, so every product is below 2^24
+// and the float quotient is off by one at most, which the two corrections undo.
+__host__ __device__ __forceinline__ uint32_t spread_in_run(const uint32_t k, const uint32_t n) {
+  if (n < 128u || k >= n) return k;
+  const uint32_t s = (n % 67u) ? 67u : 71u;
+  const uint32_t t = k * s;
+#if defined(__HIP_DEVICE_COMPILE__)
+  const float inv = __builtin_amdgcn_rcpf((float)n);
+#else
+  const float inv = 1.0f / (float)n;
+#endif
+  const uint32_t q = (uint32_t)((float)t * inv);
+  int32_t m = (int32_t)(t - q * n);
+  m = m < 0 ? m + (int32_t)n : m;
+  m = m >= (int32_t)n ? m - (int32_t)n : m;
+  return (uint32_t)m;
+}
+
+// counters[bin] += 1 from every lane that calls (LDS counters, any subset of the wave's lanes);
+// returns what a fetch-and-add of 1 would have returned to the lane, in some order of the lanes.
+// Lanes that name the same counter in one LDS atomic instruction are served one after the other,
+// and neighbouring points of a batch often fall into one bin (all points on a coarse level with
+// few bins; samples along a ray).  So the largest groups of the wave, found by comparing with the
+// first pending lane's bin, send one add of the group's size each and share out the slots by lane
+// rank; the lanes that are left use plain atomics.
+constexpr uint32_t kAggregateFrom = 20;  // lanes with one bin from which a common add pays (measured: 8 costs random batches 1%)
+template <bool RETURN>
+__device__ __forceinline__ uint32_t wave_add_one(uint32_t* counters, const uint32_t bin) {
+  uint32_t slot = 0;
+  bool todo = true;
+#pragma unroll
+  for (int round = 0; round < 2; ++round) {
+    const uint64_t pending = __ballot(todo);
+    if (pending == 0) return slot;  // uniform over the calling lanes
+    const uint32_t leader = (uint32_t)__builtin_ctzll(pending);
+    const uint32_t bin_l = (uint32_t)__builtin_amdgcn_readlane((int)bin, (int)leader);
+    const bool mine = todo && bin == bin_l;
+    const uint64_t group = __ballot(mine);
+    const uint32_t n = (uint32_t)__popcll(group);
+    if (n < kAggregateFrom) break;
+    const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(group >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)group, 0u));
+    uint32_t base = 0;
+    if (mine && rank == 0) base = __hip_atomic_fetch_add(&counters[bin_l], n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    if (RETURN) {
+      base = (uint32_t)__builtin_amdgcn_readlane((int)base, (int)__builtin_ctzll(group));
+      slot = mine ? base + rank : slot;
+    }
+    todo = todo && !mine;
+  }
+  if (todo) slot = __hip_atomic_fetch_add(&counters[bin], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  return slot;
+}
+
 }  // namespace hg

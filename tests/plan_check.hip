@@ -183,3 +183,31 @@ extern "C" uint64_t plan_check(const hashgrid_config* cfg, uint32_t B, const flo
   hashgrid_destroy(h);
   return bad;
 }
+
+// spread_in_run over every run length the scatter pass can see (a tile's records for one bin:
+// at most 2^d * 512): number of run lengths for which it is not a bijection of [0, n), or puts
+// two records that follow each other fewer than 64 slots apart in a run of 128 or more
+// (cyclically: k * s mod n steps by s or s - n).
+extern "C" uint32_t spread_check(uint32_t n_max) {
+  uint32_t bad = 0;
+  unsigned char* seen = (unsigned char*)malloc(n_max + 1);
+  for (uint32_t n = 1; n <= n_max; ++n) {
+    for (uint32_t i = 0; i < n; ++i) seen[i] = 0;
+    bool ok = true;
+    uint32_t prev = 0;
+    for (uint32_t k = 0; k < n && ok; ++k) {
+      const uint32_t p = hg::spread_in_run(k, n);
+      if (p >= n || seen[p]) ok = false;
+      else seen[p] = 1;
+      if (ok && n >= 192 && k > 0) {
+        const uint32_t dist = p > prev ? p - prev : prev - p;
+        if (dist < 64) ok = false;
+      }
+      prev = p;
+    }
+    if (hg::spread_in_run(n, n) != n || hg::spread_in_run(n + 5, n) != n + 5) ok = false;  // out of range: left alone
+    bad += ok ? 0 : 1;
+  }
+  free(seen);
+  return bad;
+}

@@ -36,6 +36,7 @@ def plan_check(tmp_path_factory):
         bad = lib.plan_check(ctypes.byref(cfg), len(x), x.ctypes.data, ctypes.byref(crossing))
         return bad, crossing.value
 
+    run.lib = lib
     return run
 
 
@@ -95,3 +96,11 @@ def test_plan_where_half_of_the_pairs_straddle_two_chunks(plan_check):
         x[:3000, 0] = ((4095.75 + 4096.0 * rng.integers(0, 2, 3000)) / 8192.0).astype(np.float32)
         bad, crossing = plan_check(d, 3, 2, 1 << 16, 8192, 32768, 0, x)
         assert bad == 0 and crossing >= 3 * 3000
+
+
+def test_order_of_records_inside_a_run_is_a_permutation(plan_check):
+    """The scatter pass spreads the records a tile puts into one bin (records of neighbouring points apart,
+    for the accumulate pass's LDS atomics): whatever the run length, every slot of the run is used exactly once."""
+    plan_check.lib.spread_check.restype = ctypes.c_uint32
+    plan_check.lib.spread_check.argtypes = [ctypes.c_uint32]
+    assert plan_check.lib.spread_check(4096) == 0
