@@ -25,6 +25,11 @@ HIPCC_FLAGS = [
 ]
 
 
+# Per-source flags.  mlp_bwd.hip: matrix-core results that the vector unit converts right away are kept
+# out of the accumulation registers (a separate move per element otherwise).
+SOURCE_FLAGS = {"mlp_bwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+
+
 def hipcc() -> str:
     for cand in (os.environ.get("HIPCC"), "/opt/rocm/bin/hipcc", "hipcc"):
         if cand and (os.path.sep not in cand or os.path.exists(cand)):
@@ -41,7 +46,8 @@ def _compile_and_link(sources, out: str, verbose: bool, extra_flags) -> str:
     with tempfile.TemporaryDirectory(prefix="hashgrid_obj_") as objdir:
         def compile_one(src):
             obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
-            cmd = [hipcc(), *flags, *extra_flags, f"-I{INCLUDE}", f"-I{CSRC}", "-c", "-o", obj, os.path.join(CSRC, src)]
+            cmd = [hipcc(), *flags, *SOURCE_FLAGS.get(src, []), *extra_flags, f"-I{INCLUDE}", f"-I{CSRC}", "-c", "-o", obj,
+                   os.path.join(CSRC, src)]
             if verbose:
                 print(" ".join(cmd), flush=True)
             subprocess.run(cmd, check=True)
