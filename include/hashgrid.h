@@ -284,20 +284,6 @@ hg_status hashgrid_mlp_bwd(uint32_t B, uint32_t n_in, uint32_t n_out, const void
                            const void* W3, const float* dLdout, void* dLdy, float* dW1, float* dW2, float* dW3,
                            void* stream);
 
-/* The same pass with a scratch buffer (Section 4, "Architecture", as above): every workgroup writes
- * its weight-gradient sums to the buffer and a second small kernel adds them up, eight atomic adds
- * per scalar instead of one per workgroup (256 workgroups adding to the same 6 K scalars queue up:
- * about a quarter of the plain call's time at 2^18 points).
- *   workspace        device, 16-byte aligned, at least hashgrid_mlp_bwd_workspace_bytes(n_in, n_out)
- *                    bytes (about 8 to 10 MiB; sized for the device that is current at the call);
- *                    overwritten; owned by the caller; calls that overlap need buffers of their own
- * HG_ERR_INVALID_ARG also for a NULL or too small workspace.  hashgrid_mlp_bwd_workspace_bytes returns
- * 0 for shapes that hashgrid_mlp_bwd does not support. */
-size_t hashgrid_mlp_bwd_workspace_bytes(uint32_t n_in, uint32_t n_out);
-hg_status hashgrid_mlp_bwd_ws(uint32_t B, uint32_t n_in, uint32_t n_out, const void* y, const void* W1, const void* W2,
-                              const void* W3, const float* dLdout, void* dLdy, float* dW1, float* dW2, float* dW3,
-                              void* workspace, size_t workspace_bytes, void* stream);
-
 /* Static, NUL-terminated description of a status code. */
 const char* hashgrid_strerror(hg_status s);
 

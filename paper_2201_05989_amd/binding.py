@@ -31,8 +31,7 @@ EXPORTS = ("hashgrid_create", "hashgrid_destroy", "hashgrid_n_entries", "hashgri
            "hashgrid_encode_fwd", "hashgrid_encode_bwd", "hashgrid_encode_bwd_input",
            "hashgrid_debug_indices", "hashgrid_debug_count_outside", "hashgrid_strerror", "hashgrid_bwd_workspace_bytes",
            "hashgrid_encode_bwd_ws", "hashgrid_encode_fwd_ws", "hashgrid_bwd_ws_pays", "hashgrid_adam_step",
-           "hashgrid_encode_mlp_fwd", "hashgrid_encode_bwd_static", "hashgrid_encode_mlp_fwd_train", "hashgrid_mlp_bwd",
-           "hashgrid_mlp_bwd_workspace_bytes", "hashgrid_mlp_bwd_ws")
+           "hashgrid_encode_mlp_fwd", "hashgrid_encode_bwd_static", "hashgrid_encode_mlp_fwd_train", "hashgrid_mlp_bwd")
 PROBE_EXPORTS = ("hashgrid_probe_copy", "hashgrid_probe_gather", "hashgrid_probe_atomic_add",
                  "hashgrid_probe_gather_lines")
 
@@ -95,10 +94,6 @@ def load_library() -> ctypes.CDLL:
     lib.hashgrid_encode_mlp_fwd_train.restype = ctypes.c_int
     lib.hashgrid_mlp_bwd.argtypes = [u32, u32, u32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.hashgrid_mlp_bwd.restype = ctypes.c_int
-    lib.hashgrid_mlp_bwd_workspace_bytes.argtypes = [u32, u32]
-    lib.hashgrid_mlp_bwd_workspace_bytes.restype = ctypes.c_size_t
-    lib.hashgrid_mlp_bwd_ws.argtypes = [u32, u32, u32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
-    lib.hashgrid_mlp_bwd_ws.restype = ctypes.c_int
     lib.hashgrid_bwd_ws_pays.argtypes = [vp, u32]
     lib.hashgrid_bwd_ws_pays.restype = ctypes.c_int
     lib.hashgrid_encode_bwd_ws.restype = ctypes.c_int
@@ -410,40 +405,15 @@ def probe_gather_lines(table: torch.Tensor, slice_words: int, n_slices: int, n_p
            "hashgrid_probe_gather_lines")
 
 
-_mlp_ws: dict = {}  # (device index, stream pointer) -> scratch buffer of mlp_bwd
-
-
 def mlp_bwd(y: torch.Tensor, W1: torch.Tensor, W2: torch.Tensor, W3: torch.Tensor, dLdout: torch.Tensor,
-            dLdy: torch.Tensor, dW1: torch.Tensor, dW2: torch.Tensor, dW3: torch.Tensor, stream=None,
-            workspace: "torch.Tensor | bool | None" = None) -> None:
-    """hashgrid_mlp_bwd[_ws]: y [B, n_in] fp16, fp16 weights, dLdout [B, n_out] fp32 -> dLdy [B, n_in] fp16 (written),
-    dW1, dW2, dW3 fp32 (accumulated into).  workspace: a device tensor of at least
-    hashgrid_mlp_bwd_workspace_bytes bytes, None for a buffer kept per device and stream, False for the call
-    without a scratch buffer (one atomic add per scalar and workgroup)."""
+            dLdy: torch.Tensor, dW1: torch.Tensor, dW2: torch.Tensor, dW3: torch.Tensor, stream=None) -> None:
+    """hashgrid_mlp_bwd: y [B, n_in] fp16, fp16 weights, dLdout [B, n_out] fp32 -> dLdy [B, n_in] fp16 (written),
+    dW1, dW2, dW3 fp32 (accumulated into)."""
     B, n_in = y.shape
     n_out = W3.shape[0]
-    lib = load_library()
-    args = (B, n_in, n_out, _dev(y, torch.float16, (B, n_in), "y"), _dev(W1, torch.float16, (64, n_in), "W1"),
-            _dev(W2, torch.float16, (64, 64), "W2"), _dev(W3, torch.float16, (n_out, 64), "W3"),
-            _dev(dLdout, torch.float32, (B, n_out), "dLdout"), _dev(dLdy, torch.float16, (B, n_in), "dLdy"),
-            _dev(dW1, torch.float32, (64, n_in), "dW1"), _dev(dW2, torch.float32, (64, 64), "dW2"),
-            _dev(dW3, torch.float32, (n_out, 64), "dW3"))
-    if workspace is False:
-        _check(lib.hashgrid_mlp_bwd(*args, _stream_ptr(stream)), "hashgrid_mlp_bwd")
-        return
-    if workspace is None or workspace is True:
-        with torch.cuda.device(y.device):
-            need = lib.hashgrid_mlp_bwd_workspace_bytes(n_in, n_out)
-        if need == 0:
-            raise HashGridError(f"hashgrid_mlp_bwd: unsupported shape n_in={n_in} n_out={n_out}")
-        key = (y.device.index, _stream_ptr(stream))
-        workspace = _mlp_ws.get(key)
-        if workspace is None or workspace.numel() < need:
-            workspace = torch.empty(need, dtype=torch.uint8, device=y.device)
-            _mlp_ws[key] = workspace
-        if stream is not None:
-            workspace.record_stream(stream)  # allocated on torch's current stream, used on this one
-    if not (workspace.is_cuda and workspace.is_contiguous()):
-        raise HashGridError("workspace must be a contiguous device tensor")
-    _check(lib.hashgrid_mlp_bwd_ws(*args, workspace.data_ptr(), workspace.numel() * workspace.element_size(),
-                                   _stream_ptr(stream)), "hashgrid_mlp_bwd_ws")
+    _check(load_library().hashgrid_mlp_bwd(
+        B, n_in, n_out, _dev(y, torch.float16, (B, n_in), "y"), _dev(W1, torch.float16, (64, n_in), "W1"),
+        _dev(W2, torch.float16, (64, 64), "W2"), _dev(W3, torch.float16, (n_out, 64), "W3"),
+        _dev(dLdout, torch.float32, (B, n_out), "dLdout"), _dev(dLdy, torch.float16, (B, n_in), "dLdy"),
+        _dev(dW1, torch.float32, (64, n_in), "dW1"), _dev(dW2, torch.float32, (64, 64), "dW2"),
+        _dev(dW3, torch.float32, (n_out, 64), "dW3"), _stream_ptr(stream)), "hashgrid_mlp_bwd")

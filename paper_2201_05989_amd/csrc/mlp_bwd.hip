@@ -130,22 +130,6 @@ __device__ __forceinline__ float* sum_target(const int g, const int lane, const 
   const int a = (g - 64 - 32 * kb) / 16;
   return row < n_out ? dW3 + row * kHid + 32 * a + c : nullptr;
 }
-constexpr int kSumSlices = 8;  // the summing kernel's share-out of the workgroups: atomic adds per scalar
-
-// Second step of the variant with a workspace: partial[w][g][lane] over the workgroups w of the first
-// kernel, added up in kSumSlices interleaved shares, each of which sends one atomic add per scalar.
-__global__ __launch_bounds__(256) void mlp_bwd_sum(const float* __restrict__ partial, const uint32_t n_wg,
-                                                   const int n_sums, const int kb, const int n_in, const int n_out,
-                                                   float* __restrict__ dW1, float* __restrict__ dW2,
-                                                   float* __restrict__ dW3) {
-  const int e = (int)(blockIdx.x * 256 + threadIdx.x);
-  if (e >= n_sums) return;
-  float v = 0.0f;
-  for (uint32_t w = blockIdx.y; w < n_wg; w += kSumSlices) v += partial[(size_t)w * n_sums + e];
-  float* t = sum_target(e / 64, e % 64, kb, n_in, n_out, dW1, dW2, dW3);
-  if (t != nullptr && v != 0.0f) __hip_atomic_fetch_add(t, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
 // KB: 32-column blocks of y (1 for up to 32 encoded features, else 2); OS: groups of eight outputs
 template <int KB, int OS>
 __global__ __launch_bounds__(64 * kWaves) void mlp_bwd_kernel(const uint32_t B, const MlpBwdShape sh,
@@ -153,7 +137,7 @@ __global__ __launch_bounds__(64 * kWaves) void mlp_bwd_kernel(const uint32_t B, 
                                                       const _Float16* __restrict__ W2, const _Float16* __restrict__ W3,
                                                       const float* __restrict__ dout, _Float16* __restrict__ dy,
                                                       float* __restrict__ dW1, float* __restrict__ dW2,
-                                                      float* __restrict__ dW3, float* __restrict__ partial) {
+                                                      float* __restrict__ dW3) {
   extern __shared__ _Float16 lds[];
   const int n_in = sh.n_in, n_out = sh.n_out;
   const int threads = (int)blockDim.x, waves = threads / 64, wave = (int)threadIdx.x / 64, lane = (int)threadIdx.x & 63;
@@ -443,14 +427,13 @@ __global__ __launch_bounds__(64 * kWaves) void mlp_bwd_kernel(const uint32_t B, 
 
   // The weight gradients of the workgroup.  Every wave writes its sums to LDS as they lie in its
   // registers ([wave][register][lane]; the weights are no longer needed), then every thread adds up
-  // the waves' values of its share of (register, lane) pairs.  Two rounds, so that the area stays
-  // below 96 KiB: the second layer's 64 registers, then the first and the output layer's.  The sums
-  // leave as the workgroup's row of `partial` (plain stores, for the summing kernel) or, without a
-  // workspace, with one atomic add per scalar: the 32 lanes of a half-wave hold 32 consecutive
-  // columns of a row.
+  // the waves' values of its share of (register, lane) pairs and sends one atomic add per scalar:
+  // the 32 lanes of a half-wave hold 32 consecutive columns of a row.  Two rounds, so that the
+  // area stays below 96 KiB: the second layer's 64 registers, then the first and the output layer's.
+  // (Writing the workgroups' sums to a scratch buffer for a second kernel to add up was measured and is
+  // slower than these atomics: 49 against 40 us at 2^18 points.)
   float* red = reinterpret_cast<float*>(lds);
   const int rot = (int)((blockIdx.x * 13u) % 64u);
-  constexpr int kSums = (64 + 32 * KB + 32) * 64;
   auto reduce = [&](auto&& store_all, const int g0, const int n_regs) {
     __syncthreads();  // the area is free: every wave is done with the weights (first round) or the round before
     store_all(red + wave * n_regs * 64 + lane);  // register r to [r * 64]
@@ -460,12 +443,8 @@ __global__ __launch_bounds__(64 * kWaves) void mlp_bwd_kernel(const uint32_t B, 
       const int r = (i + rot) % n_regs;
       float v = 0.0f;
       for (int w = 0; w < waves; ++w) v += red[(w * n_regs + r) * 64 + lane];
-      if (partial != nullptr) {  // uniform
-        partial[(size_t)blockIdx.x * kSums + (g0 + r) * 64 + lane] = v;
-      } else {
-        float* t = sum_target(g0 + r, lane, KB, n_in, n_out, dW1, dW2, dW3);
-        if (t != nullptr && v != 0.0f) __hip_atomic_fetch_add(t, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
+      float* t = sum_target(g0 + r, lane, KB, n_in, n_out, dW1, dW2, dW3);
+      if (t != nullptr && v != 0.0f) __hip_atomic_fetch_add(t, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   };
   reduce(
@@ -492,21 +471,9 @@ __global__ __launch_bounds__(64 * kWaves) void mlp_bwd_kernel(const uint32_t B, 
 
 }  // namespace hg
 
-namespace {
-
-uint32_t compute_units() {
-  // (per device: the workspace is sized and the grid chosen for the device that is current)
-  int dev = 0, n = 0;
-  if (hipGetDevice(&dev) != hipSuccess ||
-      hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-    n = 256;
-  return (uint32_t)n;
-}
-size_t sums_per_workgroup(uint32_t n_in) { return (size_t)(64 + 32 * ((n_in + 31) / 32) + 32) * 64; }
-
-hg_status mlp_bwd_launch(uint32_t B, uint32_t n_in, uint32_t n_out, const void* y, const void* W1, const void* W2,
-                         const void* W3, const float* dLdout, void* dLdy, float* dW1, float* dW2, float* dW3,
-                         void* workspace, size_t workspace_bytes, void* stream) {
+extern "C" hg_status hashgrid_mlp_bwd(uint32_t B, uint32_t n_in, uint32_t n_out, const void* y, const void* W1,
+                                      const void* W2, const void* W3, const float* dLdout, void* dLdy, float* dW1,
+                                      float* dW2, float* dW3, void* stream) {
   if (B == 0) return HG_OK;
   if (B > HG_MAX_BATCH) return HG_ERR_UNSUPPORTED;
   if (!y || !W1 || !W2 || !W3 || !dLdout || !dLdy || !dW1 || !dW2 || !dW3 || n_out == 0 || n_in == 0)
@@ -514,14 +481,14 @@ hg_status mlp_bwd_launch(uint32_t B, uint32_t n_in, uint32_t n_out, const void* 
   if (n_in % 8 != 0 || n_in > 64 || n_out > 32) return HG_ERR_UNSUPPORTED;
   auto bad = [](const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; };
   if (bad(y, 16) || bad(dLdy, 8) || bad(W1, 2) || bad(W2, 2) || bad(W3, 2) || bad(dLdout, 4) || bad(dW1, 4) ||
-      bad(dW2, 4) || bad(dW3, 4) || bad(workspace, 16))
+      bad(dW2, 4) || bad(dW3, 4))
     return HG_ERR_INVALID_ARG;
   const hg::MlpBwdShape sh = hg::MlpBwdShape::make((int)n_in, (int)n_out);
   constexpr size_t kLdsLimit = 160 * 1024;
   const int waves = hg::kWaves;
   if (sh.lds_bytes(waves) > kLdsLimit) return HG_ERR_UNSUPPORTED;
   using Kernel = void (*)(uint32_t, hg::MlpBwdShape, const _Float16*, const _Float16*, const _Float16*, const _Float16*,
-                          const float*, _Float16*, float*, float*, float*, float*);
+                          const float*, _Float16*, float*, float*, float*);
   static const Kernel kernels[2][4] = {
       {hg::mlp_bwd_kernel<1, 1>, hg::mlp_bwd_kernel<1, 2>, hg::mlp_bwd_kernel<1, 3>, hg::mlp_bwd_kernel<1, 4>},
       {hg::mlp_bwd_kernel<2, 1>, hg::mlp_bwd_kernel<2, 2>, hg::mlp_bwd_kernel<2, 3>, hg::mlp_bwd_kernel<2, 4>}};
@@ -534,40 +501,18 @@ hg_status mlp_bwd_launch(uint32_t B, uint32_t n_in, uint32_t n_out, const void* 
     return e;
   }();
   if (lds_ok != hipSuccess) return HG_ERR_DEVICE;
-  const uint32_t cus = compute_units();
+  // one workgroup per compute unit of the current device, at most
+  int dev = 0, n_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0)
+    n_cu = 256;
+  const uint32_t cus = (uint32_t)n_cu;
   const uint32_t n_rounds = (B + hg::kSub * hg::kPts - 1) / (hg::kSub * hg::kPts);
   const uint32_t want = (n_rounds + waves - 1) / waves;
   const dim3 grid(want < cus ? want : cus), block(64 * waves);
-  const size_t n_sums = sums_per_workgroup(n_in);
-  float* partial = static_cast<float*>(workspace);
-  if (partial != nullptr && workspace_bytes < (size_t)grid.x * n_sums * sizeof(float)) return HG_ERR_INVALID_ARG;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipLaunchKernelGGL(kernels[sh.kin_pad / 32 - 1][(n_out + 7) / 8 - 1], grid, block, sh.lds_bytes(waves), s, B, sh,
                      static_cast<const _Float16*>(y), static_cast<const _Float16*>(W1), static_cast<const _Float16*>(W2),
-                     static_cast<const _Float16*>(W3), dLdout, static_cast<_Float16*>(dLdy), dW1, dW2, dW3, partial);
-  if (partial != nullptr)
-    hipLaunchKernelGGL(hg::mlp_bwd_sum, dim3((unsigned)((n_sums + 255) / 256), hg::kSumSlices), dim3(256), 0, s, partial,
-                       grid.x, (int)n_sums, sh.kin_pad / 32, (int)n_in, (int)n_out, dW1, dW2, dW3);
+                     static_cast<const _Float16*>(W3), dLdout, static_cast<_Float16*>(dLdy), dW1, dW2, dW3);
   return hipGetLastError() == hipSuccess ? HG_OK : HG_ERR_DEVICE;
-}
-
-}  // namespace
-
-extern "C" hg_status hashgrid_mlp_bwd(uint32_t B, uint32_t n_in, uint32_t n_out, const void* y, const void* W1,
-                                      const void* W2, const void* W3, const float* dLdout, void* dLdy, float* dW1,
-                                      float* dW2, float* dW3, void* stream) {
-  return mlp_bwd_launch(B, n_in, n_out, y, W1, W2, W3, dLdout, dLdy, dW1, dW2, dW3, nullptr, 0, stream);
-}
-
-extern "C" size_t hashgrid_mlp_bwd_workspace_bytes(uint32_t n_in, uint32_t n_out) {
-  if (n_in == 0 || n_out == 0 || n_in % 8 != 0 || n_in > 64 || n_out > 32) return 0;
-  return (size_t)compute_units() * sums_per_workgroup(n_in) * sizeof(float);
-}
-
-extern "C" hg_status hashgrid_mlp_bwd_ws(uint32_t B, uint32_t n_in, uint32_t n_out, const void* y, const void* W1,
-                                         const void* W2, const void* W3, const float* dLdout, void* dLdy, float* dW1,
-                                         float* dW2, float* dW3, void* workspace, size_t workspace_bytes,
-                                         void* stream) {
-  if (B != 0 && workspace == nullptr) return HG_ERR_INVALID_ARG;
-  return mlp_bwd_launch(B, n_in, n_out, y, W1, W2, W3, dLdout, dLdy, dW1, dW2, dW3, workspace, workspace_bytes, stream);
 }

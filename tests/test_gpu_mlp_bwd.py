@@ -24,7 +24,7 @@ def dev(a, dtype):
     return torch.from_numpy(np.ascontiguousarray(a, dtype=dtype)).cuda()
 
 
-def run_gpu(y, W1, W2, W3, dout, workspace=None):
+def run_gpu(y, W1, W2, W3, dout):
     B, n_in = y.shape
     n_out = W3.shape[0]
     dy = torch.full((B, n_in), float("nan"), dtype=torch.float16, device="cuda")
@@ -32,15 +32,14 @@ def run_gpu(y, W1, W2, W3, dout, workspace=None):
     dW2 = torch.zeros((64, 64), device="cuda")
     dW3 = torch.zeros((n_out, 64), device="cuda")
     mlp_bwd(dev(y, np.float16), dev(W1, np.float16), dev(W2, np.float16), dev(W3, np.float16), dev(dout, np.float32),
-            dy, dW1, dW2, dW3, workspace=workspace)
+            dy, dW1, dW2, dW3)
     torch.cuda.synchronize()
     return [t.cpu().numpy().astype(np.float64) for t in (dy, dW1, dW2, dW3)]
 
 
-@pytest.mark.parametrize("workspace", [None, False], ids=["scratch", "atomics"])
 @pytest.mark.parametrize("n_in,n_out,B", [(32, 1, 64), (32, 3, 1000), (8, 8, 33), (64, 32, 257), (40, 9, 4097), (16, 2, 31),
                                           (32, 17, 40000), (24, 1, 70001)])
-def test_equal_to_the_oracle_where_nothing_rounds(n_in, n_out, B, workspace):
+def test_equal_to_the_oracle_where_nothing_rounds(n_in, n_out, B):
     # sparse small-integer weights, inputs and upstream gradients in multiples of 1/8 and 1/4: a permuted
     # operand, a transposed weight or a wrong ReLU mask changes the integers
     rng = np.random.default_rng(n_in * 100 + n_out)
@@ -51,7 +50,7 @@ def test_equal_to_the_oracle_where_nothing_rounds(n_in, n_out, B, workspace):
     dout = rng.integers(-4, 5, (B, n_out)) / 4.0
     ref = mlp.mlp_bwd(y, W1, W2, W3, dout)
     assert all(np.abs(r).max() > 0 for r in ref)
-    got = run_gpu(y, W1, W2, W3, dout, workspace)
+    got = run_gpu(y, W1, W2, W3, dout)
     # fp32 sums of dyadic numbers of this size are exact; gradients are multiples of 1/4: exact in fp16 below 512
     assert np.abs(ref[0]).max() < 512
     for g, r in zip(got, ref):
@@ -61,7 +60,7 @@ def test_equal_to_the_oracle_where_nothing_rounds(n_in, n_out, B, workspace):
     dy = torch.zeros((B, n_in), dtype=torch.float16, device="cuda")
     dWs = [dev(a, np.float32) for a in got[1:]]
     mlp_bwd(dev(y, np.float16), dev(W1, np.float16), dev(W2, np.float16), dev(W3, np.float16), dev(dout, np.float32),
-            dy, *dWs, workspace=workspace)
+            dy, *dWs)
     Bt.synchronize()
     np.testing.assert_array_equal(dy.cpu().numpy().astype(np.float64), ref[0])
     for t, r in zip(dWs, ref[1:]):
@@ -146,13 +145,3 @@ def test_argument_checks():
     assert lib.hashgrid_mlp_bwd(8, 32, 33, p, p, p, p, p, p, p, p, p, None) == 2
     assert lib.hashgrid_mlp_bwd(8, 32, 0, p, p, p, p, p, p, p, p, p, None) == 1
     assert lib.hashgrid_mlp_bwd(8, 32, 1, p + 8, p, p, p, p, p, p, p, p, None) == 1  # y not 16-byte aligned
-    # the call with a scratch buffer: its size is a function of the shape; NULL and short buffers are refused
-    need = lib.hashgrid_mlp_bwd_workspace_bytes(32, 1)
-    assert need > 0 and need % 16 == 0
-    assert lib.hashgrid_mlp_bwd_workspace_bytes(64, 32) > need
-    assert lib.hashgrid_mlp_bwd_workspace_bytes(12, 1) == 0 and lib.hashgrid_mlp_bwd_workspace_bytes(32, 33) == 0
-    assert lib.hashgrid_mlp_bwd_ws(0, 32, 1, None, None, None, None, None, None, None, None, None, None, 0, None) == 0
-    assert lib.hashgrid_mlp_bwd_ws(8, 32, 1, p, p, p, p, p, p, p, p, p, None, 0, None) == 1
-    assert lib.hashgrid_mlp_bwd_ws(8, 32, 1, p, p, p, p, p, p, p, p, p, p, 1024, None) == 1   # too small
-    assert lib.hashgrid_mlp_bwd_ws(8, 32, 1, p, p, p, p, p, p, p, p, p, p + 8, need, None) == 1  # misaligned
-    assert lib.hashgrid_mlp_bwd_ws(8, 72, 1, p, p, p, p, p, p, p, p, p, p, need, None) == 2
