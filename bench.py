@@ -291,9 +291,23 @@ def headline_extras(c, ms_fwd, ms_bwd, n, steps, torch):
     if w.param_dtype == "f16" and n_in % 8 == 0 and n_in <= 64 and w.d >= 2:
         import numpy as np
         rng = np.random.default_rng(0)
-        W1 = torch.from_numpy((rng.standard_normal((64, n_in)) * np.sqrt(2.0 / n_in)).astype(np.float16)).cuda()
-        W2 = torch.from_numpy((rng.standard_normal((64, 64)) * np.sqrt(2.0 / 64)).astype(np.float16)).cuda()
-        W3 = torch.from_numpy((rng.standard_normal((1, 64)) / 8.0).astype(np.float16)).cuda()
+        # the network's weights in one array (W1 | W2 | W3), so that one optimiser call serves them: fp32
+        # master, fp16 working copy, fp32 gradient, the matrices as views
+        shapes = [(64, n_in), (64, 64), (1, 64)]
+        init = [rng.standard_normal((64, n_in)) * np.sqrt(2.0 / n_in), rng.standard_normal((64, 64)) * np.sqrt(2.0 / 64),
+                rng.standard_normal((1, 64)) / 8.0]
+        net_master = torch.from_numpy(np.concatenate([a.ravel() for a in init]).astype(np.float32)).cuda()
+        net_half, net_grad = net_master.half(), torch.zeros_like(net_master)
+        net_m1, net_m2 = torch.zeros_like(net_master), torch.zeros_like(net_master)
+
+        def views(flat):
+            out, at = [], 0
+            for r, c_ in shapes:
+                out.append(flat[at:at + r * c_].view(r, c_))
+                at += r * c_
+            return out
+
+        W1, W2, W3 = views(net_half)
         o = torch.empty((w.B, 1), dtype=torch.float32, device="cuda")
         grid.encode_mlp_fwd(xd, td, W1, W2, W3, o)
         ms_mlp = time_launches(lambda: grid.encode_mlp_fwd(xd, td, W1, W2, W3, o), max(n // 2, 10), torch)
@@ -306,21 +320,26 @@ def headline_extras(c, ms_fwd, ms_bwd, n, steps, torch):
         from paper_2201_05989_amd import mlp_bwd
         yk = torch.empty((w.B, n_in), dtype=torch.float16, device="cuda")
         dyk = torch.empty_like(yk)
-        dWs = [torch.zeros((64, n_in), device="cuda"), torch.zeros((64, 64), device="cuda"), torch.zeros((1, 64), device="cuda")]
+        dWs = views(net_grad)
         grid.encode_mlp_fwd(xd, td, W1, W2, W3, o, y=yk)
         ms_net_bwd = time_launches(lambda: mlp_bwd(yk, W1, W2, W3, o, dyk, *dWs), max(n // 2, 10), torch)
+
+        net_counter = [0]
 
         def model_step():
             grid.encode_mlp_fwd(xd, td, W1, W2, W3, o, y=yk)
             mlp_bwd(yk, W1, W2, W3, o, dyk, *dWs)
             grid.encode_bwd(xd, dyk, grad, overwrite=True)
             adam(zero_grad=False)
+            net_counter[0] += 1  # the network's weights: a small learning rate, the gradient cleared for the next step
+            adam_step(net_master, net_grad, net_m1, net_m2, net_counter[0], lr=1e-4, params_half=net_half, zero_grad=True)
 
         ms_model = time_launches(model_step, max(n // 2, 10), torch)
         extras["network_training"] = {
             "ms_mlp_bwd": ms_net_bwd, "mlp_bwd_tflop_s": 4.0 * flops / (ms_net_bwd * 1e-3) / 1e12,
             "ms_step": ms_model, "mpoints_s": w.B / (ms_model * 1e-3) / 1e6,
-            "step": "encode_mlp_fwd_train + mlp_bwd + encode_bwd_ws (overwrite) + adam_step on the tables"}
+            "step": "encode_mlp_fwd_train + mlp_bwd + encode_bwd_ws (overwrite) + adam_step on the tables + adam_step on "
+                    "the network's weights"}
     return extras
 
 
