@@ -67,6 +67,36 @@ def test_equal_to_the_oracle_where_nothing_rounds(n_in, n_out, B):
         np.testing.assert_array_equal(t.cpu().numpy().astype(np.float64), 2 * r)
 
 
+def test_every_served_shape_and_weights_at_any_alignment():
+    # every n_in (multiples of 8 up to 64) with a spread of n_out, exact as above; the weight matrices start
+    # 2 bytes into their allocations (the staging then reads them half by half instead of in 8-byte pieces)
+    rng = np.random.default_rng(5)
+    for n_in in range(8, 65, 8):
+        for n_out in (1, 7, 8, 9, 16, 25, 32):
+            B = int(rng.integers(1, 400))
+            W1 = rng.integers(-1, 2, (64, n_in)) * (rng.random((64, n_in)) < 0.2)
+            W2 = rng.integers(-1, 2, (64, 64)) * (rng.random((64, 64)) < 0.1)
+            W3 = rng.integers(-2, 3, (n_out, 64))
+            y = rng.integers(-8, 9, (B, n_in)) / 8.0
+            dout = rng.integers(-4, 5, (B, n_out)) / 4.0
+            ref = mlp.mlp_bwd(y, W1, W2, W3, dout)
+
+            def shifted(a):
+                buf = torch.zeros(a.size + 1, dtype=torch.float16, device="cuda")
+                buf[1:] = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float16).ravel()).cuda()
+                return buf[1:].view(*a.shape)
+
+            dy = torch.full((B, n_in), float("nan"), dtype=torch.float16, device="cuda")
+            dWs = [torch.zeros((64, n_in), device="cuda"), torch.zeros((64, 64), device="cuda"),
+                   torch.zeros((n_out, 64), device="cuda")]
+            Ws = [shifted(W1), shifted(W2), shifted(W3)]
+            assert all(w_.data_ptr() % 4 == 2 for w_ in Ws)
+            mlp_bwd(dev(y, np.float16), *Ws, dev(dout, np.float32), dy, *dWs)
+            torch.cuda.synchronize()
+            for g, r in zip([dy] + dWs, ref):
+                np.testing.assert_array_equal(g.cpu().numpy().astype(np.float64), r, err_msg=f"n_in={n_in} n_out={n_out} B={B}")
+
+
 @pytest.mark.parametrize("n_in,n_out,B", [(32, 1, 20000), (32, 4, 5000), (64, 16, 3000), (24, 3, 777)])
 def test_random_networks_within_the_rounding_bound(n_in, n_out, B):
     rng = np.random.default_rng(7 * n_in + n_out)
