@@ -150,6 +150,7 @@ class Case:
         s_theta = 2 if w.param_dtype == "f16" else 4
         s_io = 2 if w.io_dtype == "f16" else 4
         self.b_fwd, self.b_bwd = algorithmic_bytes(w, s_theta, s_io)
+        self.counting = True
 
     def fwd(self):  # forward alone
         self.grid.encode_fwd(self.xd, self.td, self.y)
@@ -160,15 +161,42 @@ class Case:
     def fwd_counting(self):
         self.grid.encode_fwd(self.xd, self.td, self.y, count_for_bwd=True)
 
+    def step_fwd(self):  # the forward call of the step: counts for the backward pass where that is the faster pair
+        if self.counting:
+            self.fwd_counting()
+        else:
+            self.fwd()
+
     def step(self):
-        self.fwd_counting()
+        self.step_fwd()
         self.bwd()
+
+    def choose_step(self, n=10):
+        """The forward can count for the sorted backward pass on the side or leave the counting to it.  Which pair
+        of calls is faster depends on the order of the points (samples along rays share voxels between
+        neighbouring lanes: there the separate count pass wins), so both are timed once, as a caller would."""
+        torch, times = self.torch, {}
+        for counting in (True, False):
+            self.counting = counting
+            for _ in range(3):
+                self.step()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(n):
+                self.step()
+            torch.cuda.synchronize()
+            times[counting] = (time.perf_counter() - t0) / n
+        self.counting = times[True] <= times[False]
+        return self.counting
 
     def measure(self, steps, warmup, init=INIT_STEPS):
         """Wall-clock time of `steps` steps after `init` + `warmup` untimed ones, then the two passes as the
         step runs them, each bracketed by HIP events on the launch stream."""
         torch = self.torch
-        for _ in range(init + warmup):
+        for _ in range(init):
+            self.step()
+        self.choose_step()
+        for _ in range(warmup):
             self.step()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -180,7 +208,7 @@ class Case:
         marks = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n)]
         for ea, eb, ec in marks:
             ea.record()
-            self.fwd_counting()
+            self.step_fwd()
             eb.record()
             self.bwd()
             ec.record()
@@ -216,7 +244,7 @@ def headline_extras(c, ms_fwd, ms_bwd, n, steps, torch):
     # the same step when the backward pass replaces the gradient instead of adding to it
     # (HG_BWD_OVERWRITE: no clearing pass before it, no reading of the old values in it)
     def step_overwrite():
-        c.fwd_counting()
+        c.step_fwd()
         grid.encode_bwd(xd, gd, grad, overwrite=True)
 
     ms_bwd_ow = time_launches(lambda: grid.encode_bwd(xd, gd, grad, overwrite=True), n, torch)
@@ -393,7 +421,7 @@ def main():
     # unless the whole call takes twice as long.
     fwd_dominant = not sorted_path or ms_fwd >= 0.5 * ms_bwd
     dom = "fwd" if fwd_dominant else "bwd"
-    kernels = {"fwd": "fwd_point_major (counting variant)" if sorted_path else "fwd_point_major",
+    kernels = {"fwd": "fwd_point_major (counting variant)" if sorted_path and c.counting else "fwd_point_major",
                "bwd": "bin_scan+bin_scatter+bin_accumulate (one hashgrid_encode_bwd_ws call)" if sorted_path
                else "bwd_general"}
     traffic = {p: profile_figure(f"traffic_{w.name}.txt", f"{p}_hbm_bytes_per_launch") for p in ("fwd", "bwd")}
@@ -410,7 +438,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": c.describe(), "param_dtype": w.param_dtype, "io_dtype": w.io_dtype, "grad_dtype": "f32",
-                   "untimed_steps_before_warmup": INIT_STEPS},
+                   "untimed_steps_before_warmup": INIT_STEPS, "forward_counts_for_backward": bool(c.counting)},
         "fwd_mpoints_s": w.B / (ms_fwd * 1e-3) / 1e6,
         "bwd_mpoints_s": w.B / (ms_bwd * 1e-3) / 1e6,
         "ms_fwd": ms_fwd, "ms_bwd": ms_bwd,

@@ -304,14 +304,14 @@ __global__ __launch_bounds__(kBinThreads) void bin_count(const LevelTable lv, co
         corner_rows_of<D, true>(lv, bp, l, smooth, xp, cr);
 #pragma unroll
         for (uint32_t m = 0; m < (1u << D); ++m)
-          __hip_atomic_fetch_add(&hist[cr.bin[m] - gb_a], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+          count_one(hist, cr.bin[m] - gb_a);
       } else {
         Rows<D> rw;
         rows_of<D, true>(lv, bp, l, smooth, xp, rw);
         if (rw.cross) continue;
 #pragma unroll
         for (uint32_t r = 0; r < (1u << (D - 1)); ++r)
-          __hip_atomic_fetch_add(&hist[rw.bin[r] - gb_a], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+          count_one(hist, rw.bin[r] - gb_a);
       }
     }
   }

@@ -200,4 +200,26 @@ __device__ __forceinline__ uint32_t wave_add_one(uint32_t* counters, const uint3
   return slot;
 }
 
+// counters[bin] += 1 from every calling lane (LDS counters), for the histograms of the count pass.
+// Points that follow each other in the batch often share a voxel and with it a bin (samples along
+// a ray), and lanes that add to one address in one instruction are served one after the other.  So
+// where many neighbouring lanes (within a row of 16) name the same bin, only the first lane of a run
+// adds, the length of its run; a wave in which few do takes the plain atomic.
+constexpr int kRunsFrom = 16;  // lanes of a wave that repeat their neighbour's bin from which the runs are folded
+__device__ __forceinline__ void count_one(uint32_t* counters, const uint32_t bin) {
+  const uint32_t prev = (uint32_t)__builtin_amdgcn_update_dpp((int)0xffffffffu, (int)bin, 0x111 /* row_shr:1 */, 0xf, 0xf, false);
+  const bool same = prev == bin;
+  const uint64_t runs = __ballot(same);
+  if (__popcll(runs) < kRunsFrom) {  // uniform over the calling lanes
+    __hip_atomic_fetch_add(&counters[bin], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    return;
+  }
+  if (!same) {
+    const uint32_t lane = __lane_id();
+    const uint64_t above = lane == 63u ? 0ull : runs >> (lane + 1u);
+    __hip_atomic_fetch_add(&counters[bin], 1u + (uint32_t)__builtin_ctzll(~above), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_WORKGROUP);
+  }
+}
+
 }  // namespace hg

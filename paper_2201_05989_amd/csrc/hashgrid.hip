@@ -222,12 +222,12 @@ __global__ __launch_bounds__(kPmBlock) void fwd_point_major(const LevelTable lv,
             for (uint32_t r = 0; r < (1u << (D - 1)); ++r) {
               uint32_t row = c0[1] + (r & 1u);
               if (D == 3) row += (c0[D - 1] + (r >> 1)) * verts;
-              __hip_atomic_fetch_add(&h[gb0 + (row >> sh)], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+              count_one(h, gb0 + (row >> sh));
             }
           } else if ((c0[0] & ((1u << cl) - 1u)) != (1u << cl) - 1u) {  // else the pairs straddle two chunks: no record
 #pragma unroll
             for (uint32_t r = 0; r < (1u << (D - 1)); ++r)
-              __hip_atomic_fetch_add(&h[gb0 + (idx[2 * r] >> cl)], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+              count_one(h, gb0 + (idx[2 * r] >> cl));
           }
         }
       }
