@@ -171,7 +171,7 @@ class Case:
         self.step_fwd()
         self.bwd()
 
-    def choose_step(self, n=10):
+    def choose_step(self, n=20):
         """The forward can count for the sorted backward pass on the side or leave the counting to it.  Which pair
         of calls is faster depends on the order of the points (samples along rays share voxels between
         neighbouring lanes: there the separate count pass wins), so both are timed once, as a caller would."""
@@ -186,16 +186,19 @@ class Case:
                 self.step()
             torch.cuda.synchronize()
             times[counting] = (time.perf_counter() - t0) / n
-        self.counting = times[True] <= times[False]
+        self.counting = times[True] <= 1.01 * times[False]  # (a tie keeps the counting forward)
         return self.counting
 
-    def measure(self, steps, warmup, init=INIT_STEPS):
+    def measure(self, steps, warmup, init=INIT_STEPS, forward_counts="auto"):
         """Wall-clock time of `steps` steps after `init` + `warmup` untimed ones, then the two passes as the
         step runs them, each bracketed by HIP events on the launch stream."""
         torch = self.torch
         for _ in range(init):
             self.step()
-        self.choose_step()
+        if forward_counts == "auto":
+            self.choose_step()
+        else:
+            self.counting = forward_counts == "yes"
         for _ in range(warmup):
             self.step()
         torch.cuda.synchronize()
@@ -374,6 +377,9 @@ def headline_extras(c, ms_fwd, ms_bwd, n, steps, torch):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--forward-counts", choices=["auto", "yes", "no"], default="auto",
+                    help="whether the step's forward call counts for the sorted backward pass on the side "
+                         "(auto: both pairs of calls are timed once and the faster one is kept)")
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="sdf3d")
@@ -412,7 +418,7 @@ def main():
 
     w = synth.WORKLOADS[args.workload]
     c = Case(w, torch)
-    ms_step, ms_fwd, ms_bwd = c.measure(args.steps, args.warmup)
+    ms_step, ms_fwd, ms_bwd = c.measure(args.steps, args.warmup, forward_counts=args.forward_counts)
     passes = c.fractions(ms_step, ms_fwd, ms_bwd)
     sorted_path = bool(c.grid.bwd_workspace_bytes(w.B))
 
@@ -482,11 +488,12 @@ def main():
         for name in other_names:
             o = Case(synth.WORKLOADS[name], torch)
             steps = 100 if o.w.B <= (1 << 18) else 20
-            s, f, b = o.measure(steps, 5, init=10)
+            s, f, b = o.measure(steps, 5, init=10, forward_counts=args.forward_counts)
             fr = o.fractions(s, f, b)
             others.append({"name": name, "workload": o.describe(), "B": o.w.B, "steps": steps, "ms_step": s,
                            "mpoints_s": o.w.B / (s * 1e-3) / 1e6, "ms_fwd": f, "ms_bwd": b,
                            "sorted_backward": bool(o.grid.bwd_workspace_bytes(o.w.B)),
+                           "forward_counts_for_backward": bool(o.counting),
                            "frac": fr["step"]["frac"], "fwd_frac": fr["fwd"]["frac"], "bwd_frac": fr["bwd"]["frac"],
                            "algorithmic_bytes_per_point": {"fwd": o.b_fwd, "bwd": o.b_bwd}})
             del o
