@@ -208,14 +208,16 @@ __device__ __forceinline__ uint32_t wave_add_one(uint32_t* counters, const uint3
 constexpr int kRunsFrom = 16;  // lanes of a wave that repeat their neighbour's bin from which the runs are folded
 __device__ __forceinline__ void count_one(uint32_t* counters, const uint32_t bin) {
   const uint32_t prev = (uint32_t)__builtin_amdgcn_update_dpp((int)0xffffffffu, (int)bin, 0x111 /* row_shr:1 */, 0xf, 0xf, false);
-  const bool same = prev == bin;
-  const uint64_t runs = __ballot(same);
+  // lanes that repeat the bin of their left neighbour in the row of 16, where that neighbour takes part in the
+  // call (the register of a lane that does not may hold anything)
+  const uint64_t calling = __ballot(true);
+  const uint64_t runs = __ballot(prev == bin) & (calling << 1) & 0xfffefffefffefffeull;
   if (__popcll(runs) < kRunsFrom) {  // uniform over the calling lanes
     __hip_atomic_fetch_add(&counters[bin], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     return;
   }
-  if (!same) {
-    const uint32_t lane = __lane_id();
+  const uint32_t lane = __lane_id();
+  if (!((runs >> lane) & 1ull)) {  // the first lane of a run adds the run's length
     const uint64_t above = lane == 63u ? 0ull : runs >> (lane + 1u);
     __hip_atomic_fetch_add(&counters[bin], 1u + (uint32_t)__builtin_ctzll(~above), __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_WORKGROUP);

@@ -176,6 +176,20 @@ def test_nerf3d_full_size():
     workload_case("nerf3d", table_scale=1.0, do_indices=False)
 
 
+@pytest.mark.parametrize("B", [70001, 33, 4100])
+def test_samples_in_ray_order_with_a_ragged_end(B):
+    # neighbouring points share voxels and bins: the count pass folds runs of neighbouring lanes into one add and
+    # the scatter pass spreads a tile's records for a bin; the batch ends inside a wave (and inside a row of 16
+    # lanes), so the last wave folds runs with some of its lanes outside the batch
+    w = synth.WORKLOADS["nerf3d"]
+    lv = orc.levels(orc.OracleConfig(w.d, w.L, w.F, w.T, w.N_min, w.N_max))
+    rng = np.random.default_rng(B)
+    x = synth.points_rays(rng, B, 3)
+    theta = synth.make_tables(rng, lv.total, w.F, "f16", 1.0)
+    dy = synth.make_dy(rng, B, w.L * w.F, "f16")
+    run_case(w.d, w.L, w.F, w.T, w.N_min, w.N_max, "f16", "f16", 0, x, theta, dy, do_indices=False)
+
+
 def test_image2d_full_size():
     workload_case("image2d", table_scale=1.0, do_indices=False)
 
