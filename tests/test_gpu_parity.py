@@ -190,6 +190,51 @@ def test_samples_in_ray_order_with_a_ragged_end(B):
     run_case(w.d, w.L, w.F, w.T, w.N_min, w.N_max, "f16", "f16", 0, x, theta, dy, do_indices=False)
 
 
+def test_random_configurations_and_point_orders():
+    # a seeded sweep over shapes, types, interpolation and the order of the points: uniform, samples along rays,
+    # few distinct points in sorted order (long runs of equal bins and addresses), coordinates at 0, next to 1 and on
+    # vertices, points along one row of voxels; every path of run_case on each
+    for case in range(250):
+        rng = np.random.default_rng(900000 + case)
+        d = int(rng.choice([1, 2, 3], p=[0.15, 0.35, 0.5]))
+        F = int(rng.choice([1, 2, 4, 8]))
+        L = int(rng.choice([1, 2, 4, 7, 16]))
+        T = int(rng.choice([1 << 10, 1 << 12, 3000, 1 << 14, 1 << 16, 100003, 1 << 19]))
+        N_min = int(rng.choice([2, 4, 16]))
+        N_max = N_min if L == 1 else int(N_min * rng.choice([1, 2, 8, 32, 128]))
+        interp = int(rng.integers(0, 2))
+        pdt, iot = str(rng.choice(["f16", "f32"])), str(rng.choice(["f16", "f32"]))
+        B = int(rng.choice([1, 17, 63, 64, 65, 511, 513, 1000, 4097, 20011]))
+        lv = orc.levels(orc.OracleConfig(d, L, F, T, N_min, N_max, interp))
+        kind = str(rng.choice(["uniform", "rays", "dups", "edges", "line"]))
+        if kind == "rays" and d == 3:
+            x = synth.points_rays(rng, B, 3, samples_per_ray=int(rng.choice([16, 256, 2048])))
+        elif kind == "dups":
+            base = synth.points_uniform(rng, max(1, B // 50), d)
+            x = np.sort(base[rng.integers(0, len(base), B)], axis=0)
+        elif kind == "edges":
+            x = synth.points_uniform(rng, B, d)
+            m = rng.random((B, d))
+            x[m < 0.2] = 0.0
+            x[m > 0.8] = np.nextafter(np.float32(1.0), np.float32(0.0))
+            x[(m > 0.4) & (m < 0.5)] = 0.5
+        elif kind == "line":
+            x = np.full((B, d), 0.3, dtype=np.float32)
+            x[:, 0] = np.sort(rng.random(B).astype(np.float32)) * np.float32(0.999)
+        else:
+            x = synth.points_uniform(rng, B, d)
+        x = np.ascontiguousarray(x, dtype=np.float32)
+        theta = synth.make_tables(rng, lv.total, F, pdt, 1.0)
+        dy = synth.make_dy(rng, B, L * F, iot)
+        if rng.random() < 0.3:
+            dy[rng.random(dy.shape) < 0.5] = 0
+        try:
+            run_case(d, L, F, T, N_min, N_max, pdt, iot, interp, x, theta, dy, do_indices=False, do_dx=bool(rng.random() < 0.3))
+        except AssertionError as e:
+            raise AssertionError(f"case {case}: d={d} L={L} F={F} T={T} N={N_min}..{N_max} interp={interp} {pdt}/{iot} "
+                                 f"B={B} {kind}: {e}") from e
+
+
 def test_image2d_full_size():
     workload_case("image2d", table_scale=1.0, do_indices=False)
 
