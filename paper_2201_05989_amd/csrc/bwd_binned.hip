@@ -72,8 +72,9 @@ constexpr uint32_t kCountParts = 2;              // ... of the count grid (its w
 // workgroup keeps one LDS word per bin of its part, a scatter workgroup three, next to its staging area.
 constexpr uint32_t kMaxCountPartBins = 4096, kMaxScatterPartBins = 4096;
 // Beyond this many chunks in all, a tile is kBigTileMult * 512 points and the scatter pass does not
-// stage (bin_scatter_direct, one LDS word per bin of its part).
-constexpr uint32_t kMaxStagedBins = 16384, kBigTileMult = 8, kMaxDirectPartBins = 8192;
+// stage (bin_scatter_direct, one LDS word per bin of its part).  One level of 4096 chunks per part: the grid runs
+// part after part, so the records in flight then belong to two levels (200 MB at T = 2^24), not four (-3%).
+constexpr uint32_t kMaxStagedBins = 16384, kBigTileMult = 8, kMaxDirectPartBins = 4096;
 // A level may have this many chunks (one level is the smallest part): T up to 2^24 at 4096 entries per chunk.
 constexpr uint32_t kMaxLevelBins = 4096;
 
