@@ -84,7 +84,7 @@ struct Workspace {
   uint32_t* counts;     // [n_tiles + 1][n_bins] counts, then exclusive prefix over tiles (last row: totals)
   uint32_t* bin_start;  // [n_bins] first record of the bin
   uint32_t* bin_total;  // [n_bins] records in the bin
-  float* tile_max;      // [n_tiles * scatter_parts] largest |dL/dy| seen by each scatter workgroup
+  float* tile_max;      // [n_tiles * parts of the scatter grid (at most L)] largest |dL/dy| seen by each scatter workgroup
   uint32_t* item_counter;  // [1] next work item of the accumulate pass
   uint32_t* records;    // [B * L * rec_per_point] records (Record::kWords words each)
   uint32_t n_tiles;
@@ -108,7 +108,7 @@ static uint64_t carve(const hashgrid* h, uint32_t B, uint8_t* base, Workspace* w
     return o;
   };
   const uint64_t o_counts = take((uint64_t)(nt + 1) * nb * 4), o_start = take((uint64_t)nb * 4),
-                 o_total = take((uint64_t)nb * 4), o_max = take((uint64_t)nt * h->bp.scatter_parts * 4), o_item = take(4),
+                 o_total = take((uint64_t)nb * 4), o_max = take((uint64_t)nt * h->lv.L * 4), o_item = take(4),
                  o_rec = take((uint64_t)B * h->lv.L * h->bp.rec_per_point *
                               (8 + (h->cfg.F * (h->cfg.io_dtype == HG_F16 ? 2u : 4u) + 3u) / 4u * 4u));
   if (ws) {
@@ -1034,10 +1034,27 @@ __global__ __launch_bounds__(kAccThreads) void bin_accumulate(const LevelTable l
   }
 }
 
+// Level parts of a count or scatter grid for a batch of n_tiles tiles: the plan's, doubled (up to one level per
+// part) while the grid would leave most compute units without a workgroup.  A small batch is a few tiles, and a
+// workgroup walks the levels of its part one after the other: 2^14 points at Table 1's sizes are 32 tiles, whose
+// 128 scatter workgroups took 19 us for four levels each.
+static uint32_t parts_for_batch(uint32_t plan_parts, uint32_t L, uint32_t n_tiles) {
+  static const uint32_t cus = [] {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+      n = 256;
+    return (uint32_t)n;
+  }();
+  uint32_t parts = plan_parts;
+  while (parts < L && (uint64_t)n_tiles * parts < 2ull * cus) parts = parts * 2 < L ? parts * 2 : L;
+  return parts;
+}
+
 // The count pass by itself: counts[tile][bin] for the B points (x only).
 static hg_status launch_count(const hashgrid* h, uint32_t B, const float* x, const Workspace& ws, hipStream_t s) {
   const BinPlan& bp = h->bp;
-  const uint32_t L = h->lv.L, cparts = bp.count_parts;
+  const uint32_t L = h->lv.L, cparts = parts_for_batch(bp.count_parts, L, ws.n_tiles);
   uint32_t max_bins = 0;
   for (uint32_t p = 0; p < cparts; ++p) {
     const uint32_t nbp = bp.bin_base[(p + 1) * L / cparts] - bp.bin_base[p * L / cparts];
@@ -1071,7 +1088,7 @@ static hg_status launch_binned(const hashgrid* h, uint32_t B, const float* x, co
   plan_slices(bp, h->lv, B);
   const bool smooth = h->cfg.interp == HG_INTERP_SMOOTHSTEP;
   const uint32_t n_records = B * h->lv.L * bp.rec_per_point;
-  const uint32_t L = h->lv.L, parts = bp.scatter_parts;
+  const uint32_t L = h->lv.L, parts = parts_for_batch(bp.scatter_parts, L, ws.n_tiles);
   auto max_part_bins = [&](uint32_t np) {
     uint32_t m = 0;
     for (uint32_t p = 0; p < np; ++p) {
@@ -1215,8 +1232,8 @@ uint64_t hashgrid_bwd_workspace_bytes(const hashgrid_t* hg, uint32_t B) {
 
 int hashgrid_bwd_ws_pays(const hashgrid_t* hg, uint32_t B) {
   if (hashgrid_bwd_workspace_bytes(hg, B) == 0) return 0;
-  // Both passes in microseconds, from measurements on an MI355X.  Sorted pass: about 20 us of
-  // launches, 0.027 us per chunk (every chunk of the gradient is visited and rewritten), then the
+  // Both passes in microseconds, from measurements on an MI355X.  Sorted pass: about 16 us of
+  // launches, 0.017 us per chunk (every chunk of the gradient is visited and rewritten), then the
   // records, written once and read once: ~300 K records of 12 bytes per us, in proportion for
   // larger ones (wider entries, fp32 dL/dy) and twice as many where every corner has its own.
   // Atomic pass: ~6 us, then ~14.5 K pairs of corners per us (11 K at F = 4, 9 K at F = 8: their
@@ -1233,7 +1250,7 @@ int hashgrid_bwd_ws_pays(const hashgrid_t* hg, uint32_t B) {
     per_block = fmax(per_block, (double)B * (1u << (d - 1)) / blocks);
   }
   const double pairs_per_us = F <= 2 ? 14.5e3 : F == 4 ? 11e3 : 9e3;
-  const double sorted_us = 20.0 + 0.027 * hg->bp.bin_base[hg->lv.L] + records * (rec_bytes / 12.0) / 300e3;
+  const double sorted_us = 16.0 + 0.017 * hg->bp.bin_base[hg->lv.L] + records * (rec_bytes / 12.0) / 300e3;
   const double atomic_us = 6.0 + fmax(pairs / pairs_per_us, 0.02 * per_block);
   return atomic_us > sorted_us ? 1 : 0;
 }
