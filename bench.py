@@ -311,6 +311,15 @@ def headline_extras(c, ms_fwd, ms_bwd, n, steps, torch):
         half_grads["ms_bwd_sorted"] = time_launches(lambda: g16.encode_bwd(xd, gd, grad16, use_workspace=True), n, torch)
         half_grads["ms_bwd_sorted_overwrite"] = time_launches(
             lambda: g16.encode_bwd(xd, gd, grad16, use_workspace=True, overwrite=True), n, torch)
+        # the table-training step the way the paper runs it: half-precision gradients (here summed exactly and
+        # rounded once), full-precision master copy; the backward pass replaces the gradient
+        def train_f16():
+            g16.encode_fwd(xd, td, c.y, count_for_bwd=c.counting)
+            g16.encode_bwd(xd, gd, grad16, use_workspace=True, overwrite=True)
+            counter[0] += 1
+            adam_step(master, grad16, m1, m2, counter[0], lr=1e-2, params_half=half, zero_grad=False)
+
+        half_grads["train_step_ms"] = time_launches(train_f16, max(n // 2, 10), torch)
     grad16.zero_()
     half_grads["ms_bwd_atomic"] = time_launches(lambda: g16.encode_bwd(xd, gd, grad16, use_workspace=False), 10, torch)
     extras["grad_f16"] = half_grads

@@ -30,7 +30,7 @@
  *     must start on a 4-byte boundary and its allocation must extend to one (packed two-half
  *     atomics).  fp16 sums lose precision with every rounded addition; the sorted pass
  *     (hashgrid_encode_bwd_ws) sums exactly and rounds once per call where one workgroup owns the
- *     chunk.  hashgrid_adam_step takes fp32 gradients only.
+ *     chunk.  hashgrid_adam_step takes fp32 gradients, hashgrid_adam_step_half_grad fp16 ones.
  *   - Alignment: x 4 bytes; tables, y, dL/dy and gradients one entry (F scalars of their type) or
  *     16 bytes, whichever is smaller; anything less is HG_ERR_INVALID_ARG.  The fastest kernels
  *     want 16 bytes and rows of y that are a multiple of 16 bytes; other cases take a slower path.
@@ -246,6 +246,19 @@ typedef struct {
  * misaligned pointers.  n_scalars == 0 is HG_OK. */
 hg_status hashgrid_adam_step(uint64_t n_scalars, float* params_master, void* params_half, float* grad, float* m,
                              float* v, const hashgrid_adam_config* cfg, uint32_t step, int zero_grad, void* stream);
+
+/* The same step (Section 4, "Training", as above) on a half-precision gradient, as the backward
+ * passes write it with grad_dtype = HG_F16 (Section 4, "Performance considerations": half-precision
+ * tables and gradients, a full-precision master copy for the update).  Every gradient scalar is
+ * converted to fp32 and multiplied by grad_scale before use: 1, or the reciprocal of the factor by
+ * which the caller scaled the loss to keep small half-precision gradients out of the subnormal
+ * range (a power of two keeps the product exact).
+ *   grad_half  [n] fp16  device, 8-byte aligned, read; set to 0 where it was not when zero_grad != 0
+ *   grad_scale           finite and positive, else HG_ERR_INVALID_ARG
+ * Everything else as hashgrid_adam_step. */
+hg_status hashgrid_adam_step_half_grad(uint64_t n_scalars, float* params_master, void* params_half, void* grad_half,
+                                       float* m, float* v, const hashgrid_adam_config* cfg, uint32_t step,
+                                       int zero_grad, float grad_scale, void* stream);
 
 /* The encoding followed by the paper's network (Section 4, "Architecture": two hidden layers of 64
  * neurons, ReLU on the hidden layers, a linear output layer), in one kernel: the encoded features

@@ -31,7 +31,8 @@ EXPORTS = ("hashgrid_create", "hashgrid_destroy", "hashgrid_n_entries", "hashgri
            "hashgrid_encode_fwd", "hashgrid_encode_bwd", "hashgrid_encode_bwd_input",
            "hashgrid_debug_indices", "hashgrid_debug_count_outside", "hashgrid_strerror", "hashgrid_bwd_workspace_bytes",
            "hashgrid_encode_bwd_ws", "hashgrid_encode_fwd_ws", "hashgrid_bwd_ws_pays", "hashgrid_adam_step",
-           "hashgrid_encode_mlp_fwd", "hashgrid_encode_bwd_static", "hashgrid_encode_mlp_fwd_train", "hashgrid_mlp_bwd")
+           "hashgrid_encode_mlp_fwd", "hashgrid_encode_bwd_static", "hashgrid_encode_mlp_fwd_train", "hashgrid_mlp_bwd",
+           "hashgrid_adam_step_half_grad")
 PROBE_EXPORTS = ("hashgrid_probe_copy", "hashgrid_probe_gather", "hashgrid_probe_atomic_add",
                  "hashgrid_probe_gather_lines")
 
@@ -100,6 +101,9 @@ def load_library() -> ctypes.CDLL:
     lib.hashgrid_adam_step.argtypes = [u64, vp, vp, vp, vp, vp, ctypes.POINTER(hashgrid_adam_config), u32, ctypes.c_int,
                                        vp]
     lib.hashgrid_adam_step.restype = ctypes.c_int
+    lib.hashgrid_adam_step_half_grad.argtypes = [u64, vp, vp, vp, vp, vp, ctypes.POINTER(hashgrid_adam_config), u32,
+                                                 ctypes.c_int, ctypes.c_float, vp]
+    lib.hashgrid_adam_step_half_grad.restype = ctypes.c_int
     lib.hashgrid_strerror.argtypes = [ctypes.c_int]
     lib.hashgrid_strerror.restype = ctypes.c_char_p
     _lib = lib
@@ -347,12 +351,18 @@ class HashGrid:
 
 def adam_step(params_master: torch.Tensor, grad: torch.Tensor, m: torch.Tensor, v: torch.Tensor, step: int,
               lr: float = 1e-2, beta1: float = 0.9, beta2: float = 0.99, eps: float = 1e-15,
-              params_half: torch.Tensor | None = None, zero_grad: bool = True, stream=None) -> None:
-    """hashgrid_adam_step on flat or [n, F] fp32 tensors (in place)."""
+              params_half: torch.Tensor | None = None, zero_grad: bool = True, stream=None,
+              grad_scale: float = 1.0) -> None:
+    """hashgrid_adam_step on flat or [n, F] fp32 tensors (in place); with an fp16 gradient (grad_dtype "f16")
+    hashgrid_adam_step_half_grad, which multiplies every gradient scalar by grad_scale as it reads it."""
     n = params_master.numel()
-    for name, t in (("params_master", params_master), ("grad", grad), ("m", m), ("v", v)):
+    for name, t in (("params_master", params_master), ("m", m), ("v", v)):
         if not (t.is_cuda and t.is_contiguous() and t.dtype == torch.float32 and t.numel() == n):
             raise HashGridError(f"{name} must be a contiguous fp32 device tensor of {n} scalars")
+    if not (grad.is_cuda and grad.is_contiguous() and grad.dtype in (torch.float32, torch.float16) and grad.numel() == n):
+        raise HashGridError(f"grad must be a contiguous fp32 or fp16 device tensor of {n} scalars")
+    if grad.dtype == torch.float32 and grad_scale != 1.0:
+        raise HashGridError("grad_scale applies to fp16 gradients only")
     half_ptr = None
     if params_half is not None:
         if not (params_half.is_cuda and params_half.is_contiguous() and params_half.dtype == torch.float16
@@ -360,9 +370,15 @@ def adam_step(params_master: torch.Tensor, grad: torch.Tensor, m: torch.Tensor, 
             raise HashGridError("params_half must be a contiguous fp16 device tensor of the same size")
         half_ptr = params_half.data_ptr()
     cfg = hashgrid_adam_config(lr, beta1, beta2, eps)
-    _check(load_library().hashgrid_adam_step(n, params_master.data_ptr(), half_ptr, grad.data_ptr(), m.data_ptr(),
-                                             v.data_ptr(), ctypes.byref(cfg), step, int(zero_grad),
-                                             _stream_ptr(stream)), "hashgrid_adam_step")
+    lib = load_library()
+    if grad.dtype == torch.float16:
+        _check(lib.hashgrid_adam_step_half_grad(n, params_master.data_ptr(), half_ptr, grad.data_ptr(), m.data_ptr(),
+                                                v.data_ptr(), ctypes.byref(cfg), step, int(zero_grad), grad_scale,
+                                                _stream_ptr(stream)), "hashgrid_adam_step_half_grad")
+    else:
+        _check(lib.hashgrid_adam_step(n, params_master.data_ptr(), half_ptr, grad.data_ptr(), m.data_ptr(),
+                                      v.data_ptr(), ctypes.byref(cfg), step, int(zero_grad), _stream_ptr(stream)),
+               "hashgrid_adam_step")
 
 
 def probe_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:

@@ -73,3 +73,43 @@ def test_adam_argument_checks():
     assert ok(60, ptr + 4, None, ptr, ptr, ptr, ctypes.byref(cfg), 1, 1, None) == 1  # misaligned
     bad = binding.hashgrid_adam_config(1e-2, 1.0, 0.99, 1e-15)
     assert ok(64, ptr, None, ptr, ptr, ptr, ctypes.byref(bad), 1, 1, None) == 1      # beta1 = 1
+
+
+@pytest.mark.parametrize("n,scale", [(5, 1.0), (100003, 1.0 / 128.0), (1 << 18, 1.0 / 1024.0)])
+def test_adam_on_half_precision_gradients(n, scale):
+    # the gradient as the backward passes write it with grad_dtype fp16, scaled by the caller's loss scale: the
+    # step uses float(g16) * scale (exact for a power of two); the oracle gets exactly those values
+    rng = np.random.default_rng(n)
+    theta = rng.uniform(-1e-4, 1e-4, n).astype(np.float32)
+    p = torch.from_numpy(theta.copy()).cuda()
+    ph, m, v = p.half(), torch.zeros(n, device="cuda"), torch.zeros(n, device="cuda")
+    t64, m64, v64 = theta.astype(np.float64), np.zeros(n), np.zeros(n)
+    for step in range(1, 4):
+        g16 = np.clip((rng.standard_normal(n) * 10.0 ** rng.uniform(-3, 2, n)) / scale, -6e4, 6e4).astype(np.float16)
+        g16[rng.random(n) < 0.3] = 0.0
+        g16[~np.isfinite(g16)] = 0.0
+        g = g16.astype(np.float64) * scale
+        gd = torch.from_numpy(g16.copy()).cuda()
+        before = (p.clone(), m.clone(), v.clone(), ph.clone())
+        zero = step != 2
+        adam_step(p, gd, m, v, step, lr=1e-2, params_half=ph, zero_grad=zero, grad_scale=scale)
+        m_scale = 0.9 * np.abs(m64) + 0.1 * np.abs(g)
+        orc.adam_step(t64, g, m64, v64, lr=1e-2, step=step)
+        torch.cuda.synchronize()
+        skipped = torch.from_numpy(g16 == 0).cuda()
+        for now, was in zip((p, m, v, ph), before):
+            assert torch.equal(now[skipped], was[skipped])
+        assert torch.equal(ph[~skipped], p[~skipped].half())
+        assert bool((gd == 0).all()) if zero else torch.equal(gd.cpu(), torch.from_numpy(g16))
+        pm, pv, pp = (a.cpu().numpy().astype(np.float64) for a in (m, v, p))
+        assert (np.abs(pm - m64) <= 2e-6 * m_scale + 1e-37).all()
+        assert (np.abs(pv - v64) <= 2e-6 * np.abs(v64) + 1e-37).all()
+        assert (np.abs(pp - t64) <= 4e-6 * 1e-2 * step + 1e-7 * np.abs(t64)).all()
+        t64, m64, v64 = pp.copy(), pm.copy(), pv.copy()
+    lib = binding.load_library()
+    cfg = binding.hashgrid_adam_config(1e-2, 0.9, 0.99, 1e-15)
+    import ctypes
+    a = p.data_ptr()
+    assert lib.hashgrid_adam_step_half_grad(4, a, None, a, a, a, ctypes.byref(cfg), 1, 1, 0.0, None) == 1    # scale 0
+    assert lib.hashgrid_adam_step_half_grad(4, a, None, a + 2, a, a, ctypes.byref(cfg), 1, 1, 1.0, None) == 1  # misaligned
+    assert lib.hashgrid_adam_step_half_grad(0, None, None, None, None, None, ctypes.byref(cfg), 1, 1, 1.0, None) == 0
