@@ -372,7 +372,8 @@ def headline_extras(c, ms_fwd, ms_bwd, n, steps, torch):
             grid.encode_bwd(xd, dyk, grad, overwrite=True)
             adam(zero_grad=False)
             net_counter[0] += 1  # the network's weights: a small learning rate, the gradient cleared for the next step
-            adam_step(net_master, net_grad, net_m1, net_m2, net_counter[0], lr=1e-4, params_half=net_half, zero_grad=True)
+            adam_step(net_master, net_grad, net_m1, net_m2, net_counter[0], lr=1e-4, params_half=net_half, zero_grad=True,
+                      l2_reg=1e-6)
 
         ms_model = time_launches(model_step, max(n // 2, 10), torch)
         extras["network_training"] = {

@@ -227,14 +227,17 @@ hg_status hashgrid_debug_count_outside(const hashgrid_t* hg, uint32_t B, const f
 
 /* Hyper-parameters of the optimiser step below (paper Section 4, "Training": Adam with
  * beta1 = 0.9, beta2 = 0.99, eps = 1e-15; learning rate 1e-2, 1e-4 for signed distance
- * functions; no weight decay on table entries). */
+ * functions; an L2 regularisation of factor 1e-6 on the network's weights and none on table
+ * entries: l2_reg * value is added to every gradient scalar, 0 switches it off). */
 typedef struct {
   float lr, beta1, beta2, eps;
+  float l2_reg;
 } hashgrid_adam_config;
 
 /* One Adam step (Kingma & Ba, Algorithm 1, with bias correction for the 1-based global
- * `step`) on n_scalars table scalars, following Section 4 of the paper: a scalar whose
- * gradient is exactly 0 is skipped (value and both moments untouched); the full-precision
+ * `step`) on n_scalars table scalars or network weights, following Section 4 of the paper: a
+ * scalar whose gradient (with the regulariser's term, if any) is exactly 0 is skipped (value and
+ * both moments untouched); the full-precision
  * master copy is updated and, when params_half is not NULL, rounded (nearest even) into the
  * half-precision working copy the encoding kernels read.  All arithmetic fp32.
  *   params_master [n] fp32  device, 16-byte aligned, read and written
@@ -242,7 +245,7 @@ typedef struct {
  *   grad          [n] fp32  device, 16-byte aligned, read; set to 0 where it was not when
  *                           zero_grad != 0 (so the next backward pass can accumulate into it)
  *   m, v          [n] fp32  device, 16-byte aligned, first and second moment, read and written
- * Returns HG_ERR_INVALID_ARG for step == 0, betas outside [0,1), negative eps, NULL or
+ * Returns HG_ERR_INVALID_ARG for step == 0, betas outside [0,1), negative eps or l2_reg, NULL or
  * misaligned pointers.  n_scalars == 0 is HG_OK. */
 hg_status hashgrid_adam_step(uint64_t n_scalars, float* params_master, void* params_half, float* grad, float* m,
                              float* v, const hashgrid_adam_config* cfg, uint32_t step, int zero_grad, void* stream);

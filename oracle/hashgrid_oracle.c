@@ -309,9 +309,12 @@ int hgo_indices(const hgo_config* c, uint64_t B, const float* x, uint32_t l, uin
 /* ---------------------------------------------------------------------------
  * Optimiser step on the tables (paper Section 4, "Training"): Adam (Kingma & Ba,
  * Algorithm 1, with bias correction) with beta1, beta2, eps as given by the
- * caller (the paper uses 0.9, 0.99, 1e-15), no weight decay on table entries,
- * and the paper's rule that an entry whose gradient is exactly 0 is skipped: its
- * moments and its value are left untouched.
+ * caller (the paper uses 0.9, 0.99, 1e-15), the paper's L2 regularisation (factor
+ * l2: 1e-6 for the network's weights, 0 for table entries; read as the term
+ * l2 * theta added to the gradient, the gradient of (l2 / 2) |theta|^2), and the
+ * paper's rule that an entry whose gradient is exactly 0 is skipped: its moments
+ * and its value are left untouched (with a regulariser: whose gradient
+ * including that term is 0).
  *
  * Readings where the paper is silent: `step` (1-based) is one global counter
  * used for the bias corrections of every entry, skipped or not; "entry" is taken
@@ -321,12 +324,12 @@ int hgo_indices(const hgo_config* c, uint64_t B, const float* x, uint32_t l, uin
  * from it by rounding, which the caller does).
  */
 int hgo_adam_step(uint64_t n, double* theta, const double* grad, double* m, double* v, double lr, double beta1,
-                  double beta2, double eps, uint32_t step) {
+                  double beta2, double eps, double l2, uint32_t step) {
   if (!theta || !grad || !m || !v || step == 0) return -1;
   const double c1 = 1.0 - pow(beta1, (double)step); /* bias corrections */
   const double c2 = 1.0 - pow(beta2, (double)step);
   for (uint64_t i = 0; i < n; ++i) {
-    const double g = grad[i];
+    const double g = grad[i] + l2 * theta[i];
     if (g == 0.0) continue; /* skipped entry */
     m[i] = beta1 * m[i] + (1.0 - beta1) * g;
     v[i] = beta2 * v[i] + (1.0 - beta2) * g * g;

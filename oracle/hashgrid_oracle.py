@@ -74,7 +74,7 @@ def _load():
         lib.hgo_bwd_input.argtypes = [cfgp, u64, vp, vp, vp, vp]
         lib.hgo_indices.argtypes = [cfgp, u64, vp, u32, vp, vp]
         dbl = ctypes.c_double
-        lib.hgo_adam_step.argtypes = [u64, vp, vp, vp, vp, dbl, dbl, dbl, dbl, u32]
+        lib.hgo_adam_step.argtypes = [u64, vp, vp, vp, vp, dbl, dbl, dbl, dbl, dbl, u32]
         _lib = lib
     return _lib
 
@@ -196,13 +196,14 @@ def indices(cfg: OracleConfig, x, level: int):
     return idx, w
 
 
-def adam_step(theta, grad, m, v, lr, beta1=0.9, beta2=0.99, eps=1e-15, step=1):
-    """One optimiser step on fp64 arrays, in place (theta, m, v); entries with grad == 0 are skipped."""
+def adam_step(theta, grad, m, v, lr, beta1=0.9, beta2=0.99, eps=1e-15, step=1, l2=0.0):
+    """One optimiser step on fp64 arrays, in place (theta, m, v); entries with grad == 0 are skipped; l2: the
+    factor of the L2 regularisation (Section 4, "Training": 1e-6 on the network's weights, none on the tables)."""
     for a in (theta, m, v):
         assert a.dtype == np.float64 and a.flags.c_contiguous
     g = np.ascontiguousarray(grad, dtype=np.float64)
     assert theta.shape == g.shape == m.shape == v.shape
     rc = _load().hgo_adam_step(theta.size, theta.ctypes.data, g.ctypes.data, m.ctypes.data, v.ctypes.data,
-                               float(lr), float(beta1), float(beta2), float(eps), int(step))
+                               float(lr), float(beta1), float(beta2), float(eps), float(l2), int(step))
     if rc != 0:
         raise ValueError("invalid arguments")

@@ -47,7 +47,7 @@ class hashgrid_config(ctypes.Structure):
 
 
 class hashgrid_adam_config(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_float) for n in ("lr", "beta1", "beta2", "eps")]
+    _fields_ = [(n, ctypes.c_float) for n in ("lr", "beta1", "beta2", "eps", "l2_reg")]
 
 
 _lib = None
@@ -352,9 +352,10 @@ class HashGrid:
 def adam_step(params_master: torch.Tensor, grad: torch.Tensor, m: torch.Tensor, v: torch.Tensor, step: int,
               lr: float = 1e-2, beta1: float = 0.9, beta2: float = 0.99, eps: float = 1e-15,
               params_half: torch.Tensor | None = None, zero_grad: bool = True, stream=None,
-              grad_scale: float = 1.0) -> None:
+              grad_scale: float = 1.0, l2_reg: float = 0.0) -> None:
     """hashgrid_adam_step on flat or [n, F] fp32 tensors (in place); with an fp16 gradient (grad_dtype "f16")
-    hashgrid_adam_step_half_grad, which multiplies every gradient scalar by grad_scale as it reads it."""
+    hashgrid_adam_step_half_grad, which multiplies every gradient scalar by grad_scale as it reads it.  l2_reg: the
+    factor of the L2 regularisation (the paper: 1e-6 on the network's weights, 0 on the tables)."""
     n = params_master.numel()
     for name, t in (("params_master", params_master), ("m", m), ("v", v)):
         if not (t.is_cuda and t.is_contiguous() and t.dtype == torch.float32 and t.numel() == n):
@@ -369,7 +370,7 @@ def adam_step(params_master: torch.Tensor, grad: torch.Tensor, m: torch.Tensor, 
                 and params_half.numel() == n):
             raise HashGridError("params_half must be a contiguous fp16 device tensor of the same size")
         half_ptr = params_half.data_ptr()
-    cfg = hashgrid_adam_config(lr, beta1, beta2, eps)
+    cfg = hashgrid_adam_config(lr, beta1, beta2, eps, l2_reg)
     lib = load_library()
     if grad.dtype == torch.float16:
         _check(lib.hashgrid_adam_step_half_grad(n, params_master.data_ptr(), half_ptr, grad.data_ptr(), m.data_ptr(),

@@ -1,6 +1,7 @@
 // Optimiser step on the tables (paper Section 4, "Training"): Adam with the
-// caller's beta1, beta2, eps (the paper: 0.9, 0.99, 1e-15), no weight decay on
-// table entries, entries whose gradient is exactly 0 skipped, full-precision
+// caller's beta1, beta2, eps (the paper: 0.9, 0.99, 1e-15), the L2 regularisation the
+// paper puts on the network's weights and not on table entries (a factor, 0 for the
+// tables), entries whose gradient is exactly 0 skipped, full-precision
 // master copy plus a half-precision working copy (Section 4, "Performance
 // considerations").  A pure streaming kernel: per updated scalar it reads 16
 // bytes (gradient, two moments, master value) and writes 14 to 18 (moments,
@@ -19,7 +20,7 @@ namespace hg {
 constexpr int kAdamThreads = 256;
 
 struct AdamArgs {
-  float lr, beta1, beta2, eps;
+  float lr, beta1, beta2, eps, l2;
   float inv_c1;       // 1 / (1 - beta1^t)
   float inv_sqrt_c2;  // 1 / sqrt(1 - beta2^t)
 };
@@ -54,11 +55,22 @@ __global__ __launch_bounds__(kAdamThreads) void adam_step(const AdamArgs a, cons
                                                           const float grad_scale) {
   const uint64_t n4 = n / 4;
   for (uint64_t q = (uint64_t)blockIdx.x * kAdamThreads + threadIdx.x; q < n4; q += (uint64_t)gridDim.x * kAdamThreads) {
-    const float4 g = load_grad4(grad, q, grad_scale);
-    if (g.x == 0.0f && g.y == 0.0f && g.z == 0.0f && g.w == 0.0f) continue;  // nothing to read further, nothing to write
+    float4 g = load_grad4(grad, q, grad_scale);
+    // (without the regulariser: nothing to read further and nothing to write where the four gradients are zero)
+    if (a.l2 == 0.0f && g.x == 0.0f && g.y == 0.0f && g.z == 0.0f && g.w == 0.0f) continue;
     float4 mm = reinterpret_cast<const float4*>(m)[q];
     float4 vv = reinterpret_cast<const float4*>(v)[q];
     float4 pp = reinterpret_cast<const float4*>(p32)[q];
+    if (a.l2 != 0.0f) {  // uniform: the L2 regularisation's term in the gradient
+      g.x = fmaf(a.l2, pp.x, g.x);
+      g.y = fmaf(a.l2, pp.y, g.y);
+      g.z = fmaf(a.l2, pp.z, g.z);
+      g.w = fmaf(a.l2, pp.w, g.w);
+      if (g.x == 0.0f && g.y == 0.0f && g.z == 0.0f && g.w == 0.0f) {
+        if (ZERO_GRAD) zero_grad4(grad, q);
+        continue;
+      }
+    }
     if (g.x != 0.0f) adam_scalar(a, g.x, mm.x, vv.x, pp.x);
     if (g.y != 0.0f) adam_scalar(a, g.y, mm.y, vv.y, pp.y);
     if (g.z != 0.0f) adam_scalar(a, g.z, mm.z, vv.z, pp.z);
@@ -79,9 +91,11 @@ __global__ __launch_bounds__(kAdamThreads) void adam_step(const AdamArgs a, cons
   // tail of fewer than four scalars
   if (blockIdx.x == 0 && threadIdx.x < n - n4 * 4) {
     const uint64_t i = n4 * 4 + threadIdx.x;
-    const float g = sizeof(GT) == 2 ? (float)grad[i] * grad_scale : (float)grad[i];
+    float g = sizeof(GT) == 2 ? (float)grad[i] * grad_scale : (float)grad[i];
+    float mm = m[i], vv = v[i], pp = p32[i];
+    g = a.l2 != 0.0f ? fmaf(a.l2, pp, g) : g;
+    if (ZERO_GRAD && a.l2 != 0.0f) grad[i] = (GT)0.0f;
     if (g != 0.0f) {
-      float mm = m[i], vv = v[i], pp = p32[i];
       adam_scalar(a, g, mm, vv, pp);
       m[i] = mm;
       v[i] = vv;
@@ -102,7 +116,8 @@ hg_status adam_launch(uint64_t n_scalars, float* params_master, void* params_hal
   if (!cfg || step == 0) return HG_ERR_INVALID_ARG;
   if (n_scalars == 0) return HG_OK;
   if (!params_master || !grad || !m || !v) return HG_ERR_INVALID_ARG;
-  if (!(cfg->beta1 >= 0.0f && cfg->beta1 < 1.0f && cfg->beta2 >= 0.0f && cfg->beta2 < 1.0f && cfg->eps >= 0.0f))
+  if (!(cfg->beta1 >= 0.0f && cfg->beta1 < 1.0f && cfg->beta2 >= 0.0f && cfg->beta2 < 1.0f && cfg->eps >= 0.0f &&
+        cfg->l2_reg >= 0.0f && cfg->l2_reg < INFINITY))
     return HG_ERR_INVALID_ARG;
   if (!(grad_scale > 0.0f && grad_scale < INFINITY)) return HG_ERR_INVALID_ARG;
   const uintptr_t bits = reinterpret_cast<uintptr_t>(params_master) | reinterpret_cast<uintptr_t>(m) |
@@ -115,6 +130,7 @@ hg_status adam_launch(uint64_t n_scalars, float* params_master, void* params_hal
   a.beta1 = cfg->beta1;
   a.beta2 = cfg->beta2;
   a.eps = cfg->eps;
+  a.l2 = cfg->l2_reg;
   a.inv_c1 = (float)(1.0 / (1.0 - pow((double)cfg->beta1, (double)step)));
   a.inv_sqrt_c2 = (float)(1.0 / sqrt(1.0 - pow((double)cfg->beta2, (double)step)));
   const uint64_t groups = (n_scalars / 4 + hg::kAdamThreads - 1) / hg::kAdamThreads;

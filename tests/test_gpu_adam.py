@@ -62,7 +62,7 @@ def test_adam_full_table_size_of_the_headline_configuration():
 
 def test_adam_argument_checks():
     lib = binding.load_library()
-    cfg = binding.hashgrid_adam_config(1e-2, 0.9, 0.99, 1e-15)
+    cfg = binding.hashgrid_adam_config(1e-2, 0.9, 0.99, 1e-15, 0.0)
     import ctypes
     a = torch.zeros(64, device="cuda")
     ptr = a.data_ptr()
@@ -71,7 +71,7 @@ def test_adam_argument_checks():
     assert ok(64, ptr, None, ptr, ptr, ptr, ctypes.byref(cfg), 0, 1, None) == 1      # step 0
     assert ok(64, None, None, ptr, ptr, ptr, ctypes.byref(cfg), 1, 1, None) == 1     # NULL master
     assert ok(60, ptr + 4, None, ptr, ptr, ptr, ctypes.byref(cfg), 1, 1, None) == 1  # misaligned
-    bad = binding.hashgrid_adam_config(1e-2, 1.0, 0.99, 1e-15)
+    bad = binding.hashgrid_adam_config(1e-2, 1.0, 0.99, 1e-15, 0.0)
     assert ok(64, ptr, None, ptr, ptr, ptr, ctypes.byref(bad), 1, 1, None) == 1      # beta1 = 1
 
 
@@ -107,9 +107,50 @@ def test_adam_on_half_precision_gradients(n, scale):
         assert (np.abs(pp - t64) <= 4e-6 * 1e-2 * step + 1e-7 * np.abs(t64)).all()
         t64, m64, v64 = pp.copy(), pm.copy(), pv.copy()
     lib = binding.load_library()
-    cfg = binding.hashgrid_adam_config(1e-2, 0.9, 0.99, 1e-15)
+    cfg = binding.hashgrid_adam_config(1e-2, 0.9, 0.99, 1e-15, 0.0)
     import ctypes
     a = p.data_ptr()
     assert lib.hashgrid_adam_step_half_grad(4, a, None, a, a, a, ctypes.byref(cfg), 1, 1, 0.0, None) == 1    # scale 0
     assert lib.hashgrid_adam_step_half_grad(4, a, None, a + 2, a, a, ctypes.byref(cfg), 1, 1, 1.0, None) == 1  # misaligned
     assert lib.hashgrid_adam_step_half_grad(0, None, None, None, None, None, ctypes.byref(cfg), 1, 1, 1.0, None) == 0
+
+
+@pytest.mark.parametrize("l2", [1e-6, 1e-2])
+def test_adam_with_the_l2_regularisation_of_the_network_weights(l2):
+    # Section 4, "Training": factor 1e-6 on the network's weights; here on 6208 scalars (the 64-64 network with 32
+    # inputs and one output), some gradients exactly zero: those weights still move, by the regulariser alone
+    rng = np.random.default_rng(11)
+    n = 64 * 32 + 64 * 64 + 64
+    theta = (rng.standard_normal(n) * 0.2).astype(np.float32)
+    p = torch.from_numpy(theta.copy()).cuda()
+    ph, m, v = p.half(), torch.zeros(n, device="cuda"), torch.zeros(n, device="cuda")
+    t64, m64, v64 = theta.astype(np.float64), np.zeros(n), np.zeros(n)
+    for step in range(1, 5):
+        g = (rng.standard_normal(n) * 10.0 ** rng.uniform(-6, 0, n)).astype(np.float32)
+        g[rng.random(n) < 0.2] = 0.0
+        gd = torch.from_numpy(g.copy()).cuda()
+        before = p.clone()
+        adam_step(p, gd, m, v, step, lr=1e-3, params_half=ph, l2_reg=l2)
+        # the gradient with the regulariser's term is a sum that may cancel: errors are measured against its summands
+        g_mass = np.abs(g.astype(np.float64)) + l2 * np.abs(t64)
+        m_scale = 0.9 * np.abs(m64) + 0.1 * g_mass
+        v_scale = 0.99 * v64 + 0.01 * g_mass ** 2
+        orc.adam_step(t64, g, m64, v64, lr=1e-3, step=step, l2=l2)
+        torch.cuda.synchronize()
+        assert bool((gd == 0).all()) and torch.equal(ph, p.half())
+        moved = (p != before).cpu().numpy()
+        assert moved[(g == 0) & (np.abs(theta) > 1e-3)].all()   # (theta far from 0: l2 * theta is not lost in eps)
+        pm, pv, pp = (a.cpu().numpy().astype(np.float64) for a in (m, v, p))
+        assert (np.abs(pm - m64) <= 4e-6 * m_scale + 1e-37).all()
+        assert (np.abs(pv - v64) <= 4e-6 * v_scale + 1e-37).all()
+        # the step is lr * m_hat / sqrt(v_hat): where the two terms of the gradient nearly cancel its relative error is
+        # that of the small difference; everywhere it is at most a few lr
+        well = np.abs(g.astype(np.float64) + l2 * t64) > 1e-3 * g_mass
+        assert (np.abs(pp - t64)[well] <= 4e-5 * 1e-3 * step + 1e-7 * np.abs(t64[well])).all()
+        assert (np.abs(pp - t64) <= 1e-2 * 1e-3 * step + 1e-7 * np.abs(t64)).all()
+        t64, m64, v64 = pp.copy(), pm.copy(), pv.copy()
+    lib = binding.load_library()
+    import ctypes
+    bad = binding.hashgrid_adam_config(1e-2, 0.9, 0.99, 1e-15, -1.0)
+    a = p.data_ptr()
+    assert lib.hashgrid_adam_step(4, a, None, a, a, a, ctypes.byref(bad), 1, 1, None) == 1

@@ -120,7 +120,7 @@ def test_null_and_empty_batches_need_no_device():
 
 def test_adam_step_status_codes_need_no_device():
     lib = binding.load_library()
-    cfg = binding.hashgrid_adam_config(1e-2, 0.9, 0.99, 1e-15)
+    cfg = binding.hashgrid_adam_config(1e-2, 0.9, 0.99, 1e-15, 0.0)
     assert lib.hashgrid_adam_step(0, None, None, None, None, None, ctypes.byref(cfg), 1, 1, None) == 0
     assert lib.hashgrid_adam_step(8, None, None, None, None, None, ctypes.byref(cfg), 1, 1, None) == 1
     assert lib.hashgrid_adam_step(8, 4096, None, 4096, 4096, 4096, ctypes.byref(cfg), 0, 1, None) == 1

@@ -72,3 +72,32 @@ def test_rejects_step_zero():
         assert False
     except ValueError:
         pass
+
+
+def test_l2_regularisation_is_the_library_weight_decay_and_a_closed_form():
+    # Section 4, "Training": L2 regularisation (factor 1e-6) on the network's weights.  As a term l2 * theta in
+    # the gradient it is what torch.optim.Adam calls weight_decay (fp64 on the CPU as a third opinion) ...
+    rng = np.random.default_rng(4)
+    n = 3000
+    theta0 = rng.standard_normal(n) * 0.3
+    for l2 in (1e-6, 0.05):
+        theta, m, v = theta0.copy(), np.zeros(n), np.zeros(n)
+        p = torch.tensor(theta0, dtype=torch.float64, requires_grad=True)
+        opt = torch.optim.Adam([p], lr=1e-2, betas=(B1, B2), eps=EPS, weight_decay=l2)
+        for t in range(1, 16):
+            g = rng.standard_normal(n) * 10.0 ** rng.uniform(-6, 0, n)
+            orc.adam_step(theta, g, m, v, lr=1e-2, step=t, l2=l2)
+            p.grad = torch.tensor(g, dtype=torch.float64)
+            opt.step()
+        np.testing.assert_allclose(theta, p.detach().numpy(), rtol=1e-10, atol=1e-14)
+    # ... and with no data gradient the first step moves every weight by lr towards zero (g' = l2 * theta, so the
+    # update is lr * sign(theta) as long as |l2 * theta| >> eps), while l2 = 0 leaves it where it is
+    theta = np.array([2.0, -0.5, 1e-3])
+    m, v = np.zeros(3), np.zeros(3)
+    orc.adam_step(theta, np.zeros(3), m, v, lr=1e-2, step=1, l2=1e-6)
+    np.testing.assert_allclose(theta, np.array([2.0, -0.5, 1e-3]) - 1e-2 * np.sign([2.0, -0.5, 1e-3]), rtol=1e-5)
+    np.testing.assert_allclose(m, 0.1 * 1e-6 * np.array([2.0, -0.5, 1e-3]), rtol=1e-12)
+    theta = np.array([2.0, -0.5])
+    m, v = np.zeros(2), np.zeros(2)
+    orc.adam_step(theta, np.zeros(2), m, v, lr=1e-2, step=1)
+    assert (theta == [2.0, -0.5]).all() and (m == 0).all()
