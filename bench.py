@@ -355,9 +355,14 @@ def headline_extras(c, ms_fwd, ms_bwd, n, steps, torch):
         extras["encode_mlp_fwd"] = {"ms": ms_mlp, "mpoints_s": w.B / (ms_mlp * 1e-3) / 1e6, "n_out": 1,
                                     "network_tflop_s": flops / (ms_mlp * 1e-3) / 1e12,
                                     "ms_over_forward_alone": ms_mlp - ms_fwd_alone}
-        # training the whole model: fused forward that keeps y, backward of the network (dL/dout = out, as for
-        # a squared loss against zero), sorted backward of the encoding into the tables, optimiser on the tables
-        from paper_2201_05989_amd import mlp_bwd
+        # training the whole model: fused forward that keeps y, the loss's gradient (the workload's loss against a
+        # synthetic target), backward of the network, sorted backward of the encoding into the tables, optimiser on
+        # the tables and on the network's weights
+        from paper_2201_05989_amd import loss_grad, mlp_bwd
+        loss_kind = "mape" if w.name.startswith("sdf") else "l2"  # Section 4, "Training"
+        target = torch.from_numpy(np.random.default_rng(11).normal(size=(w.B, 1)).astype(np.float32)).cuda()
+        dout = torch.empty_like(target)
+        loss_sum = torch.zeros(1, dtype=torch.float64, device="cuda")
         yk = torch.empty((w.B, n_in), dtype=torch.float16, device="cuda")
         dyk = torch.empty_like(yk)
         dWs = views(net_grad)
@@ -368,7 +373,8 @@ def headline_extras(c, ms_fwd, ms_bwd, n, steps, torch):
 
         def model_step():
             grid.encode_mlp_fwd(xd, td, W1, W2, W3, o, y=yk)
-            mlp_bwd(yk, W1, W2, W3, o, dyk, *dWs)
+            loss_grad(o, target, loss_kind, 1.0, dout, loss_sum)
+            mlp_bwd(yk, W1, W2, W3, dout, dyk, *dWs)
             grid.encode_bwd(xd, dyk, grad, overwrite=True)
             adam(zero_grad=False)
             net_counter[0] += 1  # the network's weights: a small learning rate, the gradient cleared for the next step
@@ -379,8 +385,9 @@ def headline_extras(c, ms_fwd, ms_bwd, n, steps, torch):
         extras["network_training"] = {
             "ms_mlp_bwd": ms_net_bwd, "mlp_bwd_tflop_s": 4.0 * flops / (ms_net_bwd * 1e-3) / 1e12,
             "ms_step": ms_model, "mpoints_s": w.B / (ms_model * 1e-3) / 1e6,
-            "step": "encode_mlp_fwd_train + mlp_bwd + encode_bwd_ws (overwrite) + adam_step on the tables + adam_step on "
-                    "the network's weights"}
+            "loss": loss_kind,
+            "step": "encode_mlp_fwd_train + loss_grad + mlp_bwd + encode_bwd_ws (overwrite) + adam_step on the tables + "
+                    "adam_step on the network's weights"}
     return extras
 
 

@@ -304,6 +304,27 @@ hg_status hashgrid_mlp_bwd(uint32_t B, uint32_t n_in, uint32_t n_out, const void
                            const void* W3, const float* dLdout, void* dLdy, float* dW1, float* dW2, float* dW3,
                            void* stream);
 
+/* Training losses (Section 4, "Training"): the squared error (p - t)^2 the paper uses for images and
+ * radiance fields, and the mean absolute percentage error |p - t| / (|t| + 0.01) it uses for signed
+ * distance functions.  (Its luminance-relative loss for radiance caching is defined elsewhere and
+ * is not offered.) */
+typedef enum { HG_LOSS_L2 = 0, HG_LOSS_MAPE = 1 } hg_loss;
+
+/* The loss's derivative with respect to the network's output, per scalar and times `scale`, as
+ * hashgrid_mlp_bwd takes it:  dLdout[i] = scale * 2 (p_i - t_i)  or  scale * sign(p_i - t_i) /
+ * (|t_i| + 0.01), sign(0) = 0.  The paper's losses are means over the batch: callers pass
+ * scale = 1/n, times the factor by which they scale the loss for half-precision gradients.
+ * Arithmetic fp32.
+ *   prediction, target [n] fp32  device, 4-byte aligned, read (n = B * n_out scalars)
+ *   dLdout             [n] fp32  device, 4-byte aligned, written in full
+ *   loss_sum           one fp64  device, 8-byte aligned, may be NULL: the UNSCALED loss values of the
+ *                      n scalars are ADDED to it (clear it first; one atomic addition per
+ *                      workgroup, so the last bits vary from run to run)
+ * 16-byte aligned arrays are read and written four scalars at a time.  HG_ERR_INVALID_ARG for an
+ * unknown loss, a scale that is not finite, NULL or misaligned pointers.  n == 0 is HG_OK. */
+hg_status hashgrid_loss_grad(uint64_t n, const float* prediction, const float* target, uint32_t loss, float scale,
+                             float* dLdout, double* loss_sum, void* stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char* hashgrid_strerror(hg_status s);
 

@@ -23,6 +23,8 @@ HG_BWD_COUNTED = 1
 HG_BWD_OVERWRITE = 2
 HG_ERR_UNSUPPORTED = 2
 HG_STATIC_SCRATCH_BYTES = 64 << 20
+HG_LOSS_L2, HG_LOSS_MAPE = 0, 1
+_LOSSES = {"l2": HG_LOSS_L2, "mape": HG_LOSS_MAPE, HG_LOSS_L2: HG_LOSS_L2, HG_LOSS_MAPE: HG_LOSS_MAPE}
 
 _DTYPES = {"f32": HG_F32, "f16": HG_F16, torch.float32: HG_F32, torch.float16: HG_F16}
 _TORCH = {HG_F32: torch.float32, HG_F16: torch.float16}
@@ -32,7 +34,7 @@ EXPORTS = ("hashgrid_create", "hashgrid_destroy", "hashgrid_n_entries", "hashgri
            "hashgrid_debug_indices", "hashgrid_debug_count_outside", "hashgrid_strerror", "hashgrid_bwd_workspace_bytes",
            "hashgrid_encode_bwd_ws", "hashgrid_encode_fwd_ws", "hashgrid_bwd_ws_pays", "hashgrid_adam_step",
            "hashgrid_encode_mlp_fwd", "hashgrid_encode_bwd_static", "hashgrid_encode_mlp_fwd_train", "hashgrid_mlp_bwd",
-           "hashgrid_adam_step_half_grad")
+           "hashgrid_adam_step_half_grad", "hashgrid_loss_grad")
 PROBE_EXPORTS = ("hashgrid_probe_copy", "hashgrid_probe_gather", "hashgrid_probe_atomic_add",
                  "hashgrid_probe_gather_lines")
 
@@ -104,6 +106,8 @@ def load_library() -> ctypes.CDLL:
     lib.hashgrid_adam_step_half_grad.argtypes = [u64, vp, vp, vp, vp, vp, ctypes.POINTER(hashgrid_adam_config), u32,
                                                  ctypes.c_int, ctypes.c_float, vp]
     lib.hashgrid_adam_step_half_grad.restype = ctypes.c_int
+    lib.hashgrid_loss_grad.argtypes = [u64, vp, vp, u32, ctypes.c_float, vp, vp, vp]
+    lib.hashgrid_loss_grad.restype = ctypes.c_int
     lib.hashgrid_strerror.argtypes = [ctypes.c_int]
     lib.hashgrid_strerror.restype = ctypes.c_char_p
     _lib = lib
@@ -380,6 +384,25 @@ def adam_step(params_master: torch.Tensor, grad: torch.Tensor, m: torch.Tensor, 
         _check(lib.hashgrid_adam_step(n, params_master.data_ptr(), half_ptr, grad.data_ptr(), m.data_ptr(),
                                       v.data_ptr(), ctypes.byref(cfg), step, int(zero_grad), _stream_ptr(stream)),
                "hashgrid_adam_step")
+
+
+def loss_grad(prediction: torch.Tensor, target: torch.Tensor, loss, scale: float, dLdout: torch.Tensor,
+              loss_sum: torch.Tensor | None = None, stream=None) -> None:
+    """hashgrid_loss_grad: dLdout = scale * d loss / d prediction per scalar ("l2" or "mape"); the unscaled loss values
+    are added to loss_sum (one fp64 device scalar) when given."""
+    n = prediction.numel()
+    for name, t in (("prediction", prediction), ("target", target), ("dLdout", dLdout)):
+        if not (t.is_cuda and t.is_contiguous() and t.dtype == torch.float32 and t.numel() == n):
+            raise HashGridError(f"{name} must be a contiguous fp32 device tensor of {n} scalars")
+    if loss not in _LOSSES:
+        raise HashGridError(f"unknown loss {loss!r}")
+    sum_ptr = None
+    if loss_sum is not None:
+        if not (loss_sum.is_cuda and loss_sum.dtype == torch.float64 and loss_sum.numel() == 1):
+            raise HashGridError("loss_sum must be one fp64 device scalar")
+        sum_ptr = loss_sum.data_ptr()
+    _check(load_library().hashgrid_loss_grad(n, prediction.data_ptr(), target.data_ptr(), _LOSSES[loss], scale,
+                                             dLdout.data_ptr(), sum_ptr, _stream_ptr(stream)), "hashgrid_loss_grad")
 
 
 def probe_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:

@@ -11,7 +11,7 @@ INCLUDE = os.path.join(_ROOT, "include")
 LIB_PATH = os.environ.get("HASHGRID_LIB") or os.path.join(_PKG, "libhashgrid.so")
 PROBES_LIB_PATH = os.path.join(_PKG, "libhashgrid_probes.so")  # the benchmark's machine probes, a library of their own
 
-SOURCES = ["hashgrid.hip", "bwd_binned.hip", "adam.hip", "mlp_fused.hip", "mlp_bwd.hip"]
+SOURCES = ["hashgrid.hip", "bwd_binned.hip", "adam.hip", "loss.hip", "mlp_fused.hip", "mlp_bwd.hip"]
 PROBE_SOURCES = ["probes.hip"]
 
 # fp contraction is off so that the scale step of the encoding stays one rounded
