@@ -36,6 +36,11 @@
  *     want 16 bytes and rows of y that are a multiple of 16 bytes; other cases take a slower path.
  *   - Errors are returned as status codes; nothing aborts or throws.  B = 0 is
  *     HG_OK and launches nothing.
+ *   - Every entry point only launches kernels on the caller's stream (no allocation, no memset,
+ *     no synchronisation), so calls can be recorded into a HIP graph.  What a call derives on the
+ *     host from its scalar arguments travels as kernel arguments and is fixed at capture: a
+ *     replayed hashgrid_adam_step repeats the bias correction of the `step` it was recorded with
+ *     (callers that replay update the node's arguments or record one node per step).
  */
 #ifndef HASHGRID_H
 #define HASHGRID_H
