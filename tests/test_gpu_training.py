@@ -4,7 +4,8 @@ model must learn.  Every call is held to the oracle by the parity tests; what on
 fit together (layouts, scales, the half-precision working copies following their master copies) over hundreds of
 steps.  Targets are synthetic closed forms standing in for the paper's image and signed-distance data:
 
-* a 2-D "image" with sharp edges and fine stripes, squared error (as for the gigapixel task);
+* a 2-D "image" with sharp edges and fine stripes, squared error (as for the gigapixel task), with one and with
+  three output channels;
 * the signed distance to a sphere in 3-D, mean absolute percentage error (as for the SDF task).
 
 Bars are on the trend, with a wide margin under what a run reaches (the weight gradients are summed with
@@ -28,13 +29,19 @@ def image(x):
     return (0.5 * board + 0.4 * disc + stripes).unsqueeze(1).contiguous()
 
 
+def colour_image(x):
+    # three channels that share edges but differ in phase and scale, as the channels of a photograph do
+    g = image(x)[:, 0]
+    return torch.stack([g, 0.8 * g + 0.1 * torch.sin(40.0 * x[:, 0]), 1.0 - g], dim=1).contiguous()
+
+
 def sphere(x):
     return (torch.linalg.norm(x - 0.5, dim=1) - 0.3).unsqueeze(1).contiguous()
 
 
-def train(d, L, T, N_max, target, loss, lr, steps, B, seed):
+def train(d, L, T, N_max, target, loss, lr, steps, B, seed, n_out=1):
     torch.manual_seed(seed)
-    F, n_in, n_out = 2, 2 * L, 1
+    F, n_in = 2, 2 * L
     grid = HashGrid(d, L, F, T, 16, N_max, "f16", "f16")
     tab = (torch.rand((grid.n_entries, F), device="cuda") * 2e-4 - 1e-4)  # Section 4, "Initialization"
     tab16, tab_g = tab.half(), torch.zeros_like(tab)
@@ -71,7 +78,7 @@ def train(d, L, T, N_max, target, loss, lr, steps, B, seed):
         grid.encode_bwd(x, dy, tab_g, overwrite=True)
         adam_step(tab, tab_g, tab_m, tab_v, step, lr=lr, params_half=tab16, zero_grad=False)
         adam_step(net, net_g, net_m, net_v, step, lr=lr, params_half=net16, zero_grad=True, l2_reg=1e-6)
-        history.append(float(total.cpu()[0]) / B)
+        history.append(float(total.cpu()[0]) / (B * n_out))
     assert torch.isfinite(tab).all() and torch.isfinite(net).all()
     assert torch.equal(tab16, tab.half()) and torch.equal(net16, net.half())  # the working copies follow their masters
     return history
@@ -84,6 +91,14 @@ def test_an_image_is_learned_with_the_squared_error():
     variance = float(image(x).var())  # what the best constant prediction leaves
     print(f"image: loss {first:.4f} -> {last:.5f}; variance of the target {variance:.4f}")
     assert last < first / 30 and last < variance / 20
+
+
+def test_three_output_channels_are_learned_together():
+    h = train(d=2, L=16, T=1 << 17, N_max=1024, target=colour_image, loss="l2", lr=1e-2, steps=400, B=1 << 14, seed=3,
+              n_out=3)
+    first, last = np.mean(h[:3]), np.mean(h[-10:])
+    print(f"colour image: loss {first:.4f} -> {last:.5f}")
+    assert last < first / 30
 
 
 def test_a_signed_distance_is_learned_with_the_percentage_error():
