@@ -16,7 +16,7 @@ import numpy as np
 import pytest
 import torch
 
-from paper_2201_05989_amd import HashGrid, adam_step, loss_grad, mlp_bwd
+from paper_2201_05989_amd import HashGridModel
 
 pytestmark = pytest.mark.gpu
 
@@ -41,46 +41,22 @@ def sphere(x):
 
 def train(d, L, T, N_max, target, loss, lr, steps, B, seed, n_out=1):
     torch.manual_seed(seed)
-    F, n_in = 2, 2 * L
-    grid = HashGrid(d, L, F, T, 16, N_max, "f16", "f16")
-    tab = (torch.rand((grid.n_entries, F), device="cuda") * 2e-4 - 1e-4)  # Section 4, "Initialization"
-    tab16, tab_g = tab.half(), torch.zeros_like(tab)
-    tab_m, tab_v = torch.zeros_like(tab), torch.zeros_like(tab)
-    shapes = [(64, n_in), (64, 64), (n_out, 64)]
-    init = [(torch.rand(s, device="cuda") * 2 - 1) * np.sqrt(6.0 / (s[0] + s[1])) for s in shapes]  # Glorot and Bengio
-    net = torch.cat([a.reshape(-1) for a in init]).contiguous()
-    net16, net_g = net.half(), torch.zeros_like(net)
-    net_m, net_v = torch.zeros_like(net), torch.zeros_like(net)
-
-    def views(flat):
-        out, at = [], 0
-        for r, c in shapes:
-            out.append(flat[at:at + r * c].view(r, c))
-            at += r * c
-        return out
-
-    W, dW = views(net16), views(net_g)
-    out = torch.empty((B, n_out), device="cuda")
-    dout = torch.empty_like(out)
-    y = torch.empty((B, n_in), dtype=torch.float16, device="cuda")
-    dy = torch.empty_like(y)
-    total = torch.zeros(1, dtype=torch.float64, device="cuda")
+    model = HashGridModel(d, n_out, L=L, F=2, T=T, N_min=16, N_max=N_max, loss=loss, lr=lr, seed=seed)
     history = []
-    for step in range(1, steps + 1):
+    for _ in range(steps):
         x = torch.rand((B, d), device="cuda")
-        t = target(x)
-        grid.encode_mlp_fwd(x, tab16, *W, out, y=y)
-        total.zero_()
-        # the gradient of the summed loss: Adam does not care about the factor, and 1/B would push dL/dout, which
-        # the network's backward pass rounds to half precision, into the subnormals
-        loss_grad(out, t, loss, 1.0, dout, total)
-        mlp_bwd(y, *W, dout, dy, *dW)
-        grid.encode_bwd(x, dy, tab_g, overwrite=True)
-        adam_step(tab, tab_g, tab_m, tab_v, step, lr=lr, params_half=tab16, zero_grad=False)
-        adam_step(net, net_g, net_m, net_v, step, lr=lr, params_half=net16, zero_grad=True, l2_reg=1e-6)
-        history.append(float(total.cpu()[0]) / (B * n_out))
-    assert torch.isfinite(tab).all() and torch.isfinite(net).all()
-    assert torch.equal(tab16, tab.half()) and torch.equal(net16, net.half())  # the working copies follow their masters
+        model.step(x, target(x))
+        history.append(model.last_loss())
+    assert model.steps == steps
+    assert torch.isfinite(model.tables).all() and torch.isfinite(model.weights).all()
+    # the working copies follow their masters
+    assert torch.equal(model.tables_half, model.tables.half()) and torch.equal(model.weights_half, model.weights.half())
+    # what the model predicts on fresh points is what the training loss says
+    x = torch.rand((1 << 14, d), device="cuda")
+    t = target(x)
+    p = model.infer(x)
+    err = ((p - t) ** 2).mean() if loss == "l2" else ((p - t).abs() / (t.abs() + 0.01)).mean()
+    assert float(err) < 3 * np.mean(history[-10:])
     return history
 
 
