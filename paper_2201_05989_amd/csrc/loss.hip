@@ -82,8 +82,12 @@ extern "C" hg_status hashgrid_loss_grad(uint64_t n, const float* prediction, con
   if ((bits & 3) || (reinterpret_cast<uintptr_t>(loss_sum) & 7)) return HG_ERR_INVALID_ARG;
   const bool vec = (bits & 15) == 0;
   const uint64_t items = vec ? (n + 3) / 4 : n;
-  const uint64_t want = (items + hg::kLossThreads - 1) / hg::kLossThreads;
-  const uint32_t blocks = (uint32_t)(want > 4096 ? 4096 : want);
+  // Few, fat workgroups: each ends with one atomic addition to the same word, and those are served one
+  // after the other (256 workgroups that finish together spend 5 us there, more than the kernel's work
+  // at the size of a training batch).
+  constexpr uint64_t kItemsPerThread = 4;
+  const uint64_t want = (items + hg::kLossThreads * kItemsPerThread - 1) / (hg::kLossThreads * kItemsPerThread);
+  const uint32_t blocks = (uint32_t)(want > 512 ? 512 : want);
   hipStream_t s = static_cast<hipStream_t>(stream);
   using Kernel = void (*)(uint64_t, const float*, const float*, float, float*, double*);
   static const Kernel kernels[2][2] = {{hg::loss_grad<HG_LOSS_L2, false>, hg::loss_grad<HG_LOSS_L2, true>},
