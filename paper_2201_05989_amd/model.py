@@ -1,7 +1,8 @@
 """The paper's model as one object (Section 4): the encoding followed by the 64-64 ReLU network, trained with Adam on
 tables and weights.  Bookkeeping only: every step of a training iteration is one call into the C-ABI library
 (hashgrid_encode_mlp_fwd_train, hashgrid_loss_grad, hashgrid_mlp_bwd, hashgrid_encode_bwd[_ws], hashgrid_adam_step
-twice); this file allocates the buffers and keeps the step counter.
+twice; hashgrid_encode_bwd_input for the gradient with respect to the position); this file allocates the buffers and
+keeps the step counter.
 
 Defaults are the paper's (Section 4, "Initialization" and "Training"): tables U(-1e-4, 1e-4) in half precision behind a
 full-precision master copy, Glorot-uniform weights, Adam with beta1 = 0.9, beta2 = 0.99, eps = 1e-15, an L2 factor
@@ -62,6 +63,21 @@ class HashGridModel:
     def infer(self, x: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
         """The network's output [B, n_out] fp32 for points x [B, d] in [0,1)^d."""
         return self.grid.encode_mlp_fwd(x, self.tables_half, *self._W, out)
+
+    def input_gradient(self, x: torch.Tensor, dLdout: torch.Tensor | None = None) -> torch.Tensor:
+        """d(sum_i dLdout_i * out_i) / dx [B, d] fp32: with the default dLdout = 1 and one output, the gradient of the
+        output with respect to the position (the normal of a signed distance function, Section 3: the encoding is
+        continuous and its derivative piecewise constant).  Three calls: the fused forward keeping y, the network's
+        backward pass (its weight gradients go to a scratch array), hashgrid_encode_bwd_input."""
+        B = x.shape[0]
+        self._buffers(B)
+        self.grid.encode_mlp_fwd(x, self.tables_half, *self._W, self._out, y=self._y)
+        if dLdout is None:
+            dLdout = torch.ones((B, self.n_out), device="cuda")
+        if not hasattr(self, "_dW_scratch"):
+            self._dW_scratch = self._views(torch.zeros_like(self._net_grad))
+        mlp_bwd(self._y, *self._W, dLdout, self._dy, *self._dW_scratch)
+        return self.grid.encode_bwd_input(x, self.tables_half, self._dy)
 
     def step(self, x: torch.Tensor, target: torch.Tensor) -> None:
         """One training iteration on the batch (x [B, d], target [B, n_out], fp32 device tensors).  Nothing here
