@@ -291,6 +291,18 @@ hg_status hashgrid_encode_mlp_fwd_train(const hashgrid_t* hg, uint32_t B, const 
                                         const void* W1, const void* W2, const void* W3, uint32_t n_out, float* out,
                                         void* y, void* stream);
 
+/* That network alone (Section 4, "Architecture"), on features that are in memory: for a second
+ * network whose inputs are not (only) this encoding's output, or to re-evaluate the network on kept
+ * features.  Same arithmetic as the network part of hashgrid_encode_mlp_fwd: y is read as fp16, h1 and
+ * h2 are rounded to fp16, products accumulate in fp32 on the matrix cores.
+ *   y    [B, n_in]   fp16, device, 16-byte aligned, read
+ *   W1 [64, n_in], W2 [64, 64], W3 [n_out, 64]   fp16, device, 8-byte aligned, read
+ *   out  [B, n_out]  fp32, device, written in full
+ * HG_ERR_UNSUPPORTED unless n_in is a multiple of 8 and at most 64 and n_out at most 32;
+ * HG_ERR_INVALID_ARG for NULL or misaligned pointers, n_in == 0 or n_out == 0.  B == 0 is HG_OK. */
+hg_status hashgrid_mlp_fwd(uint32_t B, uint32_t n_in, uint32_t n_out, const void* y, const void* W1, const void* W2,
+                           const void* W3, float* out, void* stream);
+
 /* Backward pass of that network (Section 4, "Architecture"; chain rule through the three layers,
  * ReLU passing the gradient where its output is positive), in one kernel on the matrix cores.  The
  * hidden activations are recomputed from y.  Half-precision operands with fp32 accumulation: dL/dout

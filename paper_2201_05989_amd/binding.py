@@ -34,7 +34,7 @@ EXPORTS = ("hashgrid_create", "hashgrid_destroy", "hashgrid_n_entries", "hashgri
            "hashgrid_debug_indices", "hashgrid_debug_count_outside", "hashgrid_strerror", "hashgrid_bwd_workspace_bytes",
            "hashgrid_encode_bwd_ws", "hashgrid_encode_fwd_ws", "hashgrid_bwd_ws_pays", "hashgrid_adam_step",
            "hashgrid_encode_mlp_fwd", "hashgrid_encode_bwd_static", "hashgrid_encode_mlp_fwd_train", "hashgrid_mlp_bwd",
-           "hashgrid_adam_step_half_grad", "hashgrid_loss_grad")
+           "hashgrid_adam_step_half_grad", "hashgrid_loss_grad", "hashgrid_mlp_fwd")
 PROBE_EXPORTS = ("hashgrid_probe_copy", "hashgrid_probe_gather", "hashgrid_probe_atomic_add",
                  "hashgrid_probe_gather_lines")
 
@@ -97,6 +97,8 @@ def load_library() -> ctypes.CDLL:
     lib.hashgrid_encode_mlp_fwd_train.restype = ctypes.c_int
     lib.hashgrid_mlp_bwd.argtypes = [u32, u32, u32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.hashgrid_mlp_bwd.restype = ctypes.c_int
+    lib.hashgrid_mlp_fwd.argtypes = [u32, u32, u32, vp, vp, vp, vp, vp, vp]
+    lib.hashgrid_mlp_fwd.restype = ctypes.c_int
     lib.hashgrid_bwd_ws_pays.argtypes = [vp, u32]
     lib.hashgrid_bwd_ws_pays.restype = ctypes.c_int
     lib.hashgrid_encode_bwd_ws.restype = ctypes.c_int
@@ -443,6 +445,20 @@ def probe_gather_lines(table: torch.Tensor, slice_words: int, n_slices: int, n_p
     _check(load_probes().hashgrid_probe_gather_lines(table.data_ptr(), slice_words, n_slices, n_points, n_levels,
                                                      seed, sink.data_ptr(), _stream_ptr(stream)),
            "hashgrid_probe_gather_lines")
+
+
+def mlp_fwd(y: torch.Tensor, W1: torch.Tensor, W2: torch.Tensor, W3: torch.Tensor, out: torch.Tensor | None = None,
+            stream=None) -> torch.Tensor:
+    """hashgrid_mlp_fwd: the 64-64 ReLU network on features y [B, n_in] fp16 that are in memory; out [B, n_out] fp32."""
+    B, n_in = y.shape
+    n_out = W3.shape[0]
+    if out is None:
+        out = torch.empty((B, n_out), dtype=torch.float32, device=y.device)
+    _check(load_library().hashgrid_mlp_fwd(
+        B, n_in, n_out, _dev(y, torch.float16, (B, n_in), "y"), _dev(W1, torch.float16, (64, n_in), "W1"),
+        _dev(W2, torch.float16, (64, 64), "W2"), _dev(W3, torch.float16, (n_out, 64), "W3"),
+        _dev(out, torch.float32, (B, n_out), "out"), _stream_ptr(stream)), "hashgrid_mlp_fwd")
+    return out
 
 
 def mlp_bwd(y: torch.Tensor, W1: torch.Tensor, W2: torch.Tensor, W3: torch.Tensor, dLdout: torch.Tensor,

@@ -67,6 +67,96 @@ __device__ __forceinline__ void store_hidden(_Float16* __restrict__ act, int p_r
   }
 }
 
+// The network on the 64 points of the calling wave, whose rows of inputs (n_in halves each) are in
+// `act`; weights in LDS as laid out by load_weights.  A layer's four blocks are computed before its
+// results overwrite the activations they were computed from.  point0: global index of the
+// workgroup's first point.
+__device__ __forceinline__ void network_of_wave(_Float16* __restrict__ act, const _Float16* __restrict__ w1,
+                                                const int w1_stride, const _Float16* __restrict__ w2,
+                                                const _Float16* __restrict__ w3, const int n_in, const uint32_t n_out,
+                                                const uint32_t B, const uint64_t point0, float* __restrict__ out) {
+  const int p0 = (int)(threadIdx.x & ~63u);
+  float16v h[4];
+#pragma unroll
+  for (int blk = 0; blk < 4; ++blk) {
+    const int pr = p0 + 32 * (blk & 1), nr = 32 * (blk >> 1);
+    h[blk] = n_in == 64   ? block_product<64>(w1, w1_stride, nr, act, pr)
+             : n_in == 32 ? block_product<32>(w1, w1_stride, nr, act, pr)
+             : n_in == 16 ? block_product<16>(w1, w1_stride, nr, act, pr)
+             : n_in == 8  ? block_product<8>(w1, w1_stride, nr, act, pr)
+             : n_in == 24 ? block_product<24>(w1, w1_stride, nr, act, pr)
+             : n_in == 40 ? block_product<40>(w1, w1_stride, nr, act, pr)
+             : n_in == 48 ? block_product<48>(w1, w1_stride, nr, act, pr)
+                          : block_product<56>(w1, w1_stride, nr, act, pr);
+  }
+#pragma unroll
+  for (int blk = 0; blk < 4; ++blk) store_hidden(act, p0 + 32 * (blk & 1), 32 * (blk >> 1), h[blk]);
+#pragma unroll
+  for (int blk = 0; blk < 4; ++blk)
+    h[blk] = block_product<kHidden>(w2, kActStride, 32 * (blk >> 1), act, p0 + 32 * (blk & 1));
+#pragma unroll
+  for (int blk = 0; blk < 4; ++blk) store_hidden(act, p0 + 32 * (blk & 1), 32 * (blk >> 1), h[blk]);
+  const int lane = threadIdx.x & 63;
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    const float16v o = block_product<kHidden>(w3, kActStride, 0, act, p0 + 32 * half);
+    const uint64_t point = point0 + p0 + 32 * half + (lane & 31);
+    if (point < B) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const uint32_t neuron = 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
+        if (neuron < n_out) out[point * n_out + neuron] = o[r];
+      }
+    }
+  }
+}
+
+// weights -> LDS in 8-byte pieces (rows are multiples of four halves, host-checked alignment): w1
+// [kHidden][n_in + pad], w2 [kHidden][kActStride], w3 [kMaxOut][kActStride] with rows from n_out on zero
+__device__ __forceinline__ void load_weights(_Float16* __restrict__ w1, _Float16* __restrict__ w2,
+                                             _Float16* __restrict__ w3, const _Float16* __restrict__ W1,
+                                             const _Float16* __restrict__ W2, const _Float16* __restrict__ W3,
+                                             const int n_in, const uint32_t n_out) {
+  const int block = (int)blockDim.x, w1_stride = n_in + kRowPad;
+  const int q1 = n_in / 4;  // pieces per row of W1
+  for (int i = threadIdx.x; i < kHidden * q1; i += block)
+    *reinterpret_cast<half4*>(w1 + (i / q1) * w1_stride + 4 * (i % q1)) = reinterpret_cast<const half4*>(W1)[i];
+  constexpr int q2 = kHidden / 4;
+  for (int i = threadIdx.x; i < kHidden * q2; i += block)
+    *reinterpret_cast<half4*>(w2 + (i / q2) * kActStride + 4 * (i % q2)) = reinterpret_cast<const half4*>(W2)[i];
+  for (int i = threadIdx.x; i < kMaxOut * q2; i += block) {
+    half4 v = {(_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f};
+    if ((uint32_t)(i / q2) < n_out) v = reinterpret_cast<const half4*>(W3)[i];
+    *reinterpret_cast<half4*>(w3 + (i / q2) * kActStride + 4 * (i % q2)) = v;
+  }
+}
+
+// The network alone, on features that are in memory (hashgrid_mlp_fwd): every thread brings the row of
+// its point into LDS, then each wave runs the network on its 64 points.
+constexpr int kMlpOnlyBlock = 256;
+__global__ __launch_bounds__(kMlpOnlyBlock) void mlp_fwd_from_features(const uint32_t B, const int n_in,
+                                                                       const _Float16* __restrict__ y,
+                                                                       const _Float16* __restrict__ W1,
+                                                                       const _Float16* __restrict__ W2,
+                                                                       const _Float16* __restrict__ W3,
+                                                                       const uint32_t n_out, float* __restrict__ out) {
+  extern __shared__ _Float16 lds[];
+  const int w1_stride = n_in + kRowPad;
+  _Float16* act = lds;                                // [kMlpOnlyBlock][kActStride]
+  _Float16* w1 = act + kMlpOnlyBlock * kActStride;    // as in encode_mlp_fwd
+  _Float16* w2 = w1 + kHidden * w1_stride;
+  _Float16* w3 = w2 + kHidden * kActStride;
+  load_weights(w1, w2, w3, W1, W2, W3, n_in, n_out);
+  const uint64_t point0 = (uint64_t)blockIdx.x * kMlpOnlyBlock;
+  const uint64_t b0 = point0 + threadIdx.x;
+  const uint64_t b = b0 < B ? b0 : B - 1;  // idle lanes of the last workgroup shadow the last point
+  _Float16* my_row = act + threadIdx.x * kActStride;
+  for (int k = 0; k < n_in; k += 4)  // rows of y are 16-byte aligned, rows in LDS 8-byte
+    *reinterpret_cast<half4*>(my_row + k) = *reinterpret_cast<const half4*>(y + b * n_in + k);
+  __syncthreads();
+  network_of_wave(act, w1, w1_stride, w2, w3, n_in, n_out, B, point0, out);
+}
+
 template <int D, int F>
 __global__ __launch_bounds__(kMlpBlock) void encode_mlp_fwd(const LevelTable lv, const bool smooth, const uint32_t B,
                                                             const float* __restrict__ x,
@@ -84,20 +174,7 @@ __global__ __launch_bounds__(kMlpBlock) void encode_mlp_fwd(const LevelTable lv,
   _Float16* w2 = w1 + kHidden * w1_stride;            // [kHidden][kActStride]
   _Float16* w3 = w2 + kHidden * kActStride;           // [kMaxOut][kActStride], rows from n_out on are zero
 
-  // weights -> LDS in 8-byte pieces (rows are multiples of four halves, host-checked alignment)
-  {
-    const int q1 = n_in / 4;  // pieces per row of W1
-    for (int i = threadIdx.x; i < kHidden * q1; i += block)
-      *reinterpret_cast<half4*>(w1 + (i / q1) * w1_stride + 4 * (i % q1)) = reinterpret_cast<const half4*>(W1)[i];
-    constexpr int q2 = kHidden / 4;
-    for (int i = threadIdx.x; i < kHidden * q2; i += block)
-      *reinterpret_cast<half4*>(w2 + (i / q2) * kActStride + 4 * (i % q2)) = reinterpret_cast<const half4*>(W2)[i];
-    for (int i = threadIdx.x; i < kMaxOut * q2; i += block) {
-      half4 v = {(_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f};
-      if ((uint32_t)(i / q2) < n_out) v = reinterpret_cast<const half4*>(W3)[i];
-      *reinterpret_cast<half4*>(w3 + (i / q2) * kActStride + 4 * (i % q2)) = v;
-    }
-  }
+  load_weights(w1, w2, w3, W1, W2, W3, n_in, n_out);
 
   // the encoding, as in the forward kernel: one thread per point, level by level
   const uint32_t b0 = blockIdx.x * block + threadIdx.x;
@@ -149,42 +226,7 @@ __global__ __launch_bounds__(kMlpBlock) void encode_mlp_fwd(const LevelTable lv,
       *reinterpret_cast<half4*>(y_out + (uint64_t)b0 * n_in + k) = *reinterpret_cast<const half4*>(my_row + k);
   }
 
-  // the network, per wave on its own 64 points; a layer's four blocks are computed before its
-  // results overwrite the activations they were computed from
-  const int p0 = (int)(threadIdx.x & ~63u);
-  float16v h[4];
-#pragma unroll
-  for (int blk = 0; blk < 4; ++blk) {
-    const int pr = p0 + 32 * (blk & 1), nr = 32 * (blk >> 1);
-    h[blk] = n_in == 64   ? block_product<64>(w1, w1_stride, nr, act, pr)
-             : n_in == 32 ? block_product<32>(w1, w1_stride, nr, act, pr)
-             : n_in == 16 ? block_product<16>(w1, w1_stride, nr, act, pr)
-             : n_in == 8  ? block_product<8>(w1, w1_stride, nr, act, pr)
-             : n_in == 24 ? block_product<24>(w1, w1_stride, nr, act, pr)
-             : n_in == 40 ? block_product<40>(w1, w1_stride, nr, act, pr)
-             : n_in == 48 ? block_product<48>(w1, w1_stride, nr, act, pr)
-                          : block_product<56>(w1, w1_stride, nr, act, pr);
-  }
-#pragma unroll
-  for (int blk = 0; blk < 4; ++blk) store_hidden(act, p0 + 32 * (blk & 1), 32 * (blk >> 1), h[blk]);
-#pragma unroll
-  for (int blk = 0; blk < 4; ++blk)
-    h[blk] = block_product<kHidden>(w2, kActStride, 32 * (blk >> 1), act, p0 + 32 * (blk & 1));
-#pragma unroll
-  for (int blk = 0; blk < 4; ++blk) store_hidden(act, p0 + 32 * (blk & 1), 32 * (blk >> 1), h[blk]);
-  const int lane = threadIdx.x & 63;
-#pragma unroll
-  for (int half = 0; half < 2; ++half) {
-    const float16v o = block_product<kHidden>(w3, kActStride, 0, act, p0 + 32 * half);
-    const uint64_t point = (uint64_t)blockIdx.x * block + p0 + 32 * half + (lane & 31);
-    if (point < B) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const uint32_t neuron = 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
-        if (neuron < n_out) out[point * n_out + neuron] = o[r];
-      }
-    }
-  }
+  network_of_wave(act, w1, w1_stride, w2, w3, n_in, n_out, B, (uint64_t)blockIdx.x * block, out);
 }
 
 template <int D, int F>
@@ -248,4 +290,21 @@ extern "C" hg_status hashgrid_encode_mlp_fwd_train(const hashgrid_t* hg, uint32_
                                                    float* out, void* y, void* stream) {
   if (B != 0 && !y) return HG_ERR_INVALID_ARG;
   return encode_mlp_fwd_any(hg, B, x, params, W1, W2, W3, n_out, out, y, stream);
+}
+
+extern "C" hg_status hashgrid_mlp_fwd(uint32_t B, uint32_t n_in, uint32_t n_out, const void* y, const void* W1,
+                                      const void* W2, const void* W3, float* out, void* stream) {
+  if (B == 0) return HG_OK;
+  if (B > HG_MAX_BATCH) return HG_ERR_UNSUPPORTED;
+  if (!y || !W1 || !W2 || !W3 || !out || n_in == 0 || n_out == 0) return HG_ERR_INVALID_ARG;
+  if (n_in % 8 != 0 || n_in > (uint32_t)hg::kHidden || n_out > (uint32_t)hg::kMaxOut) return HG_ERR_UNSUPPORTED;
+  auto bad = [](const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; };
+  if (bad(y, 16) || bad(W1, 8) || bad(W2, 8) || bad(W3, 8) || bad(out, 4)) return HG_ERR_INVALID_ARG;
+  const size_t lds = ((size_t)hg::kMlpOnlyBlock * hg::kActStride + (size_t)hg::kHidden * (n_in + hg::kRowPad) +
+                      (size_t)(hg::kHidden + hg::kMaxOut) * hg::kActStride) * sizeof(_Float16);  // 53 KB at most
+  hipLaunchKernelGGL(hg::mlp_fwd_from_features, dim3((B + hg::kMlpOnlyBlock - 1) / hg::kMlpOnlyBlock),
+                     dim3(hg::kMlpOnlyBlock), lds, static_cast<hipStream_t>(stream), B, (int)n_in,
+                     static_cast<const _Float16*>(y), static_cast<const _Float16*>(W1),
+                     static_cast<const _Float16*>(W2), static_cast<const _Float16*>(W3), n_out, out);
+  return hipGetLastError() == hipSuccess ? HG_OK : HG_ERR_DEVICE;
 }

@@ -94,3 +94,52 @@ def test_against_oracle(d, L, F, T, N_max, n_out, B, interp):
     assert (err <= 2.0 ** -10 * M + 1e-12).all(), f"worst {np.max(err / (M + 1e-300)):.2e} of M"
     assert np.median(err / (M + 1e-300)) < 1e-5
     assert np.abs(ref).max() > 1e-3
+
+
+# ---- hashgrid_mlp_fwd: the same network on features that are in memory ----
+
+@pytest.mark.parametrize("n_in,n_out,B", [(8, 1, 1), (16, 2, 63), (24, 3, 257), (32, 1, 4097), (40, 9, 1000), (48, 16, 255),
+                                          (56, 31, 300), (64, 32, 70001)])
+def test_network_alone_is_exact_where_nothing_rounds(n_in, n_out, B):
+    # sparse small-integer weights and inputs in multiples of 1/8: every activation is exact in half precision and
+    # every fp32 sum exact; a permuted operand, a transposed weight or a row of another point changes the values
+    from paper_2201_05989_amd import mlp_fwd
+    rng = np.random.default_rng(1000 * n_in + n_out)
+    W1 = (rng.integers(-1, 2, (64, n_in)) * (rng.random((64, n_in)) < 0.2)).astype(np.float16)
+    W2 = (rng.integers(-1, 2, (64, 64)) * (rng.random((64, 64)) < 0.1)).astype(np.float16)
+    W3 = rng.integers(-2, 3, (n_out, 64)).astype(np.float16)
+    y = (rng.integers(-8, 9, (B, n_in)) / 8.0).astype(np.float16)
+    ref = mlp.mlp_fwd(y, W1, W2, W3)
+    assert 0 < np.abs(ref).max() < 2048
+    out = torch.full((B, n_out), float("nan"), device="cuda")
+    mlp_fwd(dev(y), dev(W1), dev(W2), dev(W3), out)
+    np.testing.assert_array_equal(out.cpu().numpy().astype(np.float64), ref)
+
+
+def test_network_alone_equals_the_fused_call_on_its_kept_features_and_checks_its_arguments():
+    from paper_2201_05989_amd import binding, mlp_fwd
+    w = synth.WORKLOADS["sdf3d"]
+    rng = np.random.default_rng(3)
+    grid = HashGrid(w.d, w.L, w.F, w.T, w.N_min, w.N_max, "f16", "f16")
+    B = 20011
+    x = dev(synth.points_sdf(rng, B, 3))
+    theta = dev(synth.make_tables(rng, grid.n_entries, w.F, "f16", 1.0))
+    W1, W2, W3 = (dev(a) for a in weights(rng, w.L * w.F, 3))
+    y = torch.empty((B, w.L * w.F), dtype=torch.float16, device="cuda")
+    fused = grid.encode_mlp_fwd(x, theta, W1, W2, W3, y=y)
+    alone = mlp_fwd(y, W1, W2, W3)
+    assert torch.equal(fused, alone)  # the same instructions on the same half-precision features
+    # and against the oracle on those features, within the rounding bound of the module's header
+    ref = mlp.mlp_fwd(y.cpu().numpy(), W1.cpu().numpy(), W2.cpu().numpy(), W3.cpu().numpy())
+    M = mlp.magnitude_bound(y.cpu().numpy().astype(np.float64), W1.cpu().numpy(), W2.cpu().numpy(), W3.cpu().numpy())
+    err = np.abs(alone.cpu().numpy().astype(np.float64) - ref)
+    assert (err <= 2.0 ** -10 * M + 1e-12).all() and np.median(err / M) < 1e-4
+    lib = binding.load_library()
+    p = [t.data_ptr() for t in (y, W1, W2, W3, alone)]
+    assert lib.hashgrid_mlp_fwd(0, 32, 3, None, None, None, None, None, None) == 0          # B = 0
+    assert lib.hashgrid_mlp_fwd(B, 32, 3, None, p[1], p[2], p[3], p[4], None) == 1            # NULL features
+    assert lib.hashgrid_mlp_fwd(B, 32, 3, p[0] + 8, p[1], p[2], p[3], p[4], None) == 1        # misaligned features
+    assert lib.hashgrid_mlp_fwd(B, 32, 0, p[0], p[1], p[2], p[3], p[4], None) == 1            # no outputs
+    assert lib.hashgrid_mlp_fwd(B, 36, 3, p[0], p[1], p[2], p[3], p[4], None) == 2            # n_in not a multiple of 8
+    assert lib.hashgrid_mlp_fwd(B, 72, 3, p[0], p[1], p[2], p[3], p[4], None) == 2            # n_in > 64
+    assert lib.hashgrid_mlp_fwd(B, 32, 33, p[0], p[1], p[2], p[3], p[4], None) == 2           # n_out > 32
