@@ -278,6 +278,8 @@ hg_status hashgrid_adam_step_half_grad(uint64_t n_scalars, float* params_master,
  *   W2      [64, 64]        fp16
  *   W3      [n_out, 64]     fp16, 1 <= n_out <= 32
  *   out     [B, n_out]      fp32, device, written in full
+ * A network with one hidden layer (the density network of the paper's radiance fields, Section 4,
+ * "Architecture") is this one with W2 = identity: relu(h1) = h1 exactly, in every entry point below too.
  * HG_ERR_UNSUPPORTED unless d is 2 or 3, T a power of two, L*F a multiple of 8 and at most 64 and
  * the tables fp16; HG_ERR_INVALID_ARG for NULL or misaligned pointers or n_out == 0. */
 hg_status hashgrid_encode_mlp_fwd(const hashgrid_t* hg, uint32_t B, const float* x, const void* params,

@@ -143,3 +143,34 @@ def test_network_alone_equals_the_fused_call_on_its_kept_features_and_checks_its
     assert lib.hashgrid_mlp_fwd(B, 36, 3, p[0], p[1], p[2], p[3], p[4], None) == 2            # n_in not a multiple of 8
     assert lib.hashgrid_mlp_fwd(B, 72, 3, p[0], p[1], p[2], p[3], p[4], None) == 2            # n_in > 64
     assert lib.hashgrid_mlp_fwd(B, 32, 33, p[0], p[1], p[2], p[3], p[4], None) == 2           # n_out > 32
+
+
+def test_identity_second_layer_is_a_network_with_one_hidden_layer():
+    # Section 4, "Architecture": the density network of the radiance fields has one hidden layer.  With W2 = identity
+    # the second layer passes h1 through unchanged (h1 >= 0 and already half precision), forward and backward.
+    from paper_2201_05989_amd import mlp_bwd, mlp_fwd
+    rng = np.random.default_rng(9)
+    n_in, n_out, B = 32, 16, 5000
+    W1, _, W3 = weights(rng, n_in, n_out)
+    W2 = np.eye(64, dtype=np.float16)
+    y = rng.uniform(-1, 1, (B, n_in)).astype(np.float16)
+    out = mlp_fwd(dev(y), dev(W1), dev(W2), dev(W3)).cpu().numpy().astype(np.float64)
+    h1 = np.maximum(y.astype(np.float64) @ W1.astype(np.float64).T, 0).astype(np.float16).astype(np.float64)
+    ref = h1 @ W3.astype(np.float64).T
+    M = np.abs(y.astype(np.float64)) @ np.abs(W1.astype(np.float64)).T @ np.abs(W3.astype(np.float64)).T
+    assert (np.abs(out - ref) <= 2.0 ** -10 * M + 1e-12).all()
+    np.testing.assert_allclose(out, mlp.mlp_fwd(y, W1, W2, W3), rtol=0, atol=2.0 ** -10 * M.max())
+    # backward: dL/dy, dW1 and dW3 of the one-hidden-layer network from the two-hidden-layer kernel (points with a
+    # pre-activation next to the ReLU kink left out, as in test_gpu_mlp_bwd.py)
+    y = y[np.abs(y.astype(np.float64) @ W1.astype(np.float64).T).min(axis=1) > 1e-4]
+    B = len(y)
+    assert B > 4500
+    dout = rng.standard_normal((B, n_out)).astype(np.float32)
+    dy = torch.empty((B, n_in), dtype=torch.float16, device="cuda")
+    dWs = [torch.zeros((64, n_in), device="cuda"), torch.zeros((64, 64), device="cuda"), torch.zeros((n_out, 64), device="cuda")]
+    mlp_bwd(dev(y), dev(W1), dev(W2), dev(W3), dev(dout), dy, *dWs)
+    r = mlp.mlp_bwd(y, W1, W2, W3, dout)
+    mags = mlp.bwd_magnitudes(y, W1, W2, W3, dout)
+    for name, g, ref_g, m in (("dy", dy, r[0], mags[0]), ("dW1", dWs[0], r[1], mags[1]), ("dW3", dWs[2], r[3], mags[3])):
+        err = np.abs(g.cpu().numpy().astype(np.float64) - ref_g)
+        assert (err <= 2.0 ** -10 * m + (2.0 ** -11 * np.abs(ref_g) + 2.0 ** -24 if name == "dy" else 0.0) + 1e-30).all(), name
